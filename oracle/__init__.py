@@ -1,0 +1,6 @@
+"""TEST INFRASTRUCTURE: plain CPU oracle of the estimate / drop / compaction path.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package.  It shares nothing with the GPU library.
+"""
+from .reference import (build_oracle, compact, estimate_drop, expand_paths, run, stage_cost)  # noqa: F401

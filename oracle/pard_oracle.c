@@ -1,0 +1,310 @@
+/*
+ * TEST INFRASTRUCTURE -- plain CPU oracle for the batched latency estimate, drop
+ * decision and survivor compaction of PARD's proactive request dropping.
+ *
+ * This file is the slow, obviously-correct statement of what the GPU library
+ * must compute.  It is used only by the tests, the smoke check and the
+ * benchmark's CPU-baseline leg; the product path never calls it and shares no
+ * code, header, table or helper with it.
+ *
+ * What it follows (paper sections):
+ *   - Section 3.2 Eq.(1): end-to-end latency = preceding + current + subsequent modules.
+ *   - Section 3.2 Eq.(2): per-module latency = queueing delay + batch wait + execution.
+ *   - Section 3.2 Eq.(4) and the DAG sentence before it: the estimate is the sum of
+ *     the per-module terms along a downstream path; for a DAG, the maximum over all
+ *     downstream paths.
+ *   - Section 3.3: the queue is ordered by remaining latency budget (low budget first
+ *     or high budget first); arrival order is the paper's FCFS ablation (Section 5.3).
+ *   - Drop when the estimated end-to-end latency exceeds the SLO, i.e. when
+ *     now + estimate lies after the request's deadline (Section 3.2, end).
+ *
+ * Snapshot form (the paper's runtime averages need history, a snapshot has none):
+ * the wait of a request with `a` requests ahead of it in a stage with batch size B,
+ * W workers and batch-latency table lat[] is  floor(ceil(a/B) * lat[B] / W), and its
+ * execution latency is lat[min(B, a+1)].  In its own stage `a` is its queue position;
+ * in every downstream stage `a` is that stage's whole queue length.  All arithmetic
+ * is integer microseconds in 128-bit integers, so nothing can overflow; results are
+ * clamped to INT32_MAX on output only.
+ *
+ * Parity status: no value in the paper pins this path (it prints none for it).
+ * The pins are brute force on tiny inputs, closed forms, invariants and a hand-worked
+ * vector (tests/test_oracle_*.py).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define LAT_ENTRIES 64
+#define MODE_LBF 0
+#define MODE_HBF 1
+#define MODE_FCFS 2
+
+typedef __int128 wide_t;
+
+typedef struct {
+    int64_t key;
+    int32_t idx;
+} queued_t;
+
+static int cmp_queued(const void* pa, const void* pb) {
+    const queued_t* a = (const queued_t*)pa;
+    const queued_t* b = (const queued_t*)pb;
+    if (a->key != b->key) return a->key < b->key ? -1 : 1;
+    if (a->idx != b->idx) return a->idx < b->idx ? -1 : 1;   /* ties: original index ascending */
+    return 0;
+}
+
+/* A stage id outside [0,S) is a caller error; both implementations agree to read it
+ * as the nearest valid stage so that nothing is ever indexed out of bounds. */
+static int clamp_stage(int32_t s, int S) {
+    if (s < 0) return 0;
+    if (s >= S) return S - 1;
+    return s;
+}
+
+/* Eq.(2) in snapshot form: wait (queueing + batch wait) plus execution, with `a`
+ * requests ahead.  lat points at the stage's 64-entry table, lat[b-1] = latency of a
+ * batch of b. */
+static wide_t stage_cost(const int32_t* lat, int32_t B, int32_t W, int64_t a) {
+    int64_t batches_ahead = (a + B - 1) / B;                    /* ceil(a / B) */
+    wide_t wait = ((wide_t)batches_ahead * (wide_t)lat[B - 1]) / (wide_t)W;
+    int64_t b_seen = (a + 1 < B) ? a + 1 : B;                   /* batch the request runs in */
+    return wait + (wide_t)lat[b_seen - 1];
+}
+
+/* ---- all source-to-sink paths of one DAG, by depth-first search -------------- */
+
+typedef struct {
+    int32_t* ptr;      /* [P+1] */
+    int32_t* stage;    /* [ptr[P]] */
+    int64_t P, cap_ptr, len, cap_len;
+    int err;
+} paths_t;
+
+static void paths_push(paths_t* ps, const int32_t* stack, int depth) {
+    if (ps->P + 2 > ps->cap_ptr) {
+        ps->cap_ptr = ps->cap_ptr ? ps->cap_ptr * 2 : 16;
+        ps->ptr = (int32_t*)realloc(ps->ptr, sizeof(int32_t) * (size_t)ps->cap_ptr);
+    }
+    if (ps->len + depth > ps->cap_len) {
+        while (ps->len + depth > ps->cap_len) ps->cap_len = ps->cap_len ? ps->cap_len * 2 : 64;
+        ps->stage = (int32_t*)realloc(ps->stage, sizeof(int32_t) * (size_t)ps->cap_len);
+    }
+    if (ps->P == 0) ps->ptr[0] = 0;
+    memcpy(ps->stage + ps->len, stack, sizeof(int32_t) * (size_t)depth);
+    ps->len += depth;
+    ps->P += 1;
+    ps->ptr[ps->P] = (int32_t)ps->len;
+}
+
+static void paths_dfs(paths_t* ps, int S, const int32_t* row_ptr, const int32_t* col,
+                      int32_t* stack, int depth) {
+    if (ps->err) return;
+    if (depth > S) { ps->err = 1; return; }                     /* longer than S stages: a cycle */
+    int32_t v = stack[depth - 1];
+    if (row_ptr[v] == row_ptr[v + 1]) { paths_push(ps, stack, depth); return; }
+    for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+        int32_t w = col[e];
+        if (w < 0 || w >= S) { ps->err = 2; return; }
+        stack[depth] = w;
+        paths_dfs(ps, S, row_ptr, col, stack, depth + 1);
+    }
+}
+
+static int enumerate_paths(int S, const int32_t* row_ptr, const int32_t* col, paths_t* ps) {
+    memset(ps, 0, sizeof(*ps));
+    int32_t* indeg = (int32_t*)calloc((size_t)S, sizeof(int32_t));
+    int32_t* stack = (int32_t*)malloc(sizeof(int32_t) * (size_t)(S + 2));
+    for (int32_t e = row_ptr[0]; e < row_ptr[S]; ++e)
+        if (col[e] >= 0 && col[e] < S) indeg[col[e]] += 1; else ps->err = 2;
+    /* acyclic check (Kahn): peel stages whose predecessors are all peeled */
+    if (!ps->err) {
+        int32_t* left = (int32_t*)malloc(sizeof(int32_t) * (size_t)(S + 1));
+        int32_t* ready = (int32_t*)malloc(sizeof(int32_t) * (size_t)(S + 1));
+        int nready = 0, peeled = 0;
+        for (int s = 0; s < S; ++s) { left[s] = indeg[s]; if (!left[s]) ready[nready++] = s; }
+        while (nready) {
+            int32_t v = ready[--nready];
+            peeled += 1;
+            for (int32_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e)
+                if (--left[col[e]] == 0) ready[nready++] = col[e];
+        }
+        if (peeled != S) ps->err = 1;
+        free(left);
+        free(ready);
+    }
+    int nsrc = 0;
+    for (int s = 0; s < S && !ps->err; ++s) {
+        if (indeg[s] != 0) continue;
+        nsrc += 1;
+        stack[0] = s;
+        paths_dfs(ps, S, row_ptr, col, stack, 1);
+    }
+    if (!ps->err && nsrc == 0 && S > 0) ps->err = 1;            /* no source: every stage is on a cycle */
+    free(indeg);
+    free(stack);
+    return ps->err;
+}
+
+static void paths_free(paths_t* ps) {
+    free(ps->ptr);
+    free(ps->stage);
+}
+
+/* Exported for the tests: number of source-to-sink paths, longest path length (in
+ * stages) and, when out arrays are given, the paths themselves.  Returns 0, or
+ * 1 = cycle, 2 = edge out of range, 3 = output capacity too small. */
+int pard_oracle_paths(int32_t S, const int32_t* row_ptr, const int32_t* col,
+                      int64_t* num_paths, int64_t* max_len,
+                      int32_t* out_ptr, int64_t cap_ptr, int32_t* out_stage, int64_t cap_stage) {
+    paths_t ps;
+    int err = enumerate_paths(S, row_ptr, col, &ps);
+    if (err) { paths_free(&ps); return err; }
+    int64_t mx = 0;
+    for (int64_t p = 0; p < ps.P; ++p) {
+        int64_t L = ps.ptr[p + 1] - ps.ptr[p];
+        if (L > mx) mx = L;
+    }
+    if (num_paths) *num_paths = ps.P;
+    if (max_len) *max_len = mx;
+    if (out_ptr && out_stage) {
+        if (cap_ptr < ps.P + 1 || cap_stage < ps.len) { paths_free(&ps); return 3; }
+        if (ps.P) memcpy(out_ptr, ps.ptr, sizeof(int32_t) * (size_t)(ps.P + 1)); else out_ptr[0] = 0;
+        if (ps.len) memcpy(out_stage, ps.stage, sizeof(int32_t) * (size_t)ps.len);
+    }
+    paths_free(&ps);
+    return 0;
+}
+
+/* Exported for the tests: the per-stage cost alone, clamped to INT64_MAX. */
+int64_t pard_oracle_stage_cost(const int32_t* lat, int32_t B, int32_t W, int64_t a) {
+    wide_t c = stage_cost(lat, B, W, a);
+    wide_t cap = (wide_t)INT64_MAX;
+    return (int64_t)(c > cap ? cap : c);
+}
+
+/*
+ * Estimate + drop decision for K snapshots.
+ *
+ * Plan arrays (D = dag_shared ? 1 : K copies): row_ptr[D*(S+1)] with offsets relative
+ * to each DAG's own col block (blocks are concatenated in order), batch[D*S],
+ * workers[D*S], lat[D*S*64], mode[D*S].
+ * Snapshot arrays: arrival/deadline/stage[n], snap_ptr[K+1], now[K].
+ * Outputs: est[n], drop[n] in request order; order[n] (sorted position -> request id),
+ * seg_ptr[K*S+1] offsets of the (snapshot, stage) queues inside order.
+ * Returns 0, or a positive code for a malformed DAG.
+ */
+int pard_oracle_estimate_drop(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
+        int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+        const int32_t* snap_ptr, const int32_t* now,
+        int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
+        int32_t nthreads) {
+    (void)n;
+    if (nthreads < 1) nthreads = 1;
+    int status = 0;
+    /* start of each DAG's block inside col */
+    int64_t D = dag_shared ? 1 : K;
+    int64_t* col_base = (int64_t*)malloc(sizeof(int64_t) * (size_t)(D + 1));
+    col_base[0] = 0;
+    for (int64_t d = 0; d < D; ++d) col_base[d + 1] = col_base[d] + row_ptr[d * (S + 1) + S];
+
+    for (int32_t u = 0; u < K; ++u) {
+        int64_t d = dag_shared ? 0 : u;
+        const int32_t* rp = row_ptr + d * (S + 1);
+        const int32_t* cl = col + col_base[d];
+        const int32_t* B = batch + d * S;
+        const int32_t* Wk = workers + d * S;
+        const int32_t* L = lat + d * S * LAT_ENTRIES;
+        const int32_t* M = mode + d * S;
+        int64_t lo = snap_ptr[u], hi = snap_ptr[u + 1];
+        int64_t m = hi - lo;
+
+        /* 1. paths */
+        paths_t ps;
+        int err = enumerate_paths(S, rp, cl, &ps);
+        if (err) { status = err; paths_free(&ps); break; }
+
+        /* 2. queues: requests of this snapshot grouped by current stage */
+        int64_t* qlen = (int64_t*)calloc((size_t)S, sizeof(int64_t));
+        for (int64_t r = lo; r < hi; ++r) qlen[clamp_stage(stage[r], S)] += 1;
+        int64_t* qstart = (int64_t*)malloc(sizeof(int64_t) * (size_t)(S + 1));
+        qstart[0] = 0;
+        for (int s = 0; s < S; ++s) qstart[s + 1] = qstart[s] + qlen[s];
+        queued_t* q = (queued_t*)malloc(sizeof(queued_t) * (size_t)(m > 0 ? m : 1));
+        int64_t* fill = (int64_t*)calloc((size_t)S, sizeof(int64_t));
+        for (int64_t r = lo; r < hi; ++r) {
+            int s = clamp_stage(stage[r], S);
+            int64_t key;
+            if (M[s] == MODE_HBF) key = -(int64_t)deadline[r];       /* largest budget first */
+            else if (M[s] == MODE_FCFS) key = (int64_t)arrival[r];   /* arrival order */
+            else key = (int64_t)deadline[r];                         /* smallest budget first */
+            queued_t* slot = &q[qstart[s] + fill[s]++];
+            slot->key = key;
+            slot->idx = (int32_t)r;
+        }
+        /* 3. order every queue by (key, original index) */
+        #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+        for (int s = 0; s < S; ++s)
+            qsort(q + qstart[s], (size_t)qlen[s], sizeof(queued_t), cmp_queued);
+        for (int s = 0; s < S; ++s) seg_ptr[(int64_t)u * S + s] = (int32_t)(lo + qstart[s]);
+        for (int64_t j = 0; j < m; ++j) order[lo + j] = q[j].idx;
+
+        /* 4.-6. per request: maximum over the paths through its stage */
+        #pragma omp parallel for schedule(static) num_threads(nthreads)
+        for (int64_t j = 0; j < m; ++j) {
+            int32_t r = q[j].idx;
+            int k = clamp_stage(stage[r], S);
+            int64_t pos = j - qstart[k];                 /* requests ahead of r in its own queue */
+            wide_t best = -1;
+            for (int64_t p = 0; p < ps.P; ++p) {
+                int32_t a = ps.ptr[p], b = ps.ptr[p + 1];
+                int32_t at = -1;
+                for (int32_t t = a; t < b; ++t) if (ps.stage[t] == k) { at = t; break; }
+                if (at < 0) continue;                    /* path does not pass through stage k */
+                wide_t sum = stage_cost(L + (int64_t)k * LAT_ENTRIES, B[k], Wk[k], pos);
+                for (int32_t t = at + 1; t < b; ++t) {
+                    int32_t i = ps.stage[t];
+                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);
+                }
+                if (sum > best) best = sum;
+            }
+            wide_t cap = (wide_t)INT32_MAX;
+            wide_t finish = (wide_t)now[u] + best;
+            est[r] = (int32_t)(best > cap ? cap : best);
+            if (finish > cap) finish = cap;
+            drop[r] = (uint8_t)(finish > (wide_t)deadline[r]);
+        }
+        free(fill);
+        free(q);
+        free(qstart);
+        free(qlen);
+        paths_free(&ps);
+    }
+    seg_ptr[(int64_t)K * S] = snap_ptr[K];
+    free(col_base);
+    return status;
+}
+
+/*
+ * Survivor compaction: the queues of `order` with dropped requests removed, same
+ * order, plus their offsets.  surv_idx has capacity n; entries past surv_ptr[K*S]
+ * are left untouched.
+ */
+int pard_oracle_compact(int32_t K, int32_t S, int64_t n,
+                        const int32_t* order, const int32_t* seg_ptr, const uint8_t* drop,
+                        int32_t* surv_idx, int32_t* surv_ptr) {
+    (void)n;
+    int64_t out = 0;
+    for (int64_t g = 0; g < (int64_t)K * S; ++g) {
+        surv_ptr[g] = (int32_t)out;
+        for (int64_t j = seg_ptr[g]; j < seg_ptr[g + 1]; ++j) {
+            int32_t r = order[j];
+            if (!drop[r]) surv_idx[out++] = r;
+        }
+    }
+    surv_ptr[(int64_t)K * S] = (int32_t)out;
+    return 0;
+}
