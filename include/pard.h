@@ -1,0 +1,176 @@
+/*
+ * libpard -- batched end-to-end latency estimate, drop decision and survivor
+ * compaction for queued inference-pipeline requests, on one AMD MI355X (gfx950).
+ *
+ * The method is PARD's proactive request dropping (EuroSys '26), Section 3.2-3.3,
+ * posed on a snapshot of the queues:
+ *   - a request's end-to-end latency is split into preceding, current and subsequent
+ *     modules (Eq.(1)); every module contributes queueing + batch wait + execution
+ *     (Eq.(2)); the estimate is their sum along a downstream path (Eq.(4)) and, for a
+ *     DAG pipeline, the maximum over all downstream paths (Section 3.2, last paragraph);
+ *   - queues are ordered by remaining latency budget, lowest first (LBF) or highest
+ *     first (HBF) (Section 3.3); arrival order (FCFS) is the paper's ablation (Section 5.3);
+ *   - a request is dropped when the estimate says it cannot finish within its SLO.
+ *
+ * Snapshot form of the per-stage term, with `a` requests ahead in a stage with batch
+ * size B, W workers and batch-latency table lat[1..64] (integer microseconds):
+ *     cost(a) = floor( ceil(a / B) * lat[B] / W )  +  lat[ min(B, a + 1) ]
+ * In the request's own stage `a` is its 0-based queue position after ordering; in every
+ * downstream stage `a` is that stage's whole queue length.  estimate = max over the
+ * source-to-sink paths through the request's stage of the summed costs from its stage
+ * to the sink.  drop = (min(now + estimate, INT32_MAX) > deadline).  The estimate
+ * itself is reported clamped to INT32_MAX.  Ties in the queue order are broken by
+ * ascending request index.  A stage id outside [0, S) is read as the nearest valid one.
+ *
+ * Conventions
+ *   - C ABI.  Every function returns PARD_OK (0) or a negative pard_status; nothing
+ *     throws or aborts.
+ *   - "host" pointers are ordinary CPU memory, read only during the call.
+ *     "device" pointers are HIP device memory owned by the caller; they must stay
+ *     valid until the work queued on `stream` has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The two
+ *     hot calls only enqueue kernels: they do not allocate, free or synchronise.
+ *   - A plan is immutable after creation and may be used from several streams at
+ *     once, provided each concurrent call has its own workspace.
+ */
+#ifndef PARD_H_
+#define PARD_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PARD_LAT_ENTRIES 64      /* batch-latency table entries per stage: b = 1..64      */
+#define PARD_MAX_STAGES 64       /* S <= 64                                               */
+#define PARD_MAX_PATHS_PER_DAG 1024
+#define PARD_MAX_PATH_ENTRIES_PER_DAG 8192   /* sum of path lengths of one DAG            */
+#define PARD_MAX_WORKERS 1048576 /* W <= 2^20                                             */
+#define PARD_FUSED_SNAPSHOT_CAPACITY 8192    /* snapshots up to this size are processed by
+                                                one workgroup entirely in on-chip memory  */
+
+typedef enum {
+    PARD_OK = 0,
+    PARD_E_NULL = -1,            /* a required pointer is NULL                            */
+    PARD_E_BAD_SHAPE = -2,       /* K < 1, S outside 1..64, n < 0 or too large            */
+    PARD_E_BAD_BATCH = -3,       /* a batch size outside 1..64                            */
+    PARD_E_BAD_WORKERS = -4,     /* a worker count outside 1..PARD_MAX_WORKERS            */
+    PARD_E_BAD_LATENCY = -5,     /* a negative latency                                    */
+    PARD_E_BAD_DAG = -6,         /* edge out of range, self loop, cycle, bad row_ptr      */
+    PARD_E_TOO_MANY_PATHS = -7,  /* path expansion exceeds the per-DAG limits above       */
+    PARD_E_WORKSPACE = -8,       /* workspace NULL, misaligned or too small               */
+    PARD_E_HIP = -9,             /* a HIP runtime call failed                             */
+    PARD_E_BAD_MODE = -10,       /* order mode not one of PARD_ORDER_*                    */
+    PARD_E_UNSUPPORTED = -11     /* shape outside what this build can sort (see below)    */
+} pard_status;
+
+enum { PARD_ORDER_LBF = 0,       /* ascending deadline  (low remaining budget first)      */
+       PARD_ORDER_HBF = 1,       /* descending deadline (high remaining budget first)     */
+       PARD_ORDER_FCFS = 2 };    /* ascending arrival                                     */
+
+typedef struct pard_plan pard_plan_t;    /* opaque; owned by the library until destroyed  */
+
+/*
+ * Pipeline description (Section 4 "Implementation": a pipeline is a set of modules with
+ * predecessor/successor lists; Section 3.2: profiled batch latencies, batch sizes).
+ * All arrays are HOST memory, int32.  D = dag_shared ? 1 : num_snapshots descriptions
+ * are stored back to back.  The successor lists of DAG d are
+ * dag_col[base_d + dag_row_ptr[d*(S+1)+s] .. base_d + dag_row_ptr[d*(S+1)+s+1]) where
+ * dag_row_ptr[d*(S+1)] == 0 and base_d is the sum of the previous DAGs' edge counts.
+ */
+typedef struct {
+    int32_t num_snapshots;       /* K >= 1                                                */
+    int32_t num_stages;          /* S in 1..64, the same for every snapshot               */
+    int32_t dag_shared;          /* 1: one description for all snapshots, 0: one each     */
+    const int32_t* dag_row_ptr;  /* [D*(S+1)]                                             */
+    const int32_t* dag_col;      /* successor stage ids (may be NULL when there are none) */
+    const int32_t* batch;        /* [D*S]     B in 1..64                                  */
+    const int32_t* workers;      /* [D*S]     W in 1..PARD_MAX_WORKERS                    */
+    const int32_t* lat_us;       /* [D*S*64]  lat_us[(d*S+s)*64 + b-1] >= 0, b = 1..64    */
+    const int32_t* order_mode;   /* [D*S]     PARD_ORDER_*                                */
+} pard_plan_desc_t;
+
+/*
+ * Host-only validation and DAG -> path expansion (the DAG sentence of Section 3.2: the
+ * estimate is taken along each subsequent path).  Touches no GPU.  On success writes
+ * the number of source-to-sink paths summed over all D DAGs and the longest path in
+ * stages.  Either output pointer may be NULL.  Errors: every PARD_E_BAD_* code,
+ * PARD_E_NULL, PARD_E_TOO_MANY_PATHS.
+ */
+int pard_plan_check(const pard_plan_desc_t* desc, int64_t* total_paths, int32_t* max_path_len);
+
+/*
+ * Validates `desc` as pard_plan_check does, expands every DAG into its path CSR,
+ * precomputes the per-stage constants and copies everything to the current HIP device
+ * (synchronous; this is the cold path).  *out receives the plan.  The descriptor's
+ * arrays are copied; the caller keeps ownership of them.
+ */
+int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc);
+
+/* Frees the plan's device and host memory.  NULL is accepted. */
+int pard_plan_destroy(pard_plan_t* plan);
+
+/* Path statistics of a created plan (same meaning as in pard_plan_check). */
+int pard_plan_info(const pard_plan_t* plan, int64_t* total_paths, int32_t* max_path_len);
+
+/*
+ * Bytes of device workspace pard_estimate_drop and pard_compact need for up to
+ * max_requests requests in total and up to max_snapshot_requests in any one snapshot
+ * (pass max_requests when unknown).  The workspace must be 256-byte aligned.
+ */
+int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
+                         int64_t max_snapshot_requests, int64_t* bytes);
+
+/*
+ * Steps of the path: per-(snapshot, stage) queue lengths, segmented stable ordering
+ * of the queues, queue positions, per-request estimate with the maximum over paths,
+ * drop decision (Section 3.2 Eq.(1),(2),(4); Section 3.3 for the ordering).
+ *
+ *   n                      total requests, 0 <= n < 2^30
+ *   max_snapshot_requests  caller's upper bound on snap_ptr[u+1]-snap_ptr[u]; selects the
+ *                          on-chip path when <= PARD_FUSED_SNAPSHOT_CAPACITY.  A snapshot
+ *                          larger than the promised bound is truncated to the bound
+ *                          (memory safe, results for that snapshot unspecified).
+ *   d_arrival, d_deadline, d_stage   device int32[n], request order.  d_arrival may be
+ *                          NULL when no stage of the plan uses PARD_ORDER_FCFS.
+ *   d_snap_ptr             device int32[K+1], non-decreasing, snap_ptr[0]=0, snap_ptr[K]=n;
+ *                          the requests of snapshot u are [snap_ptr[u], snap_ptr[u+1])
+ *   d_now                  device int32[K], current time of each snapshot
+ *   d_est                  device out int32[n]  estimate, request order, clamped to INT32_MAX
+ *   d_drop                 device out uint8[n]  1 = drop, request order
+ *   d_order                device out int32[n]  queue order: sorted position -> request id
+ *   d_seg_ptr              device out int32[K*S+1] offsets of queue (u,s) inside d_order
+ *
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE, PARD_E_WORKSPACE, PARD_E_UNSUPPORTED (large
+ * snapshots whose request-index bits plus segment-id bits exceed 32), PARD_E_HIP.
+ * Contents of the request arrays are not validated on the host.
+ */
+int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                       const int32_t* d_snap_ptr, const int32_t* d_now,
+                       int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                       void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/*
+ * Drop-mask stream compaction: the survivor queues that go on to batching (Section 4.1,
+ * the Request Broker keeps or drops each request; kept requests form the next batches).
+ *
+ *   d_order, d_seg_ptr     as written by pard_estimate_drop
+ *   d_drop                 device uint8[n], request order
+ *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests
+ *                          removed, same order; entries past surv_ptr[K*S] are untouched
+ *   d_surv_ptr             device out int32[K*S+1] offsets of the survivor queues
+ */
+int pard_compact(const pard_plan_t* plan, int64_t n,
+                 const int32_t* d_order, const int32_t* d_seg_ptr, const uint8_t* d_drop,
+                 int32_t* d_surv_idx, int32_t* d_surv_ptr,
+                 void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* pard_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PARD_H_ */

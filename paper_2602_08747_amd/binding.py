@@ -1,0 +1,215 @@
+"""Thin ctypes binding of libpard.so: same names as the C entry points, argument
+marshalling only.  Device buffers are torch tensors on a ROCm device (torch is used for
+device memory and streams, nothing else); every step of the path runs in the library's
+kernels.  There is no CPU fallback: if the library cannot be loaded the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+from . import build as _build
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_lib: Optional[ctypes.CDLL] = None
+
+PARD_OK = 0
+PARD_FUSED_SNAPSHOT_CAPACITY = 8192
+STATUS_NAMES = {
+    0: "PARD_OK", -1: "PARD_E_NULL", -2: "PARD_E_BAD_SHAPE", -3: "PARD_E_BAD_BATCH", -4: "PARD_E_BAD_WORKERS",
+    -5: "PARD_E_BAD_LATENCY", -6: "PARD_E_BAD_DAG", -7: "PARD_E_TOO_MANY_PATHS", -8: "PARD_E_WORKSPACE",
+    -9: "PARD_E_HIP", -10: "PARD_E_BAD_MODE", -11: "PARD_E_UNSUPPORTED",
+}
+EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
+           "pard_workspace_bytes", "pard_estimate_drop", "pard_compact", "pard_strerror"]
+
+
+class PardError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load_library().pard_strerror(code).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(code, code)} ({msg})")
+
+
+class PlanDesc(ctypes.Structure):
+    _fields_ = [("num_snapshots", ctypes.c_int32), ("num_stages", ctypes.c_int32), ("dag_shared", ctypes.c_int32),
+                ("dag_row_ptr", _i32p), ("dag_col", _i32p), ("batch", _i32p), ("workers", _i32p),
+                ("lat_us", _i32p), ("order_mode", _i32p)]
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Loads the built library; builds it first only when no built library exists."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _build.LIB_PATH
+    if not os.path.exists(p):
+        _build.build_library()
+    lib = ctypes.CDLL(p)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.pard_plan_check.argtypes = [ctypes.POINTER(PlanDesc), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+    lib.pard_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(PlanDesc)]
+    lib.pard_plan_destroy.argtypes = [vp]
+    lib.pard_plan_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
+    lib.pard_workspace_bytes.argtypes = [vp, i64, i64, ctypes.POINTER(i64)]
+    lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
+    lib.pard_compact.argtypes = [vp, i64] + [vp] * 5 + [vp, i64, vp]
+    for name in EXPORTS[:-1]:
+        getattr(lib, name).restype = ctypes.c_int
+    lib.pard_strerror.argtypes = [ctypes.c_int]
+    lib.pard_strerror.restype = ctypes.c_char_p
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _desc(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode):
+    keep = [np.ascontiguousarray(a, dtype=np.int32) for a in (dag_row_ptr, dag_col, batch, workers, lat_us, order_mode)]
+    ptr = [a.ctypes.data_as(_i32p) if a.size else None for a in keep]
+    d = PlanDesc(int(K), int(S), int(dag_shared), *ptr)
+    return d, keep
+
+
+def pard_plan_check(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode):
+    """Host-only validation + path expansion.  Returns (status, total_paths, max_path_len)."""
+    lib = load_library()
+    d, keep = _desc(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode)
+    tp, ml = ctypes.c_int64(0), ctypes.c_int32(0)
+    rc = lib.pard_plan_check(ctypes.byref(d), ctypes.byref(tp), ctypes.byref(ml))
+    del keep
+    return rc, tp.value, ml.value
+
+
+class Plan:
+    """Owner of a pard_plan_t*."""
+
+    def __init__(self, handle: int, K: int, S: int):
+        self.handle = ctypes.c_void_p(handle)
+        self.K, self.S = K, S
+
+    def destroy(self):
+        if self.handle:
+            load_library().pard_plan_destroy(self.handle)
+            self.handle = ctypes.c_void_p(None)
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def pard_plan_create(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode) -> Plan:
+    lib = load_library()
+    d, keep = _desc(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode)
+    h = ctypes.c_void_p(None)
+    rc = lib.pard_plan_create(ctypes.byref(h), ctypes.byref(d))
+    del keep
+    if rc != PARD_OK:
+        raise PardError(rc, "pard_plan_create")
+    return Plan(h.value, int(K), int(S))
+
+
+def pard_plan_info(plan: Plan):
+    tp, ml = ctypes.c_int64(0), ctypes.c_int32(0)
+    rc = load_library().pard_plan_info(plan.handle, ctypes.byref(tp), ctypes.byref(ml))
+    if rc != PARD_OK:
+        raise PardError(rc, "pard_plan_info")
+    return tp.value, ml.value
+
+
+def pard_workspace_bytes(plan: Plan, max_requests: int, max_snapshot_requests: int) -> int:
+    b = ctypes.c_int64(0)
+    rc = load_library().pard_workspace_bytes(plan.handle, int(max_requests), int(max_snapshot_requests), ctypes.byref(b))
+    if rc != PARD_OK:
+        raise PardError(rc, "pard_workspace_bytes")
+    return b.value
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None and t.numel() > 0 else ctypes.c_void_p(None)
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def pard_estimate_drop(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now,
+                       est, drop, order, seg_ptr, workspace, stream=None, check: bool = True) -> int:
+    """Enqueues the estimate + drop kernels on `stream` (default: torch's current stream)."""
+    rc = load_library().pard_estimate_drop(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage),
+        _ptr(snap_ptr), _ptr(now), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop")
+    return rc
+
+
+def pard_compact(plan: Plan, n: int, order, seg_ptr, drop, surv_idx, surv_ptr, workspace, stream=None,
+                 check: bool = True) -> int:
+    """Enqueues the survivor-compaction kernels on `stream`."""
+    rc = load_library().pard_compact(
+        plan.handle, int(n), _ptr(order), _ptr(seg_ptr), _ptr(drop), _ptr(surv_idx), _ptr(surv_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_compact")
+    return rc
+
+
+class Session:
+    """Device buffers for one workload: inputs uploaded once, outputs and workspace allocated
+    with torch.  run() is the whole hot path: pard_estimate_drop followed by pard_compact."""
+
+    def __init__(self, w, device="cuda:0", max_snapshot_requests: Optional[int] = None):
+        import torch
+        self.torch = torch
+        self.w = w
+        self.dev = torch.device(device)
+        self.plan = pard_plan_create(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers,
+                                     w.lat_us, w.order_mode)
+        self.n = w.n
+        self.max_snap = w.max_snapshot_requests if max_snapshot_requests is None else max_snapshot_requests
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(self.dev)  # noqa: E731
+        self.arrival, self.deadline, self.stage = up(w.arrival), up(w.deadline), up(w.stage)
+        self.snap_ptr, self.now = up(w.snap_ptr), up(w.now)
+        n1 = max(self.n, 1)
+        self.est = torch.empty(n1, dtype=torch.int32, device=self.dev)
+        self.drop = torch.empty(n1, dtype=torch.uint8, device=self.dev)
+        self.order = torch.empty(n1, dtype=torch.int32, device=self.dev)
+        self.seg_ptr = torch.empty(w.K * w.S + 1, dtype=torch.int32, device=self.dev)
+        self.surv_idx = torch.empty(n1, dtype=torch.int32, device=self.dev)
+        self.surv_ptr = torch.empty(w.K * w.S + 1, dtype=torch.int32, device=self.dev)
+        self.ws_bytes = pard_workspace_bytes(self.plan, self.n, self.max_snap)
+        self.workspace = torch.zeros(self.ws_bytes // 4 + 64, dtype=torch.int32, device=self.dev)
+        assert self.workspace.data_ptr() % 256 == 0
+
+    def estimate_drop(self, stream=None):
+        pard_estimate_drop(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
+                           self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
+
+    def compact(self, stream=None):
+        pard_compact(self.plan, self.n, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
+                     self.workspace, stream)
+
+    def run(self, stream=None):
+        self.estimate_drop(stream)
+        self.compact(stream)
+
+    def status_word(self) -> int:
+        return int(self.workspace[0].item())
+
+    def results(self):
+        """Host copies of every output (synchronises)."""
+        self.torch.cuda.synchronize(self.dev)
+        n = self.n
+        sp = self.surv_ptr.cpu().numpy()
+        return dict(est=self.est[:n].cpu().numpy(), drop=self.drop[:n].cpu().numpy(),
+                    order=self.order[:n].cpu().numpy(), seg_ptr=self.seg_ptr.cpu().numpy(),
+                    surv_idx=self.surv_idx[:int(sp[-1])].cpu().numpy(), surv_ptr=sp)

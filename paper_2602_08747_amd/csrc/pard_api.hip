@@ -1,0 +1,206 @@
+// C-ABI of libpard (see include/pard.h): argument checks, plan upload, kernel launches.
+#include <cstring>
+#include <new>
+
+#include "pard_device.hpp"
+
+using namespace pard;
+
+struct pard_plan {
+    HostPlan host;
+    PlanDev dev;
+    void* blob = nullptr;      // one device allocation holding every plan table
+    int device = 0;
+};
+
+namespace {
+
+constexpr int64_t kHeaderBytes = 256;      // workspace header: word 0 = status bits
+
+int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
+
+int64_t workspace_need(const pard_plan* p, int64_t n, int64_t max_snap) {
+    int64_t need = compact_workspace_bytes(n);
+    if (max_snap > PARD_FUSED_SNAPSHOT_CAPACITY) {
+        int64_t s = sort_workspace_bytes(p->host.K, p->host.S, n);
+        if (s > need) need = s;
+    }
+    return kHeaderBytes + need;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pard_plan_check(const pard_plan_desc_t* desc, int64_t* total_paths, int32_t* max_path_len) {
+    try {
+        HostPlan hp;
+        int rc = build_host_plan(desc, hp);
+        if (rc != PARD_OK) return rc;
+        if (total_paths) *total_paths = hp.total_paths;
+        if (max_path_len) *max_path_len = hp.max_path_len;
+        return PARD_OK;
+    } catch (...) {
+        return PARD_E_BAD_SHAPE;
+    }
+}
+
+int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
+    if (!out) return PARD_E_NULL;
+    *out = nullptr;
+    pard_plan* p = nullptr;
+    try {
+        p = new pard_plan();
+        int rc = build_host_plan(desc, p->host);
+        if (rc != PARD_OK) { delete p; return rc; }
+    } catch (...) {
+        delete p;
+        return PARD_E_BAD_SHAPE;
+    }
+    const HostPlan& h = p->host;
+    const int64_t b_recs = align256((int64_t)h.recs.size() * (int64_t)sizeof(StageRec));
+    const int64_t b_lat = align256((int64_t)h.lat.size() * 4);
+    const int64_t b_dep = align256((int64_t)h.dag_entry_ptr.size() * 4);
+    const int64_t b_est = align256((int64_t)h.entry_stage.size() * 4 + 4);
+    const int64_t b_een = align256((int64_t)h.entry_end.size() * 4 + 4);
+    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een;
+    if (hipGetDevice(&p->device) != hipSuccess || hipMalloc(&p->blob, (size_t)total) != hipSuccess) {
+        (void)hipGetLastError();
+        delete p;
+        return PARD_E_HIP;
+    }
+    char* base = static_cast<char*>(p->blob);
+    int64_t off = 0;
+    auto put = [&](const void* src, size_t bytes, int64_t span) -> char* {
+        char* dst = base + off;
+        off += span;
+        if (bytes && hipMemcpy(dst, src, bytes, hipMemcpyHostToDevice) != hipSuccess) return nullptr;
+        return dst;
+    };
+    char* d_recs = put(h.recs.data(), h.recs.size() * sizeof(StageRec), b_recs);
+    char* d_lat = put(h.lat.data(), h.lat.size() * 4, b_lat);
+    char* d_dep = put(h.dag_entry_ptr.data(), h.dag_entry_ptr.size() * 4, b_dep);
+    char* d_est = put(h.entry_stage.data(), h.entry_stage.size() * 4, b_est);
+    char* d_een = put(h.entry_end.data(), h.entry_end.size() * 4, b_een);
+    if (!d_recs || !d_lat || !d_dep || !d_est || !d_een) {
+        (void)hipGetLastError();
+        (void)hipFree(p->blob);
+        delete p;
+        return PARD_E_HIP;
+    }
+    PlanDev& d = p->dev;
+    d.K = h.K; d.S = h.S; d.shared = h.shared; d.any_fcfs = h.any_fcfs ? 1 : 0;
+    d.uniform_mode = h.uniform_mode;
+    d.max_entries_per_dag = h.max_entries_per_dag;
+    d.recs = reinterpret_cast<const StageRec*>(d_recs);
+    d.lat = reinterpret_cast<const int32_t*>(d_lat);
+    d.dag_entry_ptr = reinterpret_cast<const int32_t*>(d_dep);
+    d.entry_stage = reinterpret_cast<const int32_t*>(d_est);
+    d.entry_end = reinterpret_cast<const int32_t*>(d_een);
+    *out = p;
+    return PARD_OK;
+}
+
+int pard_plan_destroy(pard_plan_t* plan) {
+    if (!plan) return PARD_OK;
+    int rc = PARD_OK;
+    if (plan->blob && hipFree(plan->blob) != hipSuccess) { (void)hipGetLastError(); rc = PARD_E_HIP; }
+    delete plan;
+    return rc;
+}
+
+int pard_plan_info(const pard_plan_t* plan, int64_t* total_paths, int32_t* max_path_len) {
+    if (!plan) return PARD_E_NULL;
+    if (total_paths) *total_paths = plan->host.total_paths;
+    if (max_path_len) *max_path_len = plan->host.max_path_len;
+    return PARD_OK;
+}
+
+int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests, int64_t max_snapshot_requests,
+                         int64_t* bytes) {
+    if (!plan || !bytes) return PARD_E_NULL;
+    if (max_requests < 0 || max_requests >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
+    if (max_snapshot_requests > PARD_FUSED_SNAPSHOT_CAPACITY &&
+        !sort_supported(plan->host.K, plan->host.S, max_requests)) return PARD_E_UNSUPPORTED;
+    *bytes = workspace_need(plan, max_requests, max_snapshot_requests);
+    return PARD_OK;
+}
+
+int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                       const int32_t* d_snap_ptr, const int32_t* d_now,
+                       int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                       void* d_workspace, int64_t workspace_bytes, void* stream) {
+    if (!plan || !d_snap_ptr || !d_now || !d_seg_ptr) return PARD_E_NULL;
+    if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
+    if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
+    if (n > 0 && plan->host.any_fcfs && !d_arrival) return PARD_E_NULL;
+    const bool fused = max_snapshot_requests <= PARD_FUSED_SNAPSHOT_CAPACITY;
+    if (!fused && !sort_supported(plan->host.K, plan->host.S, n)) return PARD_E_UNSUPPORTED;
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
+        workspace_bytes < workspace_need(plan, n, max_snapshot_requests)) return PARD_E_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint32_t* status = static_cast<uint32_t*>(d_workspace);
+    hipError_t e;
+    if (fused) {
+        FusedArgs a{};
+        a.plan = plan->dev;
+        a.arrival = d_arrival; a.deadline = d_deadline; a.stage = d_stage;
+        a.snap_ptr = d_snap_ptr; a.now = d_now;
+        a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
+        a.status = status;
+        a.cap = (int32_t)max_snapshot_requests;
+        a.n = n;
+        e = launch_fused(a, s);
+    } else {
+        SortArgs a{};
+        a.plan = plan->dev;
+        a.n = n;
+        a.arrival = d_arrival; a.deadline = d_deadline; a.stage = d_stage;
+        a.snap_ptr = d_snap_ptr; a.now = d_now;
+        a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
+        a.status = status;
+        a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+        e = launch_sort_path(a, s);
+    }
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+int pard_compact(const pard_plan_t* plan, int64_t n,
+                 const int32_t* d_order, const int32_t* d_seg_ptr, const uint8_t* d_drop,
+                 int32_t* d_surv_idx, int32_t* d_surv_ptr,
+                 void* d_workspace, int64_t workspace_bytes, void* stream) {
+    if (!plan || !d_seg_ptr || !d_surv_ptr) return PARD_E_NULL;
+    if (n < 0 || n >= ((int64_t)1 << 30)) return PARD_E_BAD_SHAPE;
+    if (n > 0 && (!d_order || !d_drop || !d_surv_idx)) return PARD_E_NULL;
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
+        workspace_bytes < kHeaderBytes + compact_workspace_bytes(n)) return PARD_E_WORKSPACE;
+    CompactArgs a{};
+    a.num_segments = plan->host.K * plan->host.S;
+    a.n = n;
+    a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
+    a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
+    a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+    hipError_t e = launch_compact(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+const char* pard_strerror(int status) {
+    switch (status) {
+        case PARD_OK: return "ok";
+        case PARD_E_NULL: return "a required pointer is NULL";
+        case PARD_E_BAD_SHAPE: return "bad shape: snapshots, stages or request count out of range";
+        case PARD_E_BAD_BATCH: return "batch size outside 1..64";
+        case PARD_E_BAD_WORKERS: return "worker count outside 1..2^20";
+        case PARD_E_BAD_LATENCY: return "negative latency";
+        case PARD_E_BAD_DAG: return "malformed DAG: bad offsets, edge out of range, self loop or cycle";
+        case PARD_E_TOO_MANY_PATHS: return "DAG expands to too many paths";
+        case PARD_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PARD_E_HIP: return "HIP runtime error";
+        case PARD_E_BAD_MODE: return "unknown order mode";
+        case PARD_E_UNSUPPORTED: return "request-index bits plus segment-id bits exceed 32 for the large-snapshot path";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

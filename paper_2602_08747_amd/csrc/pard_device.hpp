@@ -1,0 +1,120 @@
+// Device-side view of a plan and the small arithmetic helpers every kernel shares.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pard_host.hpp"
+
+namespace pard {
+
+constexpr int kWave = 64;
+constexpr uint64_t kCostCap = (uint64_t)1 << 40;   // per-term clamp, see stage_cost()
+constexpr int32_t kInt32Max = 0x7fffffff;
+
+// Plan tables in device memory (passed to kernels by value).
+struct PlanDev {
+    int32_t K, S, shared, any_fcfs;
+    int32_t uniform_mode;              // >= 0 when all stages share one order mode
+    int32_t max_entries_per_dag;
+    const StageRec* recs;              // [D*S]
+    const int32_t* lat;                // [D*S*64]
+    const int32_t* dag_entry_ptr;      // [D+1]
+    const int32_t* entry_stage;        // [E]
+    const int32_t* entry_end;          // [E]
+};
+
+// Status bits a kernel may raise in the workspace's status word.
+enum : uint32_t {
+    kStatusSnapshotTooLarge = 1u,      // a snapshot exceeded the promised bound
+    kStatusLookbackTimeout = 2u        // a decoupled look-back gave up waiting
+};
+
+__device__ __forceinline__ uint32_t magic_div_dev(uint32_t n, uint32_t m, uint32_t sh) {
+    uint32_t t = __umulhi(m, n);
+    return (t + ((n - t) >> (sh & 0xFF))) >> (sh >> 8);
+}
+
+// int32 -> uint32 preserving order, then the per-mode queue key: ascending key order
+// is the queue order (Section 3.3: LBF = smallest remaining budget first, HBF = largest).
+__device__ __forceinline__ uint32_t order_key(int32_t mode, int32_t deadline, int32_t arrival) {
+    uint32_t d = (uint32_t)deadline ^ 0x80000000u;
+    if (mode == PARD_ORDER_HBF) return ~d;
+    if (mode == PARD_ORDER_FCFS) return (uint32_t)arrival ^ 0x80000000u;
+    return d;
+}
+
+__device__ __forceinline__ int32_t clamp_stage(int32_t s, int32_t S) {
+    return s < 0 ? 0 : (s >= S ? S - 1 : s);
+}
+
+// Eq.(2) in snapshot form with `a` requests ahead (0 <= a < 2^31):
+//   floor(ceil(a/B) * lat[B] / W) + lat[min(B, a+1)]
+// clamped to 2^40.  Clamping every term at 2^40 keeps 64-bit sums of up to 65 terms
+// exact-or-saturated: any sum that reaches the clamp is far above INT32_MAX even after
+// adding the most negative `now`, so the reported estimate and the drop decision are
+// the same as with unbounded integers.
+__device__ __forceinline__ uint64_t stage_cost(const StageRec& r, uint32_t a, const int32_t* lat_row) {
+    uint32_t q = magic_div_dev(a + (uint32_t)r.B - 1u, r.mB, r.shB);
+    uint64_t x = (uint64_t)q * (uint32_t)r.latB;
+    uint64_t wait;
+    if ((x >> 32) == 0) wait = magic_div_dev((uint32_t)x, r.mW, r.shW);
+    else wait = x / (uint32_t)r.W;
+    uint32_t ex = (a + 1u >= (uint32_t)r.B) ? (uint32_t)r.latB : (uint32_t)lat_row[a];
+    uint64_t c = wait + ex;
+    return c < kCostCap ? c : kCostCap;
+}
+
+// est (clamped) and the drop decision from the 64-bit estimate.
+__device__ __forceinline__ void finish_request(uint64_t e64, int32_t now, int32_t deadline,
+                                               int32_t& est, uint8_t& drop) {
+    est = e64 > (uint64_t)kInt32Max ? kInt32Max : (int32_t)e64;
+    int64_t fin = (int64_t)now + (int64_t)e64;
+    if (fin > (int64_t)kInt32Max) fin = kInt32Max;
+    drop = fin > (int64_t)deadline ? 1 : 0;
+}
+
+__device__ __forceinline__ uint32_t lane_id() {
+    return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// ---- launchers implemented in the .hip files (host functions) ----------------
+
+struct FusedArgs {
+    PlanDev plan;
+    const int32_t *arrival, *deadline, *stage, *snap_ptr, *now;
+    int32_t *est;
+    uint8_t* drop;
+    int32_t *order, *seg_ptr;
+    uint32_t* status;
+    int32_t cap;                       // promised bound on a snapshot's size
+    int64_t n;                         // total requests (bounds every index derived from snap_ptr)
+};
+hipError_t launch_fused(const FusedArgs& a, hipStream_t stream);
+
+struct SortArgs {
+    PlanDev plan;
+    int64_t n;
+    const int32_t *arrival, *deadline, *stage, *snap_ptr, *now;
+    int32_t* est;
+    uint8_t* drop;
+    int32_t *order, *seg_ptr;
+    uint32_t* status;
+    void* workspace;                   // sort_workspace_bytes(K, S, n) bytes, 256-byte aligned
+};
+int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n);
+bool sort_supported(int32_t K, int32_t S, int64_t n);
+hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
+
+struct CompactArgs {
+    int32_t num_segments;              // K*S
+    int64_t n;
+    const int32_t *order, *seg_ptr;
+    const uint8_t* drop;
+    int32_t *surv_idx, *surv_ptr;
+    void* workspace;
+};
+int64_t compact_workspace_bytes(int64_t n);
+hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
+
+}  // namespace pard

@@ -1,0 +1,247 @@
+"""GPU parity: libpard (through its C-ABI) against the CPU oracle, bit for bit.
+
+Integer microseconds throughout, so every output must be identical: est, drop, order,
+seg_ptr, surv_idx, surv_ptr.
+"""
+import numpy as np
+import pytest
+
+from paper_2602_08747_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+INT32_MAX = 2**31 - 1
+KEYS = ("est", "drop", "order", "seg_ptr", "surv_idx", "surv_ptr")
+FORCE_SORT = 1 << 20        # promised snapshot bound above the on-chip capacity -> radix-sort path
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU and the built libpard.so")
+    from paper_2602_08747_amd import binding
+    binding.load_library()
+    return binding
+
+
+def check(gpu, oracle_mod, w, max_snap=None, threads=8):
+    print(f"case {w.name} n={w.n} K={w.K} S={w.S} max_snap={max_snap}", flush=True)
+    ref = oracle_mod.run(w, threads=threads)
+    s = gpu.Session(w, max_snapshot_requests=max_snap)
+    s.run()
+    got = s.results()
+    for k in KEYS:
+        if not np.array_equal(got[k], ref[k]):
+            bad = np.flatnonzero(got[k] != ref[k]) if got[k].shape == ref[k].shape else None
+            raise AssertionError(f"{w.name}: {k} differs (shape {got[k].shape} vs {ref[k].shape}); "
+                                 f"first bad {None if bad is None else bad[:8]}; "
+                                 f"got {None if bad is None else got[k][bad[:8]]} want {None if bad is None else ref[k][bad[:8]]}")
+    assert s.status_word() == 0
+    return s, ref
+
+
+# ---- the five benchmark configurations at full size --------------------------------------
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_full_config(gpu, oracle_mod, cfg):
+    w = wl.make_workload(cfg)
+    check(gpu, oracle_mod, w)
+
+
+@pytest.mark.parametrize("cfg,kw", [(1, {}), (2, dict(n_requests=300001)), (3, dict(n_requests=250007)),
+                                     (4, dict(n_requests=700003)), (5, dict(n_snapshots=97, per_snapshot=8192))])
+def test_config_shapes_permuted(gpu, oracle_mod, cfg, kw):
+    """Same shapes, request order shuffled (arrival-ordered input is nearly sorted), mixed drop masks."""
+    w = wl.make_workload(cfg, permute=True, **kw)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 280000).astype(np.int32)
+    if cfg in (2, 3, 4):
+        w.lat_us[:] = np.maximum(1, w.lat_us // 400)       # out of deep overload: some requests survive
+    s, ref = check(gpu, oracle_mod, w)
+    assert 0 < ref["drop"].mean() < 1
+
+
+def test_config4_half_survivors(gpu, oracle_mod):
+    """Bursty DAG with an SLO of half the arrival span: compaction with roughly half the queue surviving."""
+    w = wl.make_workload(4, n_requests=1 << 20, permute=True)
+    span = int(w.arrival.max())
+    w.deadline[:] = w.arrival + span // 2
+    w.now[:] = span // 2
+    w.lat_us[:] = np.maximum(1, w.lat_us // 200)
+    s, ref = check(gpu, oracle_mod, w)
+    assert 0.1 < ref["drop"].mean() < 0.9
+
+
+# ---- both kernel paths on the same small inputs -------------------------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_small_both_paths(gpu, oracle_mod, seed):
+    K = 1 + (seed * 5) % 7
+    S = 1 + (seed * 3) % 9
+    w = wl.random_workload(100 + seed, K=K, S=S, n_per_snapshot=50 + 37 * seed, monotone=(seed % 2 == 0),
+                           tie_heavy=(seed % 3 == 2))
+    check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+@pytest.mark.parametrize("mode", [wl.MODE_LBF, wl.MODE_HBF, wl.MODE_FCFS, None])
+def test_order_modes(gpu, oracle_mod, mode):
+    w = wl.make_workload(5, n_snapshots=9, per_snapshot=5000, permute=True, order_mode=mode)
+    if mode is None:
+        w.order_mode[:] = np.arange(w.order_mode.size) % 3          # mixed per stage
+    w.deadline[::5] = w.deadline[1::5][: w.deadline[::5].size]      # plenty of equal keys
+    check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+@pytest.mark.parametrize("m", [0, 1, 2, 63, 64, 65, 4095, 8191, 8192])
+def test_snapshot_sizes_on_chip(gpu, oracle_mod, m):
+    w = wl.make_workload(5, n_snapshots=3, per_snapshot=m, permute=True)
+    check(gpu, oracle_mod, w)
+
+
+@pytest.mark.parametrize("n", [0, 1, 2, 255, 4096, 4097, 8193, 12289, 70001])
+def test_sizes_sort_path(gpu, oracle_mod, n):
+    w = wl.make_workload(3, n_requests=n, permute=True)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+def test_ragged_multi_snapshot_large(gpu, oracle_mod):
+    """Several snapshots of very different sizes, some above the on-chip capacity, own DAG each."""
+    w = wl.random_workload(7, K=5, S=6, n_per_snapshot=9000, dag_shared=0, time_span=2_000_000,
+                           slo_choices=(150000, 400000))
+    assert w.max_snapshot_requests > 8192
+    check(gpu, oracle_mod, w)
+
+
+# ---- degenerate inputs -------------------------------------------------------------------
+
+def test_all_ties_single_stage(gpu, oracle_mod):
+    w = wl.make_workload(1, n_requests=8192)
+    w.deadline[:] = 123456
+    w.stage[:] = 1
+    check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+def test_clustered_keys(gpu, oracle_mod):
+    """Half of the keys equal, the rest spread over the whole int32 range (worst case for bucketing)."""
+    w = wl.make_workload(2, n_requests=6000, permute=True)
+    w.deadline[::2] = 77
+    w.deadline[1::4] = INT32_MAX
+    w.deadline[3::8] = 0
+    check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+def test_extreme_values(gpu, oracle_mod):
+    """INT32_MAX deadlines are never dropped; huge latencies saturate; negative times are ordered correctly."""
+    w = wl.make_workload(3, n_requests=5000, permute=True)
+    w.lat_us[:] = INT32_MAX
+    w.deadline[::3] = INT32_MAX
+    w.deadline[1::7] = -5
+    w.arrival[::2] = -100
+    w.now[:] = INT32_MAX
+    s, ref = check(gpu, oracle_mod, w)
+    assert not ref["drop"][::3].any() and (ref["est"] == INT32_MAX).all()
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+    w.now[:] = -(2**31)
+    check(gpu, oracle_mod, w)
+
+
+def test_batch_and_worker_extremes(gpu, oracle_mod):
+    for B, W in ((1, 1), (64, 1), (1, 1 << 20), (63, 7), (64, 16), (3, 1000)):
+        w = wl.make_workload(2, n_requests=7000, permute=True)
+        w.batch[:] = B
+        w.workers[:] = W
+        w.now[:] = 0
+        check(gpu, oracle_mod, w)
+    w = wl.make_workload(2, n_requests=9000, permute=True)
+    w.batch[:] = [1, 64, 5, 33, 2]
+    w.workers[:] = [1 << 20, 1, 3, 1, 999]
+    w.lat_us[:] = (w.lat_us.astype(np.int64) * 5000).clip(0, INT32_MAX).astype(np.int32)    # wait term beyond 32 bits
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+def test_out_of_range_stage_is_clamped(gpu, oracle_mod):
+    w = wl.make_workload(1, n_requests=3000)
+    w.stage[::11] = -7
+    w.stage[5::13] = 1000
+    check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
+def test_many_paths_dag(gpu, oracle_mod):
+    """Six diamonds in series: 64 paths, 13-stage paths."""
+    S = 19
+    edges = []
+    for d in range(6):
+        a = 3 * d
+        edges += [(a, a + 1), (a, a + 2), (a + 1, a + 3), (a + 2, a + 3)]
+    rp, cl = wl.csr_from_edges(S, edges)
+    w = wl.make_workload(4, n_requests=6000, permute=True)
+    rng = np.random.default_rng(1)
+    w2 = wl.Workload(name="diamonds", K=1, S=S, dag_shared=1, dag_row_ptr=rp, dag_col=cl,
+                     batch=rng.integers(1, 65, S).astype(np.int32), workers=rng.integers(1, 9, S).astype(np.int32),
+                     lat_us=wl.monotone_tables(rng, S).reshape(-1), order_mode=np.zeros(S, np.int32),
+                     arrival=w.arrival, deadline=w.deadline, stage=rng.integers(0, S, w.n).astype(np.int32),
+                     snap_ptr=w.snap_ptr, now=w.now)
+    assert gpu.pard_plan_check(1, S, 1, rp, cl, w2.batch, w2.workers, w2.lat_us, w2.order_mode)[1] == 64
+    check(gpu, oracle_mod, w2)
+    check(gpu, oracle_mod, w2, max_snap=FORCE_SORT)
+
+
+# ---- API behaviour ------------------------------------------------------------------------
+
+def test_compact_with_arbitrary_masks(gpu, oracle_mod):
+    """pard_compact is a function of (order, seg_ptr, drop) alone."""
+    import torch
+    w = wl.make_workload(5, n_snapshots=11, per_snapshot=4099, permute=True)
+    s, ref = check(gpu, oracle_mod, w)
+    rng = np.random.default_rng(9)
+    for p in (0.0, 1.0, 0.5, 0.03):
+        mask = (rng.random(w.n) < p).astype(np.uint8)
+        s.drop.copy_(torch.from_numpy(mask).to(s.dev))
+        s.compact()
+        got = s.results()
+        want_idx, want_ptr = oracle_mod.compact(w.K, w.S, ref["order"], ref["seg_ptr"], mask)
+        assert np.array_equal(got["surv_ptr"], want_ptr) and np.array_equal(got["surv_idx"], want_idx)
+
+
+def test_repeatable_and_stream(gpu, oracle_mod):
+    import torch
+    w = wl.make_workload(4, n_requests=300000, permute=True)
+    s, ref = check(gpu, oracle_mod, w)
+    side = torch.cuda.Stream()
+    for _ in range(3):
+        s.est.zero_(); s.order.zero_(); s.surv_idx.zero_()
+        side.wait_stream(torch.cuda.current_stream())
+        s.run(stream=side)
+        side.synchronize()
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k])
+
+
+def test_snapshot_larger_than_promised_sets_status(gpu, oracle_mod):
+    w = wl.make_workload(5, n_snapshots=4, per_snapshot=500)
+    s = gpu.Session(w, max_snapshot_requests=100)
+    s.run()
+    s.results()
+    assert s.status_word() & 1
+
+
+def test_error_codes_with_device(gpu):
+    import torch
+    w = wl.make_workload(1)
+    s = gpu.Session(w)
+    tiny = torch.zeros(64, dtype=torch.int32, device=s.dev)
+    assert gpu.pard_estimate_drop(s.plan, s.n, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, s.est,
+                                  s.drop, s.order, s.seg_ptr, tiny, check=False) == -8
+    assert gpu.pard_estimate_drop(s.plan, -1, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, s.est,
+                                  s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -2
+    assert gpu.pard_estimate_drop(s.plan, s.n, s.max_snap, s.arrival, None, s.stage, s.snap_ptr, s.now, s.est,
+                                  s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -1
+    assert gpu.pard_compact(s.plan, s.n, s.order, s.seg_ptr, s.drop, s.surv_idx, s.surv_ptr, tiny[:8], check=False) == -8
+    assert gpu.pard_plan_info(s.plan) == (1, 3)

@@ -1,0 +1,133 @@
+"""CPU-only checks of the GPU library: it loads, exports the declared symbols, and its
+host-side logic (validation, DAG -> path expansion, invariant-divisor constants) is right.
+No kernel is launched here."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2602_08747_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pard.h")).read()
+    declared = set(re.findall(r"\b(pard_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = binding.load_library()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert lib.pard_strerror(0) == b"ok" and b"workspace" in lib.pard_strerror(-8)
+
+
+def _check(w, **over):
+    a = dict(K=w.K, S=w.S, dag_shared=w.dag_shared, dag_row_ptr=w.dag_row_ptr, dag_col=w.dag_col, batch=w.batch,
+             workers=w.workers, lat_us=w.lat_us, order_mode=w.order_mode)
+    a.update(over)
+    return binding.pard_plan_check(**a)
+
+
+def test_plan_check_counts_paths(oracle_mod):
+    for cfg, paths, longest in ((1, 1, 3), (2, 1, 5), (3, 4, 6), (4, 16, 8)):
+        w = wl.make_workload(cfg, n_requests=4)
+        assert _check(w) == (0, paths, longest)
+    w = wl.make_workload(5, n_snapshots=40, per_snapshot=2)
+    rc, total, longest = _check(w)
+    want = 0
+    col_base = 0
+    for u in range(w.K):
+        rp = w.dag_row_ptr[u * 7:(u + 1) * 7]
+        want += wl.count_paths_any_order(6, rp, w.dag_col[col_base:col_base + rp[6]])
+        col_base += rp[6]
+    assert rc == 0 and total == want
+    for seed in range(30):      # agrees with the oracle's independent enumeration on random DAGs
+        rng = np.random.default_rng(seed)
+        S = int(rng.integers(1, 10))
+        rp, cl = wl.random_dag(rng, S, 0.4)
+        ptr, stg = oracle_mod.expand_paths(S, rp, cl)
+        one = np.ones(S, np.int32)
+        rc, total, longest = binding.pard_plan_check(1, S, 1, rp, cl, one, one, np.ones(S * 64, np.int32), one * 0)
+        assert (rc, total, longest) == (0, len(ptr) - 1, int(np.diff(ptr).max()))
+
+
+def test_plan_check_error_codes():
+    w = wl.make_workload(3, n_requests=4)
+    assert _check(w, K=0)[0] == -2
+    assert _check(w, S=65)[0] == -2
+    b = w.batch.copy(); b[2] = 0
+    assert _check(w, batch=b)[0] == -3
+    b[2] = 65
+    assert _check(w, batch=b)[0] == -3
+    x = w.workers.copy(); x[0] = 0
+    assert _check(w, workers=x)[0] == -4
+    x[0] = (1 << 20) + 1
+    assert _check(w, workers=x)[0] == -4
+    l = w.lat_us.copy(); l[100] = -1
+    assert _check(w, lat_us=l)[0] == -5
+    m = w.order_mode.copy(); m[1] = 3
+    assert _check(w, order_mode=m)[0] == -10
+    c = w.dag_col.copy(); c[0] = 8
+    assert _check(w, dag_col=c)[0] == -6                      # edge out of range
+    c = w.dag_col.copy(); c[0] = 0
+    assert _check(w, dag_col=c)[0] == -6                      # self loop
+    rp, cl = wl.csr_from_edges(3, [(0, 1), (1, 2), (2, 0)])
+    one = np.ones(3, np.int32)
+    assert binding.pard_plan_check(1, 3, 1, rp, cl, one, one, np.ones(192, np.int32), one * 0)[0] == -6   # cycle
+    rp, cl = wl.csr_from_edges(3, [(1, 2), (2, 1)])
+    assert binding.pard_plan_check(1, 3, 1, rp, cl, one, one, np.ones(192, np.int32), one * 0)[0] == -6   # unreachable cycle
+    rp2 = rp.copy(); rp2[1] = 5
+    assert binding.pard_plan_check(1, 3, 1, rp2, cl, one, one, np.ones(192, np.int32), one * 0)[0] == -6  # offsets not monotone
+    # exponential DAG: 12 diamonds in series = 4096 paths > limit
+    S, edges = 37, []
+    for d in range(12):
+        a = 3 * d
+        edges += [(a, a + 1), (a, a + 2), (a + 1, a + 3), (a + 2, a + 3)]
+    rp, cl = wl.csr_from_edges(S, edges)
+    one = np.ones(S, np.int32)
+    assert binding.pard_plan_check(1, S, 1, rp, cl, one, one, np.ones(S * 64, np.int32), one * 0)[0] == -7
+    lib = binding.load_library()
+    assert lib.pard_plan_check(None, None, None) == -1
+    assert lib.pard_plan_destroy(None) == 0
+
+
+@pytest.fixture(scope="module")
+def host_shim(tmp_path_factory):
+    """The library's host-only header compiled on its own with g++ (no HIP)."""
+    d = tmp_path_factory.mktemp("shim")
+    src = d / "shim.cpp"
+    src.write_text('#include "paper_2602_08747_amd/csrc/pard_host.hpp"\n'
+                   'extern "C" unsigned shim_div(unsigned n, unsigned d) {\n'
+                   '  return pard::magic_div(n, pard::magic_u32(d)); }\n'
+                   'extern "C" long shim_sweep(unsigned d, unsigned lo, unsigned count) {\n'
+                   '  pard::Magic32 k = pard::magic_u32(d); long bad = 0;\n'
+                   '  for (unsigned i = 0; i < count; ++i) { unsigned n = lo + i; bad += pard::magic_div(n, k) != n / d; }\n'
+                   '  return bad; }\n')
+    so = d / "shim.so"
+    subprocess.run(["g++", "-O2", "-std=c++17", "-shared", "-fPIC", "-I", ROOT, str(src), "-o", str(so)], check=True)
+    lib = ctypes.CDLL(str(so))
+    lib.shim_div.restype = ctypes.c_uint32
+    lib.shim_div.argtypes = [ctypes.c_uint32, ctypes.c_uint32]
+    lib.shim_sweep.restype = ctypes.c_long
+    lib.shim_sweep.argtypes = [ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32]
+    return lib
+
+
+def test_invariant_division_is_exact(host_shim):
+    """floor(n/d) through the multiply-high constants equals n/d: every batch size, worker
+    counts up to the limit, numerators at both ends of the 32-bit range and around multiples."""
+    rng = np.random.default_rng(0)
+    divisors = list(range(1, 130)) + [255, 256, 257, 1000, 4095, 4096, 65535, 65536, 65537, (1 << 20) - 1, 1 << 20] \
+        + rng.integers(1, 1 << 20, size=200).tolist()
+    for d in divisors:
+        assert host_shim.shim_sweep(d, 0, 70000) == 0
+        assert host_shim.shim_sweep(d, 2**32 - 70000, 70000) == 0
+        assert host_shim.shim_sweep(d, 2**31 - 35000, 70000) == 0
+        for q in rng.integers(0, 2**32 // d, size=50).tolist():
+            base = q * d
+            for n in (base - 1, base, base + 1, base + d - 1):
+                if 0 <= n < 2**32:
+                    assert host_shim.shim_div(n, d) == n // d
