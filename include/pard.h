@@ -117,7 +117,11 @@ int pard_plan_info(const pard_plan_t* plan, int64_t* total_paths, int32_t* max_p
 /*
  * Bytes of device workspace pard_estimate_drop and pard_compact need for up to
  * max_requests requests in total and up to max_snapshot_requests in any one snapshot
- * (pass max_requests when unknown).  The workspace must be 256-byte aligned.
+ * (pass max_requests when unknown).  The workspace must be 256-byte aligned.  Its first
+ * 32-bit word accumulates status bits (bit 0: a snapshot was larger than promised and was
+ * truncated; bit 1: an internal wait between workgroups timed out and the outputs of that
+ * call are invalid); the caller zero-fills the workspace once after allocating it and may
+ * copy the word back at any time.
  */
 int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
                          int64_t max_snapshot_requests, int64_t* bytes);

@@ -40,9 +40,9 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
     constexpr int CW = kCntWords / T;       // counter words scanned per thread
     static_assert(G >= 1 && CW >= 1 && kCntWords % T == 0, "shape");
 
-    __shared__ uint32_t cnt32[kCntWords + 4];       // bucket counters, then bucket starts; later the queue order
-    __shared__ uint32_t key_l[kCap];
-    __shared__ uint16_t idx_l[kCap];
+    __shared__ __align__(16) uint32_t cnt32[kCntWords + 4];       // bucket counters, then bucket starts; later the queue order
+    __shared__ __align__(16) uint32_t key_l[kCap];
+    __shared__ __align__(16) uint16_t idx_l[kCap];
     __shared__ StageRec recs[PARD_MAX_STAGES];
     __shared__ unsigned long long cfull[PARD_MAX_STAGES];
     __shared__ unsigned long long down[PARD_MAX_STAGES];

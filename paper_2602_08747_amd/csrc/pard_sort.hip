@@ -31,7 +31,7 @@ constexpr int kMaxPasses = 8;
 constexpr uint32_t kFlagAggregate = 1u << 30;          // tile published its own count
 constexpr uint32_t kFlagInclusive = 2u << 30;          // tile published the running total
 constexpr uint32_t kValueMask = (1u << 30) - 1;
-constexpr uint32_t kSpinLimit = 1u << 24;
+constexpr uint32_t kSpinLimit = 1u << 22;
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
     uint32_t inv_min;               // max over requests of ~key  (so that zero-fill is the identity)

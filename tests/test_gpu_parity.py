@@ -138,8 +138,8 @@ def test_extreme_values(gpu, oracle_mod):
     """INT32_MAX deadlines are never dropped; huge latencies saturate; negative times are ordered correctly."""
     w = wl.make_workload(3, n_requests=5000, permute=True)
     w.lat_us[:] = INT32_MAX
-    w.deadline[::3] = INT32_MAX
     w.deadline[1::7] = -5
+    w.deadline[::3] = INT32_MAX
     w.arrival[::2] = -100
     w.now[:] = INT32_MAX
     s, ref = check(gpu, oracle_mod, w)
