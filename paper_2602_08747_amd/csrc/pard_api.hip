@@ -11,6 +11,9 @@ struct pard_plan {
     PlanDev dev;
     void* blob = nullptr;      // one device allocation holding every plan table
     int device = 0;
+    int num_cus = 1;
+    int compact_resident = 1;  // co-resident workgroups of the look-back kernels on this device
+    int pass_resident = 1;
 };
 
 namespace {
@@ -88,6 +91,15 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
         delete p;
         return PARD_E_HIP;
     }
+    {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, p->device) == hipSuccess && prop.multiProcessorCount > 0)
+            p->num_cus = prop.multiProcessorCount;
+        else
+            (void)hipGetLastError();
+        p->compact_resident = p->num_cus * compact_blocks_per_cu();
+        p->pass_resident = p->num_cus * sort_pass_blocks_per_cu();
+    }
     PlanDev& d = p->dev;
     d.K = h.K; d.S = h.S; d.shared = h.shared; d.any_fcfs = h.any_fcfs ? 1 : 0;
     d.uniform_mode = h.uniform_mode;
@@ -161,6 +173,8 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
         a.status = status;
         a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+        a.resident_pass_blocks = plan->pass_resident;
+        a.num_cus = plan->num_cus;
         e = launch_sort_path(a, s);
     }
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
@@ -180,7 +194,9 @@ int pard_compact(const pard_plan_t* plan, int64_t n,
     a.n = n;
     a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
+    a.status = static_cast<uint32_t*>(d_workspace);
     a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+    a.resident_blocks = plan->compact_resident;
     hipError_t e = launch_compact(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }

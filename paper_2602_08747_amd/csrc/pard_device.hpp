@@ -48,6 +48,9 @@ __device__ __forceinline__ int32_t clamp_stage(int32_t s, int32_t S) {
     return s < 0 ? 0 : (s >= S ? S - 1 : s);
 }
 
+// 64-bit by 32-bit division, kept out of line: it is long and almost never taken.
+static __device__ __noinline__ uint64_t wide_div(uint64_t x, uint32_t d) { return x / d; }
+
 // Eq.(2) in snapshot form with `a` requests ahead (0 <= a < 2^31):
 //   floor(ceil(a/B) * lat[B] / W) + lat[min(B, a+1)]
 // clamped to 2^40.  Clamping every term at 2^40 keeps 64-bit sums of up to 65 terms
@@ -59,10 +62,29 @@ __device__ __forceinline__ uint64_t stage_cost(const StageRec& r, uint32_t a, co
     uint64_t x = (uint64_t)q * (uint32_t)r.latB;
     uint64_t wait;
     if ((x >> 32) == 0) wait = magic_div_dev((uint32_t)x, r.mW, r.shW);
-    else wait = x / (uint32_t)r.W;
+    else wait = wide_div(x, (uint32_t)r.W);
     uint32_t ex = (a + 1u >= (uint32_t)r.B) ? (uint32_t)r.latB : (uint32_t)lat_row[a];
     uint64_t c = wait + ex;
     return c < kCostCap ? c : kCostCap;
+}
+
+// The same cost for a short queue (a < 2^13), without 32x32 multiplies or integer
+// division when the stage allows it (kStageFast):
+//   q = ceil(a/B) = trunc((a + B - 1 + 0.5) * (1/B))        exact: the true value sits at
+//       least 0.5/B from an integer and the two float roundings move it by < 0.002 * 0.5/B
+//   latB = aW*W + bW  =>  floor(q*latB/W) = q*aW + floor(q*bW/W)
+//   p = q*bW < 2^21 (bW < W <= 256), floor(p/W) = trunc((p + 0.5) * (1/W))   exact: p + 0.5
+//       is a float, the true value sits at least 0.5/W from an integer, error < 0.25/W
+//   q*aW < 2^31 (aW < 2^18), so everything fits 32 bits.
+__device__ __forceinline__ uint64_t stage_cost_short(const StageRec& r, uint32_t a, const int32_t* lat_row) {
+    if (r.mode & kStageFast) {
+        const uint32_t q = (uint32_t)(((float)(a + (uint32_t)r.B - 1u) + 0.5f) * r.rcpB);
+        const uint32_t p = __umul24(q, r.bW);
+        const uint32_t wait = __umul24(q, r.aW) + (uint32_t)(((float)p + 0.5f) * r.rcpW);
+        const uint32_t ex = (a + 1u >= (uint32_t)r.B) ? (uint32_t)r.latB : (uint32_t)lat_row[a];
+        return (uint64_t)wait + ex;
+    }
+    return stage_cost(r, a, lat_row);
 }
 
 // est (clamped) and the drop decision from the 64-bit estimate.
@@ -101,7 +123,10 @@ struct SortArgs {
     int32_t *order, *seg_ptr;
     uint32_t* status;
     void* workspace;                   // sort_workspace_bytes(K, S, n) bytes, 256-byte aligned
+    int32_t resident_pass_blocks;      // workgroups of a radix-pass kernel the device holds at once
+    int32_t num_cus;
 };
+int sort_pass_blocks_per_cu();
 int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n);
 bool sort_supported(int32_t K, int32_t S, int64_t n);
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
@@ -112,8 +137,11 @@ struct CompactArgs {
     const int32_t *order, *seg_ptr;
     const uint8_t* drop;
     int32_t *surv_idx, *surv_ptr;
+    uint32_t* status;
     void* workspace;
+    int32_t resident_blocks;           // workgroups of the compaction kernel the device holds at once
 };
+int compact_blocks_per_cu();
 int64_t compact_workspace_bytes(int64_t n);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
 

@@ -6,20 +6,20 @@
 //   2. bucket every request by (stage, leading bits of key.index) with LDS counters;
 //      the bucket order is the queue order, so an exclusive scan of the counters gives
 //      every bucket's first queue slot and every stage's queue start and length
-//   3. scatter (key, index) into LDS by bucket; a request's exact rank is its bucket
-//      start plus the number of bucket mates with a smaller (key, index)
+//   3. scatter the remaining low bits of key.index into LDS by bucket; a request's exact
+//      rank is its bucket start plus the number of bucket mates with smaller low bits
 //   4. per stage: cost at full queue length; per path entry: downstream suffix sum,
 //      maximum per stage (the path CSR is walked here)
 //   5. per request: own-stage cost at its queue position + downstream maximum,
 //      drop decision; outputs leave in request order, the queue order via LDS.
 //
-// Why buckets instead of radix passes: the vector ALU, not HBM, is what limits a sort of
-// 8192 keys per workgroup at this data rate (about 130 lane-instructions per request at
-// full HBM speed).  A stable 8-bit radix pass costs ~70 of them per key per pass.  One
-// bucketing pass with ~0.7 requests per bucket and a compare loop over bucket mates costs
-// less than one radix pass.  Appending the request index below the key makes equal keys
-// spread over buckets too, so heavy ties stay cheap; only a strongly clustered key
-// distribution degrades to many compares per request (still exact).
+// Why buckets instead of radix passes: at this data rate the vector ALU, not HBM, limits a
+// sort of 8192 keys per workgroup (about 130 lane-instructions per request at full HBM
+// speed).  A stable 8-bit radix pass costs ~70 of them per key per pass.  One bucketing
+// pass with ~0.7 requests per bucket and a compare loop over bucket mates costs less than
+// one radix pass.  Appending the request index below the key makes equal keys spread over
+// buckets too, so heavy ties stay cheap; only a strongly clustered key distribution
+// degrades to many compares per request (still exact).
 #include "pard_device.hpp"
 
 namespace pard {
@@ -33,56 +33,44 @@ constexpr int kCntWords = kBuckets / 2;
 
 static_assert(kCap == (1 << kIdxBits), "local index width");
 
-template <int T>
-__global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
-    constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
-    constexpr int NW = T / kWave;
-    constexpr int CW = kCntWords / T;       // counter words scanned per thread
-    static_assert(G >= 1 && CW >= 1 && kCntWords % T == 0, "shape");
+struct SnapshotLds {
+    __align__(16) uint32_t cnt32[kCntWords + 4];     // bucket counters, then bucket starts; later the queue order
+    __align__(16) uint32_t low[kCap + 4];            // per queue slot: low bits of key.index (or the whole key)
+    __align__(16) uint16_t idx[kCap];                // per queue slot: local index (wide keys only)
+    StageRec recs[PARD_MAX_STAGES];
+    unsigned long long cfull[PARD_MAX_STAGES];
+    unsigned long long down[PARD_MAX_STAGES];
+    int32_t seg_start[PARD_MAX_STAGES + 1];
+    uint32_t wave_tot[16];
+    uint32_t red[2];
+};
 
-    __shared__ __align__(16) uint32_t cnt32[kCntWords + 4];       // bucket counters, then bucket starts; later the queue order
-    __shared__ __align__(16) uint32_t key_l[kCap];
-    __shared__ __align__(16) uint16_t idx_l[kCap];
-    __shared__ StageRec recs[PARD_MAX_STAGES];
-    __shared__ unsigned long long cfull[PARD_MAX_STAGES];
-    __shared__ unsigned long long down[PARD_MAX_STAGES];
-    __shared__ int32_t seg_start[PARD_MAX_STAGES + 1];
-    __shared__ uint32_t wave_tot[NW];
-    __shared__ uint32_t red[2];
+// FULL: the snapshot holds exactly kCap requests and every array is 16-byte aligned at its
+// start, so no per-request bounds test is needed.
+template <int T, bool FULL>
+__device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L, const int u, const int64_t lo,
+                                              const int m, const bool aligned) {
+    constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
+    constexpr int CW = kCntWords / T;       // counter words scanned per thread
+    static_assert(G >= 1 && CW >= 4 && CW % 4 == 0 && kCntWords % T == 0, "shape");
 
     const PlanDev& P = A.plan;
-    const int64_t n = A.n;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    const int u = blockIdx.x;
     const int S = P.S;
     const int dag = P.shared ? 0 : u;
-
-    // snapshot bounds, made safe whatever snap_ptr holds
-    int64_t lo64 = A.snap_ptr[u], hi64 = A.snap_ptr[u + 1];
-    if (lo64 < 0) lo64 = 0;
-    if (lo64 > n) lo64 = n;
-    if (hi64 > n) hi64 = n;
-    int64_t m64 = hi64 - lo64;
-    if (m64 < 0) m64 = 0;
-    const int limit = A.cap < kCap ? A.cap : kCap;
-    if (m64 > limit) {
-        m64 = limit;
-        if (tid == 0) atomicOr(A.status, kStatusSnapshotTooLarge);
-    }
-    const int m = (int)m64;
-    const int64_t lo = lo64;
-    const bool aligned = (lo & 3) == 0;
+    const int32_t* lat_dag = P.lat + (int64_t)dag * S * PARD_LAT_ENTRIES;
+    auto live = [&](int idx) { return FULL || idx < m; };
 
     // ---- 1. loads (issued first), LDS initialisation meanwhile ---------------
     int32_t dl[G][4], st[G][4];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
-        if (aligned && base + 3 < m) {
-            int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo + base);
-            int4 s4 = *reinterpret_cast<const int4*>(A.stage + lo + base);
+        if (FULL || (aligned && base + 3 < m)) {
+            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo + base);
+            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + lo + base);
             dl[g][0] = d4.x; dl[g][1] = d4.y; dl[g][2] = d4.z; dl[g][3] = d4.w;
             st[g][0] = s4.x; st[g][1] = s4.y; st[g][2] = s4.z; st[g][3] = s4.w;
         } else {
@@ -94,14 +82,15 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
             }
         }
     }
-    for (int i = tid; i < kCntWords + 4; i += T) cnt32[i] = 0;
     {
+        uint4* z = reinterpret_cast<uint4*>(L.cnt32);
+        for (int i = tid; i < (kCntWords + 4) / 4; i += T) z[i] = make_uint4(0, 0, 0, 0);
         const uint32_t* src = reinterpret_cast<const uint32_t*>(P.recs + (int64_t)dag * S);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(recs);
-        for (int i = tid; i < S * 8; i += T) dst[i] = src[i];
+        uint32_t* dst = reinterpret_cast<uint32_t*>(L.recs);
+        for (int i = tid; i < S * (int)(sizeof(StageRec) / 4); i += T) dst[i] = src[i];
+        if (tid < PARD_MAX_STAGES) L.down[tid] = 0;
+        if (tid == 0) { L.red[0] = 0xFFFFFFFFu; L.red[1] = 0u; }
     }
-    if (tid < PARD_MAX_STAGES) down[tid] = 0;
-    if (tid == 0) { red[0] = 0xFFFFFFFFu; red[1] = 0u; }
     __syncthreads();
 
     // ---- order keys, snapshot-wide key range ------------------------------------
@@ -112,34 +101,43 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const bool ok = base + c < m;
+            const bool ok = live(base + c);
             const int s = clamp_stage(st[g][c], S);
             st[g][c] = s;
-            const int mode = P.uniform_mode >= 0 ? P.uniform_mode : recs[s].mode;
-            int32_t arr = 0;
-            if (P.any_fcfs && mode == PARD_ORDER_FCFS && ok) arr = A.arrival[lo + base + c];
-            const uint32_t k = order_key(mode, dl[g][c], arr);
+            uint32_t k;
+            if (P.uniform_mode == PARD_ORDER_LBF) k = (uint32_t)dl[g][c] ^ 0x80000000u;
+            else if (P.uniform_mode == PARD_ORDER_HBF) k = ~((uint32_t)dl[g][c] ^ 0x80000000u);
+            else {
+                const int mode = P.uniform_mode >= 0 ? P.uniform_mode : (L.recs[s].mode & 0xFF);
+                int32_t arr = 0;
+                if (mode == PARD_ORDER_FCFS && ok) arr = A.arrival[lo + base + c];
+                k = order_key(mode, dl[g][c], arr);
+            }
             uk[g][c] = k;
             if (ok) { kmin = k < kmin ? k : kmin; kmax = k > kmax ? k : kmax; }
         }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
-        uint32_t a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
+        const uint32_t a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
         kmin = a < kmin ? a : kmin;
         kmax = b > kmax ? b : kmax;
     }
-    if (lane == 0) { atomicMin(&red[0], kmin); atomicMax(&red[1], kmax); }
+    if (lane == 0) { atomicMin(&L.red[0], kmin); atomicMax(&L.red[1], kmax); }
     __syncthreads();
 
     // ---- 2. buckets -------------------------------------------------------------
-    const uint32_t umin = red[0];
-    const uint32_t urange = m > 0 ? red[1] - umin : 0u;
+    // Conceptually comp = (key - min) << 13 | index, bucket = stage * NB + (comp >> shift),
+    // and the bits of comp below `shift` (its low part) order the requests inside a bucket.
+    const uint32_t umin = L.red[0];
+    const uint32_t urange = m > 0 ? L.red[1] - umin : 0u;
     int log2nb = 0;
     while ((2 << log2nb) * S <= kBuckets) ++log2nb;             // NB = largest power of two with S*NB <= kBuckets
-    const uint64_t crange = ((uint64_t)urange << kIdxBits) | (uint64_t)(kCap - 1);
-    const int cbits = 64 - __clzll((long long)crange);
+    const int cbits = kIdxBits + (urange ? 32 - __clz((int)urange) : 0);
     const int shift = cbits > log2nb ? cbits - log2nb : 0;
+    const bool key_split = shift >= kIdxBits;                   // bucket id takes key bits only
+    const int ksh = key_split ? shift - kIdxBits : 0;           // key bits left below the bucket id
+    const bool wide = shift > 32;                               // low part does not fit one word
 
     uint32_t bs[G][4];                       // bucket | slot << 16
 #pragma unroll
@@ -148,12 +146,19 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             bs[g][c] = 0;
-            if (base + c < m) {
-                const uint64_t comp = ((uint64_t)(uk[g][c] - umin) << kIdxBits) | (uint32_t)(base + c);
-                const uint32_t b = ((uint32_t)st[g][c] << log2nb) + (uint32_t)(comp >> shift);
-                const uint32_t old = atomicAdd(&cnt32[b >> 1], (b & 1u) ? 0x10000u : 1u);
-                const uint32_t slot = (b & 1u) ? (old >> 16) : (old & 0xFFFFu);
-                bs[g][c] = b | (slot << 16);
+            if (live(base + c)) {
+                const uint32_t rel = uk[g][c] - umin, me = (uint32_t)(base + c);
+                uint32_t b;
+                if (key_split) {
+                    b = rel >> ksh;
+                    if (!wide) uk[g][c] = ((rel & ((1u << ksh) - 1u)) << kIdxBits) | me;
+                } else {
+                    b = (rel << (kIdxBits - shift)) | (me >> shift);
+                    uk[g][c] = me & ((1u << shift) - 1u);
+                }
+                b += (uint32_t)st[g][c] << log2nb;
+                const uint32_t old = atomicAdd(&L.cnt32[b >> 1], 1u << ((b & 1u) << 4));
+                bs[g][c] = b | (((old >> ((b & 1u) << 4)) & 0xFFFFu) << 16);
             }
         }
     }
@@ -164,50 +169,57 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
         uint32_t w[CW];
         uint32_t sum = 0;
 #pragma unroll
-        for (int i = 0; i < CW; ++i) { w[i] = cnt32[tid * CW + i]; sum += w[i]; }
+        for (int i = 0; i < CW / 4; ++i) {
+            const uint4 v = reinterpret_cast<const uint4*>(L.cnt32)[tid * (CW / 4) + i];
+            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
+            sum += v.x + v.y + v.z + v.w;
+        }
         const uint32_t tot = (sum & 0xFFFFu) + (sum >> 16);
         uint32_t inc = tot;
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
-            uint32_t t = __shfl_up(inc, off);
+            const uint32_t t = __shfl_up(inc, off);
             if (lane >= off) inc += t;
         }
-        if (lane == kWave - 1) wave_tot[wave] = inc;
+        if (lane == kWave - 1) L.wave_tot[wave] = inc;
         __syncthreads();
         uint32_t run = inc - tot;
-        for (int i = 0; i < wave; ++i) run += wave_tot[i];
+        for (int i = 0; i < wave; ++i) run += L.wave_tot[i];
 #pragma unroll
         for (int i = 0; i < CW; ++i) {
             const uint32_t l16 = w[i] & 0xFFFFu, h16 = w[i] >> 16;
-            cnt32[tid * CW + i] = run | ((run + l16) << 16);
+            w[i] = run | ((run + l16) << 16);
             run += l16 + h16;
         }
-        if (tid == 0) cnt32[kCntWords] = (uint32_t)m;           // start of the bucket past the last one
+#pragma unroll
+        for (int i = 0; i < CW / 4; ++i)
+            reinterpret_cast<uint4*>(L.cnt32)[tid * (CW / 4) + i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+        if (tid == 0) L.cnt32[kCntWords] = (uint32_t)m;         // start of the bucket past the last one
     }
     __syncthreads();
 
-    // ---- 3. queue starts, full-queue costs; scatter (key, index) by bucket -----------
-    const uint16_t* start16 = reinterpret_cast<const uint16_t*>(cnt32);
+    // ---- 3. queue starts, full-queue costs; scatter the low parts by bucket -----------
+    const uint16_t* start16 = reinterpret_cast<const uint16_t*>(L.cnt32);
     if (tid < S) {
         const int a = start16[tid << log2nb];
         const int b = start16[(tid + 1) << log2nb];
-        seg_start[tid] = a;
-        if (tid == S - 1) seg_start[S] = m;
-        cfull[tid] = stage_cost(recs[tid], (uint32_t)(b - a), P.lat + ((int64_t)dag * S + tid) * PARD_LAT_ENTRIES);
+        L.seg_start[tid] = a;
+        if (tid == S - 1) L.seg_start[S] = m;
+        L.cfull[tid] = stage_cost(L.recs[tid], (uint32_t)(b - a), lat_dag + tid * PARD_LAT_ENTRIES);
     }
-    uint32_t se[G][4];                       // bucket start | bucket end << 16
+    uint32_t se[G][4];                       // bucket start (13 bits) | bucket size - 1 (13 bits) | stage << 26
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             se[g][c] = 0;
-            if (base + c < m) {
+            if (live(base + c)) {
                 const uint32_t b = bs[g][c] & 0xFFFFu, slot = bs[g][c] >> 16;
                 const uint32_t s0 = start16[b], e0 = start16[b + 1];
-                key_l[s0 + slot] = uk[g][c];
-                idx_l[s0 + slot] = (uint16_t)(base + c);
-                se[g][c] = s0 | (e0 << 16);
+                L.low[s0 + slot] = uk[g][c];
+                if (wide) L.idx[s0 + slot] = (uint16_t)(base + c);
+                se[g][c] = s0 | ((e0 - s0 - 1u) << 13) | ((b >> log2nb) << 26);
             }
         }
     }
@@ -219,38 +231,45 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
         for (int e = e_lo + tid; e < e_hi; e += T) {
             const int end = P.entry_end[e];
             unsigned long long sum = 0;
-            for (int t = e + 1; t < end; ++t) sum += cfull[P.entry_stage[t]];
-            atomicMax(&down[P.entry_stage[e]], sum);
+            for (int t = e + 1; t < end; ++t) sum += L.cfull[P.entry_stage[t]];
+            atomicMax(&L.down[P.entry_stage[e]], sum);
         }
     }
-    // ---- exact rank inside the bucket; queue order into LDS (reuses cnt32) -----------
-    uint16_t* ord_l = reinterpret_cast<uint16_t*>(cnt32);
+    // ---- exact rank inside the bucket ----------------------------------------------------
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (base + c < m) {
-                const uint32_t s0 = se[g][c] & 0xFFFFu, e0 = se[g][c] >> 16;
+            if (live(base + c)) {
+                const uint32_t s0 = se[g][c] & 0x1FFFu, e0 = s0 + ((se[g][c] >> 13) & 0x1FFFu) + 1u;
                 const uint32_t k = uk[g][c], me = (uint32_t)(base + c);
                 uint32_t less = 0;
                 if (e0 - s0 > 1) {
-                    for (uint32_t j = s0; j < e0; ++j) {
-                        const uint32_t kj = key_l[j], ij = idx_l[j];
-                        less += (kj < k) | ((kj == k) & (ij < me));
+                    if (!wide) {
+                        for (uint32_t j = s0; j < e0; j += 2) {          // two bucket mates per step
+                            const uint32_t a = L.low[j], b = L.low[j + 1];
+                            less += (a < k) + ((j + 1 < e0) & (b < k));
+                        }
+                    } else {
+                        for (uint32_t j = s0; j < e0; ++j) {
+                            const uint32_t kj = L.low[j], ij = L.idx[j];
+                            less += (kj < k) | ((kj == k) & (ij < me));
+                        }
                     }
                 }
-                se[g][c] = s0 + less;        // final queue slot inside the snapshot
+                se[g][c] = (s0 + less) | (se[g][c] & 0xFC000000u);   // final queue slot | stage << 26
             }
         }
     }
-    __syncthreads();                         // every bucket start has been read; cnt32 is free
+    __syncthreads();                         // bucket starts are no longer needed; down[] is complete
+    uint16_t* ord_l = reinterpret_cast<uint16_t*>(L.cnt32);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c)
-            if (base + c < m) ord_l[se[g][c]] = (uint16_t)(base + c);
+            if (live(base + c)) ord_l[se[g][c] & 0x1FFFu] = (uint16_t)(base + c);
     }
 
     // ---- 5. estimate and drop decision, request order ---------------------------------
@@ -264,16 +283,17 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
         for (int c = 0; c < 4; ++c) {
             est[c] = 0;
             drp[c] = 0;
-            if (base + c < m) {
-                const int k = st[g][c];
-                const uint32_t pos = se[g][c] - (uint32_t)seg_start[k];
-                const uint64_t e64 = stage_cost(recs[k], pos, P.lat + ((int64_t)dag * S + k) * PARD_LAT_ENTRIES) + down[k];
+            if (live(base + c)) {
+                const int k = (int)(se[g][c] >> 26);
+                const uint32_t pos = (se[g][c] & 0x1FFFu) - (uint32_t)L.seg_start[k];
+                const uint64_t e64 = stage_cost_short(L.recs[k], pos, lat_dag + k * PARD_LAT_ENTRIES) + L.down[k];
                 finish_request(e64, now, dl[g][c], est[c], drp[c]);
             }
         }
-        if (aligned && base + 3 < m) {
+        if (FULL || (aligned && base + 3 < m)) {
             *reinterpret_cast<int4*>(A.est + lo + base) = make_int4(est[0], est[1], est[2], est[3]);
-            *reinterpret_cast<uchar4*>(A.drop + lo + base) = make_uchar4(drp[0], drp[1], drp[2], drp[3]);
+            *reinterpret_cast<uint32_t*>(A.drop + lo + base) =
+                (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -286,7 +306,7 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
-        if (aligned && base + 3 < m) {
+        if (FULL || (aligned && base + 3 < m)) {
             const uint2 o = *reinterpret_cast<const uint2*>(ord_l + base);
             const int32_t b32 = (int32_t)lo;
             *reinterpret_cast<int4*>(A.order + lo + base) =
@@ -298,8 +318,34 @@ __global__ __launch_bounds__(T) void fused_snapshot_kernel(FusedArgs A) {
                 if (base + c < m) A.order[lo + base + c] = (int32_t)lo + (int32_t)ord_l[base + c];
         }
     }
-    if (tid < S) A.seg_ptr[(int64_t)u * S + tid] = (int32_t)lo + seg_start[tid];
+    if (tid < S) A.seg_ptr[(int64_t)u * S + tid] = (int32_t)lo + L.seg_start[tid];
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
+}
+
+template <int T>
+__global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
+    __shared__ SnapshotLds L;
+    const int u = blockIdx.x;
+    const int64_t n = A.n;
+    // snapshot bounds, made safe whatever snap_ptr holds
+    int64_t lo = A.snap_ptr[u], hi = A.snap_ptr[u + 1];
+    if (lo < 0) lo = 0;
+    if (lo > n) lo = n;
+    if (hi > n) hi = n;
+    int64_t m64 = hi - lo;
+    if (m64 < 0) m64 = 0;
+    const int limit = A.cap < kCap ? A.cap : kCap;
+    if (m64 > limit) {
+        m64 = limit;
+        if (threadIdx.x == 0) atomicOr(A.status, kStatusSnapshotTooLarge);
+    }
+    const int m = (int)m64;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(A.deadline) | reinterpret_cast<uintptr_t>(A.stage) |
+                           reinterpret_cast<uintptr_t>(A.est) | reinterpret_cast<uintptr_t>(A.order) |
+                           (reinterpret_cast<uintptr_t>(A.drop) << 2);
+    const bool aligned = (lo & 3) == 0 && (bits & 15) == 0;
+    if (m == kCap && aligned) snapshot_body<T, true>(A, L, u, lo, m, true);
+    else snapshot_body<T, false>(A, L, u, lo, m, aligned);
 }
 
 }  // namespace

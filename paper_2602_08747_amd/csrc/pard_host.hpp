@@ -15,17 +15,26 @@
 
 namespace pard {
 
-// Per-(DAG, stage) constants as the kernels read them (32 bytes).
+// Per-(DAG, stage) constants as the kernels read them (48 bytes).
 struct StageRec {
     int32_t B;        // batch size, 1..64
     int32_t W;        // workers, 1..2^20
     int32_t latB;     // lat[B]: latency of a full batch
-    int32_t mode;     // PARD_ORDER_*
+    int32_t mode;     // PARD_ORDER_* in bits 0..7, kStageFast in bit 8
     uint32_t mB;      // multiplier for floor(x / B), x < 2^32
     uint32_t shB;     // shift pair for it: sh1 | sh2 << 8
     uint32_t mW;      // multiplier for floor(x / W), x < 2^32
     uint32_t shW;
+    float rcpB;       // 1/B and 1/W rounded to nearest, for the short-queue fast path
+    float rcpW;
+    uint32_t aW;      // latB / W
+    uint32_t bW;      // latB % W
 };
+
+// Set when W <= 256 and latB / W < 2^18: for queue positions below 2^13 the wait term
+// floor(ceil(a/B) * latB / W) can then be formed exactly from 24-bit multiplies and two
+// float reciprocal multiplies (see stage_cost_short in pard_device.hpp).
+constexpr int32_t kStageFast = 1 << 8;
 
 // Division of a 32-bit unsigned integer by an invariant divisor d >= 1 via one
 // high multiply (Granlund & Montgomery, "Division by invariant integers using
@@ -159,7 +168,11 @@ inline int build_host_plan(const pard_plan_desc_t* d, HostPlan& hp) {
         if (M == PARD_ORDER_FCFS) hp.any_fcfs = true;
         if (M != first_mode) uniform = false;
         Magic32 kb = magic_u32((uint32_t)B), kw = magic_u32((uint32_t)W);
-        hp.recs[(size_t)i] = StageRec{B, W, d->lat_us[i * PARD_LAT_ENTRIES + B - 1], M, kb.m, kb.sh, kw.m, kw.sh};
+        const int32_t latB = d->lat_us[i * PARD_LAT_ENTRIES + B - 1];
+        const uint32_t aW = (uint32_t)latB / (uint32_t)W, bW = (uint32_t)latB % (uint32_t)W;
+        const int32_t fast = (W <= 256 && aW < (1u << 18)) ? kStageFast : 0;
+        hp.recs[(size_t)i] = StageRec{B, W, latB, M | fast, kb.m, kb.sh, kw.m, kw.sh,
+                                      1.0f / (float)B, 1.0f / (float)W, aW, bW};
     }
     hp.uniform_mode = uniform ? first_mode : -1;
     hp.dag_path_ptr.assign(1, 0);

@@ -32,17 +32,22 @@ constexpr uint32_t kFlagAggregate = 1u << 30;          // tile published its own
 constexpr uint32_t kFlagInclusive = 2u << 30;          // tile published the running total
 constexpr uint32_t kValueMask = (1u << 30) - 1;
 constexpr uint32_t kSpinLimit = 1u << 22;
+constexpr int kPools = 16;                             // tile pools of the radix passes (see sort_pass_kernel)
+constexpr int kPoolStride = 64;                        // counters 256 bytes apart
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
     uint32_t inv_min;               // max over requests of ~key  (so that zero-fill is the identity)
     uint32_t max_key;
     uint32_t kb;                    // bits of (max key - min key)
     uint32_t passes;                // radix passes actually needed
-    uint32_t ticket[kMaxPasses];    // next tile number of each pass
+    uint32_t total_bits;            // bits of the virtual sort key
 };
 
+constexpr int kStreamBlocksMax = 1024;                 // upper bound on the grid of the streaming kernels
+constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
+
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, hist, status, zero_end, key[2], pay[2], total;
+    int64_t params, seg_count, cfull, down, hist, pool_ctr, status, zero_end, part_minmax, part_cnt, key[2], pay[2], total;
     int64_t tiles;
     int32_t max_passes, idx_bits, seg_bits;
 };
@@ -63,8 +68,11 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n) {
     L.cfull = off;      off = align256(off + segs * 8);
     L.down = off;       off = align256(off + segs * 8);
     L.hist = off;       off = align256(off + (int64_t)kMaxPasses * kRadix * 4);
+    L.pool_ctr = off;   off = align256(off + (int64_t)kMaxPasses * kPools * kPoolStride * 4);
     L.status = off;     off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
     L.zero_end = off;
+    L.part_minmax = off; off = align256(off + (int64_t)kStreamBlocksMax * 8);
+    L.part_cnt = off;    off = align256(off + (int64_t)kStreamBlocksMax * kPartialSegs * 4);
     for (int b = 0; b < 2; ++b) {
         L.key[b] = off; off = align256(off + n * 4);
         L.pay[b] = off; off = align256(off + n * 4);
@@ -85,7 +93,12 @@ struct SortDev {                    // everything the sort kernels need, by valu
     uint32_t* seg_count;
     unsigned long long *cfull, *down;
     uint32_t* hist;                 // [kMaxPasses][256]
+    uint32_t* pool_ctr;             // [kMaxPasses][kPools][kPoolStride] next tile of each pool
+    int32_t pools;
     uint32_t* tile_status;          // [max_passes][tiles][256]
+    uint32_t* part_minmax;          // [stream_blocks][2]  per-workgroup (~min key, max key)
+    uint32_t* part_cnt;             // [stream_blocks][kPartialSegs] per-workgroup queue lengths
+    int32_t stream_blocks;
     uint32_t* key[2];
     uint32_t* pay[2];
     int64_t tiles;
@@ -114,44 +127,120 @@ __device__ __forceinline__ void request_segment_key(const SortDev& A, int64_t r,
     const int32_t u = snapshot_of(A.snap_ptr, P.K, r);
     const int32_t s = clamp_stage(A.stage[r], P.S);
     const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
-                                             : P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode;
+                                             : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
     const int32_t arr = (P.any_fcfs && mode == PARD_ORDER_FCFS) ? A.arrival[r] : 0;
     seg = (uint32_t)u * (uint32_t)P.S + (uint32_t)s;
     key = order_key(mode, A.deadline[r], arr);
 }
 
-// ---- count: queue lengths and key range ------------------------------------------
-constexpr int kCountLds = 4096;
-__global__ __launch_bounds__(256) void count_kernel(SortDev A) {
-    __shared__ uint32_t h[kCountLds];
-    const int64_t segs = (int64_t)A.plan.K * A.plan.S;
-    const bool use_lds = segs <= kCountLds;            // privatise the counters when they fit
-    if (use_lds) {
-        for (int i = threadIdx.x; i < segs; i += 256) h[i] = 0;
-        __syncthreads();
+// ---- streaming reads shared by the count and histogram kernels -------------------------
+constexpr int kScanThreads = 1024;
+constexpr int kScanItems = 8;                          // requests per thread per chunk
+constexpr int kChunk = kScanThreads * kScanItems;      // 8192 requests per chunk
+
+// The 8 requests of thread `tid` in the chunk starting at request `base`: two groups of 4
+// consecutive requests (16-byte loads when the arrays allow it).
+__device__ __forceinline__ void load_chunk(const SortDev& A, int64_t base, int tid, bool vec,
+                                           uint32_t (&seg)[kScanItems], uint32_t (&key)[kScanItems],
+                                           bool (&ok)[kScanItems]) {
+    const PlanDev& P = A.plan;
+#pragma unroll
+    for (int g = 0; g < kScanItems / 4; ++g) {
+        const int64_t r0 = base + (int64_t)g * (kScanThreads * 4) + tid * 4;
+        int32_t d[4], st[4];
+        if (vec && r0 + 3 < A.n) {
+            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0);
+            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + r0);
+            d[0] = d4.x; d[1] = d4.y; d[2] = d4.z; d[3] = d4.w;
+            st[0] = s4.x; st[1] = s4.y; st[2] = s4.z; st[3] = s4.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                d[c] = r0 + c < A.n ? A.deadline[r0 + c] : 0;
+                st[c] = r0 + c < A.n ? A.stage[r0 + c] : 0;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int i = g * 4 + c;
+            const int64_t r = r0 + c;
+            ok[i] = r < A.n;
+            const int32_t u = ok[i] ? snapshot_of(A.snap_ptr, P.K, r) : 0;
+            const int32_t sidx = clamp_stage(st[c], P.S);
+            const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
+                                                     : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + sidx].mode & 0xFF);
+            const int32_t arr = (mode == PARD_ORDER_FCFS && ok[i]) ? A.arrival[r] : 0;
+            seg[i] = (uint32_t)u * (uint32_t)P.S + (uint32_t)sidx;
+            key[i] = order_key(mode, d[c], arr);
+        }
     }
+}
+
+__device__ __forceinline__ bool arrays_vectorizable(const SortDev& A) {
+    return ((reinterpret_cast<uintptr_t>(A.deadline) | reinterpret_cast<uintptr_t>(A.stage)) & 15) == 0;
+}
+
+// ---- count: queue lengths and key range ------------------------------------------
+// No atomics on a shared global word here: every workgroup leaves its partial results in
+// its own slot and the setup kernel adds them up.  (Same-address global atomics cost ~11 ns
+// each on this chip and serialise.)
+constexpr int kCountLds = 16384;
+constexpr int kCountPrivate = kCountLds / kScanThreads;    // up to 16 queues: one counter column per thread
+__global__ __launch_bounds__(kScanThreads) void count_kernel(SortDev A) {
+    __shared__ uint32_t h[kCountLds];
+    __shared__ uint32_t red[2 * (kScanThreads / kWave)];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t segs = (int64_t)A.plan.K * A.plan.S;
+    const bool priv = segs <= kCountPrivate;            // h[seg * 1024 + tid]: no two lanes share a counter
+    const bool use_lds = segs <= kCountLds;             // h[seg]: LDS atomics
+    for (int i = tid; i < kCountLds; i += kScanThreads) h[i] = 0;
+    __syncthreads();
+    const bool vec = arrays_vectorizable(A);
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < A.n; r += stride) {
-        uint32_t seg, key;
-        request_segment_key(A, r, seg, key);
-        if (use_lds) atomicAdd(&h[seg], 1u); else atomicAdd(&A.seg_count[seg], 1u);
-        kmin = key < kmin ? key : kmin;
-        kmax = key > kmax ? key : kmax;
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < A.n; base += (int64_t)gridDim.x * kChunk) {
+        uint32_t seg[kScanItems], key[kScanItems];
+        bool ok[kScanItems];
+        load_chunk(A, base, tid, vec, seg, key, ok);
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            if (ok[i]) {
+                if (priv) atomicAdd(&h[seg[i] * kScanThreads + tid], 1u);
+                else if (use_lds) atomicAdd(&h[seg[i]], 1u);
+                else atomicAdd(&A.seg_count[seg[i]], 1u);
+                kmin = key[i] < kmin ? key[i] : kmin;
+                kmax = key[i] > kmax ? key[i] : kmax;
+            }
+        }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
-        uint32_t a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
+        const uint32_t a = __shfl_xor(kmin, off), b = __shfl_xor(kmax, off);
         kmin = a < kmin ? a : kmin;
         kmax = b > kmax ? b : kmax;
     }
-    if ((threadIdx.x & (kWave - 1)) == 0) {
-        atomicMax(&A.params->inv_min, ~kmin);
-        atomicMax(&A.params->max_key, kmax);
+    if (lane == 0) { red[2 * wave] = ~kmin; red[2 * wave + 1] = kmax; }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t a = 0, b = 0;
+        for (int w = 0; w < kScanThreads / kWave; ++w) {
+            a = red[2 * w] > a ? red[2 * w] : a;
+            b = red[2 * w + 1] > b ? red[2 * w + 1] : b;
+        }
+        A.part_minmax[2 * blockIdx.x] = a;
+        A.part_minmax[2 * blockIdx.x + 1] = b;
     }
-    if (use_lds) {
-        __syncthreads();
-        for (int i = threadIdx.x; i < segs; i += 256)
+    if (priv) {
+        for (int64_t g = wave; g < segs; g += kScanThreads / kWave) {
+            uint32_t v = 0;
+            for (int j = lane; j < kScanThreads; j += kWave) v += h[g * kScanThreads + j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+            if (lane == 0) A.part_cnt[(int64_t)blockIdx.x * kPartialSegs + g] = v;
+        }
+    } else if (segs <= kPartialSegs) {
+        if (tid < segs) A.part_cnt[(int64_t)blockIdx.x * kPartialSegs + tid] = h[tid];
+    } else if (use_lds) {
+        for (int i = tid; i < segs; i += kScanThreads)
             if (h[i]) atomicAdd(&A.seg_count[i], h[i]);
     }
 }
@@ -163,6 +252,43 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)P.K * P.S;
+    // add up what the count kernel's workgroups left behind
+    {
+        __shared__ uint32_t mm[2][16];
+        uint32_t a = 0, b = 0;
+        for (int i = tid; i < A.stream_blocks; i += 1024) {
+            const uint32_t x = A.part_minmax[2 * i], y = A.part_minmax[2 * i + 1];
+            a = x > a ? x : a;
+            b = y > b ? y : b;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint32_t x = __shfl_xor(a, off), y = __shfl_xor(b, off);
+            a = x > a ? x : a;
+            b = y > b ? y : b;
+        }
+        if (lane == 0) { mm[0][wave] = a; mm[1][wave] = b; }
+        if (segs <= kPartialSegs) {
+            // thread t: queue t % 64, every 16th workgroup starting at t / 64
+            const int g = tid & (kPartialSegs - 1);
+            uint32_t v = 0;
+            if (g < segs)
+                for (int i = tid / kPartialSegs; i < A.stream_blocks; i += 1024 / kPartialSegs)
+                    v += A.part_cnt[(int64_t)i * kPartialSegs + g];
+            if (g < segs && v) atomicAdd(&A.seg_count[g], v);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int w = 1; w < 16; ++w) {
+                mm[0][0] = mm[0][w] > mm[0][0] ? mm[0][w] : mm[0][0];
+                mm[1][0] = mm[1][w] > mm[1][0] ? mm[1][w] : mm[1][0];
+            }
+            A.params->inv_min = mm[0][0];
+            A.params->max_key = mm[1][0];
+        }
+        __threadfence();
+        __syncthreads();
+    }
     if (tid == 0) {
         const uint32_t umin = ~A.params->inv_min;
         const uint32_t range = A.n > 0 ? A.params->max_key - umin : 0u;
@@ -170,6 +296,7 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         const uint32_t total = kb + (uint32_t)A.seg_bits;
         uint32_t passes = (total + kRadixBits - 1) / kRadixBits;
         A.params->kb = kb;
+        A.params->total_bits = total;
         A.params->passes = passes < 1 ? 1 : passes;
         carry = 0;
     }
@@ -177,7 +304,7 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     // queue offsets: exclusive scan of the queue lengths, 1024 at a time
     for (int64_t base = 0; base < segs + 1; base += 1024) {
         const int64_t g = base + tid;
-        const uint32_t v = g < segs ? A.seg_count[g] : 0u;
+        const uint32_t v = g < segs ? __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
         uint32_t inc = v;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -196,7 +323,8 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     // cost of every stage at its full queue length
     for (int64_t g = tid; g < segs; g += 1024) {
         const int64_t rec = P.shared ? g % P.S : g;
-        A.cfull[g] = stage_cost(P.recs[rec], A.seg_count[g], P.lat + rec * PARD_LAT_ENTRIES);
+        A.cfull[g] = stage_cost(P.recs[rec], __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                                P.lat + rec * PARD_LAT_ENTRIES);
     }
     __threadfence_block();
     __syncthreads();
@@ -219,22 +347,39 @@ __device__ __forceinline__ uint32_t digit_of(uint32_t key, uint32_t seg, uint32_
 }
 
 // ---- histogram of every pass's digit -------------------------------------------------
-__global__ __launch_bounds__(256) void histogram_kernel(SortDev A) {
+// Arrival-ordered input has long runs of equal high digits; 64 lanes adding to one LDS word
+// serialise, so a wave whose lanes all hold the same digit adds its population count once.
+__global__ __launch_bounds__(kScanThreads) void histogram_kernel(SortDev A) {
     __shared__ uint32_t h[kMaxPasses * kRadix];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < kMaxPasses * kRadix; i += 256) h[i] = 0;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < kMaxPasses * kRadix; i += kScanThreads) h[i] = 0;
     __syncthreads();
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
     const int passes = (int)A.params->passes;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + tid; r < A.n; r += stride) {
-        uint32_t seg, key;
-        request_segment_key(A, r, seg, key);
-        key -= umin;
-        for (int p = 0; p < passes; ++p) atomicAdd(&h[p * kRadix + digit_of(key, seg, kb, p)], 1u);
+    const bool vec = arrays_vectorizable(A);
+    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < A.n; base += (int64_t)gridDim.x * kChunk) {
+        uint32_t seg[kScanItems], key[kScanItems];
+        bool ok[kScanItems];
+        load_chunk(A, base, tid, vec, seg, key, ok);
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            const unsigned long long active = __ballot(ok[i]);
+            if (active == 0ull) continue;
+            const int leader = __ffsll((long long)active) - 1;
+            const uint32_t k = key[i] - umin;
+            for (int p = 0; p < passes; ++p) {
+                const uint32_t d = digit_of(k, seg[i], kb, p);
+                const uint32_t d0 = __shfl(d, leader);
+                if (__ballot(ok[i] && d == d0) == active) {
+                    if (lane == leader) atomicAdd(&h[p * kRadix + d0], (uint32_t)__popcll(active));
+                } else if (ok[i]) {
+                    atomicAdd(&h[p * kRadix + d], 1u);
+                }
+            }
+        }
     }
     __syncthreads();
-    for (int i = tid; i < passes * kRadix; i += 256)
+    for (int i = tid; i < passes * kRadix; i += kScanThreads)
         if (h[i]) atomicAdd(&A.hist[i], h[i]);
 }
 
@@ -266,21 +411,35 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
     __shared__ uint32_t tile_start[kRadix];
     __shared__ uint32_t gbase[kRadix];
     __shared__ uint32_t scan_tmp[kSortWaves];
-    __shared__ uint32_t s_tile;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid == 0) s_tile = atomicAdd(&A.params->ticket[pass], 1u);
-    for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0;
-    __syncthreads();
-    const int64_t tile = s_tile;
-    if (tile >= A.tiles) return;                       // cannot happen: one ticket per workgroup
-    const int64_t tile_base = tile * kTile;
-    const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
+    const int rem_bits = (int)A.params->total_bits - kRadixBits * pass;
+    const int nbits = rem_bits < kRadixBits ? (rem_bits < 1 ? 1 : rem_bits) : kRadixBits;   // digit bits that can differ
     const uint32_t* src_key = A.key[(pass + 1) & 1];
     const uint32_t* src_pay = A.pay[(pass + 1) & 1];
     uint32_t* dst_key = A.key[pass & 1];
     uint32_t* dst_pay = A.pay[pass & 1];
+    // first output slot of every digit: exclusive scan of this pass's global histogram
+    const uint32_t bin_base = block_exclusive_scan_256(A.hist[pass * kRadix + tid], scan_tmp, tid);
+
+    // A tile may only wait for tiles that already run.  Workgroups are persistent and claim
+    // tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, ... and hands them out
+    // in increasing order; a workgroup uses pool blockIdx % 16), so the lowest unfinished tile
+    // is either running or next in line in a pool whose workgroups have nothing unfinished
+    // left.  One ticket counter would do the same, but atomics on a single address cost
+    // ~11 ns each on this chip; 16 counters on separate cache lines run in parallel.
+    __shared__ int64_t s_tile;
+    const int pool = (int)(blockIdx.x % (unsigned)A.pools);
+    uint32_t* my_ctr = A.pool_ctr + ((int64_t)pass * kPools + pool) * kPoolStride;
+    while (true) {
+    if (tid == 0) s_tile = (int64_t)atomicAdd(my_ctr, 1u) * A.pools + pool;
+    for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t tile = s_tile;
+    if (tile >= A.tiles) break;
+    const int64_t tile_base = tile * kTile;
+    const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
 
     // load (wave-striped: wave w owns elements [w*1024, (w+1)*1024) of the tile, item i lane l
     // is element w*1024 + i*64 + l), rank every element among equal digits before it
@@ -311,9 +470,11 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
         unsigned long long peers = __ballot(ok);
 #pragma unroll
         for (int b = 0; b < kRadixBits; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const unsigned long long vote = __ballot(bit);
-            peers &= bit ? vote : ~vote;
+            if (b < nbits) {                       // higher bits of this digit are zero for every key
+                const bool bit = (d >> b) & 1u;
+                const unsigned long long vote = __ballot(bit);
+                peers &= bit ? vote : ~vote;
+            }
         }
         const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
                                     __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
@@ -343,7 +504,6 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
             __hip_atomic_store(st, kFlagInclusive | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         else
             __hip_atomic_store(st, kFlagAggregate | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t bin_base = block_exclusive_scan_256(A.hist[pass * kRadix + d], scan_tmp, tid);
         const uint32_t tstart = block_exclusive_scan_256(tile_cnt, scan_tmp, tid);
         tile_start[d] = tstart;
         uint32_t excl = 0;
@@ -392,6 +552,8 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
             if ((int64_t)dst < A.n) { dst_key[dst] = k; dst_pay[dst] = p; }
         }
     }
+    __syncthreads();                    // LDS is reused by the next tile
+    }
 }
 
 // ---- epilogue: positions -> estimates, drop decisions, queue order ------------------------
@@ -414,8 +576,9 @@ __global__ __launch_bounds__(256) void epilogue_kernel(SortDev A) {
         const uint64_t e64 = stage_cost(sr, pos, P.lat + rec * PARD_LAT_ENTRIES) + A.down[seg];
         int32_t deadline;
         const uint32_t uk = keys[j] + umin;
-        if (sr.mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
-        else if (sr.mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
+        const int32_t mode = sr.mode & 0xFF;
+        if (mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
+        else if (mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
         else deadline = A.deadline[r];
         int32_t est;
         uint8_t drp;
@@ -440,7 +603,10 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.cfull = reinterpret_cast<unsigned long long*>(ws + L.cfull);
     D.down = reinterpret_cast<unsigned long long*>(ws + L.down);
     D.hist = reinterpret_cast<uint32_t*>(ws + L.hist);
+    D.pool_ctr = reinterpret_cast<uint32_t*>(ws + L.pool_ctr);
     D.tile_status = reinterpret_cast<uint32_t*>(ws + L.status);
+    D.part_minmax = reinterpret_cast<uint32_t*>(ws + L.part_minmax);
+    D.part_cnt = reinterpret_cast<uint32_t*>(ws + L.part_cnt);
     for (int b = 0; b < 2; ++b) {
         D.key[b] = reinterpret_cast<uint32_t*>(ws + L.key[b]);
         D.pay[b] = reinterpret_cast<uint32_t*>(ws + L.pay[b]);
@@ -456,6 +622,17 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
 
 int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n) { return make_layout(K, S, n).total; }
 
+int sort_pass_blocks_per_cu() {
+    int a = 0, b = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, sort_pass_kernel<true>, kSortThreads, 0) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, sort_pass_kernel<false>, kSortThreads, 0) != hipSuccess) {
+        (void)hipGetLastError();
+        return 1;
+    }
+    const int m = a < b ? a : b;
+    return m < 1 ? 1 : m;
+}
+
 bool sort_supported(int32_t K, int32_t S, int64_t n) {
     const SortLayout L = make_layout(K, S, n);
     return L.idx_bits + L.seg_bits <= 32 && n < ((int64_t)1 << 30);
@@ -463,7 +640,7 @@ bool sort_supported(int32_t K, int32_t S, int64_t n) {
 
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     const SortLayout L = make_layout(a.plan.K, a.plan.S, a.n);
-    const SortDev D = make_dev(a, L);
+    SortDev D = make_dev(a, L);
     const int64_t zero16 = L.zero_end / 16;
     int zb = (int)((zero16 + 255) / 256);
     if (zb > 4096) zb = 4096;
@@ -472,13 +649,22 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     int gb = (int)((a.n + 256 * 8 - 1) / (256 * 8));
     if (gb > 8192) gb = 8192;
     if (gb < 1) gb = 1;
-    count_kernel<<<gb, 256, 0, stream>>>(D);
+    int sb = (int)((a.n + kChunk - 1) / kChunk);       // streaming kernels: two workgroups of 1024 threads per CU
+    if (sb > 2 * a.num_cus) sb = 2 * a.num_cus;
+    if (sb > kStreamBlocksMax) sb = kStreamBlocksMax;
+    if (sb < 1) sb = 1;
+    int64_t pg = a.resident_pass_blocks > 0 ? a.resident_pass_blocks : 1;   // radix passes: persistent workgroups
+    if (pg > L.tiles) pg = L.tiles;
+    if (pg < 1) pg = 1;
+    D.pools = pg < kPools ? (int)pg : kPools;
+    D.stream_blocks = sb;
+    count_kernel<<<sb, kScanThreads, 0, stream>>>(D);
     setup_kernel<<<1, 1024, 0, stream>>>(D);
     if (a.n > 0) {
-        histogram_kernel<<<gb, 256, 0, stream>>>(D);
+        histogram_kernel<<<sb, kScanThreads, 0, stream>>>(D);
         for (int p = 0; p < L.max_passes; ++p) {
-            if (p == 0) sort_pass_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
-            else sort_pass_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            if (p == 0) sort_pass_kernel<true><<<(unsigned)pg, kSortThreads, 0, stream>>>(D, p);
+            else sort_pass_kernel<false><<<(unsigned)pg, kSortThreads, 0, stream>>>(D, p);
         }
         epilogue_kernel<<<gb, 256, 0, stream>>>(D);
     }

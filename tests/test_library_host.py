@@ -131,3 +131,20 @@ def test_invariant_division_is_exact(host_shim):
             for n in (base - 1, base, base + 1, base + d - 1):
                 if 0 <= n < 2**32:
                     assert host_shim.shim_div(n, d) == n // d
+
+
+def test_short_queue_float_reciprocals_are_exact():
+    """The on-chip kernel forms ceil(a/B) and floor(p/W) for short queues with one float32
+    multiply each: trunc((x + 0.5) * fl(1/d)).  Replayed here in IEEE float32 (numpy) over the
+    whole domain the kernel uses it on: x = a + B - 1 < 2^13 + 64 for every B, and
+    p = q * (latB mod W) < 2^21 for every W <= 256."""
+    f32 = np.float32
+    for B in range(1, 65):
+        x = np.arange(0, 8192 + B, dtype=np.int64)
+        got = ((x.astype(f32) + f32(0.5)) * (f32(1.0) / f32(B))).astype(np.int64)
+        assert np.array_equal(got, x // B), B
+    for W in range(1, 257):
+        p = np.arange(0, 8192 * (W - 1) + 1, dtype=np.int64) if W > 1 else np.zeros(1, np.int64)
+        assert p.max() < 2**21
+        got = ((p.astype(f32) + f32(0.5)) * (f32(1.0) / f32(W))).astype(np.int64)
+        assert np.array_equal(got, p // W), W
