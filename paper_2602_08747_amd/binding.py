@@ -45,8 +45,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or _build.LIB_PATH
-    if not os.path.exists(p):
+    p = path or os.environ.get("PARD_LIBRARY") or _build.LIB_PATH
+    if p == _build.LIB_PATH and not os.path.exists(p):
         _build.build_library()
     lib = ctypes.CDLL(p)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32

@@ -4,18 +4,23 @@
 // keep[j] = !drop[order[j]] for every queue slot j; surv_idx is order filtered by keep;
 // surv_ptr[g] = number of kept slots before queue g starts.
 //
-// One pass over the data: a workgroup counts the kept slots of a tile of 4096 queue slots,
-// publishes the count, and obtains the number of kept slots in all earlier tiles by a
-// decoupled look-back (one wave inspects 64 predecessor tiles at a time).
+// One pass over the data.  A workgroup counts the kept slots of a tile of 4096 queue slots,
+// publishes the count, and receives the number of kept slots in all earlier tiles from a
+// scan service: one wave of a helper workgroup walks the tile counts in order (64 tiles per
+// load, four loads in flight, running total in a register) and hands each tile its offset
+// as soon as the tiles up to it have published.  A waiting tile polls one word.  (A
+// look-back in which every waiting tile re-reads a window of predecessor words floods the
+// memory fabric with polling traffic when ~1500 tiles are resident.)
 //
-// Tile order: a tile may only wait for tiles that already run.  Workgroups are persistent
+// Tile order: a tile must only wait for tiles that already run.  Workgroups are persistent
 // and claim tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, y+32, ... and
 // hands them out in increasing order through its own counter; a workgroup uses pool
-// blockIdx % 16).  The lowest unfinished tile is then either running or next in line in a
-// pool whose workgroups have nothing unfinished left, so every wait ends as long as 16
-// workgroups of the grid fit on the device.  A single ticket counter would give the same
-// order, but atomics on one address cost ~11 ns each here (~95 us for 8192 tiles, more
-// than the rest of the kernel); 16 counters on separate cache lines run in parallel.
+// blockIdx % 16).  The lowest tile without an offset is then either running or next in line
+// in a pool whose workgroups have nothing unfinished left, and publishing a count never
+// waits, so every wait ends as long as 17 workgroups of the grid fit on the device.  A single
+// ticket counter would give the same order, but atomics on one address cost ~11 ns each here
+// (~95 us for 8192 tiles); 16 counters on separate cache lines run in parallel.  The first
+// workgroup of pool 0 to arrive becomes the helper.
 #include "pard_device.hpp"
 
 namespace pard {
@@ -26,11 +31,11 @@ constexpr int kCThreads = 256;
 constexpr int kCItems = 16;
 constexpr int kCTile = kCThreads * kCItems;
 constexpr int kCWaves = kCThreads / kWave;
-constexpr uint32_t kFlagAggregate = 1u << 30;          // tile published its own count
-constexpr uint32_t kFlagInclusive = 2u << 30;          // tile published the running total
+constexpr uint32_t kFlagReady = 1u << 31;              // word has been published
 constexpr uint32_t kValueMask = (1u << 30) - 1;
 constexpr uint32_t kSpinLimit = 1u << 22;
 constexpr int kPools = 16;                             // tile pools (see above)
+constexpr int kLook = 4;                               // groups of 64 tile counts the scan service requests per step
 constexpr int kPoolStride = 64;                        // counters 256 bytes apart
 
 __global__ void compact_zero_kernel(uint32_t* p, int64_t count) {
@@ -65,15 +70,57 @@ __device__ __forceinline__ int64_t wave_lower_bound_i32(const int32_t* a, int64_
     return lo;
 }
 
-__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+// The scan service (one wave).  state[t] = ready | kept slots of tile t, written by the tile;
+// prefix[t] = ready | kept slots of tiles 0..t-1, written here.
+__device__ __forceinline__ void compact_scan_service(const uint32_t* state, uint32_t* prefix, int64_t tiles,
+                                                     int lane, uint32_t* status_word) {
+    int64_t base = 0;
+    uint32_t running = 0, idle = 0;
+    while (base < tiles) {
+        uint32_t v[kLook];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+        for (int c = 0; c < kLook; ++c) {
+            const int64_t t = base + 64 * c + lane;
+            const uint32_t x = __hip_atomic_load(state + (t < tiles ? t : tiles - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            v[c] = t < tiles ? x : kFlagReady;                   // past the end: nothing to add
+        }
+        int processed = 0;
+        bool go = true;
+#pragma unroll
+        for (int c = 0; c < kLook; ++c) {
+            if (!go) continue;
+            const unsigned long long ready = __ballot((v[c] & kFlagReady) != 0);
+            const int nready = ready == ~0ull ? 64 : __ffsll((long long)~ready) - 1;   // leading published tiles
+            const uint32_t val = lane < nready ? (v[c] & kValueMask) : 0u;
+            uint32_t inc = val;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const uint32_t t = __shfl_up(inc, off);
+                if (lane >= off) inc += t;
+            }
+            const int64_t t = base + 64 * c + lane;
+            if (lane < nready && t < tiles)
+                __hip_atomic_store(prefix + t, kFlagReady | ((running + inc - val) & kValueMask), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            running += __shfl(inc, 63);
+            processed += nready;
+            if (nready < 64) go = false;
+        }
+        base += processed;
+        if (processed == 0) {
+            if (++idle > kSpinLimit) { if (lane == 0) atomicOr(status_word, kStatusLookbackTimeout); return; }
+            __builtin_amdgcn_s_sleep(2);
+        } else {
+            idle = 0;
+        }
+    }
 }
 
-// tile_state[0..tiles): look-back words; pool_ctr[y * kPoolStride]: next tile of pool y.  All zero at launch.
-__global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint32_t* tile_state, uint32_t* pool_ctr,
-                                                            int64_t tiles, int pools, uint32_t* status_word) {
+// tile_state[0..tiles), tile_prefix[0..tiles): see the scan service; pool_ctr[y * kPoolStride]: next tile of
+// pool y; pool_ctr[kPools * kPoolStride]: arrival counter that elects the helper.  All zero at launch.
+__global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint32_t* tile_state, uint32_t* tile_prefix,
+                                                            uint32_t* pool_ctr, int64_t tiles, int pools,
+                                                            uint32_t* status_word) {
     __shared__ __align__(16) uint16_t excl_l[kCTile + 8];   // kept slots of this tile before each slot
     __shared__ uint32_t wave_tot[kCWaves];
     __shared__ uint32_t s_excl;
@@ -81,6 +128,16 @@ __global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint3
     __shared__ int64_t g_range[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int pool = (int)(blockIdx.x % (unsigned)pools);
+    if (tiles > 0 && pool == 0) {       // the first workgroup of pool 0 to arrive runs the scan service
+        if (tid == 0) s_excl = atomicAdd(&pool_ctr[kPools * kPoolStride], 1u);
+        __syncthreads();
+        const bool helper = s_excl == 0;
+        __syncthreads();
+        if (helper) {
+            if (wave == 0) compact_scan_service(tile_state, tile_prefix, tiles, lane, status_word);
+            return;
+        }
+    }
 
     while (true) {
     if (tid == 0)
@@ -152,45 +209,9 @@ __global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint3
         total += t;
     }
 
-    // kept slots in all earlier tiles
-    if (wave == 0) {
-        uint32_t excl = 0;
-        if (tiles > 0) {
-            if (tile == 0) {
-                if (lane == 0) __hip_atomic_store(&tile_state[0], kFlagInclusive | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                if (lane == 0) __hip_atomic_store(&tile_state[tile], kFlagAggregate | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                int64_t window = tile - 1;                  // lane l inspects tile window - l
-                bool done = false;
-                uint32_t spins = 0;
-                while (!done) {
-                    const int64_t t = window - lane;
-                    uint32_t v = kFlagInclusive;            // tiles before the first count as a finished zero
-                    if (t >= 0) v = __hip_atomic_load(&tile_state[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (__ballot((v & ~kValueMask) == 0) != 0ull) {     // someone has not published yet
-                        if (++spins > kSpinLimit) {
-                            if (lane == 0) atomicOr(status_word, kStatusLookbackTimeout);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                        continue;
-                    }
-                    const unsigned long long inc_mask = __ballot((v & ~kValueMask) == kFlagInclusive);
-                    if (inc_mask != 0ull) {
-                        const int first = __ffsll((long long)inc_mask) - 1;   // nearest tile with a running total
-                        excl += wave_sum(lane <= first ? (v & kValueMask) : 0u);
-                        done = true;
-                    } else {
-                        excl += wave_sum(v & kValueMask);
-                        window -= 64;
-                    }
-                }
-                if (lane == 0) __hip_atomic_store(&tile_state[tile], kFlagInclusive | ((excl + total) & kValueMask),
-                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        if (lane == 0) s_excl = excl;
-    }
+    // kept slots in all earlier tiles: publish this tile's count, poll its offset later
+    if (tid == 0 && tiles > 0)
+        __hip_atomic_store(&tile_state[tile], kFlagReady | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // meanwhile: per-slot counts for the queue offsets
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
@@ -199,7 +220,18 @@ __global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint3
         const uint32_t b1 = b0 + (keep[k] & 1u), b2 = b1 + ((keep[k] >> 1) & 1u), b3 = b2 + ((keep[k] >> 2) & 1u);
         *reinterpret_cast<uint2*>(excl_l + e) = make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
     }
-    if (tid == 0) excl_l[kCTile] = (uint16_t)total;
+    if (tid == 0) {
+        excl_l[kCTile] = (uint16_t)total;
+        uint32_t pv = kFlagReady;
+        if (tiles > 0) {
+            uint32_t spins = 0;
+            while (!((pv = __hip_atomic_load(&tile_prefix[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kFlagReady)) {
+                if (++spins > kSpinLimit) { atomicOr(status_word, kStatusLookbackTimeout); break; }
+                __builtin_amdgcn_s_sleep(2);
+            }
+        }
+        s_excl = pv & kValueMask;
+    }
     __syncthreads();
     const uint32_t off0 = s_excl;
 #pragma unroll
@@ -225,7 +257,7 @@ __global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint3
 
 int64_t compact_workspace_bytes(int64_t n) {
     const int64_t tiles = (n + kCTile - 1) / kCTile;
-    return (int64_t)kPools * kPoolStride * 4 + (((tiles + 1) * 4 + 255) & ~(int64_t)255);
+    return (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255);
 }
 
 int compact_blocks_per_cu() {
@@ -240,16 +272,19 @@ int compact_blocks_per_cu() {
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     const int64_t tiles = (a.n + kCTile - 1) / kCTile;
     uint32_t* pool_ctr = static_cast<uint32_t*>(a.workspace);
-    uint32_t* tile_state = pool_ctr + kPools * kPoolStride;
-    const int64_t words = (int64_t)kPools * kPoolStride + tiles + 1;
+    const int64_t row = ((tiles + 1) * 4 + 255) / 256 * 64;          // words per array, 256-byte multiple
+    uint32_t* tile_state = pool_ctr + (kPools + 1) * kPoolStride;
+    uint32_t* tile_prefix = tile_state + row;
+    const int64_t words = (int64_t)(kPools + 1) * kPoolStride + 2 * row;
     int zb = (int)((words + 255) / 256);
     if (zb > 1024) zb = 1024;
     compact_zero_kernel<<<zb, 256, 0, stream>>>(pool_ctr, words);
     int64_t grid = a.resident_blocks > 0 ? a.resident_blocks : 1;     // persistent: what the device holds at once
     if (grid > tiles) grid = tiles;
     if (grid < 1) grid = 1;
-    const int pools = grid < kPools ? (int)grid : kPools;
-    compact_kernel<<<(unsigned)grid, kCThreads, 0, stream>>>(a, tile_state, pool_ctr, tiles, pools, a.status);
+    const int pools = grid < kPools ? (int)grid : kPools;                 // pool 0 then holds at least two workgroups
+    if (tiles > 0) grid += 1;                                             // one workgroup becomes the scan service
+    compact_kernel<<<(unsigned)grid, kCThreads, 0, stream>>>(a, tile_state, tile_prefix, pool_ctr, tiles, pools, a.status);
     return hipGetLastError();
 }
 
