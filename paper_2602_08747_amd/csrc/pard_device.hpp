@@ -87,13 +87,15 @@ __device__ __forceinline__ uint64_t stage_cost_short(const StageRec& r, uint32_t
     return stage_cost(r, a, lat_row);
 }
 
-// est (clamped) and the drop decision from the 64-bit estimate.
+// est (clamped) and the drop decision from the 64-bit estimate:
+//   drop = min(now + e64, INT32_MAX) > deadline.
+// A deadline of INT32_MAX can never be exceeded by the clamped finish time; for any smaller
+// deadline the clamp does not change the comparison.
 __device__ __forceinline__ void finish_request(uint64_t e64, int32_t now, int32_t deadline,
                                                int32_t& est, uint8_t& drop) {
     est = e64 > (uint64_t)kInt32Max ? kInt32Max : (int32_t)e64;
-    int64_t fin = (int64_t)now + (int64_t)e64;
-    if (fin > (int64_t)kInt32Max) fin = kInt32Max;
-    drop = fin > (int64_t)deadline ? 1 : 0;
+    const int64_t fin = (int64_t)now + (int64_t)e64;
+    drop = ((deadline != kInt32Max) & (fin > (int64_t)deadline)) ? 1 : 0;
 }
 
 __device__ __forceinline__ uint32_t lane_id() {

@@ -36,11 +36,14 @@ static_assert(kCap == (1 << kIdxBits), "local index width");
 struct SnapshotLds {
     __align__(16) uint32_t cnt32[kCntWords + 4];     // bucket counters, then bucket starts; later the queue order
     __align__(16) uint32_t low[kCap + 4];            // per queue slot: low bits of key.index (or the whole key)
-    __align__(16) uint16_t idx[kCap];                // per queue slot: local index (wide keys only)
+    __align__(16) uint16_t idx[kCap];                // per queue slot: local index (wide keys only); otherwise
+                                                     // 4096 words of cache: latency tables, then path entries
     StageRec recs[PARD_MAX_STAGES];
     unsigned long long cfull[PARD_MAX_STAGES];
     unsigned long long down[PARD_MAX_STAGES];
     int32_t seg_start[PARD_MAX_STAGES + 1];
+    __align__(16) uint32_t quick[PARD_MAX_STAGES][8];   // per stage: B-1, 1/B, 1/W, aW, bW, queue start (short-queue form)
+    uint32_t slow_stages;                            // set when some stage cannot use the short-queue form
     uint32_t wave_tot[16];
     uint32_t red[2];
 };
@@ -52,7 +55,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
                                               const int m, const bool aligned) {
     constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
     constexpr int CW = kCntWords / T;       // counter words scanned per thread
-    static_assert(G >= 1 && CW >= 4 && CW % 4 == 0 && kCntWords % T == 0, "shape");
+    static_assert(G >= 1 && CW >= 2 && CW % 2 == 0 && kCntWords % T == 0, "shape");
 
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x;
@@ -62,6 +65,10 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     const int dag = P.shared ? 0 : u;
     const int32_t* lat_dag = P.lat + (int64_t)dag * S * PARD_LAT_ENTRIES;
     auto live = [&](int idx) { return FULL || idx < m; };
+    uint32_t* aux = reinterpret_cast<uint32_t*>(L.idx);           // kCap / 2 words
+    const int e_lo = P.dag_entry_ptr[dag], n_entries = P.dag_entry_ptr[dag + 1] - e_lo;
+    const bool entries_cached = S * PARD_LAT_ENTRIES + n_entries <= kCap / 2;
+    const int32_t now = A.now[u];
 
     // ---- 1. loads (issued first), LDS initialisation meanwhile ---------------
     int32_t dl[G][4], st[G][4];
@@ -89,7 +96,12 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
         uint32_t* dst = reinterpret_cast<uint32_t*>(L.recs);
         for (int i = tid; i < S * (int)(sizeof(StageRec) / 4); i += T) dst[i] = src[i];
         if (tid < PARD_MAX_STAGES) L.down[tid] = 0;
-        if (tid == 0) { L.red[0] = 0xFFFFFFFFu; L.red[1] = 0u; }
+        if (tid == 0) { L.red[0] = 0xFFFFFFFFu; L.red[1] = 0u; L.slow_stages = 0u; }
+        // cache in the (so far unused) index array: the DAG's latency tables and path entries
+        for (int i = tid; i < S * PARD_LAT_ENTRIES; i += T) aux[i] = (uint32_t)lat_dag[i];
+        if (entries_cached)
+            for (int e = tid; e < n_entries; e += T)
+                aux[S * PARD_LAT_ENTRIES + e] = (uint32_t)P.entry_stage[e_lo + e] | ((uint32_t)(P.entry_end[e_lo + e] - e_lo) << 8);
     }
     __syncthreads();
 
@@ -169,10 +181,10 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
         uint32_t w[CW];
         uint32_t sum = 0;
 #pragma unroll
-        for (int i = 0; i < CW / 4; ++i) {
-            const uint4 v = reinterpret_cast<const uint4*>(L.cnt32)[tid * (CW / 4) + i];
-            w[4 * i] = v.x; w[4 * i + 1] = v.y; w[4 * i + 2] = v.z; w[4 * i + 3] = v.w;
-            sum += v.x + v.y + v.z + v.w;
+        for (int i = 0; i < CW / 2; ++i) {
+            const uint2 v = reinterpret_cast<const uint2*>(L.cnt32)[tid * (CW / 2) + i];
+            w[2 * i] = v.x; w[2 * i + 1] = v.y;
+            sum += v.x + v.y;
         }
         const uint32_t tot = (sum & 0xFFFFu) + (sum >> 16);
         uint32_t inc = tot;
@@ -192,8 +204,8 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
             run += l16 + h16;
         }
 #pragma unroll
-        for (int i = 0; i < CW / 4; ++i)
-            reinterpret_cast<uint4*>(L.cnt32)[tid * (CW / 4) + i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+        for (int i = 0; i < CW / 2; ++i)
+            reinterpret_cast<uint2*>(L.cnt32)[tid * (CW / 2) + i] = make_uint2(w[2 * i], w[2 * i + 1]);
         if (tid == 0) L.cnt32[kCntWords] = (uint32_t)m;         // start of the bucket past the last one
     }
     __syncthreads();
@@ -206,6 +218,14 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
         L.seg_start[tid] = a;
         if (tid == S - 1) L.seg_start[S] = m;
         L.cfull[tid] = stage_cost(L.recs[tid], (uint32_t)(b - a), lat_dag + tid * PARD_LAT_ENTRIES);
+        const StageRec& r = L.recs[tid];
+        L.quick[tid][0] = (uint32_t)r.B - 1u;
+        L.quick[tid][1] = __float_as_uint(r.rcpB);
+        L.quick[tid][2] = __float_as_uint(r.rcpW);
+        L.quick[tid][3] = r.aW;
+        L.quick[tid][4] = r.bW;
+        L.quick[tid][5] = (uint32_t)a;
+        if (!(r.mode & kStageFast)) L.slow_stages = 1u;
     }
     uint32_t se[G][4];                       // bucket start (13 bits) | bucket size - 1 (13 bits) | stage << 26
 #pragma unroll
@@ -226,9 +246,17 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     __syncthreads();
 
     // ---- 4. downstream maximum per stage over the path CSR ---------------------------
-    {
-        const int e_lo = P.dag_entry_ptr[dag], e_hi = P.dag_entry_ptr[dag + 1];
-        for (int e = e_lo + tid; e < e_hi; e += T) {
+    if (entries_cached && !wide) {
+        const uint32_t* ent = aux + S * PARD_LAT_ENTRIES;         // stage | (end of the entry's path) << 8
+        for (int e = tid; e < n_entries; e += T) {
+            const uint32_t me = ent[e];
+            const int end = (int)(me >> 8);
+            unsigned long long sum = 0;
+            for (int t = e + 1; t < end; ++t) sum += L.cfull[ent[t] & 0xFFu];
+            atomicMax(&L.down[me & 0xFFu], sum);
+        }
+    } else {
+        for (int e = e_lo + tid; e < e_lo + n_entries; e += T) {
             const int end = P.entry_end[e];
             unsigned long long sum = 0;
             for (int t = e + 1; t < end; ++t) sum += L.cfull[P.entry_stage[t]];
@@ -236,29 +264,47 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
         }
     }
     // ---- exact rank inside the bucket ----------------------------------------------------
+    if (!wide) {
+        // the first four bucket mates of every request in straight-line code (their LDS reads
+        // overlap; reads past the end of a short bucket are masked), longer buckets after that
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const int base = (g * T + tid) * 4;
+        for (int g = 0; g < G; ++g) {
+            uint32_t part[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (live(base + c)) {
-                const uint32_t s0 = se[g][c] & 0x1FFFu, e0 = s0 + ((se[g][c] >> 13) & 0x1FFFu) + 1u;
-                const uint32_t k = uk[g][c], me = (uint32_t)(base + c);
-                uint32_t less = 0;
-                if (e0 - s0 > 1) {
-                    if (!wide) {
-                        for (uint32_t j = s0; j < e0; j += 2) {          // two bucket mates per step
-                            const uint32_t a = L.low[j], b = L.low[j + 1];
-                            less += (a < k) + ((j + 1 < e0) & (b < k));
-                        }
-                    } else {
-                        for (uint32_t j = s0; j < e0; ++j) {
-                            const uint32_t kj = L.low[j], ij = L.idx[j];
-                            less += (kj < k) | ((kj == k) & (ij < me));
-                        }
-                    }
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t s0 = se[g][c] & 0x1FFFu, more = (se[g][c] >> 13) & 0x1FFFu;   // bucket size - 1
+                const uint32_t k = uk[g][c];
+                const uint32_t a0 = L.low[s0], a1 = L.low[s0 + 1], a2 = L.low[s0 + 2], a3 = L.low[s0 + 3];
+                part[c] = (uint32_t)(a0 < k) + (uint32_t)((more >= 1u) & (a1 < k)) +
+                          (uint32_t)((more >= 2u) & (a2 < k)) + (uint32_t)((more >= 3u) & (a3 < k));
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t s0 = se[g][c] & 0x1FFFu, more = (se[g][c] >> 13) & 0x1FFFu;
+                uint32_t less = part[c];
+                if (more >= 4u) {
+                    const uint32_t k = uk[g][c];
+                    for (uint32_t j = s0 + 4; j <= s0 + more; ++j) less += (uint32_t)(L.low[j] < k);
                 }
                 se[g][c] = (s0 + less) | (se[g][c] & 0xFC000000u);   // final queue slot | stage << 26
+            }
+        }
+    } else {
+        const int base0 = tid * 4;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (live(g * T * 4 + base0 + c)) {
+                    const uint32_t s0 = se[g][c] & 0x1FFFu, e0 = s0 + ((se[g][c] >> 13) & 0x1FFFu) + 1u;
+                    const uint32_t k = uk[g][c], me = (uint32_t)(g * T * 4 + base0 + c);
+                    uint32_t less = 0;
+                    for (uint32_t j = s0; j < e0; ++j) {
+                        const uint32_t kj = L.low[j], ij = L.idx[j];
+                        less += (uint32_t)((kj < k) | ((kj == k) & (ij < me)));
+                    }
+                    se[g][c] = (s0 + less) | (se[g][c] & 0xFC000000u);
+                }
             }
         }
     }
@@ -273,21 +319,40 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     }
 
     // ---- 5. estimate and drop decision, request order ---------------------------------
-    const int32_t now = A.now[u];
+    const bool quick = !wide && L.slow_stages == 0u;          // every stage admits the exact short-queue form
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
         int32_t est[4];
         uint8_t drp[4];
+        asm volatile("" ::: "memory");           // one group of four requests at a time (register pressure)
+        if (quick) {
+            // straight-line: stage_cost_short() with the per-stage constants and the latency table in LDS
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            est[c] = 0;
-            drp[c] = 0;
-            if (live(base + c)) {
-                const int k = (int)(se[g][c] >> 26);
-                const uint32_t pos = (se[g][c] & 0x1FFFu) - (uint32_t)L.seg_start[k];
-                const uint64_t e64 = stage_cost_short(L.recs[k], pos, lat_dag + k * PARD_LAT_ENTRIES) + L.down[k];
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t k = se[g][c] >> 26;
+                const uint4 qa = *reinterpret_cast<const uint4*>(&L.quick[k][0]);     // B-1, 1/B, 1/W, aW
+                const uint2 qb = *reinterpret_cast<const uint2*>(&L.quick[k][4]);     // bW, queue start
+                const unsigned long long dn = L.down[k];
+                const uint32_t pos = (se[g][c] & 0x1FFFu) - qb.y;
+                const uint32_t q = (uint32_t)(((float)(pos + qa.x) + 0.5f) * __uint_as_float(qa.y));
+                const uint32_t p = __umul24(q, qb.x);
+                const uint32_t wait = __umul24(q, qa.w) + (uint32_t)(((float)p + 0.5f) * __uint_as_float(qa.z));
+                const uint32_t seen = pos < qa.x ? pos : qa.x;
+                const uint64_t e64 = (uint64_t)wait + aux[k * PARD_LAT_ENTRIES + seen] + dn;
                 finish_request(e64, now, dl[g][c], est[c], drp[c]);
+            }
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                est[c] = 0;
+                drp[c] = 0;
+                if (live(base + c)) {
+                    const int k = (int)(se[g][c] >> 26);
+                    const uint32_t pos = (se[g][c] & 0x1FFFu) - (uint32_t)L.seg_start[k];
+                    const uint64_t cost = stage_cost_short(L.recs[k], pos, lat_dag + k * PARD_LAT_ENTRIES);
+                    finish_request(cost + L.down[k], now, dl[g][c], est[c], drp[c]);
+                }
             }
         }
         if (FULL || (aligned && base + 3 < m)) {
