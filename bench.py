@@ -30,6 +30,22 @@ def estimate_drop_bytes_per_request(fused: bool, passes: int, fcfs: bool) -> flo
     return float(io + 8 + 8 + 16 * (passes - 1) + 8 + 8)   # last +8: final pass writes pairs
 
 
+def recorded_traffic(workload_cfg: int, kernel: str, source: str):
+    """HBM bytes per launch of `kernel` taken from the committed rocprofv3 counter summary,
+    or None when there is none for this workload or the kernel source changed since."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{workload_cfg}.txt")
+    try:
+        sha = hashlib.sha256(open(os.path.join(ROOT, "paper_2602_08747_amd", "csrc", source), "rb").read()).hexdigest()[:16]
+        for line in open(path):
+            f = line.split()
+            if len(f) == 5 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel and f[3] == "source_sha256":
+                return int(f[2]) if f[4] == sha else None
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,8 +123,9 @@ def main():
     bpr = estimate_drop_bytes_per_request(fused, passes, fcfs)
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
+    traffic = recorded_traffic(args.config, "fused_snapshot_kernel", "pard_fused.hip") if fused and not args.permute else None
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4)}
 
     out = {
