@@ -10,7 +10,8 @@
 //             decoupled look-back over the tiles before it (single read + single write
 //             of the data per pass)
 //   epilogue  queue position = sorted position - queue offset; own-stage cost +
-//             downstream maximum; drop decision; est/drop scattered to request order.
+//             downstream maximum; drop decision; est|drop scattered to request order as one
+//             word, then unpacked by a streaming kernel.
 //
 // The sort key is the virtual integer  V = segment << kb | (key - min key)  where kb is
 // the number of bits of the key range; only ceil(bits(V)/8) passes run.  The segment id
@@ -269,12 +270,21 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         }
         if (lane == 0) { mm[0][wave] = a; mm[1][wave] = b; }
         if (segs <= kPartialSegs) {
-            // thread t: queue t % 64, every 16th workgroup starting at t / 64
+            // thread t: queue t % 64, workgroups t / 64, t / 64 + 16, ...; four loads in flight
             const int g = tid & (kPartialSegs - 1);
-            uint32_t v = 0;
-            if (g < segs)
-                for (int i = tid / kPartialSegs; i < A.stream_blocks; i += 1024 / kPartialSegs)
-                    v += A.part_cnt[(int64_t)i * kPartialSegs + g];
+            uint32_t v0 = 0, v1 = 0, v2 = 0, v3 = 0;
+            if (g < segs) {
+                const int step = 1024 / kPartialSegs;
+                int i = tid / kPartialSegs;
+                for (; i + 3 * step < A.stream_blocks; i += 4 * step) {
+                    v0 += A.part_cnt[(int64_t)i * kPartialSegs + g];
+                    v1 += A.part_cnt[(int64_t)(i + step) * kPartialSegs + g];
+                    v2 += A.part_cnt[(int64_t)(i + 2 * step) * kPartialSegs + g];
+                    v3 += A.part_cnt[(int64_t)(i + 3 * step) * kPartialSegs + g];
+                }
+                for (; i < A.stream_blocks; i += step) v0 += A.part_cnt[(int64_t)i * kPartialSegs + g];
+            }
+            const uint32_t v = v0 + v1 + v2 + v3;
             if (g < segs && v) atomicAdd(&A.seg_count[g], v);
         }
         __syncthreads();
@@ -557,11 +567,15 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
 }
 
 // ---- epilogue: positions -> estimates, drop decisions, queue order ------------------------
+// The estimate (31 bits, never negative) and the drop bit leave as ONE scattered 4-byte write
+// per request into the key buffer the last pass no longer needs; a streaming kernel then
+// unpacks that buffer into est[] and drop[] with coalesced accesses.
 __global__ __launch_bounds__(256) void epilogue_kernel(SortDev A) {
     const PlanDev& P = A.plan;
     const int last = ((int)A.params->passes - 1) & 1;
     const uint32_t* keys = A.key[last];
     const uint32_t* pays = A.pay[last];
+    uint32_t* packed = A.key[last ^ 1];
     const uint32_t umin = ~A.params->inv_min;
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -584,8 +598,29 @@ __global__ __launch_bounds__(256) void epilogue_kernel(SortDev A) {
         uint8_t drp;
         finish_request(e64, A.now[u], deadline, est, drp);
         A.order[j] = (int32_t)r;
-        A.est[r] = est;
-        A.drop[r] = drp;
+        if ((int64_t)r < A.n) packed[r] = (uint32_t)est | ((uint32_t)drp << 31);
+    }
+}
+
+__global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
+    const uint32_t* packed = A.key[(((int)A.params->passes - 1) & 1) ^ 1];
+    const bool vec = ((reinterpret_cast<uintptr_t>(A.est) & 15) | (reinterpret_cast<uintptr_t>(A.drop) & 3)) == 0;
+    const int64_t groups = (A.n + 3) / 4;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += stride) {
+        const int64_t r0 = g * 4;
+        if (vec && r0 + 3 < A.n) {
+            const uint4 v = *reinterpret_cast<const uint4*>(packed + r0);
+            *reinterpret_cast<int4*>(A.est + r0) = make_int4((int32_t)(v.x & 0x7FFFFFFFu), (int32_t)(v.y & 0x7FFFFFFFu),
+                                                             (int32_t)(v.z & 0x7FFFFFFFu), (int32_t)(v.w & 0x7FFFFFFFu));
+            *reinterpret_cast<uint32_t*>(A.drop + r0) = (v.x >> 31) | ((v.y >> 31) << 8) | ((v.z >> 31) << 16) | ((v.w >> 31) << 24);
+        } else {
+            for (int64_t r = r0; r < r0 + 4 && r < A.n; ++r) {
+                const uint32_t v = packed[r];
+                A.est[r] = (int32_t)(v & 0x7FFFFFFFu);
+                A.drop[r] = (uint8_t)(v >> 31);
+            }
+        }
     }
 }
 
@@ -667,6 +702,7 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             else sort_pass_kernel<false><<<(unsigned)pg, kSortThreads, 0, stream>>>(D, p);
         }
         epilogue_kernel<<<gb, 256, 0, stream>>>(D);
+        unpack_kernel<<<gb, 256, 0, stream>>>(D);
     }
     return hipGetLastError();
 }
