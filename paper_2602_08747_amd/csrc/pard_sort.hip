@@ -24,9 +24,9 @@ namespace {
 
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
-constexpr int kSortThreads = 256;
+constexpr int kSortThreads = 512;
 constexpr int kSortItems = 16;
-constexpr int kTile = kSortThreads * kSortItems;       // 4096 elements per tile
+constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxPasses = 8;
 constexpr uint32_t kFlagAggregate = 1u << 30;          // tile published its own count
@@ -393,8 +393,8 @@ __global__ __launch_bounds__(kScanThreads) void histogram_kernel(SortDev A) {
         if (h[i]) atomicAdd(&A.hist[i], h[i]);
 }
 
-// exclusive scan of one value per thread over a 256-thread workgroup
-__device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_t* tmp /*[4]*/, int tid) {
+// exclusive scan of one value per thread over the radix-pass workgroup
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* tmp /*[kSortWaves]*/, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
     uint32_t inc = v;
 #pragma unroll
@@ -412,7 +412,7 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_256(uint32_t v, uint32_
 
 // ---- one radix pass --------------------------------------------------------------------
 template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int pass) {
+__global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, int pass) {
     if (pass >= (int)A.params->passes) return;
 
     __shared__ uint32_t lds_key[kTile];
@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
     uint32_t* dst_key = A.key[pass & 1];
     uint32_t* dst_pay = A.pay[pass & 1];
     // first output slot of every digit: exclusive scan of this pass's global histogram
-    const uint32_t bin_base = block_exclusive_scan_256(A.hist[pass * kRadix + tid], scan_tmp, tid);
+    const uint32_t bin_base = block_exclusive_scan(tid < kRadix ? A.hist[pass * kRadix + tid] : 0u, scan_tmp, tid);
 
     // A tile may only wait for tiles that already run.  Workgroups are persistent and claim
     // tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, ... and hands them out
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
     const int64_t tile_base = tile * kTile;
     const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
 
-    // load (wave-striped: wave w owns elements [w*1024, (w+1)*1024) of the tile, item i lane l
+    // load (wave-striped: wave w owns 1024 consecutive elements of the tile, item i lane l
     // is element w*1024 + i*64 + l), rank every element among equal digits before it
     uint32_t key[kSortItems], pay[kSortItems], rd[kSortItems];   // rd = rank | digit << 16
 #pragma unroll
@@ -498,45 +498,52 @@ __global__ __launch_bounds__(kSortThreads) void sort_pass_kernel(SortDev A, int 
     }
     __syncthreads();
 
-    // per digit: offsets of each wave's run inside the tile, tile count, global offset
+    // per digit (threads 0..255): offsets of each wave's run inside the tile, tile count, global offset
     {
-        const int d = tid;                                   // kSortThreads == kRadix
+        const int d = tid & (kRadix - 1);
+        const bool digit_thread = tid < kRadix;
         uint32_t run = 0;
+        if (digit_thread) {
 #pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) {
-            const uint32_t t = whist[w][d];
-            whist[w][d] = run;
-            run += t;
+            for (int w = 0; w < kSortWaves; ++w) {
+                const uint32_t t = whist[w][d];
+                whist[w][d] = run;
+                run += t;
+            }
         }
         const uint32_t tile_cnt = run;
         uint32_t* st = A.tile_status + ((int64_t)pass * A.tiles + tile) * kRadix + d;
-        if (tile == 0)
-            __hip_atomic_store(st, kFlagInclusive | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else
-            __hip_atomic_store(st, kFlagAggregate | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const uint32_t tstart = block_exclusive_scan_256(tile_cnt, scan_tmp, tid);
-        tile_start[d] = tstart;
-        uint32_t excl = 0;
-        if (tile > 0) {
-            int64_t t = tile - 1;
-            uint32_t spins = 0;
-            while (true) {
-                const uint32_t v = __hip_atomic_load(A.tile_status + ((int64_t)pass * A.tiles + t) * kRadix + d,
-                                                     __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const uint32_t flag = v & ~kValueMask;
-                if (flag == 0) {
-                    if (++spins > kSpinLimit) { atomicOr(A.status_word, kStatusLookbackTimeout); break; }
-                    __builtin_amdgcn_s_sleep(2);
-                    continue;
-                }
-                excl += v & kValueMask;
-                if (flag == kFlagInclusive) break;
-                --t;                                          // tile 0 always publishes inclusive
-            }
-            __hip_atomic_store(st, kFlagInclusive | ((excl + tile_cnt) & kValueMask),
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (digit_thread) {
+            if (tile == 0)
+                __hip_atomic_store(st, kFlagInclusive | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            else
+                __hip_atomic_store(st, kFlagAggregate | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
-        gbase[d] = bin_base + excl - tstart;
+        const uint32_t tstart = block_exclusive_scan(tile_cnt, scan_tmp, tid);
+        if (digit_thread) {
+            tile_start[d] = tstart;
+            uint32_t excl = 0;
+            if (tile > 0) {
+                int64_t t = tile - 1;
+                uint32_t spins = 0;
+                while (true) {
+                    const uint32_t v = __hip_atomic_load(A.tile_status + ((int64_t)pass * A.tiles + t) * kRadix + d,
+                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint32_t flag = v & ~kValueMask;
+                    if (flag == 0) {
+                        if (++spins > kSpinLimit) { atomicOr(A.status_word, kStatusLookbackTimeout); break; }
+                        __builtin_amdgcn_s_sleep(2);
+                        continue;
+                    }
+                    excl += v & kValueMask;
+                    if (flag == kFlagInclusive) break;
+                    --t;                                          // tile 0 always publishes inclusive
+                }
+                __hip_atomic_store(st, kFlagInclusive | ((excl + tile_cnt) & kValueMask),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            gbase[d] = bin_base + excl - tstart;
+        }
     }
     __syncthreads();
 
