@@ -191,6 +191,7 @@ int pard_compact(const pard_plan_t* plan, int64_t n,
         workspace_bytes < kHeaderBytes + compact_workspace_bytes(n)) return PARD_E_WORKSPACE;
     CompactArgs a{};
     a.num_segments = plan->host.K * plan->host.S;
+    a.stages = plan->host.S;
     a.n = n;
     a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;

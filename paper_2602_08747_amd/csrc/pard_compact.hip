@@ -7,20 +7,26 @@
 // One pass over the data.  A workgroup counts the kept slots of a tile of 4096 queue slots,
 // publishes the count, and receives the number of kept slots in all earlier tiles from a
 // scan service: one wave of a helper workgroup walks the tile counts in order (64 tiles per
-// load, four loads in flight, running total in a register) and hands each tile its offset
+// load, eight loads in flight, running total in a register) and hands each tile its offset
 // as soon as the tiles up to it have published.  A waiting tile polls one word.  (A
 // look-back in which every waiting tile re-reads a window of predecessor words floods the
 // memory fabric with polling traffic when ~1500 tiles are resident.)
 //
+// A workgroup does not wait for the offset of the tile it has just counted: it parks that
+// tile's survivors in LDS, counts its next tile, and only then collects the offset and
+// writes the parked survivors out as one contiguous run.  The scan service therefore has a
+// whole tile's processing time to answer before anybody stalls on it.
+//
 // Tile order: a tile must only wait for tiles that already run.  Workgroups are persistent
 // and claim tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, y+32, ... and
 // hands them out in increasing order through its own counter; a workgroup uses pool
-// blockIdx % 16).  The lowest tile without an offset is then either running or next in line
-// in a pool whose workgroups have nothing unfinished left, and publishing a count never
-// waits, so every wait ends as long as 17 workgroups of the grid fit on the device.  A single
-// ticket counter would give the same order, but atomics on one address cost ~11 ns each here
-// (~95 us for 8192 tiles); 16 counters on separate cache lines run in parallel.  The first
-// workgroup of pool 0 to arrive becomes the helper.
+// blockIdx % 16).  The lowest tile without a published count is then either claimed (its
+// owner publishes it after at most finishing an earlier tile, whose offset is available) or
+// next in line in a pool whose workgroups only hold earlier tiles, so every wait ends as
+// long as the grid fits on the device.  A single ticket counter would give the same order,
+// but atomics on one address cost ~11 ns each here (~95 us for 8192 tiles); 16 counters on
+// separate cache lines run in parallel.  The first workgroup of pool 0 to arrive becomes the
+// helper.
 #include "pard_device.hpp"
 
 namespace pard {
@@ -29,45 +35,61 @@ namespace {
 
 constexpr int kCThreads = 256;
 constexpr int kCItems = 16;
-constexpr int kCTile = kCThreads * kCItems;
+constexpr int kCTile = kCThreads * kCItems;            // 4096 queue slots per tile
 constexpr int kCWaves = kCThreads / kWave;
 constexpr uint32_t kFlagReady = 1u << 31;              // word has been published
 constexpr uint32_t kValueMask = (1u << 30) - 1;
 constexpr uint32_t kSpinLimit = 1u << 22;
 constexpr int kPools = 16;                             // tile pools (see above)
-constexpr int kLook = 4;                               // groups of 64 tile counts the scan service requests per step
+constexpr int kLook = 8;                               // groups of 64 tile counts the scan service requests per step
 constexpr int kPoolStride = 64;                        // counters 256 bytes apart
+constexpr int kStageLds = 2 * kCTile + 256;            // bytes of LDS that stage a tile's slice of drop[]
+constexpr int kStageBytes = kStageLds - 32;            // widest request-id range staged in LDS
+constexpr int kStageChunks = (kStageLds / 16 + kCThreads - 1) / kCThreads;   // 16-byte chunks per thread
 
-__global__ void compact_zero_kernel(uint32_t* p, int64_t count) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// What a tile needs to know before it has seen its slots.
+struct TileInfo {
+    int32_t id_lo;      // the ids in the tile's slots lie in [id_lo, id_lo + id_span) ...
+    int32_t id_span;    // ... or 0 when that range is unknown or too wide to stage
+    int32_t g0, g1;     // queues g0 <= g < g1 start in this tile (their offsets are its to write)
+};
+
+// Zeroes the counters and tile words and tabulates TileInfo for every tile.
+//
+// Queue g = u * S + s holds requests of snapshot u only, and the requests of snapshot u are
+// the ids [seg_ptr[u*S], seg_ptr[(u+1)*S]) (snapshots are contiguous in the request arrays
+// and their queues contiguous in queue order), so the snapshots a tile overlaps bound its
+// ids.  The bound is only a hint: a slot whose id falls outside it is looked up in global
+// memory instead.
+__global__ void compact_prepare_kernel(uint32_t* words, int64_t count, const int32_t* seg_ptr, int32_t num_segments,
+                                       int32_t stages, int64_t n, TileInfo* info, int64_t tiles) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < count; i += stride) p[i] = 0;
-}
-
-// First index in [0, count) with a[i] >= value (count when there is none), found by one
-// whole wave: every step probes 64 evenly spaced entries, so 24k entries take 3 dependent
-// loads instead of 15.  All 64 lanes must call it together; all return the same result.
-__device__ __forceinline__ int64_t wave_lower_bound_i32(const int32_t* a, int64_t count, int64_t value, int lane) {
-    int64_t lo = 0, hi = count;
-    while (hi > lo) {
-        const int64_t chunk = (hi - lo + 63) >> 6;
-        int64_t idx = lo + (int64_t)(lane + 1) * chunk - 1;      // last entry of this lane's chunk
-        const bool in_range = idx - chunk + 1 < hi;              // the chunk is not empty
-        if (idx >= hi) idx = hi - 1;
-        const bool ge = in_range && (int64_t)a[idx] >= value;
-        const unsigned long long m = __ballot(ge);
-        if (m == 0ull) return hi;                                // every entry is smaller
-        const int f = __ffsll((long long)m) - 1;                 // first chunk whose last entry is >= value
-        const int64_t new_lo = lo + (int64_t)f * chunk;
-        int64_t new_hi = new_lo + chunk - 1;                     // that last entry is a valid answer
-        if (new_hi > hi - 1) new_hi = hi - 1;
-        if (chunk == 1) return new_lo;
-        lo = new_lo;
-        hi = new_hi;
-        // invariant: a[hi] >= value, answer in [lo, hi]; an empty [lo, hi) means the answer is hi
-        if (hi == lo) return lo;
+    for (int64_t j = i; j < count; j += stride) words[j] = 0;
+    for (int64_t t = i; t < tiles; t += stride) {
+        // first queue whose offset is >= the tile's first slot / >= the next tile's first slot
+        const int64_t ta = t * kCTile, tb = ta + kCTile;
+        int32_t la = 0, ha = num_segments + 1, lb = 0, hb = num_segments + 1;
+        while (la < ha || lb < hb) {
+            const int32_t ma = (int32_t)(((int64_t)la + ha) >> 1), mb = (int32_t)(((int64_t)lb + hb) >> 1);
+            const int64_t va = la < ha ? seg_ptr[ma] : 0, vb = lb < hb ? seg_ptr[mb] : 0;
+            if (la < ha) { if (va < ta) la = ma + 1; else ha = ma; }
+            if (lb < hb) { if (vb < tb) lb = mb + 1; else hb = mb; }
+        }
+        TileInfo ti;
+        ti.g0 = la;
+        ti.g1 = t + 1 == tiles ? num_segments + 1 : lb;       // the last tile also takes offsets equal to n
+        // queue holding the first slot, queue holding the last slot, their snapshots
+        int32_t x = (la <= num_segments && (int64_t)seg_ptr[la] == ta) ? la : la - 1;
+        int32_t y = lb - 1;
+        x = x < 0 ? 0 : (x > num_segments - 1 ? num_segments - 1 : x);
+        y = y < 0 ? 0 : (y > num_segments - 1 ? num_segments - 1 : y);
+        const int64_t lo = seg_ptr[(x / stages) * stages], hi = seg_ptr[(y / stages + 1) * stages];
+        const bool ok = lo >= 0 && hi > lo && hi <= n && hi - lo <= kStageBytes;
+        ti.id_lo = ok ? (int32_t)lo : 0;
+        ti.id_span = ok ? (int32_t)(hi - lo) : 0;
+        info[t] = ti;
     }
-    return lo;
 }
 
 // The scan service (one wave).  state[t] = ready | kept slots of tile t, written by the tile;
@@ -116,45 +138,10 @@ __device__ __forceinline__ void compact_scan_service(const uint32_t* state, uint
     }
 }
 
-// tile_state[0..tiles), tile_prefix[0..tiles): see the scan service; pool_ctr[y * kPoolStride]: next tile of
-// pool y; pool_ctr[kPools * kPoolStride]: arrival counter that elects the helper.  All zero at launch.
-__global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint32_t* tile_state, uint32_t* tile_prefix,
-                                                            uint32_t* pool_ctr, int64_t tiles, int pools,
-                                                            uint32_t* status_word) {
-    __shared__ __align__(16) uint16_t excl_l[kCTile + 8];   // kept slots of this tile before each slot
-    __shared__ uint32_t wave_tot[kCWaves];
-    __shared__ uint32_t s_excl;
-    __shared__ int64_t s_tile;
-    __shared__ int64_t g_range[2];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pool = (int)(blockIdx.x % (unsigned)pools);
-    if (tiles > 0 && pool == 0) {       // the first workgroup of pool 0 to arrive runs the scan service
-        if (tid == 0) s_excl = atomicAdd(&pool_ctr[kPools * kPoolStride], 1u);
-        __syncthreads();
-        const bool helper = s_excl == 0;
-        __syncthreads();
-        if (helper) {
-            if (wave == 0) compact_scan_service(tile_state, tile_prefix, tiles, lane, status_word);
-            return;
-        }
-    }
-
-    while (true) {
-    if (tid == 0)
-        s_tile = tiles > 0 ? (int64_t)atomicAdd(&pool_ctr[pool * kPoolStride], 1u) * pools + pool
-                           : (int64_t)blockIdx.x;          // no requests: one pass for the offsets
-    __syncthreads();
-    const int64_t tile = s_tile;
-    if (tile >= (tiles > 0 ? tiles : 1)) break;
-    const int64_t base = tile * kCTile;
-    const bool last = tile + 1 >= tiles;
-    const int64_t left = A.n - base;
-    const int valid = (int)(left < 0 ? 0 : (left < kCTile ? left : kCTile));
-    const bool vec = ((reinterpret_cast<uintptr_t>(A.order) | reinterpret_cast<uintptr_t>(A.surv_idx)) & 15) == 0;
-
-    // wave w owns slots [w*1024, (w+1)*1024) of the tile; load k covers 256 of them, 4 per lane
-    int32_t ids[4][4];
-    uint32_t keep[4], cnt[4];
+// 16 queue slots per thread: wave w owns slots [w*1024, (w+1)*1024) of the tile, load k covers
+// 256 of them, 4 consecutive slots per lane.  Slots past the end of the data read as -1.
+__device__ __forceinline__ void load_tile_ids(const CompactArgs& A, int64_t base, int valid, bool vec, int wave, int lane,
+                                              int32_t (&ids)[4][4]) {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int e = wave * 1024 + k * 256 + lane * 4;
@@ -166,98 +153,232 @@ __global__ __launch_bounds__(kCThreads) void compact_kernel(CompactArgs A, uint3
             for (int c = 0; c < 4; ++c) ids[k][c] = e + c < valid ? A.order[base + e + c] : -1;
         }
     }
+}
+
+// No requests: every queue offset is zero.
+__global__ void compact_empty_kernel(int32_t* surv_ptr, int32_t num_segments) {
+    for (int g = blockIdx.x * blockDim.x + threadIdx.x; g <= num_segments; g += gridDim.x * blockDim.x) surv_ptr[g] = 0;
+}
+
+struct CompactLds {
+    int32_t surv[kCTile + kWave];       // survivors of the tile counted last, parked until written out; + one dump word per lane
+    uint32_t group[kCTile / 4];         // same tile, per group of 4 slots: kept slots of the tile before it | keep bits << 13
+    __align__(16) uint8_t drop[kStageLds];   // the current tile's slice of drop[]
+    uint32_t wave_tot[kCWaves];
+    uint32_t excl;
+    int64_t tile;
+};
+
+// Writes out the parked tile: survivors as one contiguous run at the tile's global offset, and
+// the offsets of the queues that start inside it.
+__device__ __forceinline__ void write_parked_tile(const CompactArgs& A, CompactLds& L, const uint32_t* tile_prefix,
+                                                  int64_t ptile, uint32_t ptotal, int32_t g0, int32_t g1, int tid,
+                                                  uint32_t* status_word) {
+    const int64_t pbase = ptile * kCTile;
+    const int64_t pleft = A.n - pbase;
+    const int pvalid = (int)(pleft < kCTile ? pleft : kCTile);
+    if (tid == 0) {
+        uint32_t pv, spins = 0;
+        while (!((pv = __hip_atomic_load(&tile_prefix[ptile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kFlagReady)) {
+            if (++spins > kSpinLimit) { atomicOr(status_word, kStatusLookbackTimeout); break; }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        L.excl = pv & kValueMask;
+    }
+    __syncthreads();
+    const uint32_t off0 = L.excl;
+    for (uint32_t j = tid; j < ptotal; j += kCThreads) A.surv_idx[off0 + j] = L.surv[j];
+    for (int32_t g = g0 + tid; g < g1; g += kCThreads) {
+        int64_t p = (int64_t)A.seg_ptr[g] - pbase;
+        if (p < 0) p = 0;
+        uint32_t before = ptotal;
+        if (p < pvalid) {
+            const uint32_t v = L.group[p >> 2];
+            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
+        }
+        A.surv_ptr[g] = (int32_t)(off0 + before);
+    }
+}
+
+// tile_state[0..tiles), tile_prefix[0..tiles): see the scan service; pool_ctr[y * kPoolStride]: next tile of
+// pool y; pool_ctr[kPools * kPoolStride]: arrival counter that elects the helper.  All zero at launch.
+//
+// drop[] is indexed by request id.  When the tile's id range is known and narrow (TileInfo),
+// drop[id_lo .. id_lo + id_span) is fetched with coalesced 16-byte loads, at the same time as
+// the tile's slots, and the per-slot lookups become LDS reads; otherwise every slot costs a
+// global byte load.
+//
+// Per tile: count it, publish the count, and only then collect the offset of the tile counted
+// one round earlier and write that one out, so the scan service has had a whole round to
+// answer.
+__global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, uint32_t* tile_state, uint32_t* tile_prefix,
+                                                            uint32_t* pool_ctr, const TileInfo* info, int64_t tiles,
+                                                            int pools, uint32_t* status_word) {
+    __shared__ CompactLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pool = (int)(blockIdx.x % (unsigned)pools);
+    if (pool == 0) {                    // the first workgroup of pool 0 to arrive runs the scan service
+        if (tid == 0) L.excl = atomicAdd(&pool_ctr[kPools * kPoolStride], 1u);
+        __syncthreads();
+        const bool helper = L.excl == 0;
+        __syncthreads();
+        if (helper) {
+            if (wave == 0) compact_scan_service(tile_state, tile_prefix, tiles, lane, status_word);
+            return;
+        }
+    }
+    const bool vec = ((reinterpret_cast<uintptr_t>(A.order) | reinterpret_cast<uintptr_t>(A.surv_idx)) & 15) == 0;
+    const uintptr_t drop_addr = reinterpret_cast<uintptr_t>(A.drop);
+    const uintptr_t end_addr = drop_addr + (uintptr_t)A.n;
+
+    if (tid == 0) L.tile = (int64_t)atomicAdd(&pool_ctr[pool * kPoolStride], 1u) * pools + pool;
+    __syncthreads();
+    int64_t tile = L.tile;
+    int64_t prev_tile = -1;             // counted and parked, not yet written out
+    uint32_t prev_total = 0;
+    int32_t prev_g0 = 0, prev_g1 = 0;
+
+    while (tile < tiles) {
+    const int32_t tile_u = __builtin_amdgcn_readfirstlane((int32_t)tile);     // same in every lane: scalar loads below
+    const TileInfo ti = info[tile_u];
+    const int64_t base = (int64_t)tile_u * kCTile;
+    const int64_t left = A.n - base;
+    const int valid = (int)(left < kCTile ? left : kCTile);
+    int32_t ids[4][4];
+    load_tile_ids(A, base, valid, vec, wave, lane, ids);
+    uint32_t next_ticket = 0;
+    if (tid == 0) next_ticket = atomicAdd(&pool_ctr[pool * kPoolStride], 1u);
+    const bool staged = ti.id_span > 0;
+    uint32_t delta = 0;
+    if (staged) {
+        // 16-byte chunks at 16-byte aligned addresses from just below drop[id_lo]
+        const uintptr_t win = (drop_addr + (uint32_t)ti.id_lo) & ~(uintptr_t)15;
+        delta = (uint32_t)(drop_addr + (uint32_t)ti.id_lo - win);              // 0..15
+        const uint32_t chunks = (delta + (uint32_t)ti.id_span + 15u) >> 4;      // <= kStageLds / 16
+        uint4 chunk[kStageChunks];
+#pragma unroll
+        for (int q = 0; q < kStageChunks; ++q) {
+            const uint32_t c = (uint32_t)(q * kCThreads + tid);
+            const uintptr_t a = win + 16u * (uintptr_t)c;
+            uint4 v = make_uint4(0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u);
+            if (c < chunks) {
+                if (a >= drop_addr && a + 16 <= end_addr) {
+                    v = *reinterpret_cast<const uint4*>(a);
+                } else {                                         // chunk straddles an end of the array
+                    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+                    for (int b = 0; b < 16; ++b) {
+                        const uintptr_t ab = a + b;
+                        if (ab >= drop_addr && ab < end_addr) {
+                            const uint32_t byte = *reinterpret_cast<const uint8_t*>(ab);
+                            w[b >> 2] = (w[b >> 2] & ~(0xFFu << (8 * (b & 3)))) | (byte << (8 * (b & 3)));
+                        }
+                    }
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            chunk[q] = v;
+        }
+#pragma unroll
+        for (int q = 0; q < kStageChunks; ++q) {
+            const uint32_t c = (uint32_t)(q * kCThreads + tid);
+            if (c < chunks) *reinterpret_cast<uint4*>(L.drop + 16u * c) = chunk[q];
+        }
+    }
+    __syncthreads();
+
+    // ---- count this tile ----
+    uint32_t keep[4];
+    bool slow = !staged;                // some slot of this thread needs a global lookup
+    if (staged) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            keep[k] = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t d = (uint32_t)ids[k][c] - (uint32_t)ti.id_lo;
+                const bool in = d < (uint32_t)ti.id_span;
+                const uint32_t byte = L.drop[delta + (in ? d : 0u)];
+                keep[k] |= (uint32_t)(in && byte == 0) << c;
+                slow |= !in;
+            }
+        }
+    }
+    if (slow) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            keep[k] = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t r = (uint32_t)ids[k][c];
+                if ((int64_t)r < A.n && A.drop[r] == 0) keep[k] |= 1u << c;
+            }
+        }
+    }
+    // Kept slots before each of this lane's four groups inside the wave's 1024 slots: one scan
+    // for all four loads, their counts packed into bytes.  The scan runs over the counts shifted
+    // up by one lane, so every partial sum is an exclusive count (<= 252 fits a byte).
+    const uint32_t cnt = (uint32_t)__popc(keep[0]) | ((uint32_t)__popc(keep[1]) << 8) |
+                         ((uint32_t)__popc(keep[2]) << 16) | ((uint32_t)__popc(keep[3]) << 24);
+    uint32_t exc = __shfl_up(cnt, 1);
+    if (lane == 0) exc = 0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(exc, off);
+        if (lane >= off) exc += t;
+    }
+    const uint32_t e63 = (uint32_t)__builtin_amdgcn_readlane((int)exc, 63), c63 = (uint32_t)__builtin_amdgcn_readlane((int)cnt, 63);
+    uint32_t load_tot[4], load_before[4], wave_total = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const int e = wave * 1024 + k * 256 + lane * 4;
-        keep[k] = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t r = (uint32_t)ids[k][c];
-            if (e + c < valid && (int64_t)r < A.n && A.drop[r] == 0) keep[k] |= 1u << c;
-        }
-        cnt[k] = (uint32_t)__popc(keep[k]);
+        load_tot[k] = ((e63 >> (8 * k)) & 0xFFu) + ((c63 >> (8 * k)) & 0xFFu);
+        load_before[k] = wave_total;
+        wave_total += load_tot[k];
     }
-    // kept slots before this lane's group of 4, inside the wave's 1024 slots
-    uint32_t before[4];
-    uint32_t carry = 0;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        uint32_t inc = cnt[k];
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const uint32_t t = __shfl_up(inc, off);
-            if (lane >= off) inc += t;
-        }
-        before[k] = carry + inc - cnt[k];
-        carry += __shfl(inc, 63);
-    }
-    if (lane == 0) wave_tot[wave] = carry;
-    if (wave == kCWaves - 1) {          // queues whose offset falls into this tile
-        const int64_t g0 = wave_lower_bound_i32(A.seg_ptr, (int64_t)A.num_segments + 1, base, lane);
-        if (lane == 0) g_range[0] = g0;
-    } else if (wave == kCWaves - 2) {
-        const int64_t g1 = last ? (int64_t)A.num_segments + 1
-                                : wave_lower_bound_i32(A.seg_ptr, (int64_t)A.num_segments + 1, base + kCTile, lane);
-        if (lane == 0) g_range[1] = g1;
-    }
+    if (lane == 0) L.wave_tot[wave] = wave_total;
     __syncthreads();
     uint32_t wave_before = 0, total = 0;
 #pragma unroll
     for (int w = 0; w < kCWaves; ++w) {
-        const uint32_t t = wave_tot[w];
+        const uint32_t t = L.wave_tot[w];
         if (w < wave) wave_before += t;
         total += t;
     }
+    if (tid == 0)
+        __hip_atomic_store(&tile_state[tile_u], kFlagReady | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-    // kept slots in all earlier tiles: publish this tile's count, poll its offset later
-    if (tid == 0 && tiles > 0)
-        __hip_atomic_store(&tile_state[tile], kFlagReady | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // meanwhile: per-slot counts for the queue offsets
+    // ---- write out the tile counted in the previous round, then park this one ----
+    if (prev_tile >= 0) {
+        write_parked_tile(A, L, tile_prefix, prev_tile, prev_total, prev_g0, prev_g1, tid, status_word);
+        __syncthreads();
+    }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const int e = wave * 1024 + k * 256 + lane * 4;
-        const uint32_t b0 = wave_before + before[k];
-        const uint32_t b1 = b0 + (keep[k] & 1u), b2 = b1 + ((keep[k] >> 1) & 1u), b3 = b2 + ((keep[k] >> 2) & 1u);
-        *reinterpret_cast<uint2*>(excl_l + e) = make_uint2(b0 | (b1 << 16), b2 | (b3 << 16));
-    }
-    if (tid == 0) {
-        excl_l[kCTile] = (uint16_t)total;
-        uint32_t pv = kFlagReady;
-        if (tiles > 0) {
-            uint32_t spins = 0;
-            while (!((pv = __hip_atomic_load(&tile_prefix[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kFlagReady)) {
-                if (++spins > kSpinLimit) { atomicOr(status_word, kStatusLookbackTimeout); break; }
-                __builtin_amdgcn_s_sleep(2);
-            }
+        const uint32_t o = wave_before + load_before[k] + ((exc >> (8 * k)) & 0xFFu);
+        L.group[wave * 256 + k * 64 + lane] = o | (keep[k] << 13);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const bool kept = (keep[k] >> c) & 1u;
+            const uint32_t at = kept ? o + (uint32_t)__popc(keep[k] & ((1u << c) - 1u)) : (uint32_t)(kCTile + lane);
+            L.surv[at] = ids[k][c];
         }
-        s_excl = pv & kValueMask;
     }
+    if (tid == 0) L.tile = (int64_t)next_ticket * pools + pool;
     __syncthreads();
-    const uint32_t off0 = s_excl;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        uint32_t o = off0 + wave_before + before[k];
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-            if (keep[k] & (1u << c)) { A.surv_idx[o] = ids[k][c]; ++o; }
+    prev_tile = tile_u;
+    prev_total = total;
+    prev_g0 = ti.g0;
+    prev_g1 = ti.g1;
+    tile = L.tile;
     }
-    // queue offsets that fall into this tile (the last tile also takes those equal to n)
-    for (int64_t g = g_range[0] + tid; g < g_range[1]; g += kCThreads) {
-        int64_t p = (int64_t)A.seg_ptr[g] - base;
-        if (p < 0) p = 0;
-        if (p > valid) p = valid;
-        A.surv_ptr[g] = (int32_t)(off0 + (p >= valid ? total : (uint32_t)excl_l[p]));
-    }
-    __syncthreads();                    // LDS is reused by the next tile
-    if (tiles == 0) break;
-    }
+    if (prev_tile >= 0) write_parked_tile(A, L, tile_prefix, prev_tile, prev_total, prev_g0, prev_g1, tid, status_word);
 }
 
 }  // namespace
 
 int64_t compact_workspace_bytes(int64_t n) {
     const int64_t tiles = (n + kCTile - 1) / kCTile;
-    return (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255);
+    return (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255) +
+           (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255);
 }
 
 int compact_blocks_per_cu() {
@@ -271,20 +392,25 @@ int compact_blocks_per_cu() {
 
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     const int64_t tiles = (a.n + kCTile - 1) / kCTile;
+    if (tiles == 0) {
+        compact_empty_kernel<<<(a.num_segments + 256) / 256, 256, 0, stream>>>(a.surv_ptr, a.num_segments);
+        return hipGetLastError();
+    }
     uint32_t* pool_ctr = static_cast<uint32_t*>(a.workspace);
     const int64_t row = ((tiles + 1) * 4 + 255) / 256 * 64;          // words per array, 256-byte multiple
     uint32_t* tile_state = pool_ctr + (kPools + 1) * kPoolStride;
     uint32_t* tile_prefix = tile_state + row;
+    TileInfo* info = reinterpret_cast<TileInfo*>(tile_prefix + row);
     const int64_t words = (int64_t)(kPools + 1) * kPoolStride + 2 * row;
-    int zb = (int)((words + 255) / 256);
+    const int64_t work = words > tiles ? words : tiles;
+    int zb = (int)((work + 255) / 256);
     if (zb > 1024) zb = 1024;
-    compact_zero_kernel<<<zb, 256, 0, stream>>>(pool_ctr, words);
-    int64_t grid = a.resident_blocks > 0 ? a.resident_blocks : 1;     // persistent: what the device holds at once
-    if (grid > tiles) grid = tiles;
-    if (grid < 1) grid = 1;
-    const int pools = grid < kPools ? (int)grid : kPools;                 // pool 0 then holds at least two workgroups
-    if (tiles > 0) grid += 1;                                             // one workgroup becomes the scan service
-    compact_kernel<<<(unsigned)grid, kCThreads, 0, stream>>>(a, tile_state, tile_prefix, pool_ctr, tiles, pools, a.status);
+    compact_prepare_kernel<<<zb, 256, 0, stream>>>(pool_ctr, words, a.seg_ptr, a.num_segments, a.stages, a.n, info, tiles);
+    // persistent: no more workgroups than the device holds at once, one of them the scan service
+    int64_t grid = a.resident_blocks > 2 ? a.resident_blocks : 2;
+    if (grid > tiles + 1) grid = tiles + 1;
+    const int pools = grid - 1 < kPools ? (int)(grid - 1) : kPools;       // pool 0 holds the helper and at least one worker
+    compact_kernel<<<(unsigned)grid, kCThreads, 0, stream>>>(a, tile_state, tile_prefix, pool_ctr, info, tiles, pools, a.status);
     return hipGetLastError();
 }
 

@@ -135,6 +135,7 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
 
 struct CompactArgs {
     int32_t num_segments;              // K*S
+    int32_t stages;                    // S
     int64_t n;
     const int32_t *order, *seg_ptr;
     const uint8_t* drop;

@@ -209,6 +209,35 @@ def test_compact_with_arbitrary_masks(gpu, oracle_mod):
         assert np.array_equal(got["surv_ptr"], want_ptr) and np.array_equal(got["surv_idx"], want_idx)
 
 
+@pytest.mark.parametrize("cfg,kw", [(5, dict(n_snapshots=7, per_snapshot=8192)), (5, dict(n_snapshots=5, per_snapshot=5000)),
+                                     (4, dict(n_requests=150001))])
+def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw):
+    """Buffers that start at odd byte offsets (views into larger allocations) give the same survivors."""
+    import torch
+    w = wl.make_workload(cfg, permute=True, **kw)
+    s, ref = check(gpu, oracle_mod, w)
+    rng = np.random.default_rng(21)
+    mask = (rng.random(w.n) < 0.4).astype(np.uint8)
+    want_idx, want_ptr = oracle_mod.compact(w.K, w.S, ref["order"], ref["seg_ptr"], mask)
+    n = w.n
+    for off_drop, off_idx in ((3, 1), (13, 3), (16, 2)):
+        drop_big = torch.ones(n + 64, dtype=torch.uint8, device=s.dev)
+        drop = drop_big[off_drop:off_drop + n]
+        drop.copy_(torch.from_numpy(mask).to(s.dev))
+        order_big = torch.zeros(n + 16, dtype=torch.int32, device=s.dev)
+        order = order_big[off_idx:off_idx + n]
+        order.copy_(s.order)
+        surv_big = torch.full((n + 16,), -7, dtype=torch.int32, device=s.dev)
+        surv = surv_big[off_idx:off_idx + n]
+        gpu.pard_compact(s.plan, n, order, s.seg_ptr, drop, surv, s.surv_ptr, s.workspace)
+        torch.cuda.synchronize()
+        got_ptr = s.surv_ptr.cpu().numpy()
+        assert np.array_equal(got_ptr, want_ptr)
+        assert np.array_equal(surv.cpu().numpy()[:want_ptr[-1]], want_idx)
+        sb = surv_big.cpu().numpy()
+        assert (sb[:off_idx] == -7).all() and (sb[off_idx + want_ptr[-1]:] == -7).all()   # nothing written outside
+
+
 def test_repeatable_and_stream(gpu, oracle_mod):
     import torch
     w = wl.make_workload(4, n_requests=300000, permute=True)
