@@ -160,13 +160,22 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
  * Drop-mask stream compaction: the survivor queues that go on to batching (Section 4.1,
  * the Request Broker keeps or drops each request; kept requests form the next batches).
  *
+ *   max_snapshot_requests  promised upper bound on the requests of one snapshot, as for
+ *                          pard_estimate_drop: up to PARD_FUSED_SNAPSHOT_CAPACITY every
+ *                          snapshot is compacted by one workgroup, above it the queues are
+ *                          compacted as one stream.  A snapshot that breaks a promised
+ *                          bound of at most PARD_FUSED_SNAPSHOT_CAPACITY raises bit 0 of the
+ *                          status word; the outputs are then unspecified (never out of bounds)
  *   d_order, d_seg_ptr     as written by pard_estimate_drop
- *   d_drop                 device uint8[n], request order
+ *   d_drop                 device uint8[n], request order; zero = keep, anything else = drop
  *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests
  *                          removed, same order; entries past surv_ptr[K*S] are untouched
  *   d_surv_ptr             device out int32[K*S+1] offsets of the survivor queues
+ *
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE (n < 0, n >= 2^30, negative bound),
+ * PARD_E_WORKSPACE, PARD_E_HIP.
  */
-int pard_compact(const pard_plan_t* plan, int64_t n,
+int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
                  const int32_t* d_order, const int32_t* d_seg_ptr, const uint8_t* d_drop,
                  int32_t* d_surv_idx, int32_t* d_surv_ptr,
                  void* d_workspace, int64_t workspace_bytes, void* stream);

@@ -56,7 +56,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_plan_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
     lib.pard_workspace_bytes.argtypes = [vp, i64, i64, ctypes.POINTER(i64)]
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
-    lib.pard_compact.argtypes = [vp, i64] + [vp] * 5 + [vp, i64, vp]
+    lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.pard_strerror.argtypes = [ctypes.c_int]
@@ -152,11 +152,12 @@ def pard_estimate_drop(plan: Plan, n: int, max_snapshot_requests: int, arrival, 
     return rc
 
 
-def pard_compact(plan: Plan, n: int, order, seg_ptr, drop, surv_idx, surv_ptr, workspace, stream=None,
-                 check: bool = True) -> int:
+def pard_compact(plan: Plan, n: int, max_snapshot_requests: int, order, seg_ptr, drop, surv_idx, surv_ptr, workspace,
+                 stream=None, check: bool = True) -> int:
     """Enqueues the survivor-compaction kernels on `stream`."""
     rc = load_library().pard_compact(
-        plan.handle, int(n), _ptr(order), _ptr(seg_ptr), _ptr(drop), _ptr(surv_idx), _ptr(surv_ptr),
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(order), _ptr(seg_ptr), _ptr(drop), _ptr(surv_idx),
+        _ptr(surv_ptr),
         _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_compact")
@@ -195,7 +196,7 @@ class Session:
                            self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
 
     def compact(self, stream=None):
-        pard_compact(self.plan, self.n, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
+        pard_compact(self.plan, self.n, self.max_snap, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
                      self.workspace, stream)
 
     def run(self, stream=None):

@@ -23,7 +23,7 @@ constexpr int64_t kHeaderBytes = 256;      // workspace header: word 0 = status 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
 int64_t workspace_need(const pard_plan* p, int64_t n, int64_t max_snap) {
-    int64_t need = compact_workspace_bytes(n);
+    int64_t need = compact_workspace_bytes(n, p->host.K);
     if (max_snap > PARD_FUSED_SNAPSHOT_CAPACITY) {
         int64_t s = sort_workspace_bytes(p->host.K, p->host.S, n);
         if (s > need) need = s;
@@ -180,18 +180,19 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
-int pard_compact(const pard_plan_t* plan, int64_t n,
+int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
                  const int32_t* d_order, const int32_t* d_seg_ptr, const uint8_t* d_drop,
                  int32_t* d_surv_idx, int32_t* d_surv_ptr,
                  void* d_workspace, int64_t workspace_bytes, void* stream) {
     if (!plan || !d_seg_ptr || !d_surv_ptr) return PARD_E_NULL;
-    if (n < 0 || n >= ((int64_t)1 << 30)) return PARD_E_BAD_SHAPE;
+    if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (n > 0 && (!d_order || !d_drop || !d_surv_idx)) return PARD_E_NULL;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
-        workspace_bytes < kHeaderBytes + compact_workspace_bytes(n)) return PARD_E_WORKSPACE;
+        workspace_bytes < kHeaderBytes + compact_workspace_bytes(n, plan->host.K)) return PARD_E_WORKSPACE;
     CompactArgs a{};
     a.num_segments = plan->host.K * plan->host.S;
     a.stages = plan->host.S;
+    a.max_snapshot = max_snapshot_requests;
     a.n = n;
     a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;

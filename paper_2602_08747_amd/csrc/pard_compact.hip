@@ -373,12 +373,237 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
     if (prev_tile >= 0) write_parked_tile(A, L, tile_prefix, prev_tile, prev_total, prev_g0, prev_g1, tid, status_word);
 }
 
+// =====================================================================================
+// Snapshots that fit one workgroup (at most kLCap queue slots each): no offset chain at all.
+//
+// The queue slots of snapshot u, [seg_ptr[u*S], seg_ptr[(u+1)*S]), hold exactly the request
+// ids of the same range (snapshots are contiguous in the request arrays and order[] permutes
+// inside a snapshot), so the number of survivors of a snapshot is the number of zero bytes
+// in that range of drop[] - a contiguous read that needs neither order[] nor a scan over
+// tiles.  A first kernel counts them per snapshot; the main kernel gives every snapshot to
+// one workgroup, which adds up the counts of the snapshots before it and then works alone.
+// =====================================================================================
+constexpr int kLThreads = 512;
+constexpr int kLWaves = kLThreads / kWave;
+constexpr int kLCap = kLThreads * 16;                  // queue slots one workgroup handles
+constexpr int kDirectSumSnapshots = 8192;              // up to here every workgroup adds up the counts before it itself
+static_assert(kLCap == PARD_FUSED_SNAPSHOT_CAPACITY, "per-snapshot compaction covers the on-chip snapshot size");
+
+// number of zero bytes in a word
+__device__ __forceinline__ uint32_t zero_bytes(uint32_t w) {
+    const uint32_t t = (w & 0x7F7F7F7Fu) + 0x7F7F7F7Fu;         // bit 7 of a byte: its low 7 bits are not all zero
+    return (uint32_t)__popc(~(t | w | 0x7F7F7F7Fu));             // bit 7 set only where the whole byte is zero
+}
+
+// Slot range of snapshot u; false when it breaks the promised bound or the array limits.
+__device__ __forceinline__ bool snapshot_range(const int32_t* seg_ptr, int64_t u, int32_t stages, int64_t n,
+                                               int64_t& a, int64_t& b) {
+    a = seg_ptr[u * stages];
+    b = seg_ptr[(u + 1) * stages];
+    return a >= 0 && b >= a && b <= n && b - a <= kLCap;
+}
+
+__global__ __launch_bounds__(256) void snapshot_kept_kernel(const int32_t* seg_ptr, int32_t stages, int64_t n,
+                                                            const uint8_t* drop, uint32_t* kept, uint32_t* status_word) {
+    __shared__ uint32_t part[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t u = blockIdx.x;
+    int64_t a, b;
+    if (!snapshot_range(seg_ptr, u, stages, n, a, b)) {
+        if (tid == 0) { atomicOr(status_word, kStatusSnapshotTooLarge); kept[u] = 0; }
+        return;
+    }
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(drop) + (uintptr_t)a, hi = reinterpret_cast<uintptr_t>(drop) + (uintptr_t)b;
+    const uintptr_t win = lo & ~(uintptr_t)15;
+    const uint32_t chunks = (uint32_t)((hi - win + 15) >> 4);
+    uint32_t cnt = 0;
+    for (uint32_t c = tid; c < chunks; c += 256) {
+        const uintptr_t at = win + 16u * (uintptr_t)c;
+        if (at >= lo && at + 16 <= hi) {
+            const uint4 v = *reinterpret_cast<const uint4*>(at);
+            cnt += zero_bytes(v.x) + zero_bytes(v.y) + zero_bytes(v.z) + zero_bytes(v.w);
+        } else {
+            for (int i = 0; i < 16; ++i)
+                if (at + i >= lo && at + i < hi) cnt += *reinterpret_cast<const uint8_t*>(at + i) == 0 ? 1u : 0u;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if (lane == 0) part[wave] = cnt;
+    __syncthreads();
+    if (tid == 0) kept[u] = part[0] + part[1] + part[2] + part[3];
+}
+
+// Exclusive scan of kept[0..count) by one workgroup (only for very many snapshots).
+__global__ __launch_bounds__(1024) void snapshot_offsets_kernel(const uint32_t* kept, int64_t count, uint32_t* snap_off) {
+    __shared__ uint32_t wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t per = (count + 1023) / 1024;
+    const int64_t lo = tid * per, hi = lo + per < count ? lo + per : count;
+    uint32_t sum = 0;
+    for (int64_t i = lo; i < hi; ++i) sum += kept[i];
+    uint32_t inc = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    uint32_t run = inc - sum;
+    for (int w = 0; w < wave; ++w) run += wave_tot[w];
+    for (int64_t i = lo; i < hi; ++i) { snap_off[i] = run; run += kept[i]; }
+}
+
+struct LocalLds {
+    uint32_t group[kLCap / 4];          // per group of 4 slots: kept slots of the snapshot before it | keep bits << 13
+    __align__(16) uint8_t drop[kLCap + 32];
+    uint32_t wave_tot[kLWaves];
+    uint32_t wave_off[kLWaves];
+};
+
+__global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs A, const uint32_t* kept, const uint32_t* snap_off) {
+    __shared__ LocalLds L;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t u = blockIdx.x;
+    int64_t a, b;
+    if (!snapshot_range(A.seg_ptr, u, A.stages, A.n, a, b)) return;     // reported by the counting kernel
+    const int size = (int)(b - a);
+
+    // this snapshot's slots: wave w owns [w*1024, (w+1)*1024), load k covers 256 of them, 4 per lane
+    const int32_t* slots = A.order + a;
+    const bool vec = (reinterpret_cast<uintptr_t>(slots) & 15) == 0;
+    int32_t ids[4][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = wave * 1024 + k * 256 + lane * 4;
+        if (vec && e + 3 < size) {
+            const int4 v = *reinterpret_cast<const int4*>(slots + e);
+            ids[k][0] = v.x; ids[k][1] = v.y; ids[k][2] = v.z; ids[k][3] = v.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) ids[k][c] = e + c < size ? slots[e + c] : -1;
+        }
+    }
+    // its slice of drop[]: 16-byte chunks at 16-byte aligned addresses from just below drop[a]
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(A.drop) + (uintptr_t)a, hi = reinterpret_cast<uintptr_t>(A.drop) + (uintptr_t)b;
+    const uintptr_t win = lo & ~(uintptr_t)15;
+    const uint32_t delta = (uint32_t)(lo - win);
+    const uint32_t chunks = (uint32_t)((hi - win + 15) >> 4);              // <= kLCap / 16 + 2
+    for (uint32_t c = tid; c < chunks; c += kLThreads) {
+        const uintptr_t at = win + 16u * (uintptr_t)c;
+        uint4 v;
+        if (at >= lo && at + 16 <= hi) {
+            v = *reinterpret_cast<const uint4*>(at);
+        } else {
+            uint32_t w[4] = {0x01010101u, 0x01010101u, 0x01010101u, 0x01010101u};
+            for (int i = 0; i < 16; ++i)
+                if (at + i >= lo && at + i < hi) {
+                    const uint32_t byte = *reinterpret_cast<const uint8_t*>(at + i);
+                    w[i >> 2] = (w[i >> 2] & ~(0xFFu << (8 * (i & 3)))) | (byte << (8 * (i & 3)));
+                }
+            v = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        *reinterpret_cast<uint4*>(L.drop + 16u * c) = v;
+    }
+    // survivors of the snapshots before this one
+    uint32_t before_me = 0;
+    if (snap_off) {
+        before_me = tid == 0 ? snap_off[u] : 0u;
+    } else {
+        for (int64_t v = tid; v < u; v += kLThreads) before_me += kept[v];
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) before_me += __shfl_xor(before_me, off);
+    if (lane == 0) L.wave_off[wave] = before_me;
+    __syncthreads();
+
+    uint32_t keep[4];
+    bool slow = false;                  // an id outside the snapshot's range: look it up in global memory
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        keep[k] = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t d = (uint32_t)ids[k][c] - (uint32_t)a;
+            const bool in = d < (uint32_t)size;
+            const uint32_t byte = L.drop[delta + (in ? d : 0u)];
+            keep[k] |= (uint32_t)(in && byte == 0) << c;
+            slow |= !in && ids[k][c] != -1;
+        }
+    }
+    if (slow) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            keep[k] = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t r = (uint32_t)ids[k][c];
+                if ((int64_t)r < A.n && A.drop[r] == 0) keep[k] |= 1u << c;
+            }
+        }
+    }
+    // one scan for all four loads: counts packed into bytes, shifted up one lane so that every
+    // partial sum is an exclusive count (<= 252)
+    const uint32_t cnt = (uint32_t)__popc(keep[0]) | ((uint32_t)__popc(keep[1]) << 8) |
+                         ((uint32_t)__popc(keep[2]) << 16) | ((uint32_t)__popc(keep[3]) << 24);
+    uint32_t exc = __shfl_up(cnt, 1);
+    if (lane == 0) exc = 0;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(exc, off);
+        if (lane >= off) exc += t;
+    }
+    const uint32_t e63 = (uint32_t)__builtin_amdgcn_readlane((int)exc, 63), c63 = (uint32_t)__builtin_amdgcn_readlane((int)cnt, 63);
+    uint32_t load_before[4], wave_total = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        load_before[k] = wave_total;
+        wave_total += ((e63 >> (8 * k)) & 0xFFu) + ((c63 >> (8 * k)) & 0xFFu);
+    }
+    if (lane == 0) L.wave_tot[wave] = wave_total;
+    __syncthreads();
+    uint32_t wave_before = 0, total = 0, off0 = 0;
+#pragma unroll
+    for (int w = 0; w < kLWaves; ++w) {
+        const uint32_t t = L.wave_tot[w];
+        if (w < wave) wave_before += t;
+        total += t;
+        off0 += L.wave_off[w];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        uint32_t o = wave_before + load_before[k] + ((exc >> (8 * k)) & 0xFFu);
+        L.group[wave * 256 + k * 64 + lane] = o | (keep[k] << 13);
+        o += off0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep[k] & (1u << c)) { A.surv_idx[o] = ids[k][c]; ++o; }
+    }
+    __syncthreads();
+    // offsets of this snapshot's queues (the last snapshot also writes the end offset)
+    const int count = A.stages + (u + 1 == gridDim.x ? 1 : 0);
+    for (int j = tid; j < count; j += kLThreads) {
+        const int64_t g = u * A.stages + j;
+        int64_t p = (int64_t)A.seg_ptr[g] - a;
+        if (p < 0) p = 0;
+        uint32_t before = total;
+        if (p < size) {
+            const uint32_t v = L.group[p >> 2];
+            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
+        }
+        A.surv_ptr[g] = (int32_t)(off0 + before);
+    }
+}
+
 }  // namespace
 
-int64_t compact_workspace_bytes(int64_t n) {
+int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots) {
     const int64_t tiles = (n + kCTile - 1) / kCTile;
-    return (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255) +
-           (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255);
+    const int64_t chain = (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255) +
+                          (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255);
+    const int64_t local = 2 * ((num_snapshots * 4 + 255) & ~(int64_t)255);
+    return chain > local ? chain : local;
 }
 
 int compact_blocks_per_cu() {
@@ -394,6 +619,15 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     const int64_t tiles = (a.n + kCTile - 1) / kCTile;
     if (tiles == 0) {
         compact_empty_kernel<<<(a.num_segments + 256) / 256, 256, 0, stream>>>(a.surv_ptr, a.num_segments);
+        return hipGetLastError();
+    }
+    if (a.max_snapshot <= kLCap) {      // every snapshot fits one workgroup
+        const int64_t K = a.num_segments / a.stages;
+        uint32_t* kept = static_cast<uint32_t*>(a.workspace);
+        uint32_t* snap_off = kept + ((K * 4 + 255) & ~(int64_t)255) / 4;
+        snapshot_kept_kernel<<<(unsigned)K, 256, 0, stream>>>(a.seg_ptr, a.stages, a.n, a.drop, kept, a.status);
+        if (K > kDirectSumSnapshots) snapshot_offsets_kernel<<<1, 1024, 0, stream>>>(kept, K, snap_off);
+        compact_local_kernel<<<(unsigned)K, kLThreads, 0, stream>>>(a, kept, K > kDirectSumSnapshots ? snap_off : nullptr);
         return hipGetLastError();
     }
     uint32_t* pool_ctr = static_cast<uint32_t*>(a.workspace);

@@ -136,6 +136,7 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
 struct CompactArgs {
     int32_t num_segments;              // K*S
     int32_t stages;                    // S
+    int64_t max_snapshot;              // promised bound on a snapshot's size
     int64_t n;
     const int32_t *order, *seg_ptr;
     const uint8_t* drop;
@@ -145,7 +146,7 @@ struct CompactArgs {
     int32_t resident_blocks;           // workgroups of the compaction kernel the device holds at once
 };
 int compact_blocks_per_cu();
-int64_t compact_workspace_bytes(int64_t n);
+int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
 
 }  // namespace pard

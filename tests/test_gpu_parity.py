@@ -194,14 +194,15 @@ def test_many_paths_dag(gpu, oracle_mod):
 
 # ---- API behaviour ------------------------------------------------------------------------
 
-def test_compact_with_arbitrary_masks(gpu, oracle_mod):
-    """pard_compact is a function of (order, seg_ptr, drop) alone."""
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_compact_with_arbitrary_masks(gpu, oracle_mod, max_snap):
+    """pard_compact is a function of (order, seg_ptr, drop) alone; per-snapshot and streamed compaction."""
     import torch
     w = wl.make_workload(5, n_snapshots=11, per_snapshot=4099, permute=True)
-    s, ref = check(gpu, oracle_mod, w)
+    s, ref = check(gpu, oracle_mod, w, max_snap=max_snap)
     rng = np.random.default_rng(9)
     for p in (0.0, 1.0, 0.5, 0.03):
-        mask = (rng.random(w.n) < p).astype(np.uint8)
+        mask = ((rng.random(w.n) < p) * rng.integers(1, 256, w.n)).astype(np.uint8)     # any nonzero byte drops
         s.drop.copy_(torch.from_numpy(mask).to(s.dev))
         s.compact()
         got = s.results()
@@ -211,11 +212,12 @@ def test_compact_with_arbitrary_masks(gpu, oracle_mod):
 
 @pytest.mark.parametrize("cfg,kw", [(5, dict(n_snapshots=7, per_snapshot=8192)), (5, dict(n_snapshots=5, per_snapshot=5000)),
                                      (4, dict(n_requests=150001))])
-def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw):
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw, max_snap):
     """Buffers that start at odd byte offsets (views into larger allocations) give the same survivors."""
     import torch
     w = wl.make_workload(cfg, permute=True, **kw)
-    s, ref = check(gpu, oracle_mod, w)
+    s, ref = check(gpu, oracle_mod, w, max_snap=max_snap)
     rng = np.random.default_rng(21)
     mask = (rng.random(w.n) < 0.4).astype(np.uint8)
     want_idx, want_ptr = oracle_mod.compact(w.K, w.S, ref["order"], ref["seg_ptr"], mask)
@@ -229,7 +231,7 @@ def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw):
         order.copy_(s.order)
         surv_big = torch.full((n + 16,), -7, dtype=torch.int32, device=s.dev)
         surv = surv_big[off_idx:off_idx + n]
-        gpu.pard_compact(s.plan, n, order, s.seg_ptr, drop, surv, s.surv_ptr, s.workspace)
+        gpu.pard_compact(s.plan, n, s.max_snap, order, s.seg_ptr, drop, surv, s.surv_ptr, s.workspace)
         torch.cuda.synchronize()
         got_ptr = s.surv_ptr.cpu().numpy()
         assert np.array_equal(got_ptr, want_ptr)
@@ -272,5 +274,5 @@ def test_error_codes_with_device(gpu):
                                   s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -2
     assert gpu.pard_estimate_drop(s.plan, s.n, s.max_snap, s.arrival, None, s.stage, s.snap_ptr, s.now, s.est,
                                   s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -1
-    assert gpu.pard_compact(s.plan, s.n, s.order, s.seg_ptr, s.drop, s.surv_idx, s.surv_ptr, tiny[:8], check=False) == -8
+    assert gpu.pard_compact(s.plan, s.n, s.max_snap, s.order, s.seg_ptr, s.drop, s.surv_idx, s.surv_ptr, tiny[:8], check=False) == -8
     assert gpu.pard_plan_info(s.plan) == (1, 3)
