@@ -13,7 +13,6 @@ struct pard_plan {
     int device = 0;
     int num_cus = 1;
     int compact_resident = 1;  // co-resident workgroups of the look-back kernels on this device
-    int pass_resident = 1;
 };
 
 namespace {
@@ -98,7 +97,6 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
         else
             (void)hipGetLastError();
         p->compact_resident = p->num_cus * compact_blocks_per_cu();
-        p->pass_resident = p->num_cus * sort_pass_blocks_per_cu();
     }
     PlanDev& d = p->dev;
     d.K = h.K; d.S = h.S; d.shared = h.shared; d.any_fcfs = h.any_fcfs ? 1 : 0;
@@ -173,7 +171,6 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
         a.status = status;
         a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
-        a.resident_pass_blocks = plan->pass_resident;
         a.num_cus = plan->num_cus;
         e = launch_sort_path(a, s);
     }

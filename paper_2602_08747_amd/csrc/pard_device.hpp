@@ -125,10 +125,8 @@ struct SortArgs {
     int32_t *order, *seg_ptr;
     uint32_t* status;
     void* workspace;                   // sort_workspace_bytes(K, S, n) bytes, 256-byte aligned
-    int32_t resident_pass_blocks;      // workgroups of a radix-pass kernel the device holds at once
     int32_t num_cus;
 };
-int sort_pass_blocks_per_cu();
 int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n);
 bool sort_supported(int32_t K, int32_t S, int64_t n);
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);

@@ -4,11 +4,13 @@
 //   count     per-(snapshot, stage) queue lengths and the key range
 //   setup     queue offsets (exclusive scan), cost of every stage at its full queue
 //             length, downstream maximum per (snapshot, stage) over the path CSR
-//   histogram digit histograms of every radix pass in one read of the input
 //   passes    stable least-significant-digit radix sort of (segment, key) with 8-bit
-//             digits; one kernel per digit, each tile's global offsets obtained by a
-//             decoupled look-back over the tiles before it (single read + single write
-//             of the data per pass)
+//             digits.  Per digit: an upsweep reads the keys and leaves every tile's digit
+//             histogram, two small kernels turn the histograms into each tile's first
+//             output slot per digit (scan over tiles, then over digits), and a downsweep
+//             reads the tile again, ranks it and writes it out.  No workgroup waits for
+//             another one (a decoupled look-back over ~2000 co-resident tiles cost more
+//             than the second read of the keys)
 //   epilogue  queue position = sorted position - queue offset; own-stage cost +
 //             downstream maximum; drop decision; est|drop scattered to request order as one
 //             word, then unpacked by a streaming kernel.
@@ -29,12 +31,7 @@ constexpr int kSortItems = 16;
 constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxPasses = 8;
-constexpr uint32_t kFlagAggregate = 1u << 30;          // tile published its own count
-constexpr uint32_t kFlagInclusive = 2u << 30;          // tile published the running total
-constexpr uint32_t kValueMask = (1u << 30) - 1;
-constexpr uint32_t kSpinLimit = 1u << 22;
-constexpr int kPools = 16;                             // tile pools of the radix passes (see sort_pass_kernel)
-constexpr int kPoolStride = 64;                        // counters 256 bytes apart
+constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
     uint32_t inv_min;               // max over requests of ~key  (so that zero-fill is the identity)
@@ -48,8 +45,8 @@ constexpr int kStreamBlocksMax = 1024;                 // upper bound on the gri
 constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
 
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, hist, pool_ctr, status, zero_end, part_minmax, part_cnt, key[2], pay[2], total;
-    int64_t tiles;
+    int64_t params, seg_count, cfull, down, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2], total;
+    int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits;
 };
 
@@ -63,15 +60,15 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n) {
     L.seg_bits = bits_of((uint64_t)(segs - 1));
     L.max_passes = (32 + L.seg_bits + kRadixBits - 1) / kRadixBits;
     L.tiles = (n + kTile - 1) / kTile;
+    L.chunks = (L.tiles + kChunkTiles - 1) / kChunkTiles;
     int64_t off = 0;
     L.params = off;     off = align256(off + (int64_t)sizeof(SortParams));
     L.seg_count = off;  off = align256(off + segs * 4);
     L.cfull = off;      off = align256(off + segs * 8);
     L.down = off;       off = align256(off + segs * 8);
-    L.hist = off;       off = align256(off + (int64_t)kMaxPasses * kRadix * 4);
-    L.pool_ctr = off;   off = align256(off + (int64_t)kMaxPasses * kPools * kPoolStride * 4);
-    L.status = off;     off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
+    L.chunk_tot = off;  off = align256(off + (int64_t)L.max_passes * L.chunks * kRadix * 4);
     L.zero_end = off;
+    L.tile_hist = off;  off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
     L.part_minmax = off; off = align256(off + (int64_t)kStreamBlocksMax * 8);
     L.part_cnt = off;    off = align256(off + (int64_t)kStreamBlocksMax * kPartialSegs * 4);
     for (int b = 0; b < 2; ++b) {
@@ -93,10 +90,9 @@ struct SortDev {                    // everything the sort kernels need, by valu
     SortParams* params;
     uint32_t* seg_count;
     unsigned long long *cfull, *down;
-    uint32_t* hist;                 // [kMaxPasses][256]
-    uint32_t* pool_ctr;             // [kMaxPasses][kPools][kPoolStride] next tile of each pool
-    int32_t pools;
-    uint32_t* tile_status;          // [max_passes][tiles][256]
+    uint32_t* chunk_tot;            // [max_passes][chunks][256] digit counts per chunk of tiles, then their scan
+    uint32_t* tile_hist;            // [max_passes][tiles][256] digit counts per tile, then each tile's first output slots
+    int64_t chunks;
     uint32_t* part_minmax;          // [stream_blocks][2]  per-workgroup (~min key, max key)
     uint32_t* part_cnt;             // [stream_blocks][kPartialSegs] per-workgroup queue lengths
     int32_t stream_blocks;
@@ -356,43 +352,6 @@ __device__ __forceinline__ uint32_t digit_of(uint32_t key, uint32_t seg, uint32_
     return (uint32_t)(v >> (kRadixBits * pass)) & (kRadix - 1);
 }
 
-// ---- histogram of every pass's digit -------------------------------------------------
-// Arrival-ordered input has long runs of equal high digits; 64 lanes adding to one LDS word
-// serialise, so a wave whose lanes all hold the same digit adds its population count once.
-__global__ __launch_bounds__(kScanThreads) void histogram_kernel(SortDev A) {
-    __shared__ uint32_t h[kMaxPasses * kRadix];
-    const int tid = threadIdx.x, lane = tid & 63;
-    for (int i = tid; i < kMaxPasses * kRadix; i += kScanThreads) h[i] = 0;
-    __syncthreads();
-    const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
-    const int passes = (int)A.params->passes;
-    const bool vec = arrays_vectorizable(A);
-    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < A.n; base += (int64_t)gridDim.x * kChunk) {
-        uint32_t seg[kScanItems], key[kScanItems];
-        bool ok[kScanItems];
-        load_chunk(A, base, tid, vec, seg, key, ok);
-#pragma unroll
-        for (int i = 0; i < kScanItems; ++i) {
-            const unsigned long long active = __ballot(ok[i]);
-            if (active == 0ull) continue;
-            const int leader = __ffsll((long long)active) - 1;
-            const uint32_t k = key[i] - umin;
-            for (int p = 0; p < passes; ++p) {
-                const uint32_t d = digit_of(k, seg[i], kb, p);
-                const uint32_t d0 = __shfl(d, leader);
-                if (__ballot(ok[i] && d == d0) == active) {
-                    if (lane == leader) atomicAdd(&h[p * kRadix + d0], (uint32_t)__popcll(active));
-                } else if (ok[i]) {
-                    atomicAdd(&h[p * kRadix + d], 1u);
-                }
-            }
-        }
-    }
-    __syncthreads();
-    for (int i = tid; i < passes * kRadix; i += kScanThreads)
-        if (h[i]) atomicAdd(&A.hist[i], h[i]);
-}
-
 // exclusive scan of one value per thread over the radix-pass workgroup
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* tmp /*[kSortWaves]*/, int tid) {
     const int lane = tid & 63, wave = tid >> 6;
@@ -410,9 +369,137 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
     return pre + inc - v;
 }
 
-// ---- one radix pass --------------------------------------------------------------------
+// ---- one radix pass ----------------------------------------------------------------------
+// Element e of a tile: wave w owns 1024 consecutive elements, item i lane l is element
+// w*1024 + i*64 + l.
 template <bool FIRST>
-__global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, int pass) {
+__device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t tile_base, int valid, int wave, int lane,
+                                          uint32_t umin, bool need_pay, uint32_t (&key)[kSortItems], uint32_t (&pay)[kSortItems]) {
+    const uint32_t* src_key = A.key[(pass + 1) & 1];
+    const uint32_t* src_pay = A.pay[(pass + 1) & 1];
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+        key[i] = 0;
+        pay[i] = 0;
+        if (e < valid) {
+            if (FIRST) {
+                uint32_t seg, k;
+                request_segment_key(A, tile_base + e, seg, k);
+                key[i] = k - umin;
+                pay[i] = (uint32_t)(tile_base + e) | (seg << A.idx_bits);
+            } else {
+                key[i] = src_key[tile_base + e];
+                if (need_pay) pay[i] = src_pay[tile_base + e];
+            }
+        }
+    }
+}
+
+// Upsweep: digit histogram of every tile, and of every chunk of kChunkTiles tiles.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int pass) {
+    if (pass >= (int)A.params->passes) return;
+    __shared__ uint32_t h[kRadix];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
+    const bool need_pay = kRadixBits * (pass + 1) > (int)kb;      // the digit holds segment bits
+    if (tid < kRadix) h[tid] = 0;
+    __syncthreads();
+    const int64_t tile = blockIdx.x;
+    const int64_t tile_base = tile * kTile;
+    const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
+    uint32_t key[kSortItems], pay[kSortItems];
+    load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+        const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
+        // Sorted input puts long runs of one digit into a wave, and 64 lanes adding to one LDS
+        // word serialise: the two most common leading digits are counted with a ballot, the
+        // remaining lanes add for themselves.
+        unsigned long long todo = __ballot(e < valid);
+#pragma unroll
+        for (int round = 0; round < 2; ++round) {
+            if (todo == 0ull) break;
+            const int leader = __ffsll((long long)todo) - 1;
+            const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, leader);
+            const unsigned long long same = __ballot(d == d0) & todo;
+            if (lane == leader) atomicAdd(&h[d0], (uint32_t)__popcll(same));
+            todo &= ~same;
+        }
+        if ((todo >> lane) & 1ull) atomicAdd(&h[d], 1u);
+    }
+    __syncthreads();
+    if (tid < kRadix) {
+        const uint32_t c = h[tid];
+        A.tile_hist[((int64_t)pass * A.tiles + tile) * kRadix + tid] = c;
+        if (c) atomicAdd(&A.chunk_tot[((int64_t)pass * A.chunks + tile / kChunkTiles) * kRadix + tid], c);
+    }
+}
+
+// One workgroup: chunk_tot[pass][c][d] (counts) -> first output slot of digit d in chunk c
+// (scan over chunks inside a digit, digits in ascending order).
+__global__ __launch_bounds__(1024) void digit_scan_kernel(SortDev A, int pass) {
+    if (pass >= (int)A.params->passes) return;
+    __shared__ uint32_t part[4][kRadix];
+    __shared__ uint32_t base[kRadix];
+    __shared__ uint32_t scan_tmp[16];
+    const int tid = threadIdx.x, d = tid & (kRadix - 1), q = tid >> 8;           // quarter q of the chunks
+    uint32_t* tot = A.chunk_tot + (int64_t)pass * A.chunks * kRadix;
+    const int64_t per = (A.chunks + 3) / 4;
+    const int64_t c_lo = q * per < A.chunks ? q * per : A.chunks, c_hi = c_lo + per < A.chunks ? c_lo + per : A.chunks;
+    uint32_t sum = 0;
+    for (int64_t c = c_lo; c < c_hi; ++c) sum += tot[c * kRadix + d];
+    part[q][d] = sum;
+    __syncthreads();
+    // exclusive scan over the 256 digit totals (threads 0..255 hold them; the others add zero)
+    const int lane = tid & 63, wave = tid >> 6;
+    const uint32_t v = q == 0 ? part[0][d] + part[1][d] + part[2][d] + part[3][d] : 0u;
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t t = __shfl_up(inc, off);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) scan_tmp[wave] = inc;
+    __syncthreads();
+    if (q == 0) {
+        uint32_t pre = 0;
+        for (int w = 0; w < wave; ++w) pre += scan_tmp[w];
+        base[d] = pre + inc - v;         // first output slot of digit d
+    }
+    __syncthreads();
+    uint32_t run = base[d];
+    for (int qq = 0; qq < q; ++qq) run += part[qq][d];
+    for (int64_t c = c_lo; c < c_hi; ++c) {      // a count is read and replaced by the same thread only
+        const uint32_t x = tot[c * kRadix + d];
+        tot[c * kRadix + d] = run;
+        run += x;
+    }
+}
+
+// One workgroup per chunk: tile_hist[pass][t][d] (counts) -> first output slot of digit d of tile t.
+__global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass) {
+    if (pass >= (int)A.params->passes) return;
+    const int d = threadIdx.x;
+    const int64_t c = blockIdx.x;
+    uint32_t run = A.chunk_tot[((int64_t)pass * A.chunks + c) * kRadix + d];
+    const int64_t t_lo = c * kChunkTiles, t_hi = t_lo + kChunkTiles < A.tiles ? t_lo + kChunkTiles : A.tiles;
+    uint32_t* th = A.tile_hist + (int64_t)pass * A.tiles * kRadix;
+    uint32_t x[kChunkTiles];
+#pragma unroll
+    for (int i = 0; i < kChunkTiles; ++i) x[i] = t_lo + i < t_hi ? th[(t_lo + i) * kRadix + d] : 0u;
+#pragma unroll
+    for (int i = 0; i < kChunkTiles; ++i) {
+        if (t_lo + i < t_hi) th[(t_lo + i) * kRadix + d] = run;
+        run += x[i];
+    }
+}
+
+// Downsweep: rank the tile's elements among equal digits, reorder in LDS, write runs out.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, int pass) {
     if (pass >= (int)A.params->passes) return;
 
     __shared__ uint32_t lds_key[kTile];
@@ -426,52 +513,18 @@ __global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, i
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
     const int rem_bits = (int)A.params->total_bits - kRadixBits * pass;
     const int nbits = rem_bits < kRadixBits ? (rem_bits < 1 ? 1 : rem_bits) : kRadixBits;   // digit bits that can differ
-    const uint32_t* src_key = A.key[(pass + 1) & 1];
-    const uint32_t* src_pay = A.pay[(pass + 1) & 1];
     uint32_t* dst_key = A.key[pass & 1];
     uint32_t* dst_pay = A.pay[pass & 1];
-    // first output slot of every digit: exclusive scan of this pass's global histogram
-    const uint32_t bin_base = block_exclusive_scan(tid < kRadix ? A.hist[pass * kRadix + tid] : 0u, scan_tmp, tid);
-
-    // A tile may only wait for tiles that already run.  Workgroups are persistent and claim
-    // tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, ... and hands them out
-    // in increasing order; a workgroup uses pool blockIdx % 16), so the lowest unfinished tile
-    // is either running or next in line in a pool whose workgroups have nothing unfinished
-    // left.  One ticket counter would do the same, but atomics on a single address cost
-    // ~11 ns each on this chip; 16 counters on separate cache lines run in parallel.
-    __shared__ int64_t s_tile;
-    const int pool = (int)(blockIdx.x % (unsigned)A.pools);
-    uint32_t* my_ctr = A.pool_ctr + ((int64_t)pass * kPools + pool) * kPoolStride;
-    while (true) {
-    if (tid == 0) s_tile = (int64_t)atomicAdd(my_ctr, 1u) * A.pools + pool;
     for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0;
-    __syncthreads();
-    const int64_t tile = s_tile;
-    if (tile >= A.tiles) break;
+    const int64_t tile = blockIdx.x;
     const int64_t tile_base = tile * kTile;
     const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
+    // first output slot of every digit of this tile
+    const uint32_t first_slot = tid < kRadix ? A.tile_hist[((int64_t)pass * A.tiles + tile) * kRadix + tid] : 0u;
 
-    // load (wave-striped: wave w owns 1024 consecutive elements of the tile, item i lane l
-    // is element w*1024 + i*64 + l), rank every element among equal digits before it
     uint32_t key[kSortItems], pay[kSortItems], rd[kSortItems];   // rd = rank | digit << 16
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const int e = wave * (kWave * kSortItems) + i * kWave + lane;
-        const bool ok = e < valid;
-        key[i] = 0;
-        pay[i] = 0;
-        if (ok) {
-            if (FIRST) {
-                uint32_t seg, k;
-                request_segment_key(A, tile_base + e, seg, k);
-                key[i] = k - umin;
-                pay[i] = (uint32_t)(tile_base + e) | (seg << A.idx_bits);
-            } else {
-                key[i] = src_key[tile_base + e];
-                pay[i] = src_pay[tile_base + e];
-            }
-        }
-    }
+    load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, true, key, pay);
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const int e = wave * (kWave * kSortItems) + i * kWave + lane;
@@ -498,7 +551,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, i
     }
     __syncthreads();
 
-    // per digit (threads 0..255): offsets of each wave's run inside the tile, tile count, global offset
+    // per digit (threads 0..255): offsets of each wave's run inside the tile, tile count
     {
         const int d = tid & (kRadix - 1);
         const bool digit_thread = tid < kRadix;
@@ -511,38 +564,10 @@ __global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, i
                 run += t;
             }
         }
-        const uint32_t tile_cnt = run;
-        uint32_t* st = A.tile_status + ((int64_t)pass * A.tiles + tile) * kRadix + d;
-        if (digit_thread) {
-            if (tile == 0)
-                __hip_atomic_store(st, kFlagInclusive | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            else
-                __hip_atomic_store(st, kFlagAggregate | tile_cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        const uint32_t tstart = block_exclusive_scan(tile_cnt, scan_tmp, tid);
+        const uint32_t tstart = block_exclusive_scan(run, scan_tmp, tid);
         if (digit_thread) {
             tile_start[d] = tstart;
-            uint32_t excl = 0;
-            if (tile > 0) {
-                int64_t t = tile - 1;
-                uint32_t spins = 0;
-                while (true) {
-                    const uint32_t v = __hip_atomic_load(A.tile_status + ((int64_t)pass * A.tiles + t) * kRadix + d,
-                                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const uint32_t flag = v & ~kValueMask;
-                    if (flag == 0) {
-                        if (++spins > kSpinLimit) { atomicOr(A.status_word, kStatusLookbackTimeout); break; }
-                        __builtin_amdgcn_s_sleep(2);
-                        continue;
-                    }
-                    excl += v & kValueMask;
-                    if (flag == kFlagInclusive) break;
-                    --t;                                          // tile 0 always publishes inclusive
-                }
-                __hip_atomic_store(st, kFlagInclusive | ((excl + tile_cnt) & kValueMask),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-            gbase[d] = bin_base + excl - tstart;
+            gbase[d] = first_slot - tstart;
         }
     }
     __syncthreads();
@@ -568,8 +593,6 @@ __global__ __launch_bounds__(kSortThreads, 4) void sort_pass_kernel(SortDev A, i
             const uint32_t dst = gbase[d] + (uint32_t)j;
             if ((int64_t)dst < A.n) { dst_key[dst] = k; dst_pay[dst] = p; }
         }
-    }
-    __syncthreads();                    // LDS is reused by the next tile
     }
 }
 
@@ -644,9 +667,9 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.seg_count = reinterpret_cast<uint32_t*>(ws + L.seg_count);
     D.cfull = reinterpret_cast<unsigned long long*>(ws + L.cfull);
     D.down = reinterpret_cast<unsigned long long*>(ws + L.down);
-    D.hist = reinterpret_cast<uint32_t*>(ws + L.hist);
-    D.pool_ctr = reinterpret_cast<uint32_t*>(ws + L.pool_ctr);
-    D.tile_status = reinterpret_cast<uint32_t*>(ws + L.status);
+    D.chunk_tot = reinterpret_cast<uint32_t*>(ws + L.chunk_tot);
+    D.tile_hist = reinterpret_cast<uint32_t*>(ws + L.tile_hist);
+    D.chunks = L.chunks;
     D.part_minmax = reinterpret_cast<uint32_t*>(ws + L.part_minmax);
     D.part_cnt = reinterpret_cast<uint32_t*>(ws + L.part_cnt);
     for (int b = 0; b < 2; ++b) {
@@ -663,17 +686,6 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
 }  // namespace
 
 int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n) { return make_layout(K, S, n).total; }
-
-int sort_pass_blocks_per_cu() {
-    int a = 0, b = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&a, sort_pass_kernel<true>, kSortThreads, 0) != hipSuccess ||
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&b, sort_pass_kernel<false>, kSortThreads, 0) != hipSuccess) {
-        (void)hipGetLastError();
-        return 1;
-    }
-    const int m = a < b ? a : b;
-    return m < 1 ? 1 : m;
-}
 
 bool sort_supported(int32_t K, int32_t S, int64_t n) {
     const SortLayout L = make_layout(K, S, n);
@@ -695,18 +707,17 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     if (sb > 2 * a.num_cus) sb = 2 * a.num_cus;
     if (sb > kStreamBlocksMax) sb = kStreamBlocksMax;
     if (sb < 1) sb = 1;
-    int64_t pg = a.resident_pass_blocks > 0 ? a.resident_pass_blocks : 1;   // radix passes: persistent workgroups
-    if (pg > L.tiles) pg = L.tiles;
-    if (pg < 1) pg = 1;
-    D.pools = pg < kPools ? (int)pg : kPools;
     D.stream_blocks = sb;
     count_kernel<<<sb, kScanThreads, 0, stream>>>(D);
     setup_kernel<<<1, 1024, 0, stream>>>(D);
     if (a.n > 0) {
-        histogram_kernel<<<sb, kScanThreads, 0, stream>>>(D);
         for (int p = 0; p < L.max_passes; ++p) {
-            if (p == 0) sort_pass_kernel<true><<<(unsigned)pg, kSortThreads, 0, stream>>>(D, p);
-            else sort_pass_kernel<false><<<(unsigned)pg, kSortThreads, 0, stream>>>(D, p);
+            if (p == 0) upsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            else upsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            digit_scan_kernel<<<1, 1024, 0, stream>>>(D, p);
+            chunk_scan_kernel<<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
+            if (p == 0) downsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            else downsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
         }
         epilogue_kernel<<<gb, 256, 0, stream>>>(D);
         unpack_kernel<<<gb, 256, 0, stream>>>(D);
