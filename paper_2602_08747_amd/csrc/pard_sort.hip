@@ -32,6 +32,7 @@ constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxPasses = 8;
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
+constexpr int kFusedScanChunks = 32;                   // up to here every chunk scans the chunk totals itself
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
     uint32_t inv_min;               // max over requests of ~key  (so that zero-fill is the identity)
@@ -375,20 +376,42 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 template <bool FIRST>
 __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t tile_base, int valid, int wave, int lane,
                                           uint32_t umin, bool need_pay, uint32_t (&key)[kSortItems], uint32_t (&pay)[kSortItems]) {
-    const uint32_t* src_key = A.key[(pass + 1) & 1];
-    const uint32_t* src_pay = A.pay[(pass + 1) & 1];
+    if (FIRST) {
+        // every load is issued before the first key is formed (elements past the end re-read the
+        // tile's first request and are zeroed afterwards)
+        const PlanDev& P = A.plan;
+        int32_t dl[kSortItems], st[kSortItems], ar[kSortItems];
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const int e = wave * (kWave * kSortItems) + i * kWave + lane;
-        key[i] = 0;
-        pay[i] = 0;
-        if (e < valid) {
-            if (FIRST) {
-                uint32_t seg, k;
-                request_segment_key(A, tile_base + e, seg, k);
-                key[i] = k - umin;
-                pay[i] = (uint32_t)(tile_base + e) | (seg << A.idx_bits);
-            } else {
+        for (int i = 0; i < kSortItems; ++i) {
+            const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+            const int64_t r = tile_base + (e < valid ? e : 0);
+            dl[i] = A.deadline[r];
+            st[i] = A.stage[r];
+            ar[i] = P.any_fcfs ? A.arrival[r] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+            const int64_t r = tile_base + e;
+            const bool ok = e < valid;
+            const int32_t u = ok ? snapshot_of(A.snap_ptr, P.K, r) : 0;
+            const int32_t s = clamp_stage(st[i], P.S);
+            const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
+                                                     : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
+            const uint32_t seg = (uint32_t)u * (uint32_t)P.S + (uint32_t)s;
+            const uint32_t k = order_key(mode, dl[i], mode == PARD_ORDER_FCFS ? ar[i] : 0);
+            key[i] = ok ? k - umin : 0u;
+            pay[i] = ok ? ((uint32_t)r | (seg << A.idx_bits)) : 0u;
+        }
+    } else {
+        const uint32_t* src_key = A.key[(pass + 1) & 1];
+        const uint32_t* src_pay = A.pay[(pass + 1) & 1];
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+            key[i] = 0;
+            pay[i] = 0;
+            if (e < valid) {
                 key[i] = src_key[tile_base + e];
                 if (need_pay) pay[i] = src_pay[tile_base + e];
             }
@@ -450,7 +473,13 @@ __global__ __launch_bounds__(1024) void digit_scan_kernel(SortDev A, int pass) {
     const int64_t per = (A.chunks + 3) / 4;
     const int64_t c_lo = q * per < A.chunks ? q * per : A.chunks, c_hi = c_lo + per < A.chunks ? c_lo + per : A.chunks;
     uint32_t sum = 0;
-    for (int64_t c = c_lo; c < c_hi; ++c) sum += tot[c * kRadix + d];
+    for (int64_t c0 = c_lo; c0 < c_hi; c0 += 16) {      // 16 loads in flight
+        uint32_t x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = c0 + i < c_hi ? tot[(c0 + i) * kRadix + d] : 0u;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += x[i];
+    }
     part[q][d] = sum;
     __syncthreads();
     // exclusive scan over the 256 digit totals (threads 0..255 hold them; the others add zero)
@@ -472,19 +501,55 @@ __global__ __launch_bounds__(1024) void digit_scan_kernel(SortDev A, int pass) {
     __syncthreads();
     uint32_t run = base[d];
     for (int qq = 0; qq < q; ++qq) run += part[qq][d];
-    for (int64_t c = c_lo; c < c_hi; ++c) {      // a count is read and replaced by the same thread only
-        const uint32_t x = tot[c * kRadix + d];
-        tot[c * kRadix + d] = run;
-        run += x;
+    for (int64_t c0 = c_lo; c0 < c_hi; c0 += 16) {      // a count is read and replaced by the same thread only
+        uint32_t x[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = c0 + i < c_hi ? tot[(c0 + i) * kRadix + d] : 0u;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (c0 + i < c_hi) tot[(c0 + i) * kRadix + d] = run;
+            run += x[i];
+        }
     }
 }
 
 // One workgroup per chunk: tile_hist[pass][t][d] (counts) -> first output slot of digit d of tile t.
+// SCANNED: chunk_tot already holds every chunk's first slots (digit_scan_kernel ran).  Otherwise it
+// holds counts and every workgroup derives its own first slots from all of them (few chunks).
+template <bool SCANNED>
 __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass) {
     if (pass >= (int)A.params->passes) return;
-    const int d = threadIdx.x;
+    __shared__ uint32_t scan_tmp[kRadix / kWave];
+    const int d = threadIdx.x, lane = d & 63, wave = d >> 6;
     const int64_t c = blockIdx.x;
-    uint32_t run = A.chunk_tot[((int64_t)pass * A.chunks + c) * kRadix + d];
+    const uint32_t* tot = A.chunk_tot + (int64_t)pass * A.chunks * kRadix;
+    uint32_t run;
+    if (SCANNED) {
+        run = tot[c * kRadix + d];
+    } else {
+        uint32_t all = 0, before = 0;
+        for (int64_t c0 = 0; c0 < A.chunks; c0 += 16) {
+            uint32_t x[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) x[i] = c0 + i < A.chunks ? tot[(c0 + i) * kRadix + d] : 0u;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                all += x[i];
+                if (c0 + i < c) before += x[i];
+            }
+        }
+        uint32_t inc = all;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(inc, off);
+            if (lane >= off) inc += t;
+        }
+        if (lane == 63) scan_tmp[wave] = inc;
+        __syncthreads();
+        uint32_t pre = 0;
+        for (int w = 0; w < wave; ++w) pre += scan_tmp[w];
+        run = pre + inc - all + before;
+    }
     const int64_t t_lo = c * kChunkTiles, t_hi = t_lo + kChunkTiles < A.tiles ? t_lo + kChunkTiles : A.tiles;
     uint32_t* th = A.tile_hist + (int64_t)pass * A.tiles * kRadix;
     uint32_t x[kChunkTiles];
@@ -714,8 +779,12 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
         for (int p = 0; p < L.max_passes; ++p) {
             if (p == 0) upsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
             else upsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
-            digit_scan_kernel<<<1, 1024, 0, stream>>>(D, p);
-            chunk_scan_kernel<<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
+            if (L.chunks > kFusedScanChunks) {
+                digit_scan_kernel<<<1, 1024, 0, stream>>>(D, p);
+                chunk_scan_kernel<true><<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
+            } else {
+                chunk_scan_kernel<false><<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
+            }
             if (p == 0) downsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
             else downsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
         }
