@@ -31,6 +31,7 @@ constexpr int kSortItems = 16;
 constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxPasses = 8;
+constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 constexpr int kFusedScanChunks = 32;                   // up to here every chunk scans the chunk totals itself
 
@@ -581,7 +582,12 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     uint32_t* dst_key = A.key[pass & 1];
     uint32_t* dst_pay = A.pay[pass & 1];
     for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0;
-    const int64_t tile = blockIdx.x;
+    // Workgroups are handed to the 8 accelerator dies in turn.  Neighbouring tiles write
+    // neighbouring runs of every digit, so each die takes a contiguous range of tiles: the
+    // two halves of a cache line shared by two tiles then meet in the same L2.
+    const int64_t per_die = (A.tiles + kDies - 1) / kDies;
+    const int64_t tile = (int64_t)(blockIdx.x % kDies) * per_die + blockIdx.x / kDies;
+    if (tile >= A.tiles) return;
     const int64_t tile_base = tile * kTile;
     const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
     // first output slot of every digit of this tile
@@ -785,8 +791,9 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             } else {
                 chunk_scan_kernel<false><<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
             }
-            if (p == 0) downsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
-            else downsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            const unsigned dg = (unsigned)((L.tiles + kDies - 1) / kDies * kDies);
+            if (p == 0) downsweep_kernel<true><<<dg, kSortThreads, 0, stream>>>(D, p);
+            else downsweep_kernel<false><<<dg, kSortThreads, 0, stream>>>(D, p);
         }
         epilogue_kernel<<<gb, 256, 0, stream>>>(D);
         unpack_kernel<<<gb, 256, 0, stream>>>(D);
