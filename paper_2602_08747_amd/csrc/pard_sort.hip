@@ -671,35 +671,114 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
 // The estimate (31 bits, never negative) and the drop bit leave as ONE scattered 4-byte write
 // per request into the key buffer the last pass no longer needs; a streaming kernel then
 // unpacks that buffer into est[] and drop[] with coalesced accesses.
-__global__ __launch_bounds__(256) void epilogue_kernel(SortDev A) {
+//
+// Persistent workgroups; with at most kEpiSegs queues everything a request needs about its
+// queue (stage constants, queue start, downstream maximum, snapshot time) sits in LDS, so the
+// only global traffic per request is its key and payload in, its order entry and packed result out.
+constexpr int kEpiSegs = 64;
+constexpr int kEpiThreads = 256;
+
+struct EpiSeg {                     // 48 bytes
+    uint32_t B, W, latB, mode;
+    uint32_t mB, shB, mW, shW;
+    int32_t start, now;
+    uint32_t down_lo, down_hi;
+};
+
+__device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
+                                                 uint32_t key, uint32_t r, uint32_t umin) {
+    const uint32_t pos = (uint32_t)(j - (int64_t)q.start);
+    // stage_cost() with the record held in registers
+    const uint32_t batches = magic_div_dev(pos + q.B - 1u, q.mB, q.shB);
+    const uint64_t x = (uint64_t)batches * q.latB;
+    uint64_t wait;
+    if ((x >> 32) == 0) wait = magic_div_dev((uint32_t)x, q.mW, q.shW);
+    else wait = wide_div(x, q.W);
+    uint32_t ex = q.latB;
+    if (pos + 1u < q.B) ex = (uint32_t)lat_row[pos];             // only the first B-1 requests of a queue
+    uint64_t c = wait + ex;
+    c = c < kCostCap ? c : kCostCap;
+    const uint64_t e64 = c + (((uint64_t)q.down_hi << 32) | q.down_lo);
+    int32_t deadline;
+    const uint32_t uk = key + umin;
+    const int32_t mode = (int32_t)(q.mode & 0xFF);
+    if (mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
+    else if (mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
+    else deadline = A.deadline[r];
+    int32_t est;
+    uint8_t drp;
+    finish_request(e64, q.now, deadline, est, drp);
+    return (uint32_t)est | ((uint32_t)drp << 31);
+}
+
+__device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t seg) {
     const PlanDev& P = A.plan;
+    const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
+    const StageRec sr = P.recs[P.shared ? (int64_t)k : (int64_t)seg];
+    const unsigned long long dn = A.down[seg];
+    EpiSeg q;
+    q.B = (uint32_t)sr.B; q.W = (uint32_t)sr.W; q.latB = (uint32_t)sr.latB; q.mode = (uint32_t)sr.mode;
+    q.mB = sr.mB; q.shB = sr.shB; q.mW = sr.mW; q.shW = sr.shW;
+    q.start = A.seg_ptr[seg]; q.now = A.now[u];
+    q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
+    return q;
+}
+
+__global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
+    __shared__ EpiSeg tab[kEpiSegs];
+    const PlanDev& P = A.plan;
+    const int tid = threadIdx.x;
+    const int64_t segs = (int64_t)P.K * P.S;
+    const bool cached = segs <= kEpiSegs;
+    if (cached && tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
+    __syncthreads();
     const int last = ((int)A.params->passes - 1) & 1;
     const uint32_t* keys = A.key[last];
     const uint32_t* pays = A.pay[last];
     uint32_t* packed = A.key[last ^ 1];
     const uint32_t umin = ~A.params->inv_min;
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < A.n; j += stride) {
-        const uint32_t p = pays[j];
-        const uint32_t r = p & idx_mask;
-        const uint32_t seg = A.idx_bits < 32 ? (p >> A.idx_bits) : 0u;
-        const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
-        const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
-        const StageRec sr = P.recs[rec];
-        const uint32_t pos = (uint32_t)(j - (int64_t)A.seg_ptr[seg]);
-        const uint64_t e64 = stage_cost(sr, pos, P.lat + rec * PARD_LAT_ENTRIES) + A.down[seg];
-        int32_t deadline;
-        const uint32_t uk = keys[j] + umin;
-        const int32_t mode = sr.mode & 0xFF;
-        if (mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
-        else if (mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
-        else deadline = A.deadline[r];
-        int32_t est;
-        uint8_t drp;
-        finish_request(e64, A.now[u], deadline, est, drp);
-        A.order[j] = (int32_t)r;
-        if ((int64_t)r < A.n) packed[r] = (uint32_t)est | ((uint32_t)drp << 31);
+    const bool vec = (reinterpret_cast<uintptr_t>(A.order) & 15) == 0;     // the workspace buffers are 256-byte aligned
+    const int64_t groups = (A.n + 3) / 4;
+    const int64_t stride = (int64_t)gridDim.x * kEpiThreads;
+    for (int64_t g = (int64_t)blockIdx.x * kEpiThreads + tid; g < groups; g += stride) {
+        const int64_t j0 = g * 4;
+        uint32_t k4[4], p4[4];
+        if (j0 + 3 < A.n) {
+            const uint4 kv = *reinterpret_cast<const uint4*>(keys + j0);
+            const uint4 pv = *reinterpret_cast<const uint4*>(pays + j0);
+            k4[0] = kv.x; k4[1] = kv.y; k4[2] = kv.z; k4[3] = kv.w;
+            p4[0] = pv.x; p4[1] = pv.y; p4[2] = pv.z; p4[3] = pv.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                k4[c] = j0 + c < A.n ? keys[j0 + c] : 0u;
+                p4[c] = j0 + c < A.n ? pays[j0 + c] : 0u;
+            }
+        }
+        uint32_t r4[4], out[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            r4[c] = p4[c] & idx_mask;
+            const uint32_t seg = A.idx_bits < 32 ? (p4[c] >> A.idx_bits) : 0u;
+            const uint32_t k = seg % (uint32_t)P.S;
+            const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+            out[c] = 0;
+            if (j0 + c < A.n) {
+                if (cached) out[c] = epilogue_one(A, tab[seg], P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
+                else out[c] = epilogue_one(A, epilogue_segment(A, seg), P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
+            }
+        }
+        if (vec && j0 + 3 < A.n) {
+            *reinterpret_cast<int4*>(A.order + j0) = make_int4((int32_t)r4[0], (int32_t)r4[1], (int32_t)r4[2], (int32_t)r4[3]);
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (j0 + c < A.n) A.order[j0 + c] = (int32_t)r4[c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (j0 + c < A.n && (int64_t)r4[c] < A.n) packed[r4[c]] = out[c];
     }
 }
 
@@ -795,7 +874,12 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             if (p == 0) downsweep_kernel<true><<<dg, kSortThreads, 0, stream>>>(D, p);
             else downsweep_kernel<false><<<dg, kSortThreads, 0, stream>>>(D, p);
         }
-        epilogue_kernel<<<gb, 256, 0, stream>>>(D);
+        {
+            int64_t eg = (a.n / 4 + kEpiThreads - 1) / kEpiThreads;       // persistent: a few workgroups per compute unit
+            if (eg > 8 * (int64_t)a.num_cus) eg = 8 * (int64_t)a.num_cus;
+            if (eg < 1) eg = 1;
+            epilogue_kernel<<<(unsigned)eg, kEpiThreads, 0, stream>>>(D);
+        }
         unpack_kernel<<<gb, 256, 0, stream>>>(D);
     }
     return hipGetLastError();

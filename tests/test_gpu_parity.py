@@ -106,6 +106,13 @@ def test_sizes_sort_path(gpu, oracle_mod, n):
     check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
 
 
+def test_many_queues_sort_path(gpu, oracle_mod):
+    """More queues (snapshots x stages) than the large-snapshot path keeps on chip per workgroup."""
+    w = wl.random_workload(31, K=12, S=8, n_per_snapshot=700, dag_shared=0)
+    assert w.K * w.S > 64
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+
+
 def test_ragged_multi_snapshot_large(gpu, oracle_mod):
     """Several snapshots of very different sizes, some above the on-chip capacity, own DAG each."""
     w = wl.random_workload(7, K=5, S=6, n_per_snapshot=9000, dag_shared=0, time_span=2_000_000,
