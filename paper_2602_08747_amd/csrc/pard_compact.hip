@@ -506,12 +506,21 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
         }
         *reinterpret_cast<uint4*>(L.drop + 16u * c) = v;
     }
+    // the offsets of this snapshot's queues (the last snapshot also owns the end offset), fetched early
+    const int owned = A.stages + (u + 1 == gridDim.x ? 1 : 0);
+    static_assert(PARD_MAX_STAGES + 1 <= kLThreads, "one thread per queue offset");
+    const int64_t my_slot = tid < owned ? (int64_t)A.seg_ptr[u * A.stages + tid] - a : 0;
     // survivors of the snapshots before this one
     uint32_t before_me = 0;
     if (snap_off) {
         before_me = tid == 0 ? snap_off[u] : 0u;
     } else {
-        for (int64_t v = tid; v < u; v += kLThreads) before_me += kept[v];
+        static_assert(kDirectSumSnapshots == 16 * kLThreads, "sixteen counts per thread");
+        uint32_t x[16];                 // all loads in flight at once
+#pragma unroll
+        for (int i = 0; i < 16; ++i) x[i] = (int64_t)(tid + i * kLThreads) < u ? kept[tid + i * kLThreads] : 0u;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) before_me += x[i];
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) before_me += __shfl_xor(before_me, off);
@@ -581,18 +590,14 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
             if (keep[k] & (1u << c)) { A.surv_idx[o] = ids[k][c]; ++o; }
     }
     __syncthreads();
-    // offsets of this snapshot's queues (the last snapshot also writes the end offset)
-    const int count = A.stages + (u + 1 == gridDim.x ? 1 : 0);
-    for (int j = tid; j < count; j += kLThreads) {
-        const int64_t g = u * A.stages + j;
-        int64_t p = (int64_t)A.seg_ptr[g] - a;
-        if (p < 0) p = 0;
+    if (tid < owned) {
+        int64_t p = my_slot < 0 ? 0 : my_slot;
         uint32_t before = total;
         if (p < size) {
             const uint32_t v = L.group[p >> 2];
             before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
         }
-        A.surv_ptr[g] = (int32_t)(off0 + before);
+        A.surv_ptr[u * A.stages + tid] = (int32_t)(off0 + before);
     }
 }
 
