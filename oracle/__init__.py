@@ -3,4 +3,5 @@
 Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
 package.  It shares nothing with the GPU library.
 """
-from .reference import (build_oracle, compact, estimate_drop, expand_paths, run, stage_cost)  # noqa: F401
+from .reference import (VARIANT_BACK, VARIANT_FULL, VARIANT_LOWER, VARIANT_SF, VARIANT_UPPER,  # noqa: F401
+                        build_oracle, compact, estimate_drop, expand_paths, run, stage_cost, sub_latency)

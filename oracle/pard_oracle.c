@@ -26,7 +26,17 @@
  * is integer microseconds in 128-bit integers, so nothing can overflow; results are
  * clamped to INT32_MAX on output only.
  *
- * Parity status: no value in the paper pins this path (it prints none for it).
+ * The State Planner's part (Section 3.2 Eq.(4), "Batch wait estimation"): the latency of
+ * the modules after the current one is the sum of their queueing delays and execution
+ * durations plus w, the lambda-quantile of the aggregated batch wait time, which the paper
+ * obtains by random sampling over the collected arrival process (M = 10,000 by default).
+ * pard_oracle_sub_latency() computes that per (snapshot, stage), with the paper's ablation
+ * variants (-lower, -upper, -sf, -back; Section 5.1 Table of baselines, Section 5.3); see
+ * the comment at the function for the sampling rule.  Its pins: the quantiles the paper
+ * prints for a four-module pipeline (0.31, 0.28, 0.22, 0.10 of the summed durations),
+ * an independent numpy brute force, closed forms and identities (tests/test_oracle_sub.py).
+ *
+ * Parity status: no value in the paper pins the estimate/drop path (it prints none for it).
  * The pins are brute force on tiny inputs, closed forms, invariants and a hand-worked
  * vector (tests/test_oracle_*.py).
  */
@@ -194,12 +204,12 @@ int64_t pard_oracle_stage_cost(const int32_t* lat, int32_t B, int32_t W, int64_t
  * seg_ptr[K*S+1] offsets of the (snapshot, stage) queues inside order.
  * Returns 0, or a positive code for a malformed DAG.
  */
-int pard_oracle_estimate_drop(
+static int estimate_drop_impl(
         int32_t K, int32_t S, int32_t dag_shared,
         const int32_t* row_ptr, const int32_t* col,
         const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
         int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
-        const int32_t* snap_ptr, const int32_t* now,
+        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub,
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     (void)n;
@@ -259,6 +269,10 @@ int pard_oracle_estimate_drop(
             int k = clamp_stage(stage[r], S);
             int64_t pos = j - qstart[k];                 /* requests ahead of r in its own queue */
             wide_t best = -1;
+            if (sub) {
+                /* Eq.(4): the Request Broker's own part plus the State Planner's L_sub */
+                best = stage_cost(L + (int64_t)k * LAT_ENTRIES, B[k], Wk[k], pos) + (wide_t)sub[(int64_t)u * S + k];
+            } else
             for (int64_t p = 0; p < ps.P; ++p) {
                 int32_t a = ps.ptr[p], b = ps.ptr[p + 1];
                 int32_t at = -1;
@@ -284,6 +298,154 @@ int pard_oracle_estimate_drop(
         paths_free(&ps);
     }
     seg_ptr[(int64_t)K * S] = snap_ptr[K];
+    free(col_base);
+    return status;
+}
+
+int pard_oracle_estimate_drop(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
+        int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+        const int32_t* snap_ptr, const int32_t* now,
+        int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
+        int32_t nthreads) {
+    return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
+                              snap_ptr, now, NULL, est, drop, order, seg_ptr, nthreads);
+}
+
+/* The same with the downstream part given: est = own-stage cost at the queue position
+ * + sub[snapshot * S + stage]  (Eq.(4): Request Broker part + State Planner part). */
+int pard_oracle_estimate_drop_sub(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
+        int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub,
+        int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
+        int32_t nthreads) {
+    return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
+                              snap_ptr, now, sub, est, drop, order, seg_ptr, nthreads);
+}
+
+/*
+ * Latency of the modules after the current one, per (snapshot, stage): L_sub of Eq.(4),
+ * maximum over the downstream DAG paths.
+ *
+ * For the stages i after stage k on one path, with n_i = qlen[snapshot][i] requests queued:
+ *   q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i)     queueing delay (snapshot stand-in for the
+ *                                                     monitored average)
+ *   d_i = lat_i[min(B_i, n_i + 1)]                     execution duration at the batch size a
+ *                                                     joining request would see
+ *   (q_i + d_i is stage_cost(n_i), the term the estimate path adds per downstream stage)
+ *
+ *   variant 0, full   : sum q_i + sum d_i + w
+ *   variant 1, lower  : sum q_i + sum d_i               (batch wait assumed 0)
+ *   variant 2, upper  : sum q_i + sum d_i + sum d_i     (batch wait assumed sum d_i)
+ *   variant 3, sf     : sum d_i                         (ignores Q and W of later modules)
+ *   variant 4, back   : 0                               (preceding and current modules only)
+ *
+ * w = lambda-quantile (lambda = lam_num/lam_den) of the aggregated batch wait time, sampled:
+ * sample j (0 <= j < M) draws, independently for every stage i, one arrival of the collected
+ * arrival process, a = max(samples[picks[j*S + i] mod M], 0); a module starts a batch every d_i
+ * (batches run back to back, boundaries at multiples of d_i), so that arrival waits
+ *   W(j,i) = (d_i - a mod d_i) mod d_i      (0 when d_i = 0)
+ * for the next batch; T_j = sum over the path's later stages of W(j,i).  With the T_j sorted
+ * ascending, w = T[ceil(lambda*M) - 1]; lambda = 0 gives 0 and lambda = 1 gives sum d_i, the end
+ * points the paper states.  The random draws (picks) are inputs, not generated here.
+ *
+ * Output sub[K*S], saturated at 2^40 microseconds.  Returns 0, or a positive code for a
+ * malformed DAG, 4 for bad arguments.
+ */
+static int cmp_u64(const void* a, const void* b) {
+    uint64_t x = *(const uint64_t*)a, y = *(const uint64_t*)b;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+int pard_oracle_sub_latency(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat,
+        const int32_t* qlen,
+        int32_t variant, int64_t lam_num, int64_t lam_den,
+        int64_t M, const int32_t* samples, const uint32_t* picks,
+        int64_t* sub, int32_t nthreads) {
+    if (nthreads < 1) nthreads = 1;
+    if (variant < 0 || variant > 4) return 4;
+    if (variant == 0 && (lam_den <= 0 || lam_num < 0 || lam_num > lam_den || M < 1 || !samples || !picks)) return 4;
+    int status = 0;
+    int64_t D = dag_shared ? 1 : K;
+    int64_t* col_base = (int64_t*)malloc(sizeof(int64_t) * (size_t)(D + 1));
+    col_base[0] = 0;
+    for (int64_t d = 0; d < D; ++d) col_base[d + 1] = col_base[d] + row_ptr[d * (S + 1) + S];
+    const wide_t cap = (wide_t)1 << 40;
+
+    #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int32_t u = 0; u < K; ++u) {
+        int64_t d = dag_shared ? 0 : u;
+        const int32_t* B = batch + d * S;
+        const int32_t* Wk = workers + d * S;
+        const int32_t* L = lat + d * S * LAT_ENTRIES;
+        const int32_t* nq = qlen + (int64_t)u * S;
+        paths_t ps;
+        int err = enumerate_paths(S, row_ptr + d * (S + 1), col + col_base[d], &ps);
+        if (err) {
+            #pragma omp critical
+            status = err;
+            paths_free(&ps);
+            continue;
+        }
+        uint64_t* T = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(M > 0 ? M : 1));
+        for (int k = 0; k < S; ++k) {
+            wide_t best = 0;
+            for (int64_t p = 0; p < ps.P; ++p) {
+                int32_t a = ps.ptr[p], b = ps.ptr[p + 1];
+                int32_t at = -1;
+                for (int32_t t = a; t < b; ++t) if (ps.stage[t] == k) { at = t; break; }
+                if (at < 0) continue;                    /* path does not pass through stage k */
+                wide_t sum_qd = 0, sum_d = 0;
+                for (int32_t t = at + 1; t < b; ++t) {
+                    int32_t i = ps.stage[t];
+                    int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];
+                    sum_qd += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], nq[i]);
+                    sum_d += L[(int64_t)i * LAT_ENTRIES + seen - 1];
+                }
+                wide_t lsub;
+                if (variant == 1) lsub = sum_qd;
+                else if (variant == 2) lsub = sum_qd + sum_d;
+                else if (variant == 3) lsub = sum_d;
+                else if (variant == 4) lsub = 0;
+                else {
+                    wide_t w;
+                    if (lam_num == 0) w = 0;
+                    else if (lam_num == lam_den) w = sum_d;
+                    else {
+                        for (int64_t j = 0; j < M; ++j) {
+                            uint64_t total = 0;
+                            for (int32_t t = at + 1; t < b; ++t) {
+                                int32_t i = ps.stage[t];
+                                int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];
+                                int64_t di = L[(int64_t)i * LAT_ENTRIES + seen - 1];
+                                if (di <= 0) continue;
+                                int64_t arr = samples[picks[j * S + i] % (uint64_t)M];
+                                if (arr < 0) arr = 0;
+                                total += (uint64_t)((di - arr % di) % di);
+                            }
+                            T[j] = total;
+                        }
+                        qsort(T, (size_t)M, sizeof(uint64_t), cmp_u64);
+                        int64_t rank = (int64_t)(((wide_t)lam_num * M + lam_den - 1) / lam_den);   /* ceil(lambda*M) >= 1 */
+                        w = (wide_t)T[rank - 1];
+                    }
+                    lsub = sum_qd + w;
+                }
+                if (lsub > best) best = lsub;
+            }
+            sub[(int64_t)u * S + k] = (int64_t)(best > cap ? cap : best);
+        }
+        free(T);
+        paths_free(&ps);
+    }
     free(col_base);
     return status;
 }

@@ -43,6 +43,19 @@ def _load() -> ctypes.CDLL:
             _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
             ctypes.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p,
             _i32p, _u8p, _i32p, _i32p, ctypes.c_int32]
+        lib.pard_oracle_estimate_drop_sub.restype = ctypes.c_int
+        lib.pard_oracle_estimate_drop_sub.argtypes = [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+            _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
+            ctypes.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p, _i64p,
+            _i32p, _u8p, _i32p, _i32p, ctypes.c_int32]
+        lib.pard_oracle_sub_latency.restype = ctypes.c_int
+        lib.pard_oracle_sub_latency.argtypes = [
+            ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+            _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
+            ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
+            ctypes.c_int64, _i32p, ctypes.POINTER(ctypes.c_uint32),
+            _i64p, ctypes.c_int32]
         lib.pard_oracle_compact.restype = ctypes.c_int
         lib.pard_oracle_compact.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                             _i32p, _i32p, _u8p, _i32p, _i32p]
@@ -63,9 +76,35 @@ def _p32(a: np.ndarray):
     return a.ctypes.data_as(_i32p)
 
 
+VARIANT_FULL, VARIANT_LOWER, VARIANT_UPPER, VARIANT_SF, VARIANT_BACK = range(5)
+
+
+def sub_latency(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, qlen, variant=VARIANT_FULL,
+                lam=(1, 10), samples=None, picks=None, threads: int = 1):
+    """Downstream latency L_sub per (snapshot, stage): int64[K*S]."""
+    lib = _load()
+    rp, cl, B, W, L, q = map(_i32, (dag_row_ptr, dag_col, batch, workers, lat_us, qlen))
+    if cl.size == 0:
+        cl = np.zeros(1, np.int32)
+    M = 0 if samples is None else int(np.asarray(samples).shape[0])
+    smp = _i32(samples) if M else np.zeros(1, np.int32)
+    pk = np.ascontiguousarray(picks, dtype=np.uint32) if M else np.zeros(1, np.uint32)
+    if M:
+        assert pk.size == M * S
+    out = np.zeros(K * S, np.int64)
+    rc = lib.pard_oracle_sub_latency(
+        K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(q),
+        int(variant), int(lam[0]), int(lam[1]), M, _p32(smp), pk.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+        out.ctypes.data_as(_i64p), int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return out
+
+
 def estimate_drop(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode,
-                  arrival, deadline, stage, snap_ptr, now, threads: int = 1):
-    """Returns (est int32[n], drop uint8[n], order int32[n], seg_ptr int32[K*S+1])."""
+                  arrival, deadline, stage, snap_ptr, now, threads: int = 1, sub=None):
+    """Returns (est int32[n], drop uint8[n], order int32[n], seg_ptr int32[K*S+1]).
+    With `sub` (int64[K*S]) the downstream part of every estimate is taken from it."""
     lib = _load()
     rp, cl, B, W, L, M = map(_i32, (dag_row_ptr, dag_col, batch, workers, lat_us, order_mode))
     if cl.size == 0:
@@ -77,10 +116,18 @@ def estimate_drop(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us
     order = np.zeros(max(n, 1), np.int32)
     seg_ptr = np.zeros(K * S + 1, np.int32)
     pad = lambda a: a if a.size else np.zeros(1, np.int32)  # noqa: E731
-    rc = lib.pard_oracle_estimate_drop(
-        K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(M),
-        n, _p32(pad(arr)), _p32(pad(ddl)), _p32(pad(stg)), _p32(sp), _p32(pad(nw)),
-        _p32(est), drop.ctypes.data_as(_u8p), _p32(order), _p32(seg_ptr), int(threads))
+    if sub is None:
+        rc = lib.pard_oracle_estimate_drop(
+            K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(M),
+            n, _p32(pad(arr)), _p32(pad(ddl)), _p32(pad(stg)), _p32(sp), _p32(pad(nw)),
+            _p32(est), drop.ctypes.data_as(_u8p), _p32(order), _p32(seg_ptr), int(threads))
+    else:
+        sb = np.ascontiguousarray(sub, dtype=np.int64)
+        assert sb.size == K * S
+        rc = lib.pard_oracle_estimate_drop_sub(
+            K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(M),
+            n, _p32(pad(arr)), _p32(pad(ddl)), _p32(pad(stg)), _p32(sp), _p32(pad(nw)), sb.ctypes.data_as(_i64p),
+            _p32(est), drop.ctypes.data_as(_u8p), _p32(order), _p32(seg_ptr), int(threads))
     if rc != 0:
         raise ValueError(f"oracle rejected the DAG (code {rc})")
     return est[:n], drop[:n], order[:n], seg_ptr
