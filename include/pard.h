@@ -180,6 +180,64 @@ int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_reques
                  int32_t* d_surv_idx, int32_t* d_surv_ptr,
                  void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/* Variants of the downstream latency (Section 5.1 baseline table; Section 5.3 ablations). */
+enum { PARD_SUB_FULL = 0,        /* sum q_i + sum d_i + w, w = sampled lambda-quantile of the batch wait */
+       PARD_SUB_LOWER = 1,       /* batch wait assumed 0            (the "-lower" ablation)                */
+       PARD_SUB_UPPER = 2,       /* batch wait assumed sum d_i      (the "-upper" ablation)                */
+       PARD_SUB_SF = 3,          /* sum d_i only: ignores Q and W of later modules ("-sf")                 */
+       PARD_SUB_BACK = 4 };      /* 0: preceding and current modules only ("-back")                        */
+
+#define PARD_MAX_WAIT_SAMPLES 16384        /* samples of the arrival process, at most                     */
+#define PARD_MAX_WAIT_LATENCY (1 << 25)    /* the sampled variant needs every latency entry <= this       */
+
+/*
+ * Queue lengths: d_qlen[u*S + s] = number of requests of snapshot u whose (clamped) stage is
+ * s - the monitored queue state the State Planner works from (Section 4.1, step 1).
+ *
+ *   d_stage, d_snap_ptr    device, as for pard_estimate_drop
+ *   d_qlen                 device out int32[K*S]
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE, PARD_E_HIP.  Enqueues on `stream`, allocates nothing.
+ */
+int pard_queue_lengths(const pard_plan_t* plan, int64_t n, const int32_t* d_stage, const int32_t* d_snap_ptr,
+                       int32_t* d_qlen, void* stream);
+
+/*
+ * The State Planner's part of Eq.(4) (Section 3.2, "Batch wait estimation"): per (snapshot,
+ * stage) the latency of the modules after it, maximum over the downstream DAG paths,
+ *   L_sub = sum q_i + sum d_i + w
+ * with q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i), d_i = lat_i[min(B_i, n_i + 1)], n_i = d_qlen,
+ * and w the lambda-quantile (lambda = lambda_num / lambda_den) of the aggregated batch wait
+ * time, sampled from the collected arrival process: sample j draws for every stage i the
+ * arrival a = max(d_samples[d_picks[j*S + i] mod num_samples], 0), which waits
+ * (d_i - a mod d_i) mod d_i for module i's next batch; the waits of a path's later stages add up
+ * to T_j; w is the ceil(lambda * num_samples)-th smallest T_j (lambda = 0: 0, lambda = 1: sum d_i).
+ * The random draws are the caller's (d_picks); nothing is generated here.
+ *
+ *   variant                PARD_SUB_*; only PARD_SUB_FULL reads lambda, samples and picks
+ *   d_qlen                 device int32[K*S], >= 0 (negative values read as 0)
+ *   num_samples            1..PARD_MAX_WAIT_SAMPLES (the paper's default is 10,000)
+ *   d_samples              device int32[num_samples] arrival times, microseconds
+ *   d_picks                device uint32[num_samples * S]
+ *   d_sub                  device out int64[K*S], microseconds, saturated at 2^40
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE (variant, lambda outside [0,1], sample count),
+ * PARD_E_UNSUPPORTED (PARD_SUB_FULL with a latency entry above PARD_MAX_WAIT_LATENCY), PARD_E_HIP.
+ */
+int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t variant,
+                     int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                     const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream);
+
+/*
+ * pard_estimate_drop with the downstream part given (Eq.(4): the Request Broker adds its own
+ * stage's wait and execution to the State Planner's L_sub):
+ *   est = cost_k(pos) + d_sub[u*S + k]      (d_sub >= 0; values above 2^40 read as 2^40)
+ * Everything else as pard_estimate_drop.
+ */
+int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                           const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                           const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                           int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                           void* d_workspace, int64_t workspace_bytes, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* pard_strerror(int status);
 

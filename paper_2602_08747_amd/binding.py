@@ -24,7 +24,9 @@ STATUS_NAMES = {
     -9: "PARD_E_HIP", -10: "PARD_E_BAD_MODE", -11: "PARD_E_UNSUPPORTED",
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
-           "pard_workspace_bytes", "pard_estimate_drop", "pard_compact", "pard_strerror"]
+           "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_queue_lengths",
+           "pard_sub_latency", "pard_compact", "pard_strerror"]
+SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
 
 
 class PardError(RuntimeError):
@@ -57,6 +59,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_workspace_bytes.argtypes = [vp, i64, i64, ctypes.POINTER(i64)]
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
+    lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
+    lib.pard_queue_lengths.argtypes = [vp, i64, vp, vp, vp, vp]
+    lib.pard_sub_latency.argtypes = [vp, vp, ctypes.c_int32, i64, i64, ctypes.c_int32, vp, vp, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.pard_strerror.argtypes = [ctypes.c_int]
@@ -152,6 +157,37 @@ def pard_estimate_drop(plan: Plan, n: int, max_snapshot_requests: int, arrival, 
     return rc
 
 
+def pard_estimate_drop_sub(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now, sub,
+                           est, drop, order, seg_ptr, workspace, stream=None, check: bool = True) -> int:
+    """pard_estimate_drop with the downstream latency per (snapshot, stage) given."""
+    rc = load_library().pard_estimate_drop_sub(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage), _ptr(snap_ptr),
+        _ptr(now), _ptr(sub), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop_sub")
+    return rc
+
+
+def pard_queue_lengths(plan: Plan, n: int, stage, snap_ptr, qlen, stream=None, check: bool = True) -> int:
+    """Enqueues the queue-length count on `stream`."""
+    rc = load_library().pard_queue_lengths(plan.handle, int(n), _ptr(stage), _ptr(snap_ptr), _ptr(qlen),
+                                           _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_queue_lengths")
+    return rc
+
+
+def pard_sub_latency(plan: Plan, qlen, variant: int, lambda_num: int, lambda_den: int, num_samples: int, samples, picks,
+                     sub, stream=None, check: bool = True) -> int:
+    """Enqueues the downstream-latency kernels on `stream`."""
+    rc = load_library().pard_sub_latency(plan.handle, _ptr(qlen), int(variant), int(lambda_num), int(lambda_den),
+                                         int(num_samples), _ptr(samples), _ptr(picks), _ptr(sub), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_sub_latency")
+    return rc
+
+
 def pard_compact(plan: Plan, n: int, max_snapshot_requests: int, order, seg_ptr, drop, surv_idx, surv_ptr, workspace,
                  stream=None, check: bool = True) -> int:
     """Enqueues the survivor-compaction kernels on `stream`."""
@@ -191,16 +227,32 @@ class Session:
         self.workspace = torch.zeros(self.ws_bytes // 4 + 64, dtype=torch.int32, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
 
-    def estimate_drop(self, stream=None):
-        pard_estimate_drop(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
-                           self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
+    def estimate_drop(self, stream=None, sub=None):
+        if sub is None:
+            pard_estimate_drop(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
+                               self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
+        else:
+            pard_estimate_drop_sub(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage,
+                                   self.snap_ptr, self.now, sub, self.est, self.drop, self.order, self.seg_ptr,
+                                   self.workspace, stream)
+
+    def planner(self, variant=SUB_FULL, lam=(1, 10), samples=None, picks=None, stream=None):
+        """Queue lengths, then the downstream latency per (snapshot, stage) (device int64[K*S])."""
+        torch = self.torch
+        if not hasattr(self, "qlen"):
+            self.qlen = torch.empty(self.w.K * self.w.S, dtype=torch.int32, device=self.dev)
+            self.sub = torch.empty(self.w.K * self.w.S, dtype=torch.int64, device=self.dev)
+        pard_queue_lengths(self.plan, self.n, self.stage, self.snap_ptr, self.qlen, stream)
+        m = 0 if samples is None else int(samples.numel())
+        pard_sub_latency(self.plan, self.qlen, variant, lam[0], lam[1], m, samples, picks, self.sub, stream)
+        return self.sub
 
     def compact(self, stream=None):
         pard_compact(self.plan, self.n, self.max_snap, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
                      self.workspace, stream)
 
-    def run(self, stream=None):
-        self.estimate_drop(stream)
+    def run(self, stream=None, sub=None):
+        self.estimate_drop(stream, sub)
         self.compact(stream)
 
     def status_word(self) -> int:

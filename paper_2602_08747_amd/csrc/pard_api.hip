@@ -65,7 +65,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     const int64_t b_dep = align256((int64_t)h.dag_entry_ptr.size() * 4);
     const int64_t b_est = align256((int64_t)h.entry_stage.size() * 4 + 4);
     const int64_t b_een = align256((int64_t)h.entry_end.size() * 4 + 4);
-    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een;
+    const int64_t b_edg = align256((int64_t)h.entry_dag.size() * 4 + 4);
+    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een + b_edg;
     if (hipGetDevice(&p->device) != hipSuccess || hipMalloc(&p->blob, (size_t)total) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -84,7 +85,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     char* d_dep = put(h.dag_entry_ptr.data(), h.dag_entry_ptr.size() * 4, b_dep);
     char* d_est = put(h.entry_stage.data(), h.entry_stage.size() * 4, b_est);
     char* d_een = put(h.entry_end.data(), h.entry_end.size() * 4, b_een);
-    if (!d_recs || !d_lat || !d_dep || !d_est || !d_een) {
+    char* d_edg = put(h.entry_dag.data(), h.entry_dag.size() * 4, b_edg);
+    if (!d_recs || !d_lat || !d_dep || !d_est || !d_een || !d_edg) {
         (void)hipGetLastError();
         (void)hipFree(p->blob);
         delete p;
@@ -107,6 +109,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     d.dag_entry_ptr = reinterpret_cast<const int32_t*>(d_dep);
     d.entry_stage = reinterpret_cast<const int32_t*>(d_est);
     d.entry_end = reinterpret_cast<const int32_t*>(d_een);
+    d.entry_dag = reinterpret_cast<const int32_t*>(d_edg);
+    d.total_entries = (int64_t)h.entry_stage.size();
     *out = p;
     return PARD_OK;
 }
@@ -136,11 +140,11 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests, int64_t 
     return PARD_OK;
 }
 
-int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
-                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
-                       const int32_t* d_snap_ptr, const int32_t* d_now,
-                       int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
-                       void* d_workspace, int64_t workspace_bytes, void* stream) {
+static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                              const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                              const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                              int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                              void* d_workspace, int64_t workspace_bytes, void* stream) {
     if (!plan || !d_snap_ptr || !d_now || !d_seg_ptr) return PARD_E_NULL;
     if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
@@ -158,6 +162,7 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
         a.arrival = d_arrival; a.deadline = d_deadline; a.stage = d_stage;
         a.snap_ptr = d_snap_ptr; a.now = d_now;
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
+        a.sub = d_sub;
         a.status = status;
         a.cap = (int32_t)max_snapshot_requests;
         a.n = n;
@@ -169,11 +174,70 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
         a.arrival = d_arrival; a.deadline = d_deadline; a.stage = d_stage;
         a.snap_ptr = d_snap_ptr; a.now = d_now;
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
+        a.sub = d_sub;
         a.status = status;
         a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
         a.num_cus = plan->num_cus;
         e = launch_sort_path(a, s);
     }
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                       const int32_t* d_snap_ptr, const int32_t* d_now,
+                       int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                       void* d_workspace, int64_t workspace_bytes, void* stream) {
+    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr,
+                              d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
+}
+
+int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                           const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                           const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                           int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                           void* d_workspace, int64_t workspace_bytes, void* stream) {
+    if (!d_sub) return PARD_E_NULL;
+    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, d_sub,
+                              d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
+}
+
+int pard_queue_lengths(const pard_plan_t* plan, int64_t n, const int32_t* d_stage, const int32_t* d_snap_ptr,
+                       int32_t* d_qlen, void* stream) {
+    if (!plan || !d_snap_ptr || !d_qlen) return PARD_E_NULL;
+    if (n < 0 || n >= ((int64_t)1 << 30)) return PARD_E_BAD_SHAPE;
+    if (n > 0 && !d_stage) return PARD_E_NULL;
+    hipError_t e = launch_queue_lengths(plan->dev, n, d_stage, d_snap_ptr, d_qlen, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t variant,
+                     int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                     const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream) {
+    if (!plan || !d_qlen || !d_sub) return PARD_E_NULL;
+    if (variant < PARD_SUB_FULL || variant > PARD_SUB_BACK) return PARD_E_BAD_SHAPE;
+    SubArgs a{};
+    a.plan = plan->dev;
+    a.qlen = d_qlen;
+    a.variant = variant;
+    a.sub = reinterpret_cast<unsigned long long*>(d_sub);
+    if (variant == PARD_SUB_FULL) {
+        if (lambda_den <= 0 || lambda_num < 0 || lambda_num > lambda_den) return PARD_E_BAD_SHAPE;
+        if (lambda_num == 0) a.variant = PARD_SUB_LOWER;                 // F^-1(0) = 0
+        else if (lambda_num == lambda_den) a.variant = PARD_SUB_UPPER;   // F^-1(1) = sum d_i
+        else {
+            if (num_samples < 1 || num_samples > PARD_MAX_WAIT_SAMPLES) return PARD_E_BAD_SHAPE;
+            if (!d_samples || !d_picks) return PARD_E_NULL;
+            if (plan->host.max_lat > PARD_MAX_WAIT_LATENCY) return PARD_E_UNSUPPORTED;
+            // ceil(lambda * M), in 1..M
+            const unsigned __int128 num = (unsigned __int128)lambda_num * (unsigned)num_samples + (unsigned __int128)(lambda_den - 1);
+            a.rank = (int64_t)(num / (unsigned __int128)lambda_den);
+            a.num_samples = num_samples;
+            a.samples = d_samples;
+            a.picks = d_picks;
+        }
+    }
+    hipError_t e = launch_sub_latency(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
@@ -213,7 +277,7 @@ const char* pard_strerror(int status) {
         case PARD_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case PARD_E_HIP: return "HIP runtime error";
         case PARD_E_BAD_MODE: return "unknown order mode";
-        case PARD_E_UNSUPPORTED: return "request-index bits plus segment-id bits exceed 32 for the large-snapshot path";
+        case PARD_E_UNSUPPORTED: return "outside what this build supports: index bits plus queue-id bits above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
         default: return "unknown status";
     }
 }

@@ -22,6 +22,8 @@ struct PlanDev {
     const int32_t* dag_entry_ptr;      // [D+1]
     const int32_t* entry_stage;        // [E]
     const int32_t* entry_end;          // [E]
+    const int32_t* entry_dag;          // [E]
+    int64_t total_entries;             // E
 };
 
 // Status bits a kernel may raise in the workspace's status word.
@@ -110,6 +112,7 @@ struct FusedArgs {
     int32_t *est;
     uint8_t* drop;
     int32_t *order, *seg_ptr;
+    const int64_t* sub;                // [K*S] downstream latency per (snapshot, stage), or null: walk the paths
     uint32_t* status;
     int32_t cap;                       // promised bound on a snapshot's size
     int64_t n;                         // total requests (bounds every index derived from snap_ptr)
@@ -123,6 +126,7 @@ struct SortArgs {
     int32_t* est;
     uint8_t* drop;
     int32_t *order, *seg_ptr;
+    const int64_t* sub;                // as in FusedArgs
     uint32_t* status;
     void* workspace;                   // sort_workspace_bytes(K, S, n) bytes, 256-byte aligned
     int32_t num_cus;
@@ -146,5 +150,23 @@ struct CompactArgs {
 int compact_blocks_per_cu();
 int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
+
+// ---- State Planner side (pard_planner.hip) ------------------------------------------
+constexpr int kMaxWaitSamples = 16384;             // samples of the arrival process one workgroup holds in LDS
+constexpr int32_t kMaxWaitLatency = 1 << 25;       // durations above this are not sampled (sums of 64 must fit 32 bits)
+
+hipError_t launch_queue_lengths(const PlanDev& plan, int64_t n, const int32_t* stage, const int32_t* snap_ptr,
+                                int32_t* qlen, hipStream_t stream);
+struct SubArgs {
+    PlanDev plan;
+    const int32_t* qlen;               // [K*S]
+    int32_t variant;                   // PARD_SUB_*
+    int64_t rank;                      // 1-based order statistic of the sampled totals (full variant)
+    int32_t num_samples;
+    const int32_t* samples;            // [num_samples]
+    const uint32_t* picks;             // [num_samples * S]
+    unsigned long long* sub;           // [K*S] out
+};
+hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream);
 
 }  // namespace pard

@@ -245,8 +245,13 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     }
     __syncthreads();
 
-    // ---- 4. downstream maximum per stage over the path CSR ---------------------------
-    if (entries_cached && !wide) {
+    // ---- 4. downstream maximum per stage over the path CSR (or as given) ---------------
+    if (A.sub) {
+        if (tid < S) {
+            const int64_t v = A.sub[(int64_t)u * S + tid];
+            L.down[tid] = v < 0 ? 0ull : ((uint64_t)v < kCostCap ? (unsigned long long)v : (unsigned long long)kCostCap);
+        }
+    } else if (entries_cached && !wide) {
         const uint32_t* ent = aux + S * PARD_LAT_ENTRIES;         // stage | (end of the entry's path) << 8
         for (int e = tid; e < n_entries; e += T) {
             const uint32_t me = ent[e];

@@ -75,6 +75,8 @@ struct HostPlan {
     std::vector<int32_t> dag_entry_ptr;     // [D+1]   first path entry of each DAG
     std::vector<int32_t> entry_stage;       // [E]     stage ids along the paths
     std::vector<int32_t> entry_end;         // [E]     one past the last entry of the entry's path
+    std::vector<int32_t> entry_dag;         // [E]     the DAG an entry belongs to
+    int32_t max_lat = 0;                    // largest latency-table entry
 };
 
 // Validates one DAG and appends its source-to-sink paths.  Returns a pard_status.
@@ -175,6 +177,7 @@ inline int build_host_plan(const pard_plan_desc_t* d, HostPlan& hp) {
                                       1.0f / (float)B, 1.0f / (float)W, aW, bW};
     }
     hp.uniform_mode = uniform ? first_mode : -1;
+    for (int32_t v : hp.lat) if (v > hp.max_lat) hp.max_lat = v;
     hp.dag_path_ptr.assign(1, 0);
     hp.dag_entry_ptr.assign(1, 0);
     hp.path_ptr.assign(1, 0);
@@ -186,6 +189,7 @@ inline int build_host_plan(const pard_plan_desc_t* d, HostPlan& hp) {
         col_base += rp[S];
         hp.dag_path_ptr.push_back((int32_t)(hp.path_ptr.size() - 1));
         hp.dag_entry_ptr.push_back((int32_t)hp.entry_stage.size());
+        hp.entry_dag.resize(hp.entry_stage.size(), g);
         if (hp.entry_stage.size() > (size_t)0x7fffffff - PARD_MAX_PATH_ENTRIES_PER_DAG) return PARD_E_TOO_MANY_PATHS;
     }
     return PARD_OK;

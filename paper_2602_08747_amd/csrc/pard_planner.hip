@@ -1,0 +1,269 @@
+// The State Planner's part of the estimate (paper Section 3.2, Eq.(4) and "Batch wait
+// estimation"): per (snapshot, stage), the latency of the modules after it,
+//   L_sub = sum q_i + sum d_i + w,   maximum over the downstream DAG paths,
+// with w the lambda-quantile of the aggregated batch wait time obtained by sampling the
+// collected arrival process, and the ablation variants that replace w or drop terms
+// (Section 5.1 baseline table, Section 5.3).  Also the queue lengths those terms depend on.
+//
+//   q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i),  d_i = lat_i[min(B_i, n_i+1)],  n_i queued at stage i
+//   sample j, stage i: arrival a = max(samples[picks[j*S+i] mod M], 0) waits (d_i - a mod d_i) mod d_i
+//   for the module's next batch (batches back to back, boundaries at multiples of d_i)
+//   T_j = sum over the later stages of the path; w = rank-th smallest T_j (rank = ceil(lambda*M)).
+#include "pard_device.hpp"
+
+namespace pard {
+
+namespace {
+
+constexpr uint64_t kSubCap = (uint64_t)1 << 40;
+
+// ---- queue lengths ---------------------------------------------------------------------
+constexpr int kQThreads = 256;
+constexpr int kQChunk = 4096;                          // requests per workgroup
+constexpr int kQBins = 4096;                           // LDS counters per workgroup
+
+__global__ void fill_zero_kernel(unsigned long long* p, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0ull;
+}
+__global__ void fill_zero32_kernel(int32_t* p, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+// snapshot of request r among snapshots [lo, hi]: the u with snap_ptr[u] <= r < snap_ptr[u+1]
+__device__ __forceinline__ int32_t snapshot_in(const int32_t* snap_ptr, int32_t lo, int32_t hi, int64_t r) {
+    int32_t a = lo, b = hi + 1;                        // answer in [a, b)
+    while (b - a > 1) {
+        const int32_t mid = (a + b) >> 1;
+        if ((int64_t)snap_ptr[mid] <= r) a = mid; else b = mid;
+    }
+    return a;
+}
+
+// A workgroup counts 4096 consecutive requests.  They belong to a contiguous range of
+// snapshots; when that range's (snapshot, stage) pairs fit the LDS counters, counting happens
+// there (each counter replicated so that the lanes of a wave spread over copies) and only
+// the non-zero sums go to global memory.
+__global__ __launch_bounds__(kQThreads) void queue_lengths_kernel(int32_t K, int32_t S, int64_t n, const int32_t* stage,
+                                                                  const int32_t* snap_ptr, int32_t* qlen) {
+    __shared__ uint32_t bins[kQBins];
+    __shared__ int32_t s_range[2];
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kQChunk;
+    const int64_t end = base + kQChunk < n ? base + kQChunk : n;
+    if (tid == 0) {
+        s_range[0] = snapshot_in(snap_ptr, 0, K - 1, base);
+        s_range[1] = snapshot_in(snap_ptr, 0, K - 1, end - 1);
+    }
+    __syncthreads();
+    const int32_t u_lo = s_range[0], u_hi = s_range[1];
+    const int64_t window = ((int64_t)u_hi - u_lo + 1) * S;
+    const bool local = window <= kQBins;
+    int copies = 1;                                    // power of two, copies * window <= kQBins, at most 32
+    if (local) while (copies < 32 && (int64_t)copies * 2 * window <= kQBins) copies *= 2;
+    if (local) for (int i = tid; i < copies * (int)window; i += kQThreads) bins[i] = 0;
+    __syncthreads();
+    for (int64_t r = base + tid; r < end; r += kQThreads) {
+        const int32_t u = snapshot_in(snap_ptr, u_lo, u_hi, r);
+        const int32_t s = clamp_stage(stage[r], S);
+        if (local) atomicAdd(&bins[((u - u_lo) * S + s) * copies + (tid & (copies - 1))], 1u);
+        else atomicAdd(&qlen[(int64_t)u * S + s], 1);
+    }
+    __syncthreads();
+    if (local)
+        for (int g = tid; g < (int)window; g += kQThreads) {
+            uint32_t sum = 0;
+            for (int c = 0; c < copies; ++c) sum += bins[g * copies + c];
+            if (sum) atomicAdd(&qlen[(int64_t)u_lo * S + g], (int32_t)sum);
+        }
+}
+
+// ---- downstream latency ----------------------------------------------------------------
+// (snapshot, path entry) of work item b: with one shared DAG every snapshot has the same
+// entries; otherwise entry e belongs to snapshot entry_dag[e].
+__device__ __forceinline__ bool entry_of(const PlanDev& P, int64_t b, int32_t& u, int32_t& e) {
+    if (P.shared) {
+        const int64_t per = P.dag_entry_ptr[1];
+        if (per <= 0 || b >= per * P.K) return false;
+        u = (int32_t)(b / per);
+        e = (int32_t)(b % per);
+    } else {
+        if (b >= P.total_entries) return false;
+        e = (int32_t)b;
+        u = P.entry_dag[e];
+    }
+    return true;
+}
+
+// q_i + d_i (clamped at 2^40 like every stage cost) and d_i of stage i with n queued
+__device__ __forceinline__ void stage_terms(const PlanDev& P, int32_t u, int32_t i, const int32_t* qlen,
+                                            uint64_t& cost, uint32_t& dur) {
+    const int64_t rec = (P.shared ? 0 : (int64_t)u * P.S) + i;
+    const StageRec r = P.recs[rec];
+    const int32_t q = qlen[(int64_t)u * P.S + i];
+    const uint32_t n = q > 0 ? (uint32_t)q : 0u;
+    const int32_t* lat_row = P.lat + rec * PARD_LAT_ENTRIES;
+    cost = stage_cost(r, n, lat_row);
+    dur = (uint32_t)lat_row[(n + 1u < (uint32_t)r.B ? n + 1u : (uint32_t)r.B) - 1u];
+}
+
+// Variants without sampling: one thread per (snapshot, path entry).
+__global__ __launch_bounds__(256) void sub_simple_kernel(SubArgs A, int64_t items) {
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= items) return;
+    const PlanDev& P = A.plan;
+    int32_t u, e;
+    if (!entry_of(P, b, u, e)) return;
+    const int32_t k = P.entry_stage[e], end = P.entry_end[e];
+    uint64_t sum_qd = 0, sum_d = 0;
+    for (int32_t t = e + 1; t < end; ++t) {
+        uint64_t c;
+        uint32_t d;
+        stage_terms(P, u, P.entry_stage[t], A.qlen, c, d);
+        sum_qd += c;
+        sum_d += d;
+    }
+    uint64_t v = sum_qd;                                        // PARD_SUB_LOWER
+    if (A.variant == PARD_SUB_UPPER) v = sum_qd + sum_d;
+    else if (A.variant == PARD_SUB_SF) v = sum_d;
+    if (v > kSubCap) v = kSubCap;
+    if (v) atomicMax(&A.sub[(int64_t)u * P.S + k], (unsigned long long)v);
+}
+
+// The sampled variant: one workgroup per (snapshot, path entry).
+constexpr int kWThreads = 256;
+constexpr int kWWaves = kWThreads / kWave;
+constexpr int kSelBits = 11;                            // radix-select digits: 11 + 11 + 10 bits
+constexpr int kSelBins = 1 << kSelBits;
+
+struct WaitLds {
+    uint32_t hist[kSelBins];
+    uint32_t dur[PARD_MAX_STAGES], mul[PARD_MAX_STAGES], shf[PARD_MAX_STAGES];
+    int32_t stg[PARD_MAX_STAGES];
+    unsigned long long sum_qd;
+    uint32_t wave_tot[kWWaves];
+    uint32_t sel_bin, sel_before;
+};
+
+__global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint32_t m_mul, uint32_t m_shf) {
+    extern __shared__ __align__(16) uint32_t totals[];          // [num_samples]
+    __shared__ WaitLds L;
+    const PlanDev& P = A.plan;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int32_t u, e;
+    if (!entry_of(P, blockIdx.x, u, e)) return;
+    const int32_t k = P.entry_stage[e], end = P.entry_end[e];
+    const int len = end - e - 1;                                // stages after k on this path
+    if (len <= 0) return;                                       // nothing downstream: 0, the initial value
+    const uint32_t M = (uint32_t)A.num_samples;
+    if (tid == 0) L.sum_qd = 0ull;
+    __syncthreads();
+    if (tid < len) {
+        const int32_t i = P.entry_stage[e + 1 + tid];
+        uint64_t c;
+        uint32_t d;
+        stage_terms(P, u, i, A.qlen, c, d);
+        atomicAdd(&L.sum_qd, (unsigned long long)c);
+        // multiply-high constants for x mod d (Granlund & Montgomery, N = 32), d >= 1
+        uint32_t mul = 0, shf = 0;
+        if (d > 0) {
+            const uint32_t l = d > 1 ? 32u - (uint32_t)__clz((int)(d - 1u)) : 0u;      // ceil(log2 d)
+            mul = (uint32_t)(wide_div((((uint64_t)1 << l) - d) << 32, d) + 1u);
+            shf = (l < 1u ? l : 1u) | ((l > 0u ? l - 1u : 0u) << 8);
+        }
+        L.dur[tid] = d; L.mul[tid] = mul; L.shf[tid] = shf; L.stg[tid] = i;
+    }
+    __syncthreads();
+    for (uint32_t j = tid; j < M; j += kWThreads) {
+        uint32_t total = 0;
+        for (int l = 0; l < len; ++l) {
+            const uint32_t d = L.dur[l];
+            if (d == 0) continue;
+            const uint32_t pick = A.picks[(int64_t)j * P.S + L.stg[l]];
+            const uint32_t idx = pick - magic_div_dev(pick, m_mul, m_shf) * M;
+            const int32_t a = A.samples[idx];
+            const uint32_t au = a > 0 ? (uint32_t)a : 0u;
+            const uint32_t rem = au - magic_div_dev(au, L.mul[l], L.shf[l]) * d;
+            total += rem ? d - rem : 0u;
+        }
+        totals[j] = total;
+    }
+    // rank-th smallest total: three rounds of counting by digit, most significant first
+    uint32_t rank = (uint32_t)A.rank, prefix = 0;
+    for (int round = 0; round < 3; ++round) {
+        const int shift = round == 0 ? 21 : (round == 1 ? 10 : 0);
+        const int bits = round == 2 ? 10 : kSelBits;
+        for (int i = tid; i < kSelBins; i += kWThreads) L.hist[i] = 0;
+        __syncthreads();
+        for (uint32_t j = tid; j < M; j += kWThreads) {
+            const uint32_t v = totals[j];
+            if (round == 0 || (v >> (shift + bits)) == prefix) atomicAdd(&L.hist[(v >> shift) & ((1u << bits) - 1u)], 1u);
+        }
+        __syncthreads();
+        // thread t owns bins 8t..8t+7: find the bin that holds the rank-th candidate
+        uint32_t h[kSelBins / kWThreads], mine = 0;
+#pragma unroll
+        for (int i = 0; i < kSelBins / kWThreads; ++i) { h[i] = L.hist[tid * (kSelBins / kWThreads) + i]; mine += h[i]; }
+        uint32_t inc = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(inc, off);
+            if (lane >= off) inc += t;
+        }
+        if (lane == 63) L.wave_tot[wave] = inc;
+        __syncthreads();
+        uint32_t before = inc - mine;
+        for (int w = 0; w < wave; ++w) before += L.wave_tot[w];
+        if (rank > before && rank <= before + mine) {            // exactly one thread
+            uint32_t run = before;
+#pragma unroll
+            for (int i = 0; i < kSelBins / kWThreads; ++i) {
+                if (rank > run && rank <= run + h[i]) { L.sel_bin = (uint32_t)(tid * (kSelBins / kWThreads) + i); L.sel_before = run; }
+                run += h[i];
+            }
+        }
+        __syncthreads();
+        prefix = (prefix << bits) | L.sel_bin;
+        rank -= L.sel_before;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        uint64_t v = L.sum_qd + prefix;
+        if (v > kSubCap) v = kSubCap;
+        if (v) atomicMax(&A.sub[(int64_t)u * P.S + k], (unsigned long long)v);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_queue_lengths(const PlanDev& plan, int64_t n, const int32_t* stage, const int32_t* snap_ptr,
+                                int32_t* qlen, hipStream_t stream) {
+    const int64_t segs = (int64_t)plan.K * plan.S;
+    int zb = (int)((segs + 255) / 256);
+    if (zb > 1024) zb = 1024;
+    fill_zero32_kernel<<<zb, 256, 0, stream>>>(qlen, segs);
+    if (n > 0) {
+        const int64_t grid = (n + kQChunk - 1) / kQChunk;
+        queue_lengths_kernel<<<(unsigned)grid, kQThreads, 0, stream>>>(plan.K, plan.S, n, stage, snap_ptr, qlen);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream) {
+    const PlanDev& P = a.plan;
+    const int64_t segs = (int64_t)P.K * P.S;
+    int zb = (int)((segs + 255) / 256);
+    if (zb > 1024) zb = 1024;
+    fill_zero_kernel<<<zb, 256, 0, stream>>>(a.sub, segs);
+    if (a.variant == PARD_SUB_BACK) return hipGetLastError();
+    const int64_t items = P.shared ? (int64_t)P.K * P.max_entries_per_dag : P.total_entries;
+    if (items <= 0) return hipGetLastError();
+    if (a.variant != PARD_SUB_FULL) {
+        sub_simple_kernel<<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(a, items);
+    } else {
+        const Magic32 mm = magic_u32((uint32_t)a.num_samples);
+        sub_quantile_kernel<<<(unsigned)items, kWThreads, (size_t)a.num_samples * 4, stream>>>(a, mm.m, mm.sh);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pard

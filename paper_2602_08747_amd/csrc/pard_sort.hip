@@ -88,6 +88,7 @@ struct SortDev {                    // everything the sort kernels need, by valu
     int32_t* est;
     uint8_t* drop;
     int32_t *order, *seg_ptr;
+    const int64_t* sub;
     uint32_t* status_word;
     SortParams* params;
     uint32_t* seg_count;
@@ -336,7 +337,14 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     }
     __threadfence_block();
     __syncthreads();
-    // downstream maximum per (snapshot, stage): suffix sums along every path
+    // downstream maximum per (snapshot, stage): as given, or suffix sums along every path
+    if (A.sub) {
+        for (int64_t g = tid; g < segs; g += 1024) {
+            const int64_t v = A.sub[g];
+            A.down[g] = v < 0 ? 0ull : ((uint64_t)v < kCostCap ? (unsigned long long)v : (unsigned long long)kCostCap);
+        }
+        return;
+    }
     for (int32_t u = 0; u < P.K; ++u) {
         const int32_t dag = P.shared ? 0 : u;
         const int32_t e_lo = P.dag_entry_ptr[dag], e_hi = P.dag_entry_ptr[dag + 1];
@@ -812,6 +820,7 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.arrival = a.arrival; D.deadline = a.deadline; D.stage = a.stage;
     D.snap_ptr = a.snap_ptr; D.now = a.now;
     D.est = a.est; D.drop = a.drop; D.order = a.order; D.seg_ptr = a.seg_ptr;
+    D.sub = a.sub;
     D.status_word = a.status;
     D.params = reinterpret_cast<SortParams*>(ws + L.params);
     D.seg_count = reinterpret_cast<uint32_t*>(ws + L.seg_count);

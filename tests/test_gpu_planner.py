@@ -1,0 +1,169 @@
+"""GPU parity of the State Planner side: queue lengths, downstream latency with the sampled
+batch-wait quantile and its variants, and the estimate that takes it (C-ABI vs the CPU oracle,
+bit for bit)."""
+import numpy as np
+import pytest
+
+from paper_2602_08747_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+FORCE_SORT = 1 << 20
+KEYS = ("est", "drop", "order", "seg_ptr", "surv_idx", "surv_ptr")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU and the built libpard.so")
+    from paper_2602_08747_amd import binding
+    binding.load_library()
+    return binding
+
+
+def draws(seed, M, S, span, negatives=False):
+    rng = np.random.default_rng(seed)
+    samples = rng.integers(-1000 if negatives else 0, span, M).astype(np.int32)
+    picks = rng.integers(0, 2**32, M * S, dtype=np.uint64).astype(np.uint32)
+    return samples, picks
+
+
+def workloads():
+    yield wl.make_workload(5, n_snapshots=40, per_snapshot=3000, permute=True)          # own DAG per snapshot
+    yield wl.random_workload(11, K=7, S=9, n_per_snapshot=400, dag_shared=1)           # one DAG, several snapshots
+    yield wl.make_workload(4, n_requests=200001, permute=True)                          # 12 stages, 16 paths
+    yield wl.make_workload(1)
+    w = wl.random_workload(12, K=5, S=6, n_per_snapshot=9000, dag_shared=0)             # ragged, some large
+    yield w
+
+
+def oracle_qlen(w):
+    out = np.zeros(w.K * w.S, np.int32)
+    for u in range(w.K):
+        lo, hi = int(w.snap_ptr[u]), int(w.snap_ptr[u + 1])
+        out[u * w.S:(u + 1) * w.S] = np.bincount(np.clip(w.stage[lo:hi], 0, w.S - 1), minlength=w.S)
+    return out
+
+
+def test_queue_lengths(gpu):
+    import torch
+    cases = list(workloads())
+    cases.append(wl.make_workload(5, n_snapshots=3000, per_snapshot=1))                 # more queues per chunk than LDS counters
+    cases.append(wl.make_workload(3, n_requests=0))
+    w = wl.make_workload(1, n_requests=5000)
+    w.stage[::7] = -3
+    w.stage[3::11] = 99
+    cases.append(w)
+    for w in cases:
+        print("case", w.name, w.n, w.K, w.S, flush=True)
+        s = gpu.Session(w)
+        qlen = torch.full((w.K * w.S,), -1, dtype=torch.int32, device=s.dev)
+        gpu.pard_queue_lengths(s.plan, w.n, s.stage, s.snap_ptr, qlen)
+        torch.cuda.synchronize()
+        assert np.array_equal(qlen.cpu().numpy(), oracle_qlen(w))
+
+
+@pytest.mark.parametrize("which", range(5))
+def test_sub_latency_variants(gpu, oracle_mod, which):
+    import torch
+    w = list(workloads())[which]
+    s = gpu.Session(w)
+    qlen = oracle_qlen(w)
+    plan_args = (w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, qlen)
+    d_qlen = torch.from_numpy(qlen).to(s.dev)
+    d_sub = torch.empty(w.K * w.S, dtype=torch.int64, device=s.dev)
+    for variant in (gpu.SUB_LOWER, gpu.SUB_UPPER, gpu.SUB_SF, gpu.SUB_BACK):
+        d_sub.fill_(-5)
+        gpu.pard_sub_latency(s.plan, d_qlen, variant, 0, 1, 0, None, None, d_sub)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_sub.cpu().numpy(), oracle_mod.sub_latency(*plan_args, variant)), variant
+    for M, lam, neg in ((10_000, (1, 10), False), (1, (1, 2), False), (37, (36, 37), True), (1000, (999, 1000), False),
+                        (16384, (1, 3), True), (513, (0, 1), False), (513, (5, 5), False), (4097, (1, 4097), False)):
+        samples, picks = draws(77 + M, M, w.S, 80_000_000, neg)
+        want = oracle_mod.sub_latency(*plan_args, gpu.SUB_FULL, lam, samples, picks, threads=8)
+        d_sub.fill_(-5)
+        gpu.pard_sub_latency(s.plan, d_qlen, gpu.SUB_FULL, lam[0], lam[1], M, torch.from_numpy(samples).to(s.dev),
+                             torch.from_numpy(picks.view(np.int32)).to(s.dev), d_sub)
+        torch.cuda.synchronize()
+        got = d_sub.cpu().numpy()
+        assert np.array_equal(got, want), (M, lam, np.flatnonzero(got != want)[:5], got[got != want][:5], want[got != want][:5])
+
+
+def test_sub_latency_zero_and_equal_durations(gpu, oracle_mod):
+    """Zero durations are skipped; equal durations give many tied totals (rank inside a run of equal values)."""
+    import torch
+    w = wl.make_workload(3, n_requests=3000)
+    w.lat_us[:] = 4096
+    w.lat_us[64:128] = 0
+    s = gpu.Session(w)
+    qlen = oracle_qlen(w)
+    M = 2000
+    samples = (np.arange(M, dtype=np.int32) % 7) * 1024        # only 7 distinct arrivals: waits in {0, 1024, ...}
+    picks = np.random.default_rng(5).integers(0, 2**32, M * w.S, dtype=np.uint64).astype(np.uint32)
+    d_sub = torch.empty(w.K * w.S, dtype=torch.int64, device=s.dev)
+    for lam in ((1, 10), (1, 2), (9, 10)):
+        want = oracle_mod.sub_latency(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, qlen,
+                                      gpu.SUB_FULL, lam, samples, picks)
+        gpu.pard_sub_latency(s.plan, torch.from_numpy(qlen).to(s.dev), gpu.SUB_FULL, lam[0], lam[1], M,
+                             torch.from_numpy(samples).to(s.dev), torch.from_numpy(picks.view(np.int32)).to(s.dev), d_sub)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_sub.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_estimate_with_planner_output(gpu, oracle_mod, max_snap):
+    """Queue lengths -> L_sub -> estimate, drop, compaction, all on the GPU, against the oracle chain."""
+    import torch
+    for w in (wl.make_workload(5, n_snapshots=23, per_snapshot=5000, permute=True),
+              wl.random_workload(21, K=3, S=7, n_per_snapshot=2500, dag_shared=1)):
+        w.now[:] = np.maximum(0, w.now.astype(np.int64) - 250000).astype(np.int32)
+        M = 10_000
+        samples, picks = draws(9, M, w.S, 60_000_000)
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
+        d_samples = torch.from_numpy(samples).to(s.dev)
+        d_picks = torch.from_numpy(picks.view(np.int32)).to(s.dev)
+        qlen = oracle_qlen(w)
+        for variant, lam in ((gpu.SUB_FULL, (1, 10)), (gpu.SUB_UPPER, (0, 1)), (gpu.SUB_BACK, (0, 1)), (gpu.SUB_LOWER, (0, 1))):
+            sub = s.planner(variant, lam, d_samples, d_picks)
+            s.run(sub=sub)
+            got = s.results()
+            want_sub = oracle_mod.sub_latency(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us,
+                                              qlen, variant, lam, samples, picks, threads=8)
+            assert np.array_equal(s.sub.cpu().numpy(), want_sub)
+            est, drop, order, seg_ptr = oracle_mod.estimate_drop(
+                w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, w.order_mode,
+                w.arrival, w.deadline, w.stage, w.snap_ptr, w.now, threads=8, sub=want_sub)
+            surv_idx, surv_ptr = oracle_mod.compact(w.K, w.S, order, seg_ptr, drop)
+            ref = dict(est=est, drop=drop, order=order, seg_ptr=seg_ptr, surv_idx=surv_idx, surv_ptr=surv_ptr)
+            for k in KEYS:
+                assert np.array_equal(got[k], ref[k]), (w.name, variant, k)
+            if variant == gpu.SUB_LOWER:                       # the plain call computes the same thing on its own
+                s.run()
+                plain = s.results()
+                for k in KEYS:
+                    assert np.array_equal(plain[k], ref[k]), (w.name, "plain", k)
+            assert s.status_word() == 0
+
+
+def test_planner_error_codes(gpu):
+    import torch
+    w = wl.make_workload(1)
+    s = gpu.Session(w)
+    q = torch.zeros(w.K * w.S, dtype=torch.int32, device=s.dev)
+    sub = torch.zeros(w.K * w.S, dtype=torch.int64, device=s.dev)
+    smp = torch.zeros(16, dtype=torch.int32, device=s.dev)
+    pk = torch.zeros(16 * w.S, dtype=torch.int32, device=s.dev)
+    assert gpu.pard_sub_latency(s.plan, q, 9, 1, 10, 16, smp, pk, sub, check=False) == -2
+    assert gpu.pard_sub_latency(s.plan, q, gpu.SUB_FULL, 11, 10, 16, smp, pk, sub, check=False) == -2
+    assert gpu.pard_sub_latency(s.plan, q, gpu.SUB_FULL, 1, 10, 0, smp, pk, sub, check=False) == -2
+    assert gpu.pard_sub_latency(s.plan, q, gpu.SUB_FULL, 1, 10, 1 << 20, smp, pk, sub, check=False) == -2
+    assert gpu.pard_sub_latency(s.plan, q, gpu.SUB_FULL, 1, 10, 16, None, pk, sub, check=False) == -1
+    assert gpu.pard_sub_latency(s.plan, None, gpu.SUB_LOWER, 0, 1, 0, None, None, sub, check=False) == -1
+    assert gpu.pard_queue_lengths(s.plan, -1, s.stage, s.snap_ptr, q, check=False) == -2
+    w2 = wl.make_workload(1)
+    w2.lat_us[5] = (1 << 25) + 1
+    s2 = gpu.Session(w2)
+    assert gpu.pard_sub_latency(s2.plan, q, gpu.SUB_FULL, 1, 10, 16, smp, pk, sub, check=False) == -11
+    assert gpu.pard_sub_latency(s2.plan, q, gpu.SUB_UPPER, 1, 10, 16, smp, pk, sub, check=False) == 0
+    torch.cuda.synchronize()
