@@ -18,16 +18,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 
-# Algorithmic bytes per request of the estimate+drop call:
+INT_ALU_PEAK_TOPS = 39.3     # 256 CUs x 64 integer lanes per clock x 2.4 GHz (fp32 FMA peak 157.3 = this x 2 x 2)
+
+# Algorithmic bytes per request of the estimate+drop call (what the method must move, not
+# what this implementation moves):
 #   read deadline 4 + stage 4 (+ arrival 4 under FCFS); write est 4 + drop 1 + order 4.
 # On-chip path (snapshots <= 8192 requests): that is all, 17 B/request.
-# Radix-sort path: + count pass 8, histogram pass 8, (passes-1) * 16 for the key/index
-# ping-pong, + 8 for the epilogue's read of the sorted pairs.
+# Out-of-core sort with p digit passes: every pass but the last moves key + index in and
+# out (16 B), the last one is read once more (8 B) and leaves the outputs:
+#   8 + 16 (p - 1) + 8 + 9  B/request.
 def estimate_drop_bytes_per_request(fused: bool, passes: int, fcfs: bool) -> float:
     io = 8 + 9 + (4 if fcfs else 0)
     if fused:
         return float(io)
-    return float(io + 8 + 8 + 16 * (passes - 1) + 8 + 8)   # last +8: final pass writes pairs
+    return float(io + 16 * (passes - 1) + 8)
 
 
 def recorded_traffic(workload_cfg: int, kernel: str, source: str):
@@ -46,6 +50,105 @@ def recorded_traffic(workload_cfg: int, kernel: str, source: str):
     return None
 
 
+def suffix_lengths(S, row_ptr, col):
+    """For one DAG: the number of later stages of every (source-to-sink path, position) pair."""
+    succ = [[int(col[e]) for e in range(int(row_ptr[v]), int(row_ptr[v + 1]))] for v in range(S)]
+    indeg = [0] * S
+    for v in range(S):
+        for t in succ[v]:
+            indeg[t] += 1
+    lens = []
+
+    def walk(v, depth):
+        if not succ[v]:
+            lens.extend(range(depth, -1, -1))         # a path of depth+1 stages: suffixes of depth, ..., 0 stages
+        for t in succ[v]:
+            walk(t, depth + 1)
+
+    for v in range(S):
+        if indeg[v] == 0:
+            walk(v, 0)
+    return lens
+
+
+def bench_planner(args, w, s, gen_s):
+    """Queue lengths + L_sub (sampled variant, M = 10,000, lambda = 0.1) per step."""
+    import numpy as np
+    import torch
+    from paper_2602_08747_amd import binding
+    M, lam = 10_000, (1, 10)
+    rng = np.random.default_rng([20260208, 99])
+    samples = np.cumsum(np.floor(rng.exponential(20.0, M))).astype(np.int32)          # a 50k/s arrival process
+    picks = rng.integers(0, 2**32, M * w.S, dtype=np.uint64).astype(np.uint32)
+    d_samples = torch.from_numpy(samples).to(s.dev)
+    d_picks = torch.from_numpy(picks.view(np.int32)).to(s.dev)
+    for _ in range(max(args.warmup, 1)):
+        s.planner(binding.SUB_FULL, lam, d_samples, d_picks)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b, c in ev:
+        a.record()
+        binding.pard_queue_lengths(s.plan, s.n, s.stage, s.snap_ptr, s.qlen)
+        b.record()
+        binding.pard_sub_latency(s.plan, s.qlen, binding.SUB_FULL, lam[0], lam[1], M, d_samples, d_picks, s.sub)
+        c.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    q_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in ev]))
+    sub_ms = float(np.mean([b.elapsed_time(c) for _, b, c in ev]))
+    # integer operations the sampling itself needs: per (path entry, sample) one draw reduced mod M,
+    # one arrival reduced mod d, one complement and one add per later stage, plus three counting rounds
+    D = 1 if w.dag_shared else w.K
+    ops_per_sample = 0
+    entries = 0
+    col_base = 0
+    for d in range(D):
+        rp = w.dag_row_ptr[d * (w.S + 1):(d + 1) * (w.S + 1)]
+        lens = suffix_lengths(w.S, rp, w.dag_col[col_base:col_base + int(rp[w.S])])
+        col_base += int(rp[w.S])
+        mult = w.K if w.dag_shared else 1
+        entries += mult * sum(1 for x in lens if x > 0)
+        ops_per_sample += mult * sum(4 * x + 3 for x in lens if x > 0)
+    ops = float(ops_per_sample) * M
+    achieved = ops / (sub_ms * 1e-3) / 1e12 if sub_ms > 0 else 0.0
+    out = {
+        "metric": "downstream-latency evaluations/sec (queue lengths + L_sub with sampled batch-wait quantile)",
+        "value": round(w.K * w.S / (ms_per_step * 1e-3), 1), "unit": "snapshot-stages/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": w.name + "+planner", "requests": w.n, "snapshots": w.K, "stages": w.S,
+                   "samples": M, "lambda": "1/10", "path_entries_with_later_stages": entries,
+                   "queue_lengths_ms": round(q_ms, 4), "sub_latency_ms": round(sub_ms, 4), "generate_s": round(gen_s, 2)},
+        "roofline": {"bound": "alu", "achieved": round(achieved, 3), "peak": INT_ALU_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(achieved / INT_ALU_PEAK_TOPS, 4), "traffic": None,
+                     "kernel": "sub_quantile_kernel (the pard_sub_latency call: fill + one launch)",
+                     "ops_per_launch": ops, "launch_ms": round(sub_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(os.cpu_count() or 1, 16)
+        oracle.build_oracle()
+        Ks = w.K if w.dag_shared else min(w.K, 64)      # bounded sample: the first snapshots
+        qlen = s.qlen.cpu().numpy()
+        if w.dag_shared:
+            rp, cl, B, W, L = w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us
+        else:
+            rp = w.dag_row_ptr[:Ks * (w.S + 1)]
+            ncol = int(sum(int(rp[d * (w.S + 1) + w.S]) for d in range(Ks)))
+            cl, B, W, L = w.dag_col[:ncol], w.batch[:Ks * w.S], w.workers[:Ks * w.S], w.lat_us[:Ks * w.S * 64]
+        t0 = time.perf_counter()
+        oracle.sub_latency(Ks, w.S, w.dag_shared, rp, cl, B, W, L, qlen[:Ks * w.S], oracle.VARIANT_FULL, lam, samples, picks,
+                           threads=threads)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(Ks * w.S / cpu_s, 1), "unit": "snapshot-stages/s", "cores": threads,
+                               "kind": "oracle", "sample": f"first {Ks} of {w.K} snapshots, 1 run",
+                               "seconds": round(cpu_s, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +157,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--permute", action="store_true", help="shuffle request order inside every snapshot")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["hot-path", "planner"], default="hot-path",
+                    help="hot-path: estimate+drop+compact (default); planner: queue lengths + downstream latency "
+                         "with the sampled batch-wait quantile on the same snapshots")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -77,6 +183,10 @@ def main():
     s = binding.Session(w)
     fused = s.max_snap <= binding.PARD_FUSED_SNAPSHOT_CAPACITY
     n = w.n
+
+    if args.workload == "planner":
+        print(json.dumps(bench_planner(args, w, s, gen_s)))
+        return
 
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0")

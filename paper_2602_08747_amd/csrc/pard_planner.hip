@@ -132,6 +132,7 @@ __global__ __launch_bounds__(256) void sub_simple_kernel(SubArgs A, int64_t item
 // The sampled variant: one workgroup per (snapshot, path entry).
 constexpr int kWThreads = 256;
 constexpr int kWWaves = kWThreads / kWave;
+constexpr int kWUnroll = 8;                            // samples a thread works on at once
 constexpr int kSelBits = 11;                            // radix-select digits: 11 + 11 + 10 bits
 constexpr int kSelBins = 1 << kSelBits;
 
@@ -140,6 +141,7 @@ struct WaitLds {
     uint32_t dur[PARD_MAX_STAGES], mul[PARD_MAX_STAGES], shf[PARD_MAX_STAGES];
     int32_t stg[PARD_MAX_STAGES];
     unsigned long long sum_qd;
+    uint32_t sum_d;
     uint32_t wave_tot[kWWaves];
     uint32_t sel_bin, sel_before;
 };
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
     const int len = end - e - 1;                                // stages after k on this path
     if (len <= 0) return;                                       // nothing downstream: 0, the initial value
     const uint32_t M = (uint32_t)A.num_samples;
-    if (tid == 0) L.sum_qd = 0ull;
+    if (tid == 0) { L.sum_qd = 0ull; L.sum_d = 0u; }
     __syncthreads();
     if (tid < len) {
         const int32_t i = P.entry_stage[e + 1 + tid];
@@ -163,6 +165,7 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
         uint32_t d;
         stage_terms(P, u, i, A.qlen, c, d);
         atomicAdd(&L.sum_qd, (unsigned long long)c);
+        atomicAdd(&L.sum_d, d);                                 // < 2^32: at most 64 stages of at most 2^25
         // multiply-high constants for x mod d (Granlund & Montgomery, N = 32), d >= 1
         uint32_t mul = 0, shf = 0;
         if (d > 0) {
@@ -173,30 +176,49 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
         L.dur[tid] = d; L.mul[tid] = mul; L.shf[tid] = shf; L.stg[tid] = i;
     }
     __syncthreads();
-    for (uint32_t j = tid; j < M; j += kWThreads) {
-        uint32_t total = 0;
+    // kWUnroll samples per thread and trip, so that their dependent loads (draw, then arrival) overlap
+    for (uint32_t j0 = tid; j0 < M; j0 += kWUnroll * kWThreads) {
+        uint32_t total[kWUnroll];
+#pragma unroll
+        for (int x = 0; x < kWUnroll; ++x) total[x] = 0;
         for (int l = 0; l < len; ++l) {
             const uint32_t d = L.dur[l];
             if (d == 0) continue;
-            const uint32_t pick = A.picks[(int64_t)j * P.S + L.stg[l]];
-            const uint32_t idx = pick - magic_div_dev(pick, m_mul, m_shf) * M;
-            const int32_t a = A.samples[idx];
-            const uint32_t au = a > 0 ? (uint32_t)a : 0u;
-            const uint32_t rem = au - magic_div_dev(au, L.mul[l], L.shf[l]) * d;
-            total += rem ? d - rem : 0u;
+            const uint32_t mul = L.mul[l], shf = L.shf[l];
+            const int32_t col = L.stg[l];
+            uint32_t pick[kWUnroll];
+            int32_t a[kWUnroll];
+#pragma unroll
+            for (int x = 0; x < kWUnroll; ++x) {
+                const uint32_t j = j0 + x * kWThreads;
+                pick[x] = A.picks[(int64_t)(j < M ? j : j0) * P.S + col];
+            }
+#pragma unroll
+            for (int x = 0; x < kWUnroll; ++x) a[x] = A.samples[pick[x] - magic_div_dev(pick[x], m_mul, m_shf) * M];
+#pragma unroll
+            for (int x = 0; x < kWUnroll; ++x) {
+                const uint32_t au = a[x] > 0 ? (uint32_t)a[x] : 0u;
+                const uint32_t rem = au - magic_div_dev(au, mul, shf) * d;
+                total[x] += rem ? d - rem : 0u;
+            }
         }
-        totals[j] = total;
+#pragma unroll
+        for (int x = 0; x < kWUnroll; ++x)
+            if (j0 + x * kWThreads < M) totals[j0 + x * kWThreads] = total[x];
     }
-    // rank-th smallest total: three rounds of counting by digit, most significant first
+    // rank-th smallest total: rounds of counting by 11-bit digit, most significant first.  Every
+    // total is below sum d_i, so the digits start at its top bit: the first round then spreads
+    // the samples over the counters instead of piling them onto counter 0.
     uint32_t rank = (uint32_t)A.rank, prefix = 0;
-    for (int round = 0; round < 3; ++round) {
-        const int shift = round == 0 ? 21 : (round == 1 ? 10 : 0);
-        const int bits = round == 2 ? 10 : kSelBits;
+    int hi = 32 - __clz((int)(L.sum_d | 1u));                  // bits of the largest possible total
+    for (int round = 0; hi > 0; ++round) {
+        const int shift = hi > kSelBits ? hi - kSelBits : 0;
+        const int bits = hi - shift;
         for (int i = tid; i < kSelBins; i += kWThreads) L.hist[i] = 0;
         __syncthreads();
         for (uint32_t j = tid; j < M; j += kWThreads) {
             const uint32_t v = totals[j];
-            if (round == 0 || (v >> (shift + bits)) == prefix) atomicAdd(&L.hist[(v >> shift) & ((1u << bits) - 1u)], 1u);
+            if (round == 0 || (v >> (shift + bits)) == prefix) atomicAdd(&L.hist[(v >> shift) & ((1u << bits) - 1u)], 1u);   // round 0: no bits above
         }
         __syncthreads();
         // thread t owns bins 8t..8t+7: find the bin that holds the rank-th candidate
@@ -224,6 +246,7 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
         __syncthreads();
         prefix = (prefix << bits) | L.sel_bin;
         rank -= L.sel_before;
+        hi = shift;
         __syncthreads();
     }
     if (tid == 0) {
