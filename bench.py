@@ -164,8 +164,8 @@ def main():
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (snapshots would shard across GPUs with no "
-              "communication, see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU only (snapshots would shard across GPUs with no "
+              "communication); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

@@ -62,7 +62,7 @@ typedef enum {
     PARD_E_WORKSPACE = -8,       /* workspace NULL, misaligned or too small               */
     PARD_E_HIP = -9,             /* a HIP runtime call failed                             */
     PARD_E_BAD_MODE = -10,       /* order mode not one of PARD_ORDER_*                    */
-    PARD_E_UNSUPPORTED = -11     /* shape outside what this build can sort (see below)    */
+    PARD_E_UNSUPPORTED = -11     /* shape or value range not supported (see the calls)    */
 } pard_status;
 
 enum { PARD_ORDER_LBF = 0,       /* ascending deadline  (low remaining budget first)      */

@@ -277,7 +277,7 @@ const char* pard_strerror(int status) {
         case PARD_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case PARD_E_HIP: return "HIP runtime error";
         case PARD_E_BAD_MODE: return "unknown order mode";
-        case PARD_E_UNSUPPORTED: return "outside what this build supports: index bits plus queue-id bits above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
+        case PARD_E_UNSUPPORTED: return "not supported: index bits plus queue-id bits above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
         default: return "unknown status";
     }
 }
