@@ -209,7 +209,7 @@ static int estimate_drop_impl(
         const int32_t* row_ptr, const int32_t* col,
         const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
         int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
-        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub,
+        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub, int consistent,
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     (void)n;
@@ -262,12 +262,19 @@ static int estimate_drop_impl(
         for (int s = 0; s < S; ++s) seg_ptr[(int64_t)u * S + s] = (int32_t)(lo + qstart[s]);
         for (int64_t j = 0; j < m; ++j) order[lo + j] = q[j].idx;
 
-        /* 4.-6. per request: maximum over the paths through its stage */
-        #pragma omp parallel for schedule(static) num_threads(nthreads)
+        /* 4.-6. per request: maximum over the paths through its stage.
+         * One pass: the position of a request is the number of requests ahead of it in its
+         * queue, dropped or not, so every request can be decided on its own.
+         * Sequentially consistent: the Request Broker takes the requests of a queue in queue
+         * order and a dropped request never takes a batch slot (Section 4.1, the broker's
+         * drop-or-infer step), so the position is the number of requests ahead that were
+         * KEPT; each queue is then a chain of decisions, taken in order. */
+        int64_t* kept = (int64_t*)calloc((size_t)S, sizeof(int64_t));
+        #pragma omp parallel for schedule(static) num_threads(nthreads) if (!consistent)
         for (int64_t j = 0; j < m; ++j) {
             int32_t r = q[j].idx;
             int k = clamp_stage(stage[r], S);
-            int64_t pos = j - qstart[k];                 /* requests ahead of r in its own queue */
+            int64_t pos = consistent ? kept[k] : j - qstart[k];   /* requests ahead of r in its own queue */
             wide_t best = -1;
             if (sub) {
                 /* Eq.(4): the Request Broker's own part plus the State Planner's L_sub */
@@ -290,7 +297,9 @@ static int estimate_drop_impl(
             est[r] = (int32_t)(best > cap ? cap : best);
             if (finish > cap) finish = cap;
             drop[r] = (uint8_t)(finish > (wide_t)deadline[r]);
+            if (consistent && !drop[r]) kept[k] += 1;
         }
+        free(kept);
         free(fill);
         free(q);
         free(qstart);
@@ -311,7 +320,7 @@ int pard_oracle_estimate_drop(
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
-                              snap_ptr, now, NULL, est, drop, order, seg_ptr, nthreads);
+                              snap_ptr, now, NULL, 0, est, drop, order, seg_ptr, nthreads);
 }
 
 /* The same with the downstream part given: est = own-stage cost at the queue position
@@ -325,7 +334,21 @@ int pard_oracle_estimate_drop_sub(
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
-                              snap_ptr, now, sub, est, drop, order, seg_ptr, nthreads);
+                              snap_ptr, now, sub, 0, est, drop, order, seg_ptr, nthreads);
+}
+
+/* Sequentially consistent dropping: as above (sub may be NULL), but a request's position is
+ * the number of requests ahead of it in its queue that were kept. */
+int pard_oracle_estimate_drop_consistent(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
+        int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub,
+        int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
+        int32_t nthreads) {
+    return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
+                              snap_ptr, now, sub, 1, est, drop, order, seg_ptr, nthreads);
 }
 
 /*

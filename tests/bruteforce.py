@@ -21,8 +21,9 @@ def cost(lat, B, W, a):
     return wait + int(lat[min(B, a + 1) - 1])
 
 
-def brute(w):
-    """est, drop, pos for every request of workload w (any K)."""
+def brute(w, consistent=False):
+    """est, drop, pos for every request of workload w (any K).  consistent: a request's position
+    counts only the requests ahead of it that were kept, decided one after the other in queue order."""
     n = w.n
     est = [0] * n
     drop = [0] * n
@@ -56,13 +57,25 @@ def brute(w):
                 best = max(best, cost(L[t], int(B[t]), int(W[t]), qlen[t]) + downstream(t))
             return best
 
-        for i in range(hi - lo):
-            k = stage[i]
-            ahead = sum(1 for j in range(hi - lo)
-                        if stage[j] == k and (key(j), j) < (key(i), i))
-            e = cost(L[k], int(B[k]), int(W[k]), ahead) + downstream(k)
-            pos[lo + i] = ahead
-            est[lo + i] = min(e, INT32_MAX)
-            finish = min(int(w.now[u]) + e, INT32_MAX)
-            drop[lo + i] = 1 if finish > int(w.deadline[lo + i]) else 0
+        if not consistent:
+            for i in range(hi - lo):
+                k = stage[i]
+                ahead = sum(1 for j in range(hi - lo)
+                            if stage[j] == k and (key(j), j) < (key(i), i))
+                e = cost(L[k], int(B[k]), int(W[k]), ahead) + downstream(k)
+                pos[lo + i] = ahead
+                est[lo + i] = min(e, INT32_MAX)
+                finish = min(int(w.now[u]) + e, INT32_MAX)
+                drop[lo + i] = 1 if finish > int(w.deadline[lo + i]) else 0
+        else:
+            for k in range(S):
+                queue = sorted((i for i in range(hi - lo) if stage[i] == k), key=lambda i: (key(i), i))
+                kept = 0
+                for i in queue:
+                    e = cost(L[k], int(B[k]), int(W[k]), kept) + downstream(k)
+                    pos[lo + i] = kept
+                    est[lo + i] = min(e, INT32_MAX)
+                    finish = min(int(w.now[u]) + e, INT32_MAX)
+                    drop[lo + i] = 1 if finish > int(w.deadline[lo + i]) else 0
+                    kept += 1 - drop[lo + i]
     return est, drop, pos
