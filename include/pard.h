@@ -238,6 +238,23 @@ int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snaps
                            int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                            void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Sequentially consistent dropping: the Request Broker takes the requests of a queue in queue
+ * order and decides each one before the next (Section 4.1); a dropped request never takes a
+ * batch slot, so the position that enters a request's own-stage cost is the number of requests
+ * ahead of it in its queue that were KEPT, not all of them.  Everything else as
+ * pard_estimate_drop (d_sub == NULL) or pard_estimate_drop_sub (d_sub given).  d_order and
+ * d_seg_ptr are the same as in the one-pass calls; d_est and d_drop differ.
+ *
+ * Only snapshots of at most PARD_FUSED_SNAPSHOT_CAPACITY requests: a larger
+ * max_snapshot_requests returns PARD_E_UNSUPPORTED.
+ */
+int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                                  const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                                  const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                                  int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                                  void* d_workspace, int64_t workspace_bytes, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* pard_strerror(int status);
 

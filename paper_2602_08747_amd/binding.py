@@ -24,7 +24,8 @@ STATUS_NAMES = {
     -9: "PARD_E_HIP", -10: "PARD_E_BAD_MODE", -11: "PARD_E_UNSUPPORTED",
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
-           "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_queue_lengths",
+           "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
+           "pard_queue_lengths",
            "pard_sub_latency", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
 
@@ -60,6 +61,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
+    lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_queue_lengths.argtypes = [vp, i64, vp, vp, vp, vp]
     lib.pard_sub_latency.argtypes = [vp, vp, ctypes.c_int32, i64, i64, ctypes.c_int32, vp, vp, vp, vp]
     for name in EXPORTS[:-1]:
@@ -169,6 +171,18 @@ def pard_estimate_drop_sub(plan: Plan, n: int, max_snapshot_requests: int, arriv
     return rc
 
 
+def pard_estimate_drop_consistent(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now,
+                                  sub, est, drop, order, seg_ptr, workspace, stream=None, check: bool = True) -> int:
+    """Sequentially consistent dropping (positions count kept requests only); `sub` may be None."""
+    rc = load_library().pard_estimate_drop_consistent(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage), _ptr(snap_ptr),
+        _ptr(now), _ptr(sub), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop_consistent")
+    return rc
+
+
 def pard_queue_lengths(plan: Plan, n: int, stage, snap_ptr, qlen, stream=None, check: bool = True) -> int:
     """Enqueues the queue-length count on `stream`."""
     rc = load_library().pard_queue_lengths(plan.handle, int(n), _ptr(stage), _ptr(snap_ptr), _ptr(qlen),
@@ -227,8 +241,12 @@ class Session:
         self.workspace = torch.zeros(self.ws_bytes // 4 + 64, dtype=torch.int32, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
 
-    def estimate_drop(self, stream=None, sub=None):
-        if sub is None:
+    def estimate_drop(self, stream=None, sub=None, consistent=False):
+        if consistent:
+            pard_estimate_drop_consistent(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage,
+                                          self.snap_ptr, self.now, sub, self.est, self.drop, self.order, self.seg_ptr,
+                                          self.workspace, stream)
+        elif sub is None:
             pard_estimate_drop(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
                                self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
         else:
@@ -251,8 +269,8 @@ class Session:
         pard_compact(self.plan, self.n, self.max_snap, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
                      self.workspace, stream)
 
-    def run(self, stream=None, sub=None):
-        self.estimate_drop(stream, sub)
+    def run(self, stream=None, sub=None, consistent=False):
+        self.estimate_drop(stream, sub, consistent)
         self.compact(stream)
 
     def status_word(self) -> int:

@@ -142,7 +142,7 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests, int64_t 
 
 static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
                               const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
-                              const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                              const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub, bool consistent,
                               int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                               void* d_workspace, int64_t workspace_bytes, void* stream) {
     if (!plan || !d_snap_ptr || !d_now || !d_seg_ptr) return PARD_E_NULL;
@@ -150,7 +150,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
     if (n > 0 && plan->host.any_fcfs && !d_arrival) return PARD_E_NULL;
     const bool fused = max_snapshot_requests <= PARD_FUSED_SNAPSHOT_CAPACITY;
-    if (!fused && !sort_supported(plan->host.K, plan->host.S, n)) return PARD_E_UNSUPPORTED;
+    if (!fused && (consistent || !sort_supported(plan->host.K, plan->host.S, n))) return PARD_E_UNSUPPORTED;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
         workspace_bytes < workspace_need(plan, n, max_snapshot_requests)) return PARD_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -165,6 +165,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         a.sub = d_sub;
         a.status = status;
         a.cap = (int32_t)max_snapshot_requests;
+        a.consistent = consistent ? 1 : 0;
         a.n = n;
         e = launch_fused(a, s);
     } else {
@@ -188,7 +189,7 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
                        const int32_t* d_snap_ptr, const int32_t* d_now,
                        int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                        void* d_workspace, int64_t workspace_bytes, void* stream) {
-    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr,
+    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr, false,
                               d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
 }
 
@@ -198,7 +199,16 @@ int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snaps
                            int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                            void* d_workspace, int64_t workspace_bytes, void* stream) {
     if (!d_sub) return PARD_E_NULL;
-    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, d_sub,
+    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, d_sub, false,
+                              d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
+}
+
+int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                                  const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                                  const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub,
+                                  int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                                  void* d_workspace, int64_t workspace_bytes, void* stream) {
+    return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, d_sub, true,
                               d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
 }
 

@@ -115,6 +115,7 @@ struct FusedArgs {
     const int64_t* sub;                // [K*S] downstream latency per (snapshot, stage), or null: walk the paths
     uint32_t* status;
     int32_t cap;                       // promised bound on a snapshot's size
+    int32_t consistent;                // positions count only the kept requests ahead
     int64_t n;                         // total requests (bounds every index derived from snap_ptr)
 };
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream);

@@ -12,6 +12,10 @@
 //      maximum per stage (the path CSR is walked here)
 //   5. per request: own-stage cost at its queue position + downstream maximum,
 //      drop decision; outputs leave in request order, the queue order via LDS.
+//      Sequentially consistent variant: the position counts only the requests ahead that
+//      were kept (the Request Broker takes a queue in order and a dropped request never
+//      takes a batch slot, Section 4.1), so a queue is a chain of decisions; one wave walks
+//      it 64 requests at a time and settles each group by iterating to the fixed point.
 //
 // Why buckets instead of radix passes: at this data rate the vector ALU, not HBM, limits a
 // sort of 8192 keys per workgroup (about 130 lane-instructions per request at full HBM
@@ -50,7 +54,7 @@ struct SnapshotLds {
 
 // FULL: the snapshot holds exactly kCap requests and every array is 16-byte aligned at its
 // start, so no per-request bounds test is needed.
-template <int T, bool FULL>
+template <int T, bool FULL, bool CONSISTENT>
 __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L, const int u, const int64_t lo,
                                               const int m, const bool aligned) {
     constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
@@ -323,10 +327,72 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
             if (live(base + c)) ord_l[se[g][c] & 0x1FFFu] = (uint16_t)(base + c);
     }
 
+    if (CONSISTENT) {
+        // ---- 5'. decisions in queue order, positions = kept requests ahead -------------------
+        // deadlines by queue slot (L.low is free: every read of the rank phase is behind the barrier above)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int base = (g * T + tid) * 4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (live(base + c)) L.low[se[g][c] & 0x1FFFu] = (uint32_t)dl[g][c];
+        }
+        __syncthreads();
+        for (int k = wave; k < S; k += T / kWave) {            // one wave per queue
+            const int s0 = L.seg_start[k], s1 = L.seg_start[k + 1];
+            const unsigned long long dn = L.down[k];
+            const int32_t* lat_row = lat_dag + k * PARD_LAT_ENTRIES;
+            uint32_t kept = 0;                                  // kept requests of this queue so far (same in every lane)
+            for (int first = s0; first < s1; first += kWave) {
+                const int j = first + lane;
+                const bool ok = j < s1;
+                const int32_t deadline = ok ? (int32_t)L.low[j] : 0;
+                // Guess that all 64 are kept, evaluate everybody at the position that guess implies,
+                // take the decisions as the next guess: after t rounds the first t lanes are final,
+                // and a guess that reproduces itself is the in-order result.
+                unsigned long long keep = __ballot(ok);
+                int32_t est = 0;
+                uint8_t drp = 0;
+                for (int round = 0; round <= kWave; ++round) {
+                    const uint32_t ahead = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(keep >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)keep, 0u));
+                    finish_request(stage_cost_short(L.recs[k], ahead, lat_row) + dn, now, deadline, est, drp);
+                    const unsigned long long next = __ballot(ok && drp == 0);
+                    if (next == keep) break;
+                    keep = next;
+                }
+                if (ok) L.low[j] = (uint32_t)est | ((uint32_t)drp << 31);
+                kept += (uint32_t)__popcll(keep);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int base = (g * T + tid) * 4;
+            int32_t est[4];
+            uint8_t drp[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t v = live(base + c) ? L.low[se[g][c] & 0x1FFFu] : 0u;
+                est[c] = (int32_t)(v & 0x7FFFFFFFu);
+                drp[c] = (uint8_t)(v >> 31);
+            }
+            if (FULL || (aligned && base + 3 < m)) {
+                *reinterpret_cast<int4*>(A.est + lo + base) = make_int4(est[0], est[1], est[2], est[3]);
+                *reinterpret_cast<uint32_t*>(A.drop + lo + base) =
+                    (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (base + c < m) { A.est[lo + base + c] = est[c]; A.drop[lo + base + c] = drp[c]; }
+            }
+        }
+    }
+
     // ---- 5. estimate and drop decision, request order ---------------------------------
     const bool quick = !wide && L.slow_stages == 0u;          // every stage admits the exact short-queue form
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
+    for (int g = 0; g < (CONSISTENT ? 0 : G); ++g) {
         const int base = (g * T + tid) * 4;
         int32_t est[4];
         uint8_t drp[4];
@@ -392,7 +458,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
 }
 
-template <int T>
+template <int T, bool CONSISTENT>
 __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     __shared__ SnapshotLds L;
     const int u = blockIdx.x;
@@ -414,15 +480,16 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
                            reinterpret_cast<uintptr_t>(A.est) | reinterpret_cast<uintptr_t>(A.order) |
                            (reinterpret_cast<uintptr_t>(A.drop) << 2);
     const bool aligned = (lo & 3) == 0 && (bits & 15) == 0;
-    if (m == kCap && aligned) snapshot_body<T, true>(A, L, u, lo, m, true);
-    else snapshot_body<T, false>(A, L, u, lo, m, aligned);
+    if (m == kCap && aligned) snapshot_body<T, true, CONSISTENT>(A, L, u, lo, m, true);
+    else snapshot_body<T, false, CONSISTENT>(A, L, u, lo, m, aligned);
 }
 
 }  // namespace
 
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
     constexpr int T = 512;
-    fused_snapshot_kernel<T><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    if (a.consistent) fused_snapshot_kernel<T, true><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    else fused_snapshot_kernel<T, false><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
     return hipGetLastError();
 }
 

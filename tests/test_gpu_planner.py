@@ -167,3 +167,72 @@ def test_planner_error_codes(gpu):
     assert gpu.pard_sub_latency(s2.plan, q, gpu.SUB_FULL, 1, 10, 16, smp, pk, sub, check=False) == -11
     assert gpu.pard_sub_latency(s2.plan, q, gpu.SUB_UPPER, 1, 10, 16, smp, pk, sub, check=False) == 0
     torch.cuda.synchronize()
+
+
+# ---- sequentially consistent dropping ------------------------------------------------------------
+
+def consistent_cases():
+    w = wl.make_workload(5, n_snapshots=31, per_snapshot=8192, permute=True)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 250000).astype(np.int32)
+    yield w
+    w = wl.make_workload(5, n_snapshots=9, per_snapshot=5000, permute=True, order_mode=None)
+    w.order_mode[:] = np.arange(w.order_mode.size) % 3
+    w.deadline[::5] = w.deadline[1::5][: w.deadline[::5].size]
+    yield w
+    yield wl.make_workload(1)
+    for seed in range(6):
+        yield wl.random_workload(300 + seed, K=1 + seed, S=1 + (seed * 5) % 9, n_per_snapshot=200 + 311 * seed,
+                                 monotone=(seed % 2 == 0), tie_heavy=(seed % 3 == 1), dag_shared=seed % 2)
+    for m in (0, 1, 63, 64, 65, 8191):
+        yield wl.make_workload(5, n_snapshots=3, per_snapshot=m, permute=True)
+    w = wl.make_workload(2, n_requests=6000, permute=True)          # slow-path stage constants, huge latencies
+    w.batch[:] = [1, 64, 5, 33, 2]
+    w.workers[:] = [1 << 20, 1, 3, 1, 999]
+    w.lat_us[:] = (w.lat_us.astype(np.int64) * 5000).clip(0, 2**31 - 1).astype(np.int32)
+    yield w
+    w = wl.make_workload(3, n_requests=5000, permute=True)          # clustered keys: the wide-key bucket path
+    w.deadline[::2] = 77
+    w.deadline[1::4] = 2**31 - 1
+    w.deadline[3::8] = 0
+    yield w
+
+
+def test_consistent_dropping(gpu, oracle_mod):
+    mixed = 0
+    for w in consistent_cases():
+        print("case", w.name, w.n, w.K, w.S, flush=True)
+        ref = oracle_mod.run(w, threads=8, consistent=True)
+        s = gpu.Session(w)
+        s.run(consistent=True)
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (w.name, k)
+        assert s.status_word() == 0
+        one = oracle_mod.run(w, threads=8)
+        mixed += int(not np.array_equal(one["drop"], ref["drop"]))
+    assert mixed >= 3                       # the variant really decides differently on several of them
+
+
+def test_consistent_with_planner_output(gpu, oracle_mod):
+    import torch
+    w = wl.make_workload(5, n_snapshots=12, per_snapshot=6000, permute=True)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 200000).astype(np.int32)
+    M = 3000
+    samples, picks = draws(4, M, w.S, 60_000_000)
+    s = gpu.Session(w)
+    sub = s.planner(gpu.SUB_FULL, (1, 10), torch.from_numpy(samples).to(s.dev), torch.from_numpy(picks.view(np.int32)).to(s.dev))
+    s.run(sub=sub, consistent=True)
+    got = s.results()
+    want_sub = oracle_mod.sub_latency(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us,
+                                      oracle_qlen(w), gpu.SUB_FULL, (1, 10), samples, picks, threads=8)
+    ref = oracle_mod.run(w, threads=8, sub=want_sub, consistent=True)
+    for k in KEYS:
+        assert np.array_equal(got[k], ref[k]), k
+    assert 0 < ref["drop"].mean() < 1
+
+
+def test_consistent_rejects_large_snapshots(gpu):
+    w = wl.make_workload(3, n_requests=20000)
+    s = gpu.Session(w)
+    assert gpu.pard_estimate_drop_consistent(s.plan, s.n, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, None,
+                                             s.est, s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -11
