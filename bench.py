@@ -157,6 +157,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--permute", action="store_true", help="shuffle request order inside every snapshot")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--consistent", action="store_true",
+                    help="sequentially consistent dropping (positions count kept requests only; on-chip path only)")
     ap.add_argument("--workload", choices=["hot-path", "planner"], default="hot-path",
                     help="hot-path: estimate+drop+compact (default); planner: queue lengths + downstream latency "
                          "with the sampled batch-wait quantile on the same snapshots")
@@ -197,7 +199,7 @@ def main():
         del src, dst
 
     for _ in range(max(args.warmup, 1)):
-        s.run()
+        s.run(consistent=args.consistent)
     torch.cuda.synchronize()
 
     # timed region: exactly --steps passes of the whole path
@@ -207,7 +209,7 @@ def main():
     t0 = time.perf_counter()
     for a, b, c in ev:
         a.record()
-        s.estimate_drop()
+        s.estimate_drop(consistent=args.consistent)
         b.record()
         s.compact()
         c.record()
@@ -233,7 +235,8 @@ def main():
     bpr = estimate_drop_bytes_per_request(fused, passes, fcfs)
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
-    traffic = recorded_traffic(args.config, "fused_snapshot_kernel", "pard_fused.hip") if fused and not args.permute else None
+    traffic = (recorded_traffic(args.config, "fused_snapshot_kernel", "pard_fused.hip")
+               if fused and not args.permute and not args.consistent else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4)}
@@ -246,8 +249,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": w.name, "requests": n, "snapshots": w.K, "stages": w.S,
-                   "path": "on-chip" if fused else "radix-sort", "radix_passes": passes,
+        "config": {"workload": w.name + ("+consistent" if args.consistent else ""), "requests": n, "snapshots": w.K,
+                   "stages": w.S, "path": "on-chip" if fused else "radix-sort", "radix_passes": passes,
                    "drop_fraction": round(drop_frac, 4), "status_word": status,
                    "estimate_drop_ms": round(est_ms, 4), "compact_ms": round(cmp_ms, 4),
                    "generate_s": round(gen_s, 2)},
@@ -262,7 +265,7 @@ def main():
         sample = f"whole workload ({n} requests), 1 run"
         oracle.build_oracle()
         t0 = time.perf_counter()
-        oracle.run(sub, threads=threads)
+        oracle.run(sub, threads=threads, consistent=args.consistent)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(sub.n / cpu_s, 1), "unit": "requests/s", "cores": threads,
                                "kind": "oracle", "sample": sample, "seconds": round(cpu_s, 3)}
