@@ -147,7 +147,8 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
  *   d_seg_ptr              device out int32[K*S+1] offsets of queue (u,s) inside d_order
  *
  * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE, PARD_E_WORKSPACE, PARD_E_UNSUPPORTED (large
- * snapshots whose request-index bits plus segment-id bits exceed 32), PARD_E_HIP.
+ * snapshots for which the bits of max_snapshot_requests - 1 plus the bits of K*S - 1
+ * exceed 32), PARD_E_HIP.
  * Contents of the request arrays are not validated on the host.
  */
 int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,

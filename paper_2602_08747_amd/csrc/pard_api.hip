@@ -135,7 +135,7 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests, int64_t 
     if (!plan || !bytes) return PARD_E_NULL;
     if (max_requests < 0 || max_requests >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (max_snapshot_requests > PARD_FUSED_SNAPSHOT_CAPACITY &&
-        !sort_supported(plan->host.K, plan->host.S, max_requests)) return PARD_E_UNSUPPORTED;
+        !sort_supported(plan->host.K, plan->host.S, max_requests, max_snapshot_requests)) return PARD_E_UNSUPPORTED;
     *bytes = workspace_need(plan, max_requests, max_snapshot_requests);
     return PARD_OK;
 }
@@ -150,7 +150,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
     if (n > 0 && plan->host.any_fcfs && !d_arrival) return PARD_E_NULL;
     const bool fused = max_snapshot_requests <= PARD_FUSED_SNAPSHOT_CAPACITY;
-    if (!fused && (consistent || !sort_supported(plan->host.K, plan->host.S, n))) return PARD_E_UNSUPPORTED;
+    if (!fused && (consistent || !sort_supported(plan->host.K, plan->host.S, n, max_snapshot_requests))) return PARD_E_UNSUPPORTED;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
         workspace_bytes < workspace_need(plan, n, max_snapshot_requests)) return PARD_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -172,6 +172,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         SortArgs a{};
         a.plan = plan->dev;
         a.n = n;
+        a.max_snapshot = max_snapshot_requests;
         a.arrival = d_arrival; a.deadline = d_deadline; a.stage = d_stage;
         a.snap_ptr = d_snap_ptr; a.now = d_now;
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
@@ -287,7 +288,7 @@ const char* pard_strerror(int status) {
         case PARD_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case PARD_E_HIP: return "HIP runtime error";
         case PARD_E_BAD_MODE: return "unknown order mode";
-        case PARD_E_UNSUPPORTED: return "not supported: index bits plus queue-id bits above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
+        case PARD_E_UNSUPPORTED: return "not supported: bits of the snapshot bound plus bits of the queue count above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
         default: return "unknown status";
     }
 }

@@ -123,6 +123,7 @@ hipError_t launch_fused(const FusedArgs& a, hipStream_t stream);
 struct SortArgs {
     PlanDev plan;
     int64_t n;
+    int64_t max_snapshot;              // promised bound on a snapshot's size
     const int32_t *arrival, *deadline, *stage, *snap_ptr, *now;
     int32_t* est;
     uint8_t* drop;
@@ -133,7 +134,7 @@ struct SortArgs {
     int32_t num_cus;
 };
 int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n);
-bool sort_supported(int32_t K, int32_t S, int64_t n);
+bool sort_supported(int32_t K, int32_t S, int64_t n, int64_t max_snapshot);
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
 
 struct CompactArgs {

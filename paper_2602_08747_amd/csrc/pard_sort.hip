@@ -16,8 +16,9 @@
 //             word, then unpacked by a streaming kernel.
 //
 // The sort key is the virtual integer  V = segment << kb | (key - min key)  where kb is
-// the number of bits of the key range; only ceil(bits(V)/8) passes run.  The segment id
-// travels in the otherwise unused top bits of the 32-bit request index.
+// the number of bits of the key range; only ceil(bits(V)/8) passes run.  The payload word
+// carries the request's index inside its snapshot (as many bits as the promised snapshot
+// bound needs) and the segment id above it; the epilogue adds the snapshot's first request.
 #include "pard_device.hpp"
 
 namespace pard {
@@ -55,10 +56,11 @@ struct SortLayout {
 int bits_of(uint64_t x) { int b = 0; while (x) { ++b; x >>= 1; } return b; }
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
-SortLayout make_layout(int32_t K, int32_t S, int64_t n) {
+SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     SortLayout L{};
     const int64_t segs = (int64_t)K * S;
-    L.idx_bits = bits_of(n > 0 ? (uint64_t)(n - 1) : 0);
+    const int64_t span = max_snap < n ? max_snap : n;            // no snapshot holds more requests than this
+    L.idx_bits = bits_of(span > 0 ? (uint64_t)(span - 1) : 0);
     L.seg_bits = bits_of((uint64_t)(segs - 1));
     L.max_passes = (32 + L.seg_bits + kRadixBits - 1) / kRadixBits;
     L.tiles = (n + kTile - 1) / kTile;
@@ -409,8 +411,15 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
                                                      : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
             const uint32_t seg = (uint32_t)u * (uint32_t)P.S + (uint32_t)s;
             const uint32_t k = order_key(mode, dl[i], mode == PARD_ORDER_FCFS ? ar[i] : 0);
+            // index inside the snapshot; a snapshot larger than promised is flagged and its
+            // surplus indices wrap (outputs unspecified then, never out of bounds)
+            uint32_t local = ok ? (uint32_t)(r - (int64_t)A.snap_ptr[u]) : 0u;
+            if (A.idx_bits < 32 && (local >> A.idx_bits) != 0u) {
+                atomicOr(A.status_word, kStatusSnapshotTooLarge);
+                local &= (1u << A.idx_bits) - 1u;
+            }
             key[i] = ok ? k - umin : 0u;
-            pay[i] = ok ? ((uint32_t)r | (seg << A.idx_bits)) : 0u;
+            pay[i] = ok ? (local | (A.idx_bits < 32 ? seg << A.idx_bits : 0u)) : 0u;
         }
     } else {
         const uint32_t* src_key = A.key[(pass + 1) & 1];
@@ -686,11 +695,13 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
 constexpr int kEpiSegs = 64;
 constexpr int kEpiThreads = 256;
 
-struct EpiSeg {                     // 48 bytes
+struct EpiSeg {                     // 64 bytes
     uint32_t B, W, latB, mode;
     uint32_t mB, shB, mW, shW;
     int32_t start, now;
     uint32_t down_lo, down_hi;
+    int32_t first;                  // first request of the queue's snapshot
+    int32_t pad[3];
 };
 
 __device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
@@ -712,7 +723,7 @@ __device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg&
     const int32_t mode = (int32_t)(q.mode & 0xFF);
     if (mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
     else if (mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
-    else deadline = A.deadline[r];
+    else deadline = (int64_t)r < A.n ? A.deadline[r] : 0;
     int32_t est;
     uint8_t drp;
     finish_request(e64, q.now, deadline, est, drp);
@@ -728,6 +739,8 @@ __device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t se
     q.B = (uint32_t)sr.B; q.W = (uint32_t)sr.W; q.latB = (uint32_t)sr.latB; q.mode = (uint32_t)sr.mode;
     q.mB = sr.mB; q.shB = sr.shB; q.mW = sr.mW; q.shW = sr.shW;
     q.start = A.seg_ptr[seg]; q.now = A.now[u];
+    q.first = A.snap_ptr[u];
+    q.pad[0] = q.pad[1] = q.pad[2] = 0;
     q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
     return q;
 }
@@ -767,14 +780,22 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
         uint32_t r4[4], out[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            r4[c] = p4[c] & idx_mask;
+            const uint32_t local = p4[c] & idx_mask;
             const uint32_t seg = A.idx_bits < 32 ? (p4[c] >> A.idx_bits) : 0u;
             const uint32_t k = seg % (uint32_t)P.S;
             const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
             out[c] = 0;
+            r4[c] = 0;
             if (j0 + c < A.n) {
-                if (cached) out[c] = epilogue_one(A, tab[seg], P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
-                else out[c] = epilogue_one(A, epilogue_segment(A, seg), P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
+                if (cached) {
+                    const EpiSeg& q = tab[seg];
+                    r4[c] = (uint32_t)q.first + local;
+                    out[c] = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
+                } else {
+                    const EpiSeg q = epilogue_segment(A, seg);
+                    r4[c] = (uint32_t)q.first + local;
+                    out[c] = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
+                }
             }
         }
         if (vec && j0 + 3 < A.n) {
@@ -844,15 +865,15 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
 
 }  // namespace
 
-int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n) { return make_layout(K, S, n).total; }
+int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n) { return make_layout(K, S, n, n).total; }
 
-bool sort_supported(int32_t K, int32_t S, int64_t n) {
-    const SortLayout L = make_layout(K, S, n);
+bool sort_supported(int32_t K, int32_t S, int64_t n, int64_t max_snapshot) {
+    const SortLayout L = make_layout(K, S, n, max_snapshot);
     return L.idx_bits + L.seg_bits <= 32 && n < ((int64_t)1 << 30);
 }
 
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
-    const SortLayout L = make_layout(a.plan.K, a.plan.S, a.n);
+    const SortLayout L = make_layout(a.plan.K, a.plan.S, a.n, a.max_snapshot);
     SortDev D = make_dev(a, L);
     const int64_t zero16 = L.zero_end / 16;
     int zb = (int)((zero16 + 255) / 256);

@@ -113,6 +113,24 @@ def test_many_queues_sort_path(gpu, oracle_mod):
     check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
 
 
+def test_many_large_snapshots(gpu, oracle_mod):
+    """So many snapshots above the on-chip size that global request index and queue id no longer fit
+    one 32-bit word together: the large-snapshot path carries the index inside the snapshot instead."""
+    w = wl.make_workload(5, n_snapshots=300, per_snapshot=9000, permute=True)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 250000).astype(np.int32)
+    assert (w.n - 1).bit_length() + (w.K * w.S - 1).bit_length() > 32
+    s, ref = check(gpu, oracle_mod, w, threads=16)
+    assert 0 < ref["drop"].mean() < 1
+
+
+def test_snapshot_larger_than_promised_on_the_large_path(gpu):
+    w = wl.make_workload(5, n_snapshots=3, per_snapshot=20000)
+    s = gpu.Session(w, max_snapshot_requests=9000)
+    s.run()
+    s.results()
+    assert s.status_word() & 1
+
+
 def test_ragged_multi_snapshot_large(gpu, oracle_mod):
     """Several snapshots of very different sizes, some above the on-chip capacity, own DAG each."""
     w = wl.random_workload(7, K=5, S=6, n_per_snapshot=9000, dag_shared=0, time_span=2_000_000,
