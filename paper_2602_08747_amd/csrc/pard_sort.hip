@@ -400,12 +400,19 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
             st[i] = A.stage[r];
             ar[i] = P.any_fcfs ? A.arrival[r] : 0;
         }
+        // most tiles lie inside one snapshot: its number and first request are then the same for
+        // every element
+        const int32_t u_first = snapshot_of(A.snap_ptr, P.K, tile_base);
+        const int32_t u_last = snapshot_of(A.snap_ptr, P.K, tile_base + valid - 1);
+        const int32_t first_of_u = A.snap_ptr[u_first];
+        const uint32_t idx_mask = A.idx_bits < 32 ? (1u << A.idx_bits) - 1u : 0xFFFFFFFFu;
+        uint32_t surplus = 0;
 #pragma unroll
         for (int i = 0; i < kSortItems; ++i) {
             const int e = wave * (kWave * kSortItems) + i * kWave + lane;
             const int64_t r = tile_base + e;
             const bool ok = e < valid;
-            const int32_t u = ok ? snapshot_of(A.snap_ptr, P.K, r) : 0;
+            const int32_t u = (ok && u_first != u_last) ? snapshot_of(A.snap_ptr, P.K, r) : u_first;
             const int32_t s = clamp_stage(st[i], P.S);
             const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
                                                      : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
@@ -413,14 +420,13 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
             const uint32_t k = order_key(mode, dl[i], mode == PARD_ORDER_FCFS ? ar[i] : 0);
             // index inside the snapshot; a snapshot larger than promised is flagged and its
             // surplus indices wrap (outputs unspecified then, never out of bounds)
-            uint32_t local = ok ? (uint32_t)(r - (int64_t)A.snap_ptr[u]) : 0u;
-            if (A.idx_bits < 32 && (local >> A.idx_bits) != 0u) {
-                atomicOr(A.status_word, kStatusSnapshotTooLarge);
-                local &= (1u << A.idx_bits) - 1u;
-            }
+            uint32_t local = ok ? (uint32_t)(r - (int64_t)(u_first != u_last ? A.snap_ptr[u] : first_of_u)) : 0u;
+            surplus |= local & ~idx_mask;
+            local &= idx_mask;
             key[i] = ok ? k - umin : 0u;
             pay[i] = ok ? (local | (A.idx_bits < 32 ? seg << A.idx_bits : 0u)) : 0u;
         }
+        if (surplus) atomicOr(A.status_word, kStatusSnapshotTooLarge);
     } else {
         const uint32_t* src_key = A.key[(pass + 1) & 1];
         const uint32_t* src_pay = A.pay[(pass + 1) & 1];
@@ -451,10 +457,27 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
     const int64_t tile_base = tile * kTile;
     const int valid = (int)((A.n - tile_base) < kTile ? (A.n - tile_base) : kTile);
     uint32_t key[kSortItems], pay[kSortItems];
-    load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
+    // A histogram does not care which element a lane holds: later passes read four consecutive
+    // elements per lane with 16-byte loads (element (i/4)*256 + lane*4 + i%4 of the wave's 1024).
+    const bool quads = !FIRST && valid == kTile;
+    if (quads) {
+        const uint32_t* src_key = A.key[(pass + 1) & 1];
+        const uint32_t* src_pay = A.pay[(pass + 1) & 1];
+#pragma unroll
+        for (int g = 0; g < kSortItems / 4; ++g) {
+            const int64_t at = tile_base + wave * (kWave * kSortItems) + g * (kWave * 4) + lane * 4;
+            const uint4 kv = *reinterpret_cast<const uint4*>(src_key + at);
+            key[4 * g] = kv.x; key[4 * g + 1] = kv.y; key[4 * g + 2] = kv.z; key[4 * g + 3] = kv.w;
+            uint4 pv = make_uint4(0, 0, 0, 0);
+            if (need_pay) pv = *reinterpret_cast<const uint4*>(src_pay + at);
+            pay[4 * g] = pv.x; pay[4 * g + 1] = pv.y; pay[4 * g + 2] = pv.z; pay[4 * g + 3] = pv.w;
+        }
+    } else {
+        load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
+    }
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
-        const int e = wave * (kWave * kSortItems) + i * kWave + lane;
+        const int e = quads ? 0 : wave * (kWave * kSortItems) + i * kWave + lane;       // a full tile: every element counts
         const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
         // Sorted input puts long runs of one digit into a wave, and 64 lanes adding to one LDS
         // word serialise: the two most common leading digits are counted with a ballot, the
