@@ -1,0 +1,108 @@
+"""Are the pins strong enough?  Every entry below plants one plausible mistake in a COPY of the
+oracle's C source (CPU only, in a temporary directory), builds it, and runs the pin tests against
+the mutated copy: at least one pin must fail.  The committed oracle itself is never modified."""
+import importlib.util
+import os
+import shutil
+import sys
+
+import pytest
+
+from tests import test_oracle_consistent as pins_consistent
+from tests import test_oracle_pins as pins
+from tests import test_oracle_sub as pins_sub
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+# (name, text in oracle/pard_oracle.c, replacement, pins that must notice)
+MUTATIONS = [
+    ("floor instead of ceil of a/B", "int64_t batches_ahead = (a + B - 1) / B;", "int64_t batches_ahead = a / B;", "core"),
+    ("divide by W before multiplying", "((wide_t)batches_ahead * (wide_t)lat[B - 1]) / (wide_t)W;",
+     "((wide_t)batches_ahead / (wide_t)W) * (wide_t)lat[B - 1];", "core"),
+    ("execution at the full batch size", "int64_t b_seen = (a + 1 < B) ? a + 1 : B;", "int64_t b_seen = B;", "core"),
+    ("execution at batch a instead of a+1", "int64_t b_seen = (a + 1 < B) ? a + 1 : B;",
+     "int64_t b_seen = (a + 1 < B) ? (a > 0 ? a : 1) : B;", "core"),
+    ("ties by descending index", "if (a->idx != b->idx) return a->idx < b->idx ? -1 : 1;",
+     "if (a->idx != b->idx) return a->idx > b->idx ? -1 : 1;", "core"),
+    ("HBF sorted like LBF", "if (M[s] == MODE_HBF) key = -(int64_t)deadline[r];", "if (M[s] == MODE_HBF) key = (int64_t)deadline[r];", "core"),
+    ("FCFS keyed by deadline", "else if (M[s] == MODE_FCFS) key = (int64_t)arrival[r];", "else if (M[s] == MODE_FCFS) key = (int64_t)deadline[r];", "core"),
+    ("minimum over paths", "                if (sum > best) best = sum;\n            }\n            wide_t cap = (wide_t)INT32_MAX;",
+     "                if (best < 0 || sum < best) best = sum;\n            }\n            wide_t cap = (wide_t)INT32_MAX;", "core"),
+    ("downstream stage at the request's own position", "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
+     "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], pos);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap", "core"),
+    ("current stage counted twice", "for (int32_t t = at + 1; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
+     "for (int32_t t = at; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap", "core"),
+    ("now not added", "wide_t finish = (wide_t)now[u] + best;", "wide_t finish = best;", "core"),
+    ("drop at equality", "drop[r] = (uint8_t)(finish > (wide_t)deadline[r]);", "drop[r] = (uint8_t)(finish >= (wide_t)deadline[r]);", "core"),
+    ("compaction keeps the dropped", "if (!drop[r]) surv_idx[out++] = r;", "if (drop[r]) surv_idx[out++] = r;", "core"),
+    ("position counts everybody in the consistent variant", "if (consistent && !drop[r]) kept[k] += 1;", "if (consistent) kept[k] += 1;", "consistent"),
+    ("position counts the dropped in the consistent variant", "if (consistent && !drop[r]) kept[k] += 1;", "if (consistent && drop[r]) kept[k] += 1;", "consistent"),
+    ("batch wait is the time since the last batch", "total += (uint64_t)((di - arr % di) % di);", "total += (uint64_t)(arr % di);", "sub"),
+    ("quantile rank one too high", "w = (wide_t)T[rank - 1];", "w = (wide_t)T[rank < M ? rank : M - 1];", "sub"),
+    ("one draw for all stages of a sample", "int64_t arr = samples[picks[j * S + i] % (uint64_t)M];", "int64_t arr = samples[picks[j * S] % (uint64_t)M];", "sub"),
+    ("draws indexed stage-major", "int64_t arr = samples[picks[j * S + i] % (uint64_t)M];", "int64_t arr = samples[picks[(int64_t)i * M + j] % (uint64_t)M];", "sub"),
+    ("upper variant adds the durations once", "else if (variant == 2) lsub = sum_qd + sum_d;", "else if (variant == 2) lsub = sum_qd;", "sub"),
+    ("sf variant keeps the queueing delay", "else if (variant == 3) lsub = sum_d;", "else if (variant == 3) lsub = sum_qd;", "sub"),
+    ("duration at the full batch size", "int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];\n                    sum_qd", "int64_t seen = B[i];\n                    sum_qd", "sub"),
+    ("sum over paths instead of maximum (downstream latency)", "if (lsub > best) best = lsub;", "best += lsub;", "sub"),
+]
+
+
+def load_mutant(tmp_path, old, new):
+    dst = os.path.join(tmp_path, "oracle_mutant")
+    shutil.copytree(os.path.join(ROOT, "oracle"), dst, ignore=shutil.ignore_patterns("*.so", "__pycache__"))
+    src = os.path.join(dst, "pard_oracle.c")
+    text = open(src).read()
+    assert text.count(old) >= 1, "the mutation does not apply to the oracle source any more"
+    open(src, "w").write(text.replace(old, new))
+    name = "oracle_mutant_" + os.path.basename(str(tmp_path))
+    spec = importlib.util.spec_from_file_location(name, os.path.join(dst, "__init__.py"), submodule_search_locations=[dst])
+    mod = importlib.util.module_from_spec(spec)
+    sys.modules[name] = mod
+    spec.loader.exec_module(mod)
+    mod.build_oracle(force=True)
+    return mod
+
+
+def core_pins(m):
+    pins.test_hand_vector_diamond(m)
+    for seed in range(24):
+        pins.test_bruteforce_small_random(m, seed)
+    pins.test_stage_cost_against_batch_simulation(m)
+    pins.test_linear_pipeline_is_single_suffix_sum(m)
+    pins.test_lone_request_sees_batch1_latencies(m)
+    pins.test_single_stage_unit_batch_is_rank_times_latency(m)
+    pins.test_infinite_deadline_never_dropped_and_saturation(m)
+    pins.test_permutation_invariance(m)
+    pins.test_compaction_invariants(m)
+
+
+def consistent_pins(m):
+    pins_consistent.test_hand_worked_queue(m)
+    for seed in range(20):
+        pins_consistent.test_brute_force(m, seed)
+
+
+def sub_pins(m):
+    pins_sub.test_paper_printed_quantiles(m)
+    pins_sub.test_single_module_exact(m)
+    for seed in range(16):
+        pins_sub.test_brute_force_random_dags(m, seed)
+    pins_sub.test_variant_identities_and_bounds(m)
+
+
+GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins}
+
+
+@pytest.mark.parametrize("name,old,new,group", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_planted_mistake_is_caught(tmp_path, name, old, new, group):
+    mutant = load_mutant(str(tmp_path), old, new)
+    with pytest.raises((AssertionError, ValueError)):
+        GROUPS[group](mutant)
+
+
+def test_unmodified_copy_passes(tmp_path):
+    """The harness itself: a copy without a planted mistake passes every group."""
+    clean = load_mutant(str(tmp_path), "#define LAT_ENTRIES 64", "#define LAT_ENTRIES 64 ")
+    for run in GROUPS.values():
+        run(clean)
