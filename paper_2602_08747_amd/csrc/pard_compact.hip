@@ -469,6 +469,9 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
     int64_t a, b;
     if (!snapshot_range(A.seg_ptr, u, A.stages, A.n, a, b)) return;     // reported by the counting kernel
     const int size = (int)(b - a);
+    // a snapshot without survivors (its slice of drop[] has no zero byte) only owes its queue offsets:
+    // neither its slots nor its drop bytes are read
+    const int load_size = kept[u] == 0 ? 0 : size;
 
     // this snapshot's slots: wave w owns [w*1024, (w+1)*1024), load k covers 256 of them, 4 per lane
     const int32_t* slots = A.order + a;
@@ -477,19 +480,19 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int e = wave * 1024 + k * 256 + lane * 4;
-        if (vec && e + 3 < size) {
+        if (vec && e + 3 < load_size) {
             const int4 v = *reinterpret_cast<const int4*>(slots + e);
             ids[k][0] = v.x; ids[k][1] = v.y; ids[k][2] = v.z; ids[k][3] = v.w;
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) ids[k][c] = e + c < size ? slots[e + c] : -1;
+            for (int c = 0; c < 4; ++c) ids[k][c] = e + c < load_size ? slots[e + c] : -1;
         }
     }
     // its slice of drop[]: 16-byte chunks at 16-byte aligned addresses from just below drop[a]
     const uintptr_t lo = reinterpret_cast<uintptr_t>(A.drop) + (uintptr_t)a, hi = reinterpret_cast<uintptr_t>(A.drop) + (uintptr_t)b;
     const uintptr_t win = lo & ~(uintptr_t)15;
     const uint32_t delta = (uint32_t)(lo - win);
-    const uint32_t chunks = (uint32_t)((hi - win + 15) >> 4);              // <= kLCap / 16 + 2
+    const uint32_t chunks = load_size ? (uint32_t)((hi - win + 15) >> 4) : 0u;   // <= kLCap / 16 + 2
     for (uint32_t c = tid; c < chunks; c += kLThreads) {
         const uintptr_t at = win + 16u * (uintptr_t)c;
         uint4 v;
