@@ -36,6 +36,13 @@
  * prints for a four-module pipeline (0.31, 0.28, 0.22, 0.10 of the summed durations),
  * an independent numpy brute force, closed forms and identities (tests/test_oracle_sub.py).
  *
+ * Adaptive priority with delayed transition (Section 3.3): pard_oracle_priority_modes()
+ * decides per (snapshot, stage) between High-Budget-First and Low-Budget-First from the
+ * module load factor mu = T_in / T_m with the two thresholds 1 +- epsilon; see the comment
+ * at the function.  Pins: hand-worked series, closed forms and an independent Python brute
+ * force with exact rationals (tests/test_oracle_priority.py); the paper prints no value for it
+ * and its algorithm listing is absent, so parity with the paper is unpinned for this function.
+ *
  * Parity status: no value in the paper pins the estimate/drop path (it prints none for it).
  * The pins are brute force on tiny inputs, closed forms, invariants and a hand-worked
  * vector (tests/test_oracle_*.py).
@@ -471,6 +478,64 @@ int pard_oracle_sub_latency(
     }
     free(col_base);
     return status;
+}
+
+/*
+ * Adaptive request priority with delayed transition (Section 3.3).
+ *
+ * Per (snapshot u, stage s), from the series rate[(u*S+s)*T + t], t = 0..T-1, of the module's
+ * monitored input workload T_in (requests per second):
+ *   T_m     = W * B / lat[B]                      module throughput (lat in microseconds, so
+ *                                                 T_m = W * B * 10^6 / lat[B] requests per second)
+ *   T_s[t]  = floor(mean of rate[max(0,t-w+1) .. t])   the workload filtered by a sliding-window
+ *                                                 average of width w
+ *   eps     = sum_t |rate[t] - T_s[t]| / sum_t rate[t]     (0 when the series sums to 0)
+ *   mu[t]   = rate[t] / T_m
+ *   mode[t] = HBF if mu[t] > 1 + eps,  LBF if mu[t] < 1 - eps,  otherwise mode[t-1]
+ *   mode[-1] = prev_mode[u*S+s] (LBF when prev_mode is NULL)
+ * Output: mode[T-1], the priority in force after the series.  Every comparison is evaluated
+ * exactly in integers (cross-multiplied); lat[B] = 0 means unbounded throughput, mu = 0.
+ * Returns 0, or 4 for bad arguments.
+ */
+int pard_oracle_priority_modes(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat,
+        int32_t T, int32_t window, const int32_t* rate, const int32_t* prev_mode, int32_t* mode_out) {
+    if (T < 1 || window < 1) return 4;
+    for (int64_t g = 0; g < (int64_t)K * S; ++g) {
+        int64_t rec = dag_shared ? g % S : g;
+        const int32_t* r = rate + g * T;
+        wide_t B = batch[rec], W = workers[rec], latB = lat[rec * LAT_ENTRIES + batch[rec] - 1];
+        wide_t sum = 0, dev = 0;
+        for (int32_t t = 0; t < T; ++t) {
+            int32_t lo = t - window + 1 < 0 ? 0 : t - window + 1;
+            wide_t win = 0;
+            for (int32_t i = lo; i <= t; ++i) win += r[i];
+            wide_t ts = win / (t - lo + 1);                       /* floor of the window mean */
+            wide_t d = (wide_t)r[t] - ts;
+            dev += d < 0 ? -d : d;
+            sum += r[t];
+        }
+        int32_t mode = prev_mode ? prev_mode[g] : MODE_LBF;
+        for (int32_t t = 0; t < T; ++t) {
+            /* mu > 1 + eps  <=>  rate * lat[B] * sum > W * B * 10^6 * (sum + dev)   (sum > 0)
+             * mu < 1 - eps  <=>  rate * lat[B] * sum < W * B * 10^6 * (sum - dev)
+             * with sum = 0 (all rates 0): eps = 0 and mu = 0 < 1 */
+            wide_t lhs, hi, lo;
+            if (sum > 0) {
+                lhs = (wide_t)r[t] * latB * sum;
+                hi = W * B * 1000000 * (sum + dev);
+                lo = W * B * 1000000 * (sum - dev);
+            } else {
+                lhs = (wide_t)r[t] * latB;
+                hi = lo = W * B * 1000000;
+            }
+            if (lhs > hi) mode = MODE_HBF;
+            else if (lhs < lo) mode = MODE_LBF;
+        }
+        mode_out[g] = mode;
+    }
+    return 0;
 }
 
 /*

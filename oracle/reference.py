@@ -58,6 +58,9 @@ def _load() -> ctypes.CDLL:
             ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
             ctypes.c_int64, _i32p, ctypes.POINTER(ctypes.c_uint32),
             _i64p, ctypes.c_int32]
+        lib.pard_oracle_priority_modes.restype = ctypes.c_int
+        lib.pard_oracle_priority_modes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p,
+                                                   ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p]
         lib.pard_oracle_compact.restype = ctypes.c_int
         lib.pard_oracle_compact.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                             _i32p, _i32p, _u8p, _i32p, _i32p]
@@ -98,6 +101,22 @@ def sub_latency(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, 
         K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(q),
         int(variant), int(lam[0]), int(lam[1]), M, _p32(smp), pk.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
         out.ctypes.data_as(_i64p), int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return out
+
+
+def priority_modes(K, S, dag_shared, batch, workers, lat_us, rate, window, prev_mode=None):
+    """Priority (0 = LBF, 1 = HBF) in force per (snapshot, stage) after the rate series: int32[K*S].
+    rate: int32[K*S, T]."""
+    lib = _load()
+    B, W, L = map(_i32, (batch, workers, lat_us))
+    rt = _i32(rate).reshape(K * S, -1)
+    T = int(rt.shape[1])
+    pm = None if prev_mode is None else _i32(prev_mode)
+    out = np.zeros(K * S, np.int32)
+    rc = lib.pard_oracle_priority_modes(K, S, int(dag_shared), _p32(B), _p32(W), _p32(L), T, int(window),
+                                        _p32(np.ascontiguousarray(rt)), None if pm is None else _p32(pm), _p32(out))
     if rc != 0:
         raise ValueError(f"oracle rejected the arguments (code {rc})")
     return out

@@ -10,6 +10,7 @@ import pytest
 
 from tests import test_oracle_consistent as pins_consistent
 from tests import test_oracle_pins as pins
+from tests import test_oracle_priority as pins_priority
 from tests import test_oracle_sub as pins_sub
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -45,6 +46,12 @@ MUTATIONS = [
     ("sf variant keeps the queueing delay", "else if (variant == 3) lsub = sum_d;", "else if (variant == 3) lsub = sum_qd;", "sub"),
     ("duration at the full batch size", "int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];\n                    sum_qd", "int64_t seen = B[i];\n                    sum_qd", "sub"),
     ("sum over paths instead of maximum (downstream latency)", "if (lsub > best) best = lsub;", "best += lsub;", "sub"),
+    ("no hysteresis: LBF whenever not above the upper threshold", "else if (lhs < lo) mode = MODE_LBF;", "else mode = MODE_LBF;", "priority"),
+    ("epsilon from the window sum instead of its mean", "wide_t ts = win / (t - lo + 1);", "wide_t ts = win;", "priority"),
+    ("thresholds without epsilon", "hi = W * B * 1000000 * (sum + dev);\n                lo = W * B * 1000000 * (sum - dev);",
+     "hi = W * B * 1000000 * sum;\n                lo = W * B * 1000000 * sum;", "priority"),
+    ("throughput ignores the worker count", "hi = W * B * 1000000 * (sum + dev);", "hi = B * 1000000 * (sum + dev);", "priority"),
+    ("previous priority ignored", "int32_t mode = prev_mode ? prev_mode[g] : MODE_LBF;", "int32_t mode = MODE_LBF;", "priority"),
 ]
 
 
@@ -91,7 +98,15 @@ def sub_pins(m):
     pins_sub.test_variant_identities_and_bounds(m)
 
 
-GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins}
+def priority_pins(m):
+    pins_priority.test_hand_worked_series(m)
+    pins_priority.test_delayed_transition_holds_inside_the_band(m)
+    pins_priority.test_constant_load_closed_form(m)
+    for seed in range(12):
+        pins_priority.test_brute_force(m, seed)
+
+
+GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins}
 
 
 @pytest.mark.parametrize("name,old,new,group", MUTATIONS, ids=[m[0] for m in MUTATIONS])
