@@ -256,6 +256,32 @@ int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t ma
                                   int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                                   void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Adaptive request priority with delayed transition (Section 3.3).  Per (snapshot u, stage s), from
+ * the series d_rate[(u*S + s)*series_len + t] of the module's monitored input workload T_in
+ * (requests per second, >= 0):
+ *   T_m     = W * B * 10^6 / lat[B] requests per second        the module's throughput
+ *   T_s[t]  = floor(mean of the last `window` samples up to t)  the sliding-window average
+ *   eps     = sum |T_in - T_s| / sum T_in                       (0 for an all-zero series)
+ *   mu[t]   = T_in[t] / T_m
+ *   HBF when mu[t] > 1 + eps, LBF when mu[t] < 1 - eps, unchanged in between, starting from
+ *   d_prev_mode[u*S + s] (PARD_ORDER_LBF when d_prev_mode is NULL).
+ * d_mode[u*S + s] receives the priority in force after the last sample (PARD_ORDER_LBF or
+ * PARD_ORDER_HBF).  All comparisons are exact (cross-multiplied integers).
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE (series_len < 1, window < 1), PARD_E_HIP.
+ */
+int pard_priority_modes(const pard_plan_t* plan, int32_t series_len, int32_t window, const int32_t* d_rate,
+                        const int32_t* d_prev_mode, int32_t* d_mode, void* stream);
+
+/*
+ * Installs queue orders in a plan: d_mode holds one PARD_ORDER_LBF / PARD_ORDER_HBF per stage
+ * record (S entries for a plan with one shared DAG, K*S otherwise, e.g. the output of
+ * pard_priority_modes).  The update is enqueued on `stream`; calls that use the plan must be
+ * ordered after it, and no other stream may be using the plan meanwhile.  A stage that was
+ * PARD_ORDER_FCFS loses that order.
+ */
+int pard_plan_set_modes(pard_plan_t* plan, const int32_t* d_mode, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* pard_strerror(int status);
 

@@ -25,7 +25,7 @@ STATUS_NAMES = {
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
-           "pard_queue_lengths",
+           "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
            "pard_sub_latency", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
 
@@ -63,6 +63,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_queue_lengths.argtypes = [vp, i64, vp, vp, vp, vp]
+    lib.pard_priority_modes.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
+    lib.pard_plan_set_modes.argtypes = [vp, vp, vp]
     lib.pard_sub_latency.argtypes = [vp, vp, ctypes.c_int32, i64, i64, ctypes.c_int32, vp, vp, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
@@ -189,6 +191,23 @@ def pard_queue_lengths(plan: Plan, n: int, stage, snap_ptr, qlen, stream=None, c
                                            _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_queue_lengths")
+    return rc
+
+
+def pard_priority_modes(plan: Plan, series_len: int, window: int, rate, prev_mode, mode, stream=None, check: bool = True) -> int:
+    """Enqueues the adaptive-priority decision (one mode per (snapshot, stage)) on `stream`."""
+    rc = load_library().pard_priority_modes(plan.handle, int(series_len), int(window), _ptr(rate), _ptr(prev_mode), _ptr(mode),
+                                            _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_priority_modes")
+    return rc
+
+
+def pard_plan_set_modes(plan: Plan, mode, stream=None, check: bool = True) -> int:
+    """Installs per-stage queue orders (device int32 array) in the plan."""
+    rc = load_library().pard_plan_set_modes(plan.handle, _ptr(mode), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_plan_set_modes")
     return rc
 
 

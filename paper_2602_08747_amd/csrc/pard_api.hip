@@ -252,6 +252,25 @@ int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t var
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
+int pard_priority_modes(const pard_plan_t* plan, int32_t series_len, int32_t window, const int32_t* d_rate,
+                        const int32_t* d_prev_mode, int32_t* d_mode, void* stream) {
+    if (!plan || !d_rate || !d_mode) return PARD_E_NULL;
+    if (series_len < 1 || window < 1) return PARD_E_BAD_SHAPE;
+    hipError_t e = launch_priority_modes(plan->dev, series_len, window, d_rate, d_prev_mode, d_mode,
+                                         static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+int pard_plan_set_modes(pard_plan_t* plan, const int32_t* d_mode, void* stream) {
+    if (!plan || !d_mode) return PARD_E_NULL;
+    const int64_t count = (int64_t)plan->host.D * plan->host.S;
+    hipError_t e = launch_set_modes(const_cast<StageRec*>(plan->dev.recs), d_mode, count, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return PARD_E_HIP;
+    plan->host.uniform_mode = -1;          // the stages' modes now live on the device only
+    plan->dev.uniform_mode = -1;
+    return PARD_OK;
+}
+
 int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
                  const int32_t* d_order, const int32_t* d_seg_ptr, const uint8_t* d_drop,
                  int32_t* d_surv_idx, int32_t* d_surv_ptr,

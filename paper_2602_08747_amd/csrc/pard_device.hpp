@@ -170,5 +170,8 @@ struct SubArgs {
     unsigned long long* sub;           // [K*S] out
 };
 hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream);
+hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_t window, const int32_t* rate,
+                                 const int32_t* prev_mode, int32_t* mode_out, hipStream_t stream);
+hipError_t launch_set_modes(StageRec* recs, const int32_t* modes, int64_t count, hipStream_t stream);
 
 }  // namespace pard

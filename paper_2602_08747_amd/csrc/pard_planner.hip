@@ -256,7 +256,107 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
     }
 }
 
+// ---- adaptive priority (Section 3.3) --------------------------------------------------------
+// One wave per rate series, 64 samples at a time.  The window sum at t is the prefix sum of
+// rate[t] - rate[t - w], so one running scan gives the smoothed workload; a second sweep over the
+// series (now in cache) compares every sample with the two thresholds and keeps the last one
+// that decides - which is the priority in force at the end, since samples inside the band
+// change nothing.
+constexpr int kPThreads = 256;
+
+__device__ __forceinline__ unsigned __int128 mul_64_64(uint64_t a, uint64_t b) {
+    return ((unsigned __int128)__umul64hi(a, b) << 64) | (unsigned __int128)(a * b);
+}
+
+__global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, int32_t T, int32_t window, const int32_t* rate,
+                                                                   const int32_t* prev_mode, int32_t* mode_out) {
+    const int lane = threadIdx.x & 63;
+    const int64_t series = (int64_t)P.K * P.S;
+    const int64_t wave_id = ((int64_t)blockIdx.x * kPThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPThreads) >> 6;
+    for (int64_t g = wave_id; g < series; g += waves) {
+        const int64_t rec = P.shared ? g % P.S : g;
+        const StageRec sr = P.recs[rec];
+        const int32_t* r = rate + g * T;
+        // sum of the series and of |rate - smoothed rate|
+        uint64_t sum = 0, dev = 0;
+        int64_t carry = 0;                                          // window sum up to the previous chunk's last sample
+        for (int32_t t0 = 0; t0 < T; t0 += 64) {
+            const int32_t t = t0 + lane;
+            const bool ok = t < T;
+            const int64_t x = ok ? (int64_t)r[t] : 0;
+            const int64_t old = (ok && t >= window) ? (int64_t)r[t - window] : 0;
+            int64_t inc = x - old;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int64_t up = __shfl_up(inc, off);
+                if (lane >= off) inc += up;
+            }
+            const int64_t win = carry + inc;                         // rate[max(0, t-w+1)] + ... + rate[t]
+            carry += __shfl(inc, 63);
+            if (ok) {
+                const int64_t cnt = t + 1 < window ? t + 1 : window;
+                const int64_t ts = win / cnt;
+                const int64_t d = x - ts;
+                dev += (uint64_t)(d < 0 ? -d : d);
+                sum += (uint64_t)x;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            sum += __shfl_xor(sum, off);
+            dev += __shfl_xor(dev, off);
+        }
+        // thresholds, cross-multiplied:  mu > 1 + eps  <=>  rate * lat[B] * sum > W * B * 10^6 * (sum + dev)
+        const uint64_t cap = (uint64_t)(uint32_t)sr.W * (uint32_t)sr.B * 1000000ull;            // < 2^46
+        unsigned __int128 hi, lo;
+        if (sum > 0) {
+            hi = mul_64_64(cap, sum + dev);
+            lo = dev <= sum ? mul_64_64(cap, sum - dev) : (unsigned __int128)0;                   // 1 - eps < 0: never below
+        } else {
+            hi = lo = cap;
+        }
+        const bool never_below = sum > 0 && dev > sum;
+        int32_t mode = prev_mode ? prev_mode[g] : PARD_ORDER_LBF;
+        for (int32_t t0 = 0; t0 < T; t0 += 64) {
+            const int32_t t = t0 + lane;
+            const bool ok = t < T;
+            const uint64_t x = ok ? (uint64_t)(uint32_t)r[t] : 0;
+            const uint64_t xl = x * (uint32_t)sr.latB;                                            // < 2^62
+            const unsigned __int128 lhs = sum > 0 ? mul_64_64(xl, sum) : (unsigned __int128)xl;
+            const bool above = ok && lhs > hi;
+            const bool below = ok && !never_below && lhs < lo;
+            const unsigned long long decided = __ballot(above || below);
+            if (decided) {
+                const int last = 63 - __clzll((long long)decided);
+                mode = ((__ballot(above) >> last) & 1ull) ? PARD_ORDER_HBF : PARD_ORDER_LBF;
+            }
+        }
+        if (lane == 0) mode_out[g] = mode;
+    }
+}
+
+// mode byte of every stage record <- modes[D*S]
+__global__ void set_modes_kernel(StageRec* recs, const int32_t* modes, int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) recs[i].mode = (recs[i].mode & ~0xFF) | (modes[i] == PARD_ORDER_HBF ? PARD_ORDER_HBF : PARD_ORDER_LBF);
+}
+
 }  // namespace
+
+hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_t window, const int32_t* rate,
+                                 const int32_t* prev_mode, int32_t* mode_out, hipStream_t stream) {
+    const int64_t series = (int64_t)plan.K * plan.S;
+    int64_t grid = (series + 3) / 4;
+    if (grid > 4096) grid = 4096;
+    priority_modes_kernel<<<(unsigned)grid, kPThreads, 0, stream>>>(plan, series_len, window, rate, prev_mode, mode_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_set_modes(StageRec* recs, const int32_t* modes, int64_t count, hipStream_t stream) {
+    set_modes_kernel<<<(unsigned)((count + 255) / 256), 256, 0, stream>>>(recs, modes, count);
+    return hipGetLastError();
+}
 
 hipError_t launch_queue_lengths(const PlanDev& plan, int64_t n, const int32_t* stage, const int32_t* snap_ptr,
                                 int32_t* qlen, hipStream_t stream) {

@@ -236,3 +236,81 @@ def test_consistent_rejects_large_snapshots(gpu):
     s = gpu.Session(w)
     assert gpu.pard_estimate_drop_consistent(s.plan, s.n, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, None,
                                              s.est, s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -11
+
+
+# ---- adaptive priority -----------------------------------------------------------------------
+
+def rate_series(w, T, seed, lat=None):
+    """Per (snapshot, stage) a series around the stage's throughput, some far off, some zero."""
+    rng = np.random.default_rng(seed)
+    lat = w.lat_us if lat is None else lat
+    latB = lat.reshape(-1, 64)[np.arange(w.batch.size), w.batch - 1].astype(np.int64)
+    cap = w.workers.astype(np.int64) * w.batch * 1_000_000 // np.maximum(1, latB)
+    idx = np.arange(w.K * w.S) % w.S if w.dag_shared else np.arange(w.K * w.S)
+    base = np.repeat(cap[idx], T).reshape(w.K * w.S, T)
+    rate = np.clip(base * rng.uniform(0.6, 1.5, (w.K * w.S, T)), 0, 2**31 - 1).astype(np.int32)
+    rate[rng.random((w.K * w.S, T)) < 0.05] = 0
+    return rate
+
+
+@pytest.mark.parametrize("T,window", [(1, 1), (7, 3), (64, 5), (65, 64), (200, 250), (1000, 50), (4097, 129)])
+def test_priority_modes(gpu, oracle_mod, T, window):
+    import torch
+    for w in (wl.make_workload(5, n_snapshots=37, per_snapshot=10), wl.random_workload(55, K=6, S=9, n_per_snapshot=10, dag_shared=1),
+              wl.make_workload(4, n_requests=10)):
+        s = gpu.Session(w)
+        rate = rate_series(w, T, 5 * T + window)
+        for prev in (None, (np.arange(w.K * w.S) % 2).astype(np.int32)):
+            want = oracle_mod.priority_modes(w.K, w.S, w.dag_shared, w.batch, w.workers, w.lat_us, rate, window, prev)
+            d_mode = torch.full((w.K * w.S,), -1, dtype=torch.int32, device=s.dev)
+            gpu.pard_priority_modes(s.plan, T, window, torch.from_numpy(rate).to(s.dev),
+                                    None if prev is None else torch.from_numpy(prev).to(s.dev), d_mode)
+            torch.cuda.synchronize()
+            got = d_mode.cpu().numpy()
+            assert np.array_equal(got, want), (w.name, T, window, np.flatnonzero(got != want)[:5])
+        assert 0 < want.mean() < 1 or T == 1
+
+
+def test_priority_extremes(gpu, oracle_mod):
+    import torch
+    w = wl.make_workload(1)
+    w.batch[:] = 64
+    w.workers[:] = 1 << 20
+    lat = w.lat_us.copy()
+    lat[:] = 2**31 - 1
+    lat[64:128] = 0                                    # unbounded throughput: the load factor is 0
+    w.lat_us = lat
+    s = gpu.Session(w)
+    T = 3000
+    rate = np.full((w.K * w.S, T), 2**31 - 1, np.int32)
+    rate[2, ::2] = 0
+    want = oracle_mod.priority_modes(w.K, w.S, w.dag_shared, w.batch, w.workers, lat, rate, 7)
+    d_mode = torch.empty(w.K * w.S, dtype=torch.int32, device=s.dev)
+    gpu.pard_priority_modes(s.plan, T, 7, torch.from_numpy(rate).to(s.dev), None, d_mode)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_mode.cpu().numpy(), want)
+    assert gpu.pard_priority_modes(s.plan, 0, 7, torch.from_numpy(rate).to(s.dev), None, d_mode, check=False) == -2
+    assert gpu.pard_priority_modes(s.plan, T, 0, torch.from_numpy(rate).to(s.dev), None, d_mode, check=False) == -2
+    assert gpu.pard_priority_modes(s.plan, T, 7, None, None, d_mode, check=False) == -1
+
+
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_priority_feeds_the_queue_order(gpu, oracle_mod, max_snap):
+    """Rates -> priorities -> plan -> estimate: the same as the oracle run with those order modes."""
+    import torch
+    for w in (wl.make_workload(5, n_snapshots=14, per_snapshot=3000, permute=True),
+              wl.random_workload(56, K=1, S=7, n_per_snapshot=6000, dag_shared=1)):
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
+        T, window = 300, 20
+        rate = rate_series(w, T, 11)
+        modes = oracle_mod.priority_modes(w.K, w.S, w.dag_shared, w.batch, w.workers, w.lat_us, rate, window)
+        d_mode = torch.empty(w.K * w.S, dtype=torch.int32, device=s.dev)
+        gpu.pard_priority_modes(s.plan, T, window, torch.from_numpy(rate).to(s.dev), None, d_mode)
+        gpu.pard_plan_set_modes(s.plan, d_mode)
+        s.run()
+        got = s.results()
+        assert np.array_equal(d_mode.cpu().numpy(), modes) and 0 < modes.mean() < 1
+        w.order_mode = modes[: w.order_mode.size].astype(np.int32)
+        ref = oracle_mod.run(w, threads=8)
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (w.name, k)
