@@ -4,6 +4,10 @@
 // keep[j] = !drop[order[j]] for every queue slot j; surv_idx is order filtered by keep;
 // surv_ptr[g] = number of kept slots before queue g starts.
 //
+// Two paths.  Snapshots that fit one workgroup are compacted one per workgroup with no
+// dependency between workgroups (second half of this file).  Anything larger is compacted as
+// one stream of tiles:
+//
 // One pass over the data.  A workgroup counts the kept slots of a tile of 4096 queue slots,
 // publishes the count, and receives the number of kept slots in all earlier tiles from a
 // scan service: one wave of a helper workgroup walks the tile counts in order (64 tiles per
