@@ -43,6 +43,14 @@
  * force with exact rationals (tests/test_oracle_priority.py); the paper prints no value for it
  * and its algorithm listing is absent, so parity with the paper is unpinned for this function.
  *
+ * Monitored queueing delay (Section 3.2, State Planner, first item and its footnote: a sliding
+ * window over the recent queueing delays, 5 s and linearly weighted by default):
+ * pard_oracle_queue_delay() gives q_i per (snapshot, stage) from time-stamped delay samples,
+ * and pard_oracle_sub_latency() takes those q_i in place of the snapshot stand-in when they
+ * are passed.  The paper prints no value for it, so parity with the paper is unpinned; the pins
+ * are hand-worked windows, the closed form of a linearly weighted mean over equally spaced
+ * samples, and an exact-rational brute force (tests/test_oracle_window.py).
+ *
  * Parity status: no value in the paper pins the estimate/drop path (it prints none for it).
  * The pins are brute force on tiny inputs, closed forms, invariants and a hand-worked
  * vector (tests/test_oracle_*.py).
@@ -364,10 +372,12 @@ int pard_oracle_estimate_drop_consistent(
  *
  * For the stages i after stage k on one path, with n_i = qlen[snapshot][i] requests queued:
  *   q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i)     queueing delay (snapshot stand-in for the
- *                                                     monitored average)
+ *                                                     monitored average), or, when qdelay is not
+ *                                                     NULL, the monitored q_i = max(qdelay[u*S+i], 0)
  *   d_i = lat_i[min(B_i, n_i + 1)]                     execution duration at the batch size a
  *                                                     joining request would see
- *   (q_i + d_i is stage_cost(n_i), the term the estimate path adds per downstream stage)
+ *   (with the stand-in, q_i + d_i is stage_cost(n_i), the term the estimate path adds per
+ *   downstream stage)
  *
  *   variant 0, full   : sum q_i + sum d_i + w
  *   variant 1, lower  : sum q_i + sum d_i               (batch wait assumed 0)
@@ -396,7 +406,7 @@ int pard_oracle_sub_latency(
         int32_t K, int32_t S, int32_t dag_shared,
         const int32_t* row_ptr, const int32_t* col,
         const int32_t* batch, const int32_t* workers, const int32_t* lat,
-        const int32_t* qlen,
+        const int32_t* qlen, const int32_t* qdelay,
         int32_t variant, int64_t lam_num, int64_t lam_den,
         int64_t M, const int32_t* samples, const uint32_t* picks,
         int64_t* sub, int32_t nthreads) {
@@ -437,8 +447,14 @@ int pard_oracle_sub_latency(
                 for (int32_t t = at + 1; t < b; ++t) {
                     int32_t i = ps.stage[t];
                     int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];
-                    sum_qd += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], nq[i]);
-                    sum_d += L[(int64_t)i * LAT_ENTRIES + seen - 1];
+                    wide_t d_i = L[(int64_t)i * LAT_ENTRIES + seen - 1];
+                    if (qdelay) {
+                        int32_t q_i = qdelay[(int64_t)u * S + i];
+                        sum_qd += (q_i > 0 ? q_i : 0) + d_i;
+                    } else {
+                        sum_qd += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], nq[i]);
+                    }
+                    sum_d += d_i;
                 }
                 wide_t lsub;
                 if (variant == 1) lsub = sum_qd;
@@ -478,6 +494,37 @@ int pard_oracle_sub_latency(
     }
     free(col_base);
     return status;
+}
+
+/*
+ * Monitored queueing delay q_i per (snapshot u, stage s): the linearly weighted mean of the
+ * recent delay samples inside a sliding window (Section 3.2, State Planner; default window 5 s).
+ *
+ * Series g = u*S + s holds `len` samples (time[g*len + j], delay[g*len + j]), in any order: a
+ * request left the queue at `time` after waiting `delay` there (microseconds).  Seen from
+ * now[u], a sample of age = now - time weighs
+ *   w = window - age   for 0 <= age < window,   0 otherwise (older than the window, or later than now)
+ * so the newest sample counts most and the weight falls linearly to nothing at the window's far
+ * edge.  q = floor(sum w * max(delay, 0) / sum w), and 0 when no sample lies in the window.
+ * Returns 0, or 4 for bad arguments.
+ */
+int pard_oracle_queue_delay(
+        int32_t K, int32_t S, int32_t len, int64_t window,
+        const int32_t* time, const int32_t* delay, const int32_t* now, int32_t* q) {
+    if (len < 0 || window < 1) return 4;
+    for (int64_t g = 0; g < (int64_t)K * S; ++g) {
+        wide_t num = 0, den = 0;
+        for (int32_t j = 0; j < len; ++j) {
+            wide_t age = (wide_t)now[g / S] - time[g * len + j];
+            if (age < 0 || age >= window) continue;
+            wide_t w = window - age;
+            wide_t x = delay[g * len + j] > 0 ? delay[g * len + j] : 0;
+            num += w * x;
+            den += w;
+        }
+        q[g] = den > 0 ? (int32_t)(num / den) : 0;
+    }
+    return 0;
 }
 
 /*

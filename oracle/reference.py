@@ -54,13 +54,16 @@ def _load() -> ctypes.CDLL:
         lib.pard_oracle_sub_latency.restype = ctypes.c_int
         lib.pard_oracle_sub_latency.argtypes = [
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
-            _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
+            _i32p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
             ctypes.c_int32, ctypes.c_int64, ctypes.c_int64,
             ctypes.c_int64, _i32p, ctypes.POINTER(ctypes.c_uint32),
             _i64p, ctypes.c_int32]
         lib.pard_oracle_priority_modes.restype = ctypes.c_int
         lib.pard_oracle_priority_modes.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p,
                                                    ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p]
+        lib.pard_oracle_queue_delay.restype = ctypes.c_int
+        lib.pard_oracle_queue_delay.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
+                                                _i32p, _i32p, _i32p, _i32p]
         lib.pard_oracle_compact.restype = ctypes.c_int
         lib.pard_oracle_compact.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                             _i32p, _i32p, _u8p, _i32p, _i32p]
@@ -85,8 +88,8 @@ VARIANT_FULL, VARIANT_LOWER, VARIANT_UPPER, VARIANT_SF, VARIANT_BACK = range(5)
 
 
 def sub_latency(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, qlen, variant=VARIANT_FULL,
-                lam=(1, 10), samples=None, picks=None, threads: int = 1):
-    """Downstream latency L_sub per (snapshot, stage): int64[K*S]."""
+                lam=(1, 10), samples=None, picks=None, threads: int = 1, qdelay=None):
+    """Downstream latency L_sub per (snapshot, stage): int64[K*S].  qdelay: monitored q_i, int32[K*S]."""
     lib = _load()
     rp, cl, B, W, L, q = map(_i32, (dag_row_ptr, dag_col, batch, workers, lat_us, qlen))
     if cl.size == 0:
@@ -96,11 +99,35 @@ def sub_latency(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, 
     pk = np.ascontiguousarray(picks, dtype=np.uint32) if M else np.zeros(1, np.uint32)
     if M:
         assert pk.size == M * S
+    qd = None if qdelay is None else _i32(qdelay)
+    if qd is not None:
+        assert qd.size == K * S
     out = np.zeros(K * S, np.int64)
     rc = lib.pard_oracle_sub_latency(
         K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(q),
+        None if qd is None else _p32(qd),
         int(variant), int(lam[0]), int(lam[1]), M, _p32(smp), pk.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
         out.ctypes.data_as(_i64p), int(threads))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return out
+
+
+def queue_delay(K, S, time, delay, now, window):
+    """Linearly weighted sliding-window mean of the delay samples per (snapshot, stage): int32[K*S].
+    time, delay: int32[K*S, len]; now: int32[K]."""
+    lib = _load()
+    tm = np.ascontiguousarray(_i32(time).reshape(K * S, -1))
+    dl = np.ascontiguousarray(_i32(delay).reshape(K * S, -1))
+    assert tm.shape == dl.shape
+    nw = _i32(now)
+    assert nw.size == K
+    out = np.zeros(K * S, np.int32)
+    if tm.shape[1] == 0:
+        tm = np.zeros((K * S, 1), np.int32); dl = tm.copy(); length = 0
+    else:
+        length = int(tm.shape[1])
+    rc = lib.pard_oracle_queue_delay(K, S, length, int(window), _p32(tm), _p32(dl), _p32(nw), _p32(out))
     if rc != 0:
         raise ValueError(f"oracle rejected the arguments (code {rc})")
     return out

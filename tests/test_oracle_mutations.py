@@ -12,6 +12,7 @@ from tests import test_oracle_consistent as pins_consistent
 from tests import test_oracle_pins as pins
 from tests import test_oracle_priority as pins_priority
 from tests import test_oracle_sub as pins_sub
+from tests import test_oracle_window as pins_window
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -52,6 +53,16 @@ MUTATIONS = [
      "hi = W * B * 1000000 * sum;\n                lo = W * B * 1000000 * sum;", "priority"),
     ("throughput ignores the worker count", "hi = W * B * 1000000 * (sum + dev);", "hi = B * 1000000 * (sum + dev);", "priority"),
     ("previous priority ignored", "int32_t mode = prev_mode ? prev_mode[g] : MODE_LBF;", "int32_t mode = MODE_LBF;", "priority"),
+    ("old samples weigh most", "wide_t w = window - age;", "wide_t w = age + 1;", "window"),
+    ("plain mean inside the window", "wide_t w = window - age;", "wide_t w = 1;", "window"),
+    ("samples later than now counted", "if (age < 0 || age >= window) continue;", "if (age >= window) continue;", "window"),
+    ("window never ends", "if (age < 0 || age >= window) continue;", "if (age < 0) continue;", "window"),
+    ("negative delays kept", "wide_t x = delay[g * len + j] > 0 ? delay[g * len + j] : 0;", "wide_t x = delay[g * len + j];", "window"),
+    ("every series seen from the first snapshot's clock", "wide_t age = (wide_t)now[g / S] - time[g * len + j];",
+     "wide_t age = (wide_t)now[0] - time[g * len + j];", "window"),
+    ("monitored delay on top of the queue-length term", "sum_qd += (q_i > 0 ? q_i : 0) + d_i;",
+     "sum_qd += (q_i > 0 ? q_i : 0) + stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], nq[i]);", "window"),
+    ("monitored delay without the execution duration", "sum_qd += (q_i > 0 ? q_i : 0) + d_i;", "sum_qd += (q_i > 0 ? q_i : 0);", "window"),
 ]
 
 
@@ -106,7 +117,18 @@ def priority_pins(m):
         pins_priority.test_brute_force(m, seed)
 
 
-GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins}
+def window_pins(m):
+    pins_window.test_hand_worked_windows(m)
+    pins_window.test_constant_delay_is_its_own_mean(m)
+    pins_window.test_equally_spaced_linear_trend_closed_form(m)
+    pins_window.test_order_and_padding_do_not_matter(m)
+    for seed in range(12):
+        pins_window.test_brute_force(m, seed)
+    pins_window.test_monitored_delay_replaces_the_queue_term(m)
+
+
+GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins,
+          "window": window_pins}
 
 
 @pytest.mark.parametrize("name,old,new,group", MUTATIONS, ids=[m[0] for m in MUTATIONS])
