@@ -45,7 +45,7 @@ MUTATIONS = [
     ("draws indexed stage-major", "int64_t arr = samples[picks[j * S + i] % (uint64_t)M];", "int64_t arr = samples[picks[(int64_t)i * M + j] % (uint64_t)M];", "sub"),
     ("upper variant adds the durations once", "else if (variant == 2) lsub = sum_qd + sum_d;", "else if (variant == 2) lsub = sum_qd;", "sub"),
     ("sf variant keeps the queueing delay", "else if (variant == 3) lsub = sum_d;", "else if (variant == 3) lsub = sum_qd;", "sub"),
-    ("duration at the full batch size", "int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];\n                    sum_qd", "int64_t seen = B[i];\n                    sum_qd", "sub"),
+    ("duration at the full batch size", "int64_t seen = (int64_t)nq[i] + 1 < B[i] ? (int64_t)nq[i] + 1 : B[i];\n                    wide_t d_i", "int64_t seen = B[i];\n                    wide_t d_i", "sub"),
     ("sum over paths instead of maximum (downstream latency)", "if (lsub > best) best = lsub;", "best += lsub;", "sub"),
     ("no hysteresis: LBF whenever not above the upper threshold", "else if (lhs < lo) mode = MODE_LBF;", "else mode = MODE_LBF;", "priority"),
     ("epsilon from the window sum instead of its mean", "wide_t ts = win / (t - lo + 1);", "wide_t ts = win;", "priority"),
