@@ -201,6 +201,57 @@ def bench_priority(args, w, s, gen_s):
     return out
 
 
+def bench_queue_delay(args, w, s, gen_s):
+    """Monitored queueing delay: 1024 time-stamped delay samples per (snapshot, stage), 5 s window."""
+    import numpy as np
+    import torch
+    from paper_2602_08747_amd import binding
+    L, window = 1024, 5_000_000
+    rng = np.random.default_rng([20260208, 97])
+    G = w.K * w.S
+    now = w.now.astype(np.int64).repeat(w.S)[:, None]
+    tm = (now - rng.integers(0, 2 * window, size=(G, L))).clip(-2**31, 2**31 - 1).astype(np.int32)   # half inside the window
+    dl = rng.integers(0, 400_000, size=(G, L)).astype(np.int32)
+    d_time, d_delay = torch.from_numpy(tm).to(s.dev), torch.from_numpy(dl).to(s.dev)
+    d_q = torch.empty(G, dtype=torch.int32, device=s.dev)
+    for _ in range(max(args.warmup, 1)):
+        binding.pard_queue_delay(s.plan, L, window, d_time, d_delay, s.now, d_q)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        binding.pard_queue_delay(s.plan, L, window, d_time, d_delay, s.now, d_q)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    k_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    alg_bytes = 8.0 * tm.size                         # time and delay of every sample, once
+    achieved = alg_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
+    out = {
+        "metric": "queueing-delay estimates/sec (linearly weighted 5 s window over 1024 delay samples per stage)",
+        "value": round(G / (ms_per_step * 1e-3), 1), "unit": "snapshot-stages/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": w.name + "+queue-delay", "snapshots": w.K, "stages": w.S, "series_len": L, "window_us": window,
+                   "mean_q_us": round(float(d_q.float().mean().item()), 1), "generate_s": round(gen_s, 2)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None, "kernel": "queue_delay_kernel",
+                     "bytes_per_sample": 8.0, "launch_ms": round(k_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build_oracle()
+        Ks = min(w.K, 1024)
+        t0 = time.perf_counter()
+        oracle.queue_delay(Ks, w.S, tm[:Ks * w.S], dl[:Ks * w.S], w.now[:Ks], window)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(Ks * w.S / cpu_s, 1), "unit": "snapshot-stages/s", "cores": 1, "kind": "oracle",
+                               "sample": f"first {Ks} of {w.K} snapshots, 1 run", "seconds": round(cpu_s, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,10 +262,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--consistent", action="store_true",
                     help="sequentially consistent dropping (positions count kept requests only; on-chip path only)")
-    ap.add_argument("--workload", choices=["hot-path", "planner", "priority"], default="hot-path",
+    ap.add_argument("--workload", choices=["hot-path", "planner", "priority", "queue-delay"], default="hot-path",
                     help="hot-path: estimate+drop+compact (default); planner: queue lengths + downstream latency "
                          "with the sampled batch-wait quantile on the same snapshots; priority: adaptive priority "
-                         "from a rate series per (snapshot, stage)")
+                         "from a rate series per (snapshot, stage); queue-delay: the sliding-window queueing delay "
+                         "from delay samples per (snapshot, stage)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -244,6 +296,9 @@ def main():
         return
     if args.workload == "priority":
         print(json.dumps(bench_priority(args, w, s, gen_s)))
+        return
+    if args.workload == "queue-delay":
+        print(json.dumps(bench_queue_delay(args, w, s, gen_s)))
         return
 
     if args.calibration_copy_mib > 0:

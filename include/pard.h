@@ -228,6 +228,35 @@ int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t var
                      const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream);
 
 /*
+ * The monitored queueing delay q_i of every (snapshot, stage) (Section 3.2, State Planner: the
+ * recent average queueing delay from a sliding window, by default 5 s and linearly weighted).
+ * Series u*S + s holds series_len samples, in any order: a request left that queue at
+ * d_time[(u*S + s)*series_len + j] after waiting d_delay[...] there (microseconds, negative
+ * delays read as 0).  Seen from d_now[u], a sample of age = now - time weighs window_us - age
+ * when 0 <= age < window_us and nothing otherwise (pad unused slots with a time after now);
+ *   d_q[u*S + s] = floor(sum w * delay / sum w),  0 when no sample lies in the window.
+ *
+ *   series_len             0..PARD_MAX_DELAY_SAMPLES
+ *   window_us              1..2^31-1
+ *   d_time, d_delay        device int32[K*S*series_len]
+ *   d_now                  device int32[K]
+ *   d_q                    device out int32[K*S]
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE, PARD_E_HIP.  Enqueues on `stream`, allocates nothing.
+ */
+#define PARD_MAX_DELAY_SAMPLES (1 << 30)
+int pard_queue_delay(const pard_plan_t* plan, int32_t series_len, int64_t window_us, const int32_t* d_time,
+                     const int32_t* d_delay, const int32_t* d_now, int32_t* d_q, void* stream);
+
+/*
+ * pard_sub_latency with the monitored queueing delays in place of the ones derived from the
+ * queue lengths: q_i = max(d_qdelay[u*S + i], 0) (e.g. the output of pard_queue_delay); d_i still
+ * follows d_qlen.  Everything else as for pard_sub_latency; d_qdelay NULL is PARD_E_NULL.
+ */
+int pard_sub_latency_q(const pard_plan_t* plan, const int32_t* d_qlen, const int32_t* d_qdelay, int32_t variant,
+                       int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                       const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream);
+
+/*
  * pard_estimate_drop with the downstream part given (Eq.(4): the Request Broker adds its own
  * stage's wait and execution to the State Planner's L_sub):
  *   est = cost_k(pos) + d_sub[u*S + k]      (d_sub >= 0; values above 2^40 read as 2^40)

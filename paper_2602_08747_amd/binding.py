@@ -26,7 +26,7 @@ STATUS_NAMES = {
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
            "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
-           "pard_sub_latency", "pard_compact", "pard_strerror"]
+           "pard_sub_latency", "pard_sub_latency_q", "pard_queue_delay", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
 
 
@@ -66,6 +66,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_priority_modes.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp, vp, vp]
     lib.pard_plan_set_modes.argtypes = [vp, vp, vp]
     lib.pard_sub_latency.argtypes = [vp, vp, ctypes.c_int32, i64, i64, ctypes.c_int32, vp, vp, vp, vp]
+    lib.pard_sub_latency_q.argtypes = [vp, vp, vp, ctypes.c_int32, i64, i64, ctypes.c_int32, vp, vp, vp, vp]
+    lib.pard_queue_delay.argtypes = [vp, ctypes.c_int32, i64, vp, vp, vp, vp, vp]
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ctypes.c_int
     lib.pard_strerror.argtypes = [ctypes.c_int]
@@ -221,6 +223,26 @@ def pard_sub_latency(plan: Plan, qlen, variant: int, lambda_num: int, lambda_den
     return rc
 
 
+def pard_sub_latency_q(plan: Plan, qlen, qdelay, variant: int, lambda_num: int, lambda_den: int, num_samples: int, samples,
+                       picks, sub, stream=None, check: bool = True) -> int:
+    """pard_sub_latency with monitored queueing delays (device int32[K*S]) for the q_i."""
+    rc = load_library().pard_sub_latency_q(plan.handle, _ptr(qlen), _ptr(qdelay), int(variant), int(lambda_num),
+                                           int(lambda_den), int(num_samples), _ptr(samples), _ptr(picks), _ptr(sub),
+                                           _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_sub_latency_q")
+    return rc
+
+
+def pard_queue_delay(plan: Plan, series_len: int, window_us: int, time, delay, now, q, stream=None, check: bool = True) -> int:
+    """Enqueues the sliding-window queueing delay (one value per (snapshot, stage)) on `stream`."""
+    rc = load_library().pard_queue_delay(plan.handle, int(series_len), int(window_us), _ptr(time), _ptr(delay), _ptr(now),
+                                         _ptr(q), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_queue_delay")
+    return rc
+
+
 def pard_compact(plan: Plan, n: int, max_snapshot_requests: int, order, seg_ptr, drop, surv_idx, surv_ptr, workspace,
                  stream=None, check: bool = True) -> int:
     """Enqueues the survivor-compaction kernels on `stream`."""
@@ -273,15 +295,19 @@ class Session:
                                    self.snap_ptr, self.now, sub, self.est, self.drop, self.order, self.seg_ptr,
                                    self.workspace, stream)
 
-    def planner(self, variant=SUB_FULL, lam=(1, 10), samples=None, picks=None, stream=None):
-        """Queue lengths, then the downstream latency per (snapshot, stage) (device int64[K*S])."""
+    def planner(self, variant=SUB_FULL, lam=(1, 10), samples=None, picks=None, stream=None, qdelay=None):
+        """Queue lengths, then the downstream latency per (snapshot, stage) (device int64[K*S]).
+        qdelay: monitored queueing delays (device int32[K*S]) to use for the q_i."""
         torch = self.torch
         if not hasattr(self, "qlen"):
             self.qlen = torch.empty(self.w.K * self.w.S, dtype=torch.int32, device=self.dev)
             self.sub = torch.empty(self.w.K * self.w.S, dtype=torch.int64, device=self.dev)
         pard_queue_lengths(self.plan, self.n, self.stage, self.snap_ptr, self.qlen, stream)
         m = 0 if samples is None else int(samples.numel())
-        pard_sub_latency(self.plan, self.qlen, variant, lam[0], lam[1], m, samples, picks, self.sub, stream)
+        if qdelay is None:
+            pard_sub_latency(self.plan, self.qlen, variant, lam[0], lam[1], m, samples, picks, self.sub, stream)
+        else:
+            pard_sub_latency_q(self.plan, self.qlen, qdelay, variant, lam[0], lam[1], m, samples, picks, self.sub, stream)
         return self.sub
 
     def compact(self, stream=None):

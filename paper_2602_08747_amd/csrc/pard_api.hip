@@ -222,14 +222,15 @@ int pard_queue_lengths(const pard_plan_t* plan, int64_t n, const int32_t* d_stag
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
-int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t variant,
-                     int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
-                     const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream) {
+static int sub_latency_impl(const pard_plan_t* plan, const int32_t* d_qlen, const int32_t* d_qdelay, int32_t variant,
+                            int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                            const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream) {
     if (!plan || !d_qlen || !d_sub) return PARD_E_NULL;
     if (variant < PARD_SUB_FULL || variant > PARD_SUB_BACK) return PARD_E_BAD_SHAPE;
     SubArgs a{};
     a.plan = plan->dev;
     a.qlen = d_qlen;
+    a.qdelay = d_qdelay;
     a.variant = variant;
     a.sub = reinterpret_cast<unsigned long long*>(d_sub);
     if (variant == PARD_SUB_FULL) {
@@ -249,6 +250,29 @@ int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t var
         }
     }
     hipError_t e = launch_sub_latency(a, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
+int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t variant,
+                     int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                     const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream) {
+    return sub_latency_impl(plan, d_qlen, nullptr, variant, lambda_num, lambda_den, num_samples, d_samples, d_picks, d_sub, stream);
+}
+
+int pard_sub_latency_q(const pard_plan_t* plan, const int32_t* d_qlen, const int32_t* d_qdelay, int32_t variant,
+                       int64_t lambda_num, int64_t lambda_den, int32_t num_samples,
+                       const int32_t* d_samples, const uint32_t* d_picks, int64_t* d_sub, void* stream) {
+    if (!d_qdelay) return PARD_E_NULL;
+    return sub_latency_impl(plan, d_qlen, d_qdelay, variant, lambda_num, lambda_den, num_samples, d_samples, d_picks, d_sub, stream);
+}
+
+int pard_queue_delay(const pard_plan_t* plan, int32_t series_len, int64_t window_us, const int32_t* d_time,
+                     const int32_t* d_delay, const int32_t* d_now, int32_t* d_q, void* stream) {
+    if (!plan || !d_now || !d_q) return PARD_E_NULL;
+    if (series_len < 0 || series_len > PARD_MAX_DELAY_SAMPLES || window_us < 1 || window_us > 0x7fffffff) return PARD_E_BAD_SHAPE;
+    if (series_len > 0 && (!d_time || !d_delay)) return PARD_E_NULL;
+    hipError_t e = launch_queue_delay(plan->host.K, plan->host.S, series_len, (uint32_t)window_us, d_time, d_delay, d_now, d_q,
+                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 

@@ -162,6 +162,7 @@ hipError_t launch_queue_lengths(const PlanDev& plan, int64_t n, const int32_t* s
 struct SubArgs {
     PlanDev plan;
     const int32_t* qlen;               // [K*S]
+    const int32_t* qdelay;             // [K*S] monitored queueing delays, or null: derived from qlen
     int32_t variant;                   // PARD_SUB_*
     int64_t rank;                      // 1-based order statistic of the sampled totals (full variant)
     int32_t num_samples;
@@ -172,6 +173,8 @@ struct SubArgs {
 hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream);
 hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_t window, const int32_t* rate,
                                  const int32_t* prev_mode, int32_t* mode_out, hipStream_t stream);
+hipError_t launch_queue_delay(int32_t K, int32_t S, int32_t len, uint32_t window, const int32_t* time, const int32_t* delay,
+                              const int32_t* now, int32_t* q, hipStream_t stream);
 hipError_t launch_set_modes(StageRec* recs, const int32_t* modes, int64_t count, hipStream_t stream);
 
 }  // namespace pard

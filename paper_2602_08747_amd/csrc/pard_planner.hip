@@ -5,7 +5,9 @@
 // collected arrival process, and the ablation variants that replace w or drop terms
 // (Section 5.1 baseline table, Section 5.3).  Also the queue lengths those terms depend on.
 //
-//   q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i),  d_i = lat_i[min(B_i, n_i+1)],  n_i queued at stage i
+//   q_i = floor(ceil(n_i/B_i) * lat_i[B_i] / W_i) from the queue length, or the monitored delay
+//   (linearly weighted sliding window over time-stamped delay samples, further down) when given;
+//   d_i = lat_i[min(B_i, n_i+1)],  n_i queued at stage i
 //   sample j, stage i: arrival a = max(samples[picks[j*S+i] mod M], 0) waits (d_i - a mod d_i) mod d_i
 //   for the module's next batch (batches back to back, boundaries at multiples of d_i)
 //   T_j = sum over the later stages of the path; w = rank-th smallest T_j (rank = ceil(lambda*M)).
@@ -96,14 +98,19 @@ __device__ __forceinline__ bool entry_of(const PlanDev& P, int64_t b, int32_t& u
 
 // q_i + d_i (clamped at 2^40 like every stage cost) and d_i of stage i with n queued
 __device__ __forceinline__ void stage_terms(const PlanDev& P, int32_t u, int32_t i, const int32_t* qlen,
-                                            uint64_t& cost, uint32_t& dur) {
+                                            const int32_t* qdelay, uint64_t& cost, uint32_t& dur) {
     const int64_t rec = (P.shared ? 0 : (int64_t)u * P.S) + i;
     const StageRec r = P.recs[rec];
     const int32_t q = qlen[(int64_t)u * P.S + i];
     const uint32_t n = q > 0 ? (uint32_t)q : 0u;
     const int32_t* lat_row = P.lat + rec * PARD_LAT_ENTRIES;
-    cost = stage_cost(r, n, lat_row);
     dur = (uint32_t)lat_row[(n + 1u < (uint32_t)r.B ? n + 1u : (uint32_t)r.B) - 1u];
+    if (qdelay) {
+        const int32_t qd = qdelay[(int64_t)u * P.S + i];
+        cost = (uint64_t)(qd > 0 ? (uint32_t)qd : 0u) + dur;
+    } else {
+        cost = stage_cost(r, n, lat_row);
+    }
 }
 
 // Variants without sampling: one thread per (snapshot, path entry).
@@ -118,7 +125,7 @@ __global__ __launch_bounds__(256) void sub_simple_kernel(SubArgs A, int64_t item
     for (int32_t t = e + 1; t < end; ++t) {
         uint64_t c;
         uint32_t d;
-        stage_terms(P, u, P.entry_stage[t], A.qlen, c, d);
+        stage_terms(P, u, P.entry_stage[t], A.qlen, A.qdelay, c, d);
         sum_qd += c;
         sum_d += d;
     }
@@ -163,7 +170,7 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
         const int32_t i = P.entry_stage[e + 1 + tid];
         uint64_t c;
         uint32_t d;
-        stage_terms(P, u, i, A.qlen, c, d);
+        stage_terms(P, u, i, A.qlen, A.qdelay, c, d);
         atomicAdd(&L.sum_qd, (unsigned long long)c);
         atomicAdd(&L.sum_d, d);                                 // < 2^32: at most 64 stages of at most 2^25
         // multiply-high constants for x mod d (Granlund & Montgomery, N = 32), d >= 1
@@ -336,6 +343,92 @@ __global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, in
     }
 }
 
+// ---- monitored queueing delay (Section 3.2, State Planner: sliding window over recent delays) ----
+// One wave per series of (time, delay) samples.  A sample of age = now - time inside
+// [0, window) weighs window - age; the result is floor(sum w * delay / sum w).  Weights and
+// delays are below 2^31, so a product fits 62 bits and the sums are carried in 128 bits.
+constexpr int kDUnroll = 4;                             // loads of a lane in flight
+
+__global__ __launch_bounds__(kPThreads) void queue_delay_kernel(int32_t K, int32_t S, int32_t len, uint32_t window,
+                                                                const int32_t* time, const int32_t* delay,
+                                                                const int32_t* now, int32_t* q) {
+    const int lane = threadIdx.x & 63;
+    const int64_t series = (int64_t)K * S;
+    const int64_t wave_id = ((int64_t)blockIdx.x * kPThreads + threadIdx.x) >> 6;
+    const int64_t waves = ((int64_t)gridDim.x * kPThreads) >> 6;
+    // every series starts on a 16-byte boundary when the arrays do and the length is a multiple of 4
+    const bool vec = (len & 3) == 0 && ((reinterpret_cast<uintptr_t>(time) | reinterpret_cast<uintptr_t>(delay)) & 15) == 0;
+    for (int64_t g = wave_id; g < series; g += waves) {
+        const int64_t t_now = now[g / S];
+        const int32_t* tm = time + g * len;
+        const int32_t* dl = delay + g * len;
+        uint64_t lo = 0, hi = 0, den = 0;
+        auto add = [&](bool ok, int32_t t, int32_t x) {
+            const int64_t age = t_now - (int64_t)t;
+            const bool in = ok && age >= 0 && age < (int64_t)window;
+            const uint64_t w = in ? (uint64_t)window - (uint64_t)age : 0ull;
+            const uint64_t p = w * (uint64_t)(x > 0 ? (uint32_t)x : 0u);
+            lo += p;
+            hi += (uint64_t)(lo < p);
+            den += w;
+        };
+        if (vec) {                                      // four samples per load
+            const int4* tm4 = reinterpret_cast<const int4*>(tm);
+            const int4* dl4 = reinterpret_cast<const int4*>(dl);
+            const int32_t len4 = len >> 2;
+            for (int32_t j0 = lane; j0 < len4; j0 += 64 * kDUnroll) {
+                int4 t[kDUnroll], x[kDUnroll];
+#pragma unroll
+                for (int i = 0; i < kDUnroll; ++i) {
+                    const int32_t j = j0 + 64 * i;
+                    const bool ok = j < len4;
+                    t[i] = ok ? tm4[j] : make_int4(0, 0, 0, 0);
+                    x[i] = ok ? dl4[j] : make_int4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < kDUnroll; ++i) {
+                    const bool ok = j0 + 64 * i < len4;
+                    add(ok, t[i].x, x[i].x);
+                    add(ok, t[i].y, x[i].y);
+                    add(ok, t[i].z, x[i].z);
+                    add(ok, t[i].w, x[i].w);
+                }
+            }
+        } else {
+            for (int32_t j0 = lane; j0 < len; j0 += 64 * kDUnroll) {
+                int32_t t[kDUnroll], x[kDUnroll];
+#pragma unroll
+                for (int i = 0; i < kDUnroll; ++i) {
+                    const int32_t j = j0 + 64 * i;
+                    const bool ok = j < len;
+                    t[i] = ok ? tm[j] : 0;
+                    x[i] = ok ? dl[j] : 0;
+                }
+#pragma unroll
+                for (int i = 0; i < kDUnroll; ++i) add(j0 + 64 * i < len, t[i], x[i]);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const uint64_t lo2 = __shfl_xor(lo, off), hi2 = __shfl_xor(hi, off);
+            lo += lo2;
+            hi += hi2 + (uint64_t)(lo < lo2);
+            den += __shfl_xor(den, off);
+        }
+        if (lane == 0) {
+            // the quotient is a weighted mean of values below 2^31: settle its 31 bits from the top
+            const unsigned __int128 num = ((unsigned __int128)hi << 64) | (unsigned __int128)lo;
+            uint32_t quo = 0;
+            if (den > 0)
+                for (int b = 30; b >= 0; --b) {
+                    const uint32_t cand = quo | (1u << b);
+                    if (mul_64_64(den, cand) <= num) quo = cand;
+                }
+            q[g] = (int32_t)quo;
+        }
+    }
+}
+
 // mode byte of every stage record <- modes[D*S]
 __global__ void set_modes_kernel(StageRec* recs, const int32_t* modes, int64_t count) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -350,6 +443,15 @@ hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_
     int64_t grid = (series + 3) / 4;
     if (grid > 4096) grid = 4096;
     priority_modes_kernel<<<(unsigned)grid, kPThreads, 0, stream>>>(plan, series_len, window, rate, prev_mode, mode_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_queue_delay(int32_t K, int32_t S, int32_t len, uint32_t window, const int32_t* time, const int32_t* delay,
+                              const int32_t* now, int32_t* q, hipStream_t stream) {
+    const int64_t series = (int64_t)K * S;
+    int64_t grid = (series + 3) / 4;
+    if (grid > 8192) grid = 8192;
+    queue_delay_kernel<<<(unsigned)grid, kPThreads, 0, stream>>>(K, S, len, window, time, delay, now, q);
     return hipGetLastError();
 }
 

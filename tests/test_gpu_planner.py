@@ -314,3 +314,109 @@ def test_priority_feeds_the_queue_order(gpu, oracle_mod, max_snap):
         ref = oracle_mod.run(w, threads=8)
         for k in KEYS:
             assert np.array_equal(got[k], ref[k]), (w.name, k)
+
+
+# ---- monitored queueing delay (sliding window) -------------------------------------------------------
+
+def delay_series(w, L, window, seed, wide=False):
+    """Time-stamped delay samples per (snapshot, stage): ages spread over about two windows, some later
+    than now."""
+    rng = np.random.default_rng(seed)
+    G = w.K * w.S
+    now = w.now.astype(np.int64).repeat(w.S)[:, None]
+    span = min(2 * window, 2**31 - 1)
+    time = (now - rng.integers(-span // 16 - 1, span, size=(G, L))).clip(-2**31, 2**31 - 1).astype(np.int32)
+    delay = rng.integers(-1000, 2**31 - 1 if wide else 400_000, size=(G, L)).astype(np.int32)
+    return time, delay
+
+
+@pytest.mark.parametrize("L,window", [(0, 5_000_000), (1, 5_000_000), (63, 1000), (64, 5_000_000), (65, 7),
+                                      (257, 2**31 - 1), (1000, 5_000_000), (4099, 1_000_000)])
+def test_queue_delay(gpu, oracle_mod, L, window):
+    import torch
+    for w in (wl.make_workload(5, n_snapshots=50, per_snapshot=10), wl.random_workload(31, K=3, S=5, n_per_snapshot=4, dag_shared=1)):
+        for wide in (False, True):
+            print("case", w.name, L, window, wide, flush=True)
+            s = gpu.Session(w)
+            time, delay = delay_series(w, L, window, 7 + L, wide)
+            want = oracle_mod.queue_delay(w.K, w.S, time, delay, w.now, window)
+            q = torch.full((w.K * w.S,), -9, dtype=torch.int32, device=s.dev)
+            d_time = torch.from_numpy(time.ravel().copy()).to(s.dev) if L else None
+            d_delay = torch.from_numpy(delay.ravel().copy()).to(s.dev) if L else None
+            gpu.pard_queue_delay(s.plan, L, window, d_time, d_delay, s.now, q)
+            torch.cuda.synchronize()
+            got = q.cpu().numpy()
+            assert np.array_equal(got, want), (np.flatnonzero(got != want)[:5], got[got != want][:5], want[got != want][:5])
+
+
+def test_queue_delay_extremes_and_errors(gpu, oracle_mod):
+    import torch
+    w = wl.make_workload(1)
+    w.now[:] = 2**31 - 1
+    s = gpu.Session(w)
+    L = 5000
+    big = 2**31 - 1
+    time = np.full((w.S, L), big, np.int32)
+    delay = np.full((w.S, L), big, np.int32)
+    time[1, ::2] = 0                                     # half the samples at the far edge: weight 0 at age = window
+    delay[2, :] = np.arange(L)
+    q = torch.empty(w.S, dtype=torch.int32, device=s.dev)
+    d_time, d_delay = torch.from_numpy(time.ravel()).to(s.dev), torch.from_numpy(delay.ravel()).to(s.dev)
+    gpu.pard_queue_delay(s.plan, L, big, d_time, d_delay, s.now, q)
+    torch.cuda.synchronize()
+    assert np.array_equal(q.cpu().numpy(), oracle_mod.queue_delay(w.K, w.S, time, delay, w.now, big))
+    assert q.cpu().numpy()[0] == big
+    # the same series from buffers that do not start on a 16-byte boundary
+    pad = torch.zeros(1, dtype=torch.int32, device=s.dev)
+    o_time, o_delay = torch.cat([pad, d_time])[1:], torch.cat([pad, d_delay])[1:]
+    assert o_time.data_ptr() % 16 == 4
+    q2 = torch.empty_like(q)
+    gpu.pard_queue_delay(s.plan, L, big, o_time, o_delay, s.now, q2)
+    torch.cuda.synchronize()
+    assert torch.equal(q, q2)
+    assert gpu.pard_queue_delay(s.plan, L, 0, d_time, d_delay, s.now, q, check=False) == -2
+    assert gpu.pard_queue_delay(s.plan, L, 2**31, d_time, d_delay, s.now, q, check=False) == -2
+    assert gpu.pard_queue_delay(s.plan, -1, 10, d_time, d_delay, s.now, q, check=False) == -2
+    assert gpu.pard_queue_delay(s.plan, L, 10, None, d_delay, s.now, q, check=False) == -1
+    assert gpu.pard_queue_delay(s.plan, L, 10, d_time, d_delay, s.now, None, check=False) == -1
+    sub = torch.zeros(w.K * w.S, dtype=torch.int64, device=s.dev)
+    assert gpu.pard_sub_latency_q(s.plan, q, None, gpu.SUB_LOWER, 0, 1, 0, None, None, sub, check=False) == -1
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_monitored_delay_feeds_the_estimate(gpu, oracle_mod, max_snap):
+    """Delay samples -> q_i -> L_sub with the sampled batch wait -> estimate, drop, compaction on the GPU,
+    against the same chain of oracle calls."""
+    import torch
+    for w in (wl.make_workload(5, n_snapshots=19, per_snapshot=4000, permute=True),
+              wl.random_workload(41, K=4, S=6, n_per_snapshot=1500, dag_shared=1)):
+        w.now[:] = np.maximum(0, w.now.astype(np.int64) - 200000).astype(np.int32)
+        window = 5_000_000
+        time, delay = delay_series(w, 300, window, 99)
+        M = 2000
+        samples, picks = draws(19, M, w.S, 60_000_000)
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
+        d_q = torch.empty(w.K * w.S, dtype=torch.int32, device=s.dev)
+        gpu.pard_queue_delay(s.plan, 300, window, torch.from_numpy(time.ravel().copy()).to(s.dev),
+                             torch.from_numpy(delay.ravel().copy()).to(s.dev), s.now, d_q)
+        want_q = oracle_mod.queue_delay(w.K, w.S, time, delay, w.now, window)
+        qlen = oracle_qlen(w)
+        d_samples = torch.from_numpy(samples).to(s.dev)
+        d_picks = torch.from_numpy(picks.view(np.int32)).to(s.dev)
+        for variant, lam in ((gpu.SUB_FULL, (1, 10)), (gpu.SUB_LOWER, (0, 1)), (gpu.SUB_UPPER, (0, 1)), (gpu.SUB_SF, (0, 1))):
+            sub = s.planner(variant, lam, d_samples, d_picks, qdelay=d_q)
+            s.run(sub=sub)
+            got = s.results()
+            assert np.array_equal(d_q.cpu().numpy(), want_q)
+            want_sub = oracle_mod.sub_latency(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us,
+                                              qlen, variant, lam, samples, picks, threads=8, qdelay=want_q)
+            assert np.array_equal(s.sub.cpu().numpy(), want_sub), variant
+            est, drop, order, seg_ptr = oracle_mod.estimate_drop(
+                w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, w.order_mode,
+                w.arrival, w.deadline, w.stage, w.snap_ptr, w.now, threads=8, sub=want_sub)
+            surv_idx, surv_ptr = oracle_mod.compact(w.K, w.S, order, seg_ptr, drop)
+            ref = dict(est=est, drop=drop, order=order, seg_ptr=seg_ptr, surv_idx=surv_idx, surv_ptr=surv_ptr)
+            for k in KEYS:
+                assert np.array_equal(got[k], ref[k]), (w.name, variant, k)
+            assert 0 < drop.mean() < 1, drop.mean()
