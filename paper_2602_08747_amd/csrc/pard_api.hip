@@ -150,7 +150,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
     if (n > 0 && plan->host.any_fcfs && !d_arrival) return PARD_E_NULL;
     const bool fused = max_snapshot_requests <= PARD_FUSED_SNAPSHOT_CAPACITY;
-    if (!fused && (consistent || !sort_supported(plan->host.K, plan->host.S, n, max_snapshot_requests))) return PARD_E_UNSUPPORTED;
+    if (!fused && !sort_supported(plan->host.K, plan->host.S, n, max_snapshot_requests)) return PARD_E_UNSUPPORTED;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
         workspace_bytes < workspace_need(plan, n, max_snapshot_requests)) return PARD_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -177,6 +177,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         a.snap_ptr = d_snap_ptr; a.now = d_now;
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
         a.sub = d_sub;
+        a.consistent = consistent ? 1 : 0;
         a.status = status;
         a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
         a.num_cus = plan->num_cus;

@@ -129,6 +129,7 @@ struct SortArgs {
     uint8_t* drop;
     int32_t *order, *seg_ptr;
     const int64_t* sub;                // as in FusedArgs
+    int32_t consistent;                // as in FusedArgs
     uint32_t* status;
     void* workspace;                   // sort_workspace_bytes(K, S, n) bytes, 256-byte aligned
     int32_t num_cus;

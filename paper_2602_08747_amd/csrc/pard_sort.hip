@@ -48,7 +48,8 @@ constexpr int kStreamBlocksMax = 1024;                 // upper bound on the gri
 constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
 
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2], total;
+    int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2],
+            min_lat, alive, wkept, total;
     int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits;
 };
@@ -70,6 +71,8 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.seg_count = off;  off = align256(off + segs * 4);
     L.cfull = off;      off = align256(off + segs * 8);
     L.down = off;       off = align256(off + segs * 8);
+    const int64_t words = (n + 63) / 64 + 1;                     // 64 queue slots per mask word
+    L.keepm = off;      off = align256(off + words * 8);
     L.chunk_tot = off;  off = align256(off + (int64_t)L.max_passes * L.chunks * kRadix * 4);
     L.zero_end = off;
     L.tile_hist = off;  off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
@@ -79,6 +82,9 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
         L.key[b] = off; off = align256(off + n * 4);
         L.pay[b] = off; off = align256(off + n * 4);
     }
+    L.min_lat = off;    off = align256(off + segs * 4);
+    L.alive = off;      off = align256(off + words * 8);
+    L.wkept = off;      off = align256(off + words * 4);
     L.total = off;
     return L;
 }
@@ -105,6 +111,11 @@ struct SortDev {                    // everything the sort kernels need, by valu
     uint32_t* pay[2];
     int64_t tiles;
     int32_t idx_bits, seg_bits, max_passes;
+    // sequentially consistent dropping
+    uint32_t* min_lat;              // [K*S] smallest execution latency a request of the queue can see
+    unsigned long long* alive;      // bit j: the request in queue slot j survives at the smallest possible cost
+    unsigned long long* keepm;      // bit j: the request in queue slot j is kept (zeroed with the counters)
+    uint32_t* wkept;                // [word w]: kept requests of the queue that owns slot 64w, in its slots before 64w
 };
 
 __global__ void zero_kernel(uint4* p, int64_t count16) {
@@ -336,6 +347,15 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         const int64_t rec = P.shared ? g % P.S : g;
         A.cfull[g] = stage_cost(P.recs[rec], __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
                                 P.lat + rec * PARD_LAT_ENTRIES);
+    }
+    // smallest execution latency of every queue: lat[min(B, a + 1)] over all positions a
+    for (int64_t g = tid; g < segs; g += 1024) {
+        const int64_t rec = P.shared ? g % P.S : g;
+        const int32_t* row = P.lat + rec * PARD_LAT_ENTRIES;
+        const int32_t B = P.recs[rec].B;
+        uint32_t m = (uint32_t)row[0];
+        for (int32_t b = 1; b < B; ++b) m = (uint32_t)row[b] < m ? (uint32_t)row[b] : m;
+        A.min_lat[g] = m;
     }
     __threadfence_block();
     __syncthreads();
@@ -727,10 +747,9 @@ struct EpiSeg {                     // 64 bytes
     int32_t pad[3];
 };
 
-__device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
-                                                 uint32_t key, uint32_t r, uint32_t umin) {
-    const uint32_t pos = (uint32_t)(j - (int64_t)q.start);
-    // stage_cost() with the record held in registers
+// own-stage cost at queue position pos plus the downstream maximum: stage_cost() with the record
+// held in registers
+__device__ __forceinline__ uint64_t epilogue_estimate(const EpiSeg& q, const int32_t* lat_row, uint32_t pos) {
     const uint32_t batches = magic_div_dev(pos + q.B - 1u, q.mB, q.shB);
     const uint64_t x = (uint64_t)batches * q.latB;
     uint64_t wait;
@@ -740,16 +759,24 @@ __device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg&
     if (pos + 1u < q.B) ex = (uint32_t)lat_row[pos];             // only the first B-1 requests of a queue
     uint64_t c = wait + ex;
     c = c < kCostCap ? c : kCostCap;
-    const uint64_t e64 = c + (((uint64_t)q.down_hi << 32) | q.down_lo);
-    int32_t deadline;
+    return c + (((uint64_t)q.down_hi << 32) | q.down_lo);
+}
+
+// the deadline of request r back from its sort key (or from the input when the key is the arrival)
+__device__ __forceinline__ int32_t epilogue_deadline(const SortDev& A, const EpiSeg& q, uint32_t key, uint32_t r, uint32_t umin) {
     const uint32_t uk = key + umin;
     const int32_t mode = (int32_t)(q.mode & 0xFF);
-    if (mode == PARD_ORDER_LBF) deadline = (int32_t)(uk ^ 0x80000000u);
-    else if (mode == PARD_ORDER_HBF) deadline = (int32_t)(~uk ^ 0x80000000u);
-    else deadline = (int64_t)r < A.n ? A.deadline[r] : 0;
+    if (mode == PARD_ORDER_LBF) return (int32_t)(uk ^ 0x80000000u);
+    if (mode == PARD_ORDER_HBF) return (int32_t)(~uk ^ 0x80000000u);
+    return (int64_t)r < A.n ? A.deadline[r] : 0;
+}
+
+__device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
+                                                 uint32_t key, uint32_t r, uint32_t umin) {
+    const uint64_t e64 = epilogue_estimate(q, lat_row, (uint32_t)(j - (int64_t)q.start));
     int32_t est;
     uint8_t drp;
-    finish_request(e64, q.now, deadline, est, drp);
+    finish_request(e64, q.now, epilogue_deadline(A, q, key, r, umin), est, drp);
     return (uint32_t)est | ((uint32_t)drp << 31);
 }
 
@@ -856,6 +883,196 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
     }
 }
 
+// ---- sequentially consistent dropping on sorted queues --------------------------------------
+// A request's position counts only the kept requests ahead of it (the Request Broker takes a
+// queue in order and a dropped request never takes a batch slot, paper Section 4.1), so every
+// queue is one chain of decisions.  Three kernels after the last radix pass:
+//   prepare   per queue slot: the deadline (replacing the sort key in place) and one bit that
+//             says whether the request could be kept at all, i.e. at the smallest cost any
+//             position can have; in an overloaded queue most requests fail that test, and they
+//             are dropped whatever happens ahead of them
+//   chain     one wave per queue walks the words of that bit mask in order, skipping words
+//             without candidates; the 64 slots of a word are settled together by iterating the
+//             decisions to their fixed point (after t rounds the first t lanes are final); it
+//             leaves the keep bits and, per mask word, the number of kept requests before it
+//   finish    per queue slot: position = kept requests ahead from the keep bits, then estimate
+//             and drop decision as in the plain epilogue.
+constexpr int kChainWords = 64;                         // mask words (of 64 slots) a chain step looks at
+constexpr int kChainAhead = 32;                         // steps whose mask words are in flight together
+
+__global__ __launch_bounds__(256) void consistent_prepare_kernel(SortDev A) {
+    __shared__ EpiSeg tab[kEpiSegs];
+    const PlanDev& P = A.plan;
+    const int tid = threadIdx.x;
+    const int64_t segs = (int64_t)P.K * P.S;
+    const bool cached = segs <= kEpiSegs;
+    if (cached && tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
+    __syncthreads();
+    const int last = ((int)A.params->passes - 1) & 1;
+    uint32_t* keys = A.key[last];
+    const uint32_t* pays = A.pay[last];
+    const uint32_t umin = ~A.params->inv_min;
+    const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t j = (int64_t)blockIdx.x * 256 + tid; (j & ~(int64_t)63) < A.n; j += stride) {     // whole waves
+        const bool ok = j < A.n;
+        bool can = false;
+        if (ok) {
+            const uint32_t key = keys[j], pay = pays[j];
+            const uint32_t local = pay & idx_mask;
+            const uint32_t seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
+            EpiSeg q;
+            if (cached) q = tab[seg]; else q = epilogue_segment(A, seg);
+            const int32_t deadline = epilogue_deadline(A, q, key, (uint32_t)q.first + local, umin);
+            keys[j] = (uint32_t)deadline;
+            int32_t est;
+            uint8_t drp;
+            finish_request((uint64_t)A.min_lat[seg] + (((uint64_t)q.down_hi << 32) | q.down_lo), q.now, deadline, est, drp);
+            can = drp == 0;
+        }
+        const unsigned long long word = __ballot(can);
+        if ((tid & 63) == 0) A.alive[j >> 6] = word;
+    }
+}
+
+__global__ __launch_bounds__(64) void consistent_chain_kernel(SortDev A) {
+    __shared__ int32_t dls[kChainWords * 64];           // deadlines of the slots of one step's words
+    __shared__ unsigned long long words[kChainAhead * 64];
+    const PlanDev& P = A.plan;
+    const int lane = threadIdx.x;
+    const uint32_t seg = blockIdx.x;
+    const int64_t s0 = A.seg_ptr[seg], s1 = A.seg_ptr[seg + 1];
+    if (s1 <= s0 || s1 > A.n || s0 < 0) return;
+    const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
+    const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+    const StageRec sr = P.recs[rec];
+    const int32_t* lat_row = P.lat + rec * PARD_LAT_ENTRIES;
+    const unsigned long long dn = A.down[seg];
+    const int32_t now = A.now[u];
+    const int32_t* dl = reinterpret_cast<const int32_t*>(A.key[((int)A.params->passes - 1) & 1]);
+    const int64_t w_first = s0 >> 6, w_last = (s1 - 1) >> 6;
+    auto candidates = [&](int64_t w) -> unsigned long long {       // the queue's own bits of mask word w
+        if (w > w_last) return 0ull;
+        unsigned long long v = A.alive[w];
+        if (w == w_first) v &= ~0ull << (s0 & 63);
+        if (w == w_last && (s1 & 63)) v &= (1ull << (s1 & 63)) - 1ull;
+        return v;
+    };
+    uint32_t kept = 0;                                  // kept requests of the queue so far (same in every lane)
+    // one step settles the 64 mask words w0 .. w0+63 (lane l holds word w0 + l)
+    auto step = [&](int64_t w0, unsigned long long mine) {
+        const unsigned long long busy = __ballot(mine != 0ull);
+        const int64_t w = w0 + lane;
+        if (busy == 0ull) {                              // nobody here can be kept
+            if (w <= w_last && w > w_first) A.wkept[w] = kept;
+            return;
+        }
+        const uint32_t kept_before_step = kept;
+        unsigned long long keep_mine = 0ull;
+        // deadlines of the busy words into LDS, eight words' loads in flight
+        for (int b0 = 0; b0 < kChainWords; b0 += 8) {
+            if (((busy >> b0) & 0xFFull) == 0ull) continue;
+            int32_t v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t j = (w0 + b0 + i) * 64 + lane;
+                v[i] = (((busy >> (b0 + i)) & 1ull) && j < A.n) ? dl[j] : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) dls[(b0 + i) * 64 + lane] = v[i];
+        }
+        __syncthreads();
+        unsigned long long rest = busy;
+        while (rest) {
+            const int b = __ffsll((long long)rest) - 1;
+            rest &= rest - 1ull;
+            const unsigned long long m = __shfl(mine, b);
+            const bool ok = (m >> lane) & 1ull;
+            const int32_t deadline = dls[b * 64 + lane];
+            // guess that all candidates are kept, evaluate everybody at the position the guess
+            // implies, take the decisions as the next guess; a guess that reproduces itself is
+            // the in-order result
+            unsigned long long keep = m;
+            for (int round = 0; round <= 64; ++round) {
+                const uint32_t ahead = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(keep >> 32),
+                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)keep, 0u));
+                int32_t est;
+                uint8_t drp;
+                finish_request(stage_cost(sr, ahead, lat_row) + dn, now, deadline, est, drp);
+                const unsigned long long next = __ballot(ok && drp == 0);
+                if (next == keep) break;
+                keep = next;
+            }
+            if (lane == b) keep_mine = keep;
+            kept += (uint32_t)__popcll(keep);
+        }
+        __syncthreads();
+        // kept requests of this queue before each word of the step
+        const uint32_t c = (uint32_t)__popcll(keep_mine);
+        uint32_t inc = c;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t t = __shfl_up(inc, off);
+            if (lane >= off) inc += t;
+        }
+        if (w <= w_last) {
+            if (w > w_first) A.wkept[w] = kept_before_step + inc - c;
+            if (keep_mine) atomicOr(&A.keepm[w], keep_mine);     // the first and last word may be shared with other queues
+        }
+    };
+    // The mask words of kChainAhead steps are loaded at once (the next batch while this one is
+    // worked on) and handed to the steps through LDS.
+    unsigned long long nxt[kChainAhead];
+#pragma unroll
+    for (int i = 0; i < kChainAhead; ++i) nxt[i] = candidates(w_first + i * kChainWords + lane);
+    for (int64_t w0 = w_first; w0 <= w_last; w0 += kChainAhead * kChainWords) {
+#pragma unroll
+        for (int i = 0; i < kChainAhead; ++i) words[i * 64 + lane] = nxt[i];
+#pragma unroll
+        for (int i = 0; i < kChainAhead; ++i) nxt[i] = candidates(w0 + (kChainAhead + i) * kChainWords + lane);
+        __syncthreads();
+        for (int i = 0; i < kChainAhead && w0 + i * kChainWords <= w_last; ++i) step(w0 + i * kChainWords, words[i * 64 + lane]);
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void consistent_finish_kernel(SortDev A) {
+    __shared__ EpiSeg tab[kEpiSegs];
+    const PlanDev& P = A.plan;
+    const int tid = threadIdx.x;
+    const int64_t segs = (int64_t)P.K * P.S;
+    const bool cached = segs <= kEpiSegs;
+    if (cached && tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
+    __syncthreads();
+    const int last = ((int)A.params->passes - 1) & 1;
+    const int32_t* dl = reinterpret_cast<const int32_t*>(A.key[last]);
+    const uint32_t* pays = A.pay[last];
+    uint32_t* packed = A.key[last ^ 1];
+    const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t j = (int64_t)blockIdx.x * 256 + tid; j < A.n; j += stride) {
+        const uint32_t pay = pays[j];
+        const int32_t deadline = dl[j];
+        const uint32_t local = pay & idx_mask;
+        const uint32_t seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
+        const uint32_t k = seg % (uint32_t)P.S;
+        const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+        EpiSeg q;
+        if (cached) q = tab[seg]; else q = epilogue_segment(A, seg);
+        const int64_t w = j >> 6;
+        const unsigned long long below = A.keepm[w] & ((1ull << (j & 63)) - 1ull);
+        uint32_t pos;
+        if (w == ((int64_t)q.start >> 6)) pos = (uint32_t)__popcll(below >> (q.start & 63));     // the queue starts inside this word
+        else pos = A.wkept[w] + (uint32_t)__popcll(below);
+        int32_t est;
+        uint8_t drp;
+        finish_request(epilogue_estimate(q, P.lat + rec * PARD_LAT_ENTRIES, pos), q.now, deadline, est, drp);
+        const uint32_t r = (uint32_t)q.first + local;
+        A.order[j] = (int32_t)r;
+        if ((int64_t)r < A.n) packed[r] = (uint32_t)est | ((uint32_t)drp << 31);
+    }
+}
+
 SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     SortDev D{};
     char* ws = static_cast<char*>(a.workspace);
@@ -879,6 +1096,10 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
         D.key[b] = reinterpret_cast<uint32_t*>(ws + L.key[b]);
         D.pay[b] = reinterpret_cast<uint32_t*>(ws + L.pay[b]);
     }
+    D.min_lat = reinterpret_cast<uint32_t*>(ws + L.min_lat);
+    D.alive = reinterpret_cast<unsigned long long*>(ws + L.alive);
+    D.keepm = reinterpret_cast<unsigned long long*>(ws + L.keepm);
+    D.wkept = reinterpret_cast<uint32_t*>(ws + L.wkept);
     D.tiles = L.tiles;
     D.idx_bits = L.idx_bits;
     D.seg_bits = L.seg_bits;
@@ -927,7 +1148,13 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             if (p == 0) downsweep_kernel<true><<<dg, kSortThreads, 0, stream>>>(D, p);
             else downsweep_kernel<false><<<dg, kSortThreads, 0, stream>>>(D, p);
         }
-        {
+        if (a.consistent) {
+            int64_t pg = (a.n + 255) / 256;
+            if (pg > 16 * (int64_t)a.num_cus) pg = 16 * (int64_t)a.num_cus;
+            consistent_prepare_kernel<<<(unsigned)pg, 256, 0, stream>>>(D);
+            consistent_chain_kernel<<<(unsigned)((int64_t)a.plan.K * a.plan.S), 64, 0, stream>>>(D);
+            consistent_finish_kernel<<<(unsigned)pg, 256, 0, stream>>>(D);
+        } else {
             int64_t eg = (a.n / 4 + kEpiThreads - 1) / kEpiThreads;       // persistent: a few workgroups per compute unit
             if (eg > 8 * (int64_t)a.num_cus) eg = 8 * (int64_t)a.num_cus;
             if (eg < 1) eg = 1;

@@ -197,12 +197,13 @@ def consistent_cases():
     yield w
 
 
-def test_consistent_dropping(gpu, oracle_mod):
+@pytest.mark.parametrize("max_snap", [None, FORCE_SORT])
+def test_consistent_dropping(gpu, oracle_mod, max_snap):
     mixed = 0
     for w in consistent_cases():
         print("case", w.name, w.n, w.K, w.S, flush=True)
         ref = oracle_mod.run(w, threads=8, consistent=True)
-        s = gpu.Session(w)
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
         s.run(consistent=True)
         got = s.results()
         for k in KEYS:
@@ -231,11 +232,48 @@ def test_consistent_with_planner_output(gpu, oracle_mod):
     assert 0 < ref["drop"].mean() < 1
 
 
-def test_consistent_rejects_large_snapshots(gpu):
-    w = wl.make_workload(3, n_requests=20000)
-    s = gpu.Session(w)
-    assert gpu.pard_estimate_drop_consistent(s.plan, s.n, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, None,
-                                             s.est, s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -11
+def large_consistent_cases():
+    """(workload, downstream latency or None).  With the downstream term taken from the snapshot the later
+    stages' full queues swamp every budget in these overloaded snapshots; a given, modest L_sub lets the
+    position in the own queue decide."""
+    yield wl.make_workload(3, n_requests=200_003), None                    # deep overload: few candidates, at the queues' ends
+    w = wl.make_workload(4, n_requests=300_000, permute=True)              # skewed queues, high budget first
+    yield w, np.full(w.K * w.S, 30_000, np.int64)
+    w = wl.make_workload(2, n_requests=250_000)                            # nothing has expired: every request is a candidate
+    w.now[:] = 0
+    yield w, None
+    w = wl.make_workload(3, n_requests=180_000, permute=True)              # in between, mixed orders, FCFS among them
+    w.now[:] = int(np.median(w.arrival))
+    w.order_mode[:] = np.arange(w.order_mode.size) % 3
+    yield w, (np.arange(w.K * w.S, dtype=np.int64) * 7000)
+    w = wl.make_workload(4, n_requests=150_001)                            # candidates scattered: random deadlines
+    rng = np.random.default_rng(8)
+    w.now[:] = 2**30
+    w.deadline[:] = (2**30 + rng.integers(-10_000_000, 60_000_000, w.n)).astype(np.int32)
+    w.deadline[::9] = 2**31 - 1
+    yield w, np.zeros(w.K * w.S, np.int64)
+    w = wl.random_workload(77, K=5, S=6, n_per_snapshot=9000, dag_shared=0)  # ragged snapshots, queues that start inside a mask word
+    yield w, None
+    w = wl.random_workload(78, K=40, S=3, n_per_snapshot=700, dag_shared=1, tie_heavy=True)   # more queues than the LDS table holds
+    yield w, np.full(w.K * w.S, 1000, np.int64)
+
+
+def test_consistent_large_snapshots(gpu, oracle_mod):
+    import torch
+    mixed = 0
+    for w, sub in large_consistent_cases():
+        print("case", w.name, w.n, w.K, w.S, flush=True)
+        ref = oracle_mod.run(w, threads=8, sub=sub, consistent=True)
+        s = gpu.Session(w, max_snapshot_requests=max(FORCE_SORT, w.max_snapshot_requests))
+        s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=True)
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (w.name, k, np.flatnonzero(got[k] != ref[k])[:5])
+        assert s.status_word() == 0
+        one = oracle_mod.run(w, threads=8, sub=sub)
+        mixed += int(not np.array_equal(one["drop"], ref["drop"]))
+        print("   drop fraction", ref["drop"].mean(), "plain", one["drop"].mean(), flush=True)
+    assert mixed >= 5
 
 
 # ---- adaptive priority -----------------------------------------------------------------------
