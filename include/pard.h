@@ -274,10 +274,8 @@ int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snaps
  * batch slot, so the position that enters a request's own-stage cost is the number of requests
  * ahead of it in its queue that were KEPT, not all of them.  Everything else as
  * pard_estimate_drop (d_sub == NULL) or pard_estimate_drop_sub (d_sub given).  d_order and
- * d_seg_ptr are the same as in the one-pass calls; d_est and d_drop differ.
- *
- * Only snapshots of at most PARD_FUSED_SNAPSHOT_CAPACITY requests: a larger
- * max_snapshot_requests returns PARD_E_UNSUPPORTED.
+ * d_seg_ptr are the same as in the one-pass calls; d_est and d_drop differ.  Both snapshot
+ * sizes are served (on chip up to PARD_FUSED_SNAPSHOT_CAPACITY requests, after the sort above).
  */
 int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
                                   const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,

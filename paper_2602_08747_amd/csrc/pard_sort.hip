@@ -34,7 +34,10 @@ constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kMaxPasses = 8;
 constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
+constexpr int kConsTile = 256;                         // queue slots per workgroup in the consistent-dropping kernels
 constexpr int kFusedScanChunks = 32;                   // up to here every chunk scans the chunk totals itself
+
+constexpr uint32_t kSegScan = 1u << 31;                // queue flag: consistent positions by prefix minimum (see below)
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
     uint32_t inv_min;               // max over requests of ~key  (so that zero-fill is the identity)
@@ -49,7 +52,7 @@ constexpr int kPartialSegs = 64;                       // up to this many queues
 
 struct SortLayout {
     int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2],
-            min_lat, alive, wkept, total;
+            min_lat, alive, wkept, tile_tot, carry, total;
     int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits;
 };
@@ -85,6 +88,9 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.min_lat = off;    off = align256(off + segs * 4);
     L.alive = off;      off = align256(off + words * 8);
     L.wkept = off;      off = align256(off + words * 4);
+    const int64_t ctiles = (n + kConsTile - 1) / kConsTile + 1;
+    L.tile_tot = off;   off = align256(off + ctiles * 8);
+    L.carry = off;      off = align256(off + ctiles * 4);
     L.total = off;
     return L;
 }
@@ -116,6 +122,8 @@ struct SortDev {                    // everything the sort kernels need, by valu
     unsigned long long* alive;      // bit j: the request in queue slot j survives at the smallest possible cost
     unsigned long long* keepm;      // bit j: the request in queue slot j is kept (zeroed with the counters)
     uint32_t* wkept;                // [word w]: kept requests of the queue that owns slot 64w, in its slots before 64w
+    uint2* tile_tot;                // [tile of kConsTile slots]: (a queue starts in it, minimum since the last start)
+    int32_t* carry;                 // [tile]: minimum over the slots before the tile since the last queue start
 };
 
 __global__ void zero_kernel(uint4* p, int64_t count16) {
@@ -354,8 +362,13 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         const int32_t* row = P.lat + rec * PARD_LAT_ENTRIES;
         const int32_t B = P.recs[rec].B;
         uint32_t m = (uint32_t)row[0];
-        for (int32_t b = 1; b < B; ++b) m = (uint32_t)row[b] < m ? (uint32_t)row[b] : m;
-        A.min_lat[g] = m;
+        bool rising = true;                              // then the cost never falls as the position grows
+        for (int32_t b = 1; b < B; ++b) {
+            m = (uint32_t)row[b] < m ? (uint32_t)row[b] : m;
+            rising = rising && row[b] >= row[b - 1];
+        }
+        const bool by_deadline = (P.recs[rec].mode & 0xFF) != PARD_ORDER_FCFS;
+        A.min_lat[g] = m | ((rising && by_deadline) ? kSegScan : 0u);
     }
     __threadfence_block();
     __syncthreads();
@@ -744,7 +757,9 @@ struct EpiSeg {                     // 64 bytes
     int32_t start, now;
     uint32_t down_lo, down_hi;
     int32_t first;                  // first request of the queue's snapshot
-    int32_t pad[3];
+    int32_t len;                    // queue length
+    uint32_t aux;                   // smallest execution latency | kSegScan << 31
+    int32_t pad;
 };
 
 // own-stage cost at queue position pos plus the downstream maximum: stage_cost() with the record
@@ -790,7 +805,9 @@ __device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t se
     q.mB = sr.mB; q.shB = sr.shB; q.mW = sr.mW; q.shW = sr.shW;
     q.start = A.seg_ptr[seg]; q.now = A.now[u];
     q.first = A.snap_ptr[u];
-    q.pad[0] = q.pad[1] = q.pad[2] = 0;
+    q.len = A.seg_ptr[seg + 1] - q.start;
+    q.aux = A.min_lat[seg];
+    q.pad = 0;
     q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
     return q;
 }
@@ -886,24 +903,83 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
 // ---- sequentially consistent dropping on sorted queues --------------------------------------
 // A request's position counts only the kept requests ahead of it (the Request Broker takes a
 // queue in order and a dropped request never takes a batch slot, paper Section 4.1), so every
-// queue is one chain of decisions.  Three kernels after the last radix pass:
-//   prepare   per queue slot: the deadline (replacing the sort key in place) and one bit that
-//             says whether the request could be kept at all, i.e. at the smallest cost any
-//             position can have; in an overloaded queue most requests fail that test, and they
-//             are dropped whatever happens ahead of them
-//   chain     one wave per queue walks the words of that bit mask in order, skipping words
-//             without candidates; the 64 slots of a word are settled together by iterating the
-//             decisions to their fixed point (after t rounds the first t lanes are final); it
-//             leaves the keep bits and, per mask word, the number of kept requests before it
-//   finish    per queue slot: position = kept requests ahead from the keep bits, then estimate
-//             and drop decision as in the plain epilogue.
+// queue is one chain of decisions:  a_0 = 0,  a_{i+1} = a_i + [request i is kept at position a_i].
+//
+// Queues ordered by deadline whose cost never falls with the position (latency table rising up
+// to the batch size) need no chain.  Let c_i be the number of positions at which request i
+// would still be in time (they form a prefix 0..c_i-1), so request i is kept iff a_i < c_i.
+//   Low budget first:  budgets rise along the queue, so c_i never falls, a_i <= c_i always
+//   holds and the recurrence is a_{i+1} = min(a_i + 1, c_i), i.e.
+//        a_i = min(i, i - 1 + min over i' < i of (c_i' - i'))        an exclusive prefix minimum.
+//   High budget first:  c_i never rises; the kept requests are exactly the leading ones that the
+//   plain rule (position = i) keeps, so  a_i = min(i, first i' < i with i' >= c_i').
+// Both are segmented exclusive prefix minima over the queue slots: per-tile totals from the
+// prepare kernel, one small scan over the tiles, and the finish kernel redoes the scan inside
+// its tile.  c_i has a closed form (positions_in_time).
+//
+// Any other queue (arrival order, or a latency table that falls somewhere) is walked:
+//   prepare   also leaves one bit per slot that says whether the request could be kept at all,
+//             i.e. at the smallest cost any position can have; in an overloaded queue most
+//             requests fail that test, and they are dropped whatever happens ahead of them
+//   chain     one wave per such queue walks the words of that bit mask in order, skipping
+//             words without candidates; the 64 slots of a word are settled together by
+//             iterating the decisions to their fixed point (after t rounds the first t lanes are
+//             final); it leaves the keep bits and, per mask word, the kept requests before it
+//   finish    position = kept requests ahead from the keep bits.
+// In both cases prepare replaces the sort key by the deadline in place, and finish ends like the
+// plain epilogue: estimate and drop decision at the position found.
 constexpr int kChainWords = 64;                         // mask words (of 64 slots) a chain step looks at
 constexpr int kChainAhead = 32;                         // steps whose mask words are in flight together
+constexpr int32_t kNoMin = 0x7fffffff;
 
-__global__ __launch_bounds__(256) void consistent_prepare_kernel(SortDev A) {
+// Number of positions a in [0, queue length) at which a request with T microseconds left for
+// its own stage (deadline - now - downstream) is in time, for a cost that never falls with a.
+__device__ __forceinline__ uint32_t positions_in_time(const EpiSeg& q, const int32_t* lat_row, int64_t T) {
+    const uint32_t L = (uint32_t)q.len;
+    if (T < 0) return 0u;
+    const uint32_t w1 = magic_div_dev(q.latB, q.mW, q.shW);      // floor(lat[B] / W): the wait behind one batch
+    const uint32_t r1 = L < q.B - 1u ? L : q.B - 1u;              // positions that see a partial batch
+    uint32_t lo = 0, hi = r1;                                     // first late position among them
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const uint64_t c = (uint64_t)(mid ? w1 : 0u) + (uint32_t)lat_row[mid];
+        if ((int64_t)c <= T) lo = mid + 1u; else hi = mid;
+    }
+    if (lo < r1 || L <= q.B - 1u) return lo;
+    // positions a >= B-1: cost = floor(ceil(a/B) * lat[B] / W) + lat[B] <= T
+    //   <=>  ceil(a/B) * lat[B] <= (T - lat[B] + 1) * W - 1
+    const int64_t T2 = T - (int64_t)q.latB;
+    if (T2 < 0) return lo;
+    if (q.latB == 0u) return L;
+    const uint64_t m_max = wide_div((uint64_t)(T2 + 1) * q.W - 1ull, q.latB);
+    if (m_max >= (uint64_t)L) return L;
+    const uint64_t a_max = m_max * q.B;                           // ceil(a/B) <= m_max  <=>  a <= m_max * B
+    if (a_max + 1ull < (uint64_t)q.B) return lo;                  // below B-1: nothing of this range
+    return a_max + 1ull < (uint64_t)L ? (uint32_t)(a_max + 1ull) : L;
+}
+
+// (start flag, minimum since the last start): the operator of a segmented minimum scan
+__device__ __forceinline__ void seg_min_combine(uint32_t lf, int32_t lv, uint32_t& f, int32_t& v) {
+    v = f ? v : (lv < v ? lv : v);
+    f |= lf;
+}
+
+// inclusive segmented minimum scan across the wave
+__device__ __forceinline__ void seg_min_wave_scan(uint32_t& f, int32_t& v, int lane) {
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t lf = __shfl_up(f, off);
+        const int32_t lv = __shfl_up(v, off);
+        if (lane >= off) seg_min_combine(lf, lv, f, v);
+    }
+}
+
+__global__ __launch_bounds__(kConsTile) void consistent_prepare_kernel(SortDev A) {
     __shared__ EpiSeg tab[kEpiSegs];
+    __shared__ uint32_t wave_f[kConsTile / 64];
+    __shared__ int32_t wave_v[kConsTile / 64];
     const PlanDev& P = A.plan;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)P.K * P.S;
     const bool cached = segs <= kEpiSegs;
     if (cached && tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
@@ -911,12 +987,16 @@ __global__ __launch_bounds__(256) void consistent_prepare_kernel(SortDev A) {
     const int last = ((int)A.params->passes - 1) & 1;
     uint32_t* keys = A.key[last];
     const uint32_t* pays = A.pay[last];
+    int32_t* thr = reinterpret_cast<int32_t*>(A.pay[last ^ 1]);   // free since the last pass
     const uint32_t umin = ~A.params->inv_min;
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t j = (int64_t)blockIdx.x * 256 + tid; (j & ~(int64_t)63) < A.n; j += stride) {     // whole waves
+    const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int64_t j = t * kConsTile + tid;
         const bool ok = j < A.n;
         bool can = false;
+        uint32_t f = 0;
+        int32_t v = kNoMin;
         if (ok) {
             const uint32_t key = keys[j], pay = pays[j];
             const uint32_t local = pay & idx_mask;
@@ -925,13 +1005,85 @@ __global__ __launch_bounds__(256) void consistent_prepare_kernel(SortDev A) {
             if (cached) q = tab[seg]; else q = epilogue_segment(A, seg);
             const int32_t deadline = epilogue_deadline(A, q, key, (uint32_t)q.first + local, umin);
             keys[j] = (uint32_t)deadline;
-            int32_t est;
-            uint8_t drp;
-            finish_request((uint64_t)A.min_lat[seg] + (((uint64_t)q.down_hi << 32) | q.down_lo), q.now, deadline, est, drp);
-            can = drp == 0;
+            const unsigned long long dn = ((unsigned long long)q.down_hi << 32) | q.down_lo;
+            f = j == (int64_t)q.start ? 1u : 0u;
+            if (q.aux & kSegScan) {
+                const int64_t rec = P.shared ? (int64_t)(seg % (uint32_t)P.S) : (int64_t)seg;
+                const uint32_t i = (uint32_t)(j - (int64_t)q.start);
+                const uint32_t c = deadline == kInt32Max ? (uint32_t)q.len
+                                   : positions_in_time(q, P.lat + rec * PARD_LAT_ENTRIES, (int64_t)deadline - (int64_t)q.now - (int64_t)dn);
+                if ((q.mode & 0xFF) == PARD_ORDER_LBF) v = (int32_t)c - (int32_t)i;
+                else v = i >= c ? (int32_t)i : kNoMin;
+                thr[j] = v;
+            } else {
+                int32_t est;
+                uint8_t drp;
+                finish_request((uint64_t)(q.aux & ~kSegScan) + dn, q.now, deadline, est, drp);
+                can = drp == 0;
+            }
         }
         const unsigned long long word = __ballot(can);
-        if ((tid & 63) == 0) A.alive[j >> 6] = word;
+        if (lane == 0 && t * kConsTile + wave * 64 < A.n) A.alive[(t * kConsTile + wave * 64) >> 6] = word;
+        // the tile's total of the segmented minimum scan
+        seg_min_wave_scan(f, v, lane);
+        if (lane == 63) { wave_f[wave] = f; wave_v[wave] = v; }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t tf = wave_f[0];
+            int32_t tv = wave_v[0];
+            for (int w = 1; w < kConsTile / 64; ++w) {
+                uint32_t wf = wave_f[w];
+                int32_t wv = wave_v[w];
+                seg_min_combine(tf, tv, wf, wv);
+                tf = wf; tv = wv;
+            }
+            A.tile_tot[t] = make_uint2(tf, (uint32_t)tv);
+        }
+        __syncthreads();
+    }
+}
+
+// carry[t] = minimum over the slots before tile t since the last queue start (one workgroup:
+// every wave scans a contiguous range of tiles 64 at a time, then the ranges are stitched)
+__global__ __launch_bounds__(1024) void consistent_tile_scan_kernel(SortDev A) {
+    __shared__ uint32_t range_f[16];
+    __shared__ int32_t range_v[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
+    const int64_t per = ((tiles + 15) / 16 + 63) / 64 * 64;      // tiles per wave, a multiple of 64
+    const int64_t t_lo = wave * per, t_hi = t_lo + per < tiles ? t_lo + per : tiles;
+    for (int pass = 0; pass < 2; ++pass) {
+        // pass 0: the range's total; pass 1: the carries, starting from what the earlier ranges leave
+        uint32_t run_f = 0;
+        int32_t run_v = kNoMin;
+        if (pass == 1)
+            for (int w = 0; w < wave; ++w) {
+                uint32_t wf = range_f[w];
+                int32_t wv = range_v[w];
+                seg_min_combine(run_f, run_v, wf, wv);
+                run_f = wf; run_v = wv;
+            }
+        for (int64_t t0 = t_lo; t0 < t_hi; t0 += 64) {
+            const int64_t t = t0 + lane;
+            uint32_t f = 0;
+            int32_t v = kNoMin;
+            if (t < t_hi) { const uint2 x = A.tile_tot[t]; f = x.x; v = (int32_t)x.y; }
+            seg_min_wave_scan(f, v, lane);                        // inclusive over the 64 tiles
+            seg_min_combine(run_f, run_v, f, v);                  // ... and everything before them
+            if (pass == 1) {
+                uint32_t pf = __shfl_up(f, 1);
+                int32_t pv = __shfl_up(v, 1);
+                if (lane == 0) { pf = run_f; pv = run_v; }
+                if (t < t_hi) A.carry[t] = pv;                    // exclusive: what lies before tile t
+                (void)pf;
+            }
+            run_f = __shfl(f, 63);
+            run_v = __shfl(v, 63);
+        }
+        if (pass == 0) {
+            if (lane == 0) { range_f[wave] = run_f; range_v[wave] = run_v; }
+            __syncthreads();
+        }
     }
 }
 
@@ -943,6 +1095,7 @@ __global__ __launch_bounds__(64) void consistent_chain_kernel(SortDev A) {
     const uint32_t seg = blockIdx.x;
     const int64_t s0 = A.seg_ptr[seg], s1 = A.seg_ptr[seg + 1];
     if (s1 <= s0 || s1 > A.n || s0 < 0) return;
+    if (A.min_lat[seg] & kSegScan) return;              // positions by prefix minimum, no walk
     const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
     const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
     const StageRec sr = P.recs[rec];
@@ -1036,10 +1189,12 @@ __global__ __launch_bounds__(64) void consistent_chain_kernel(SortDev A) {
     }
 }
 
-__global__ __launch_bounds__(256) void consistent_finish_kernel(SortDev A) {
+__global__ __launch_bounds__(kConsTile) void consistent_finish_kernel(SortDev A) {
     __shared__ EpiSeg tab[kEpiSegs];
+    __shared__ uint32_t wave_f[kConsTile / 64];
+    __shared__ int32_t wave_v[kConsTile / 64];
     const PlanDev& P = A.plan;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)P.K * P.S;
     const bool cached = segs <= kEpiSegs;
     if (cached && tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
@@ -1047,29 +1202,75 @@ __global__ __launch_bounds__(256) void consistent_finish_kernel(SortDev A) {
     const int last = ((int)A.params->passes - 1) & 1;
     const int32_t* dl = reinterpret_cast<const int32_t*>(A.key[last]);
     const uint32_t* pays = A.pay[last];
+    const int32_t* thr = reinterpret_cast<const int32_t*>(A.pay[last ^ 1]);
     uint32_t* packed = A.key[last ^ 1];
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t j = (int64_t)blockIdx.x * 256 + tid; j < A.n; j += stride) {
-        const uint32_t pay = pays[j];
-        const int32_t deadline = dl[j];
-        const uint32_t local = pay & idx_mask;
-        const uint32_t seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
-        const uint32_t k = seg % (uint32_t)P.S;
-        const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
-        EpiSeg q;
-        if (cached) q = tab[seg]; else q = epilogue_segment(A, seg);
-        const int64_t w = j >> 6;
-        const unsigned long long below = A.keepm[w] & ((1ull << (j & 63)) - 1ull);
-        uint32_t pos;
-        if (w == ((int64_t)q.start >> 6)) pos = (uint32_t)__popcll(below >> (q.start & 63));     // the queue starts inside this word
-        else pos = A.wkept[w] + (uint32_t)__popcll(below);
-        int32_t est;
-        uint8_t drp;
-        finish_request(epilogue_estimate(q, P.lat + rec * PARD_LAT_ENTRIES, pos), q.now, deadline, est, drp);
-        const uint32_t r = (uint32_t)q.first + local;
-        A.order[j] = (int32_t)r;
-        if ((int64_t)r < A.n) packed[r] = (uint32_t)est | ((uint32_t)drp << 31);
+    const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int64_t j = t * kConsTile + tid;
+        const bool ok = j < A.n;
+        EpiSeg q{};
+        uint32_t pay = 0, seg = 0, f = 0;
+        int32_t deadline = 0, v = kNoMin;
+        bool scanned = false;
+        if (ok) {
+            pay = pays[j];
+            deadline = dl[j];
+            seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
+            if (cached) q = tab[seg]; else q = epilogue_segment(A, seg);
+            f = j == (int64_t)q.start ? 1u : 0u;
+            scanned = (q.aux & kSegScan) != 0u;
+            if (scanned) v = thr[j];
+        }
+        // exclusive segmented minimum over the slots before j: inside the wave, the earlier waves
+        // of the tile, the earlier tiles
+        const uint32_t own_f = f;
+        seg_min_wave_scan(f, v, lane);
+        if (lane == 63) { wave_f[wave] = f; wave_v[wave] = v; }
+        __syncthreads();
+        uint32_t ef = __shfl_up(f, 1);
+        int32_t ev = __shfl_up(v, 1);
+        if (lane == 0) { ef = 0; ev = kNoMin; }
+        {
+            uint32_t run_f = 0;
+            int32_t run_v = A.carry[t];
+            for (int w = 0; w < wave; ++w) {
+                uint32_t wf = wave_f[w];
+                int32_t wv = wave_v[w];
+                seg_min_combine(run_f, run_v, wf, wv);
+                run_f = wf; run_v = wv;
+            }
+            seg_min_combine(run_f, run_v, ef, ev);
+        }
+        const int32_t before = own_f ? kNoMin : ev;            // nothing lies before a queue's first slot
+        __syncthreads();
+        if (ok) {
+            const uint32_t local = pay & idx_mask;
+            const uint32_t k = seg % (uint32_t)P.S;
+            const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+            const uint32_t i = (uint32_t)(j - (int64_t)q.start);
+            uint32_t pos;
+            if (scanned) {
+                if (before == kNoMin) pos = i;
+                else if ((q.mode & 0xFF) == PARD_ORDER_LBF) {
+                    const int64_t a = (int64_t)i - 1 + (int64_t)before;
+                    pos = a < (int64_t)i ? (uint32_t)a : i;
+                } else {
+                    pos = (uint32_t)before < i ? (uint32_t)before : i;
+                }
+            } else {
+                const int64_t w = j >> 6;
+                const unsigned long long below = A.keepm[w] & ((1ull << (j & 63)) - 1ull);
+                if (w == ((int64_t)q.start >> 6)) pos = (uint32_t)__popcll(below >> (q.start & 63));     // the queue starts inside this word
+                else pos = A.wkept[w] + (uint32_t)__popcll(below);
+            }
+            int32_t est;
+            uint8_t drp;
+            finish_request(epilogue_estimate(q, P.lat + rec * PARD_LAT_ENTRIES, pos), q.now, deadline, est, drp);
+            const uint32_t r = (uint32_t)q.first + local;
+            A.order[j] = (int32_t)r;
+            if ((int64_t)r < A.n) packed[r] = (uint32_t)est | ((uint32_t)drp << 31);
+        }
     }
 }
 
@@ -1100,6 +1301,8 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.alive = reinterpret_cast<unsigned long long*>(ws + L.alive);
     D.keepm = reinterpret_cast<unsigned long long*>(ws + L.keepm);
     D.wkept = reinterpret_cast<uint32_t*>(ws + L.wkept);
+    D.tile_tot = reinterpret_cast<uint2*>(ws + L.tile_tot);
+    D.carry = reinterpret_cast<int32_t*>(ws + L.carry);
     D.tiles = L.tiles;
     D.idx_bits = L.idx_bits;
     D.seg_bits = L.seg_bits;
@@ -1149,11 +1352,12 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             else downsweep_kernel<false><<<dg, kSortThreads, 0, stream>>>(D, p);
         }
         if (a.consistent) {
-            int64_t pg = (a.n + 255) / 256;
+            int64_t pg = (a.n + kConsTile - 1) / kConsTile;
             if (pg > 16 * (int64_t)a.num_cus) pg = 16 * (int64_t)a.num_cus;
-            consistent_prepare_kernel<<<(unsigned)pg, 256, 0, stream>>>(D);
+            consistent_prepare_kernel<<<(unsigned)pg, kConsTile, 0, stream>>>(D);
+            consistent_tile_scan_kernel<<<1, 1024, 0, stream>>>(D);
             consistent_chain_kernel<<<(unsigned)((int64_t)a.plan.K * a.plan.S), 64, 0, stream>>>(D);
-            consistent_finish_kernel<<<(unsigned)pg, 256, 0, stream>>>(D);
+            consistent_finish_kernel<<<(unsigned)pg, kConsTile, 0, stream>>>(D);
         } else {
             int64_t eg = (a.n / 4 + kEpiThreads - 1) / kEpiThreads;       // persistent: a few workgroups per compute unit
             if (eg > 8 * (int64_t)a.num_cus) eg = 8 * (int64_t)a.num_cus;

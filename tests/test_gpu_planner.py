@@ -252,6 +252,18 @@ def large_consistent_cases():
     w.deadline[:] = (2**30 + rng.integers(-10_000_000, 60_000_000, w.n)).astype(np.int32)
     w.deadline[::9] = 2**31 - 1
     yield w, np.zeros(w.K * w.S, np.int64)
+    w = wl.make_workload(2, n_requests=60_000, permute=True)               # degenerate stage constants on the closed-form side
+    w.now[:] = int(np.quantile(w.arrival, 0.9))
+    w.batch[:] = [1, 2, 64, 7, 64]
+    w.workers[:] = [1, 3, 1 << 20, 5, 1]
+    lat = w.lat_us.reshape(w.S, 64)
+    lat[0] = 0                                                             # free stage: nobody is ever late there
+    lat[1] = 5000                                                          # flat table
+    lat[2] = np.minimum(lat[2].astype(np.int64) * 3000, 2**31 - 1)         # huge latencies, huge worker count
+    lat[4, :63] = 100                                                      # a queue shorter than one batch sees only these
+    w.order_mode[:] = [0, 1, 0, 1, 0]
+    w.deadline[::13] = 2**31 - 1
+    yield w, np.array([0, 1_000_000, 0, 250_000, 0], np.int64)
     w = wl.random_workload(77, K=5, S=6, n_per_snapshot=9000, dag_shared=0)  # ragged snapshots, queues that start inside a mask word
     yield w, None
     w = wl.random_workload(78, K=40, S=3, n_per_snapshot=700, dag_shared=1, tie_heavy=True)   # more queues than the LDS table holds
@@ -273,7 +285,7 @@ def test_consistent_large_snapshots(gpu, oracle_mod):
         one = oracle_mod.run(w, threads=8, sub=sub)
         mixed += int(not np.array_equal(one["drop"], ref["drop"]))
         print("   drop fraction", ref["drop"].mean(), "plain", one["drop"].mean(), flush=True)
-    assert mixed >= 5
+    assert mixed >= 6
 
 
 # ---- adaptive priority -----------------------------------------------------------------------
