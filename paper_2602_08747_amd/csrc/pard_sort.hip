@@ -35,6 +35,7 @@ constexpr int kMaxPasses = 8;
 constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 constexpr int kConsTile = 256;                         // queue slots per workgroup in the consistent-dropping kernels
+constexpr int kConsRanges = 8192;                      // workgroups of those kernels at most (each owns a range of tiles)
 constexpr int kFusedScanChunks = 32;                   // up to here every chunk scans the chunk totals itself
 
 constexpr uint32_t kSegScan = 1u << 31;                // queue flag: consistent positions by prefix minimum (see below)
@@ -52,7 +53,7 @@ constexpr int kPartialSegs = 64;                       // up to this many queues
 
 struct SortLayout {
     int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2],
-            min_lat, alive, wkept, tile_tot, carry, total;
+            min_lat, alive, wkept, tile_tot, range_tot, carry, total;
     int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits;
 };
@@ -90,7 +91,8 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.wkept = off;      off = align256(off + words * 4);
     const int64_t ctiles = (n + kConsTile - 1) / kConsTile + 1;
     L.tile_tot = off;   off = align256(off + ctiles * 8);
-    L.carry = off;      off = align256(off + ctiles * 4);
+    L.range_tot = off;  off = align256(off + (int64_t)kConsRanges * 8);
+    L.carry = off;      off = align256(off + (int64_t)kConsRanges * 4);
     L.total = off;
     return L;
 }
@@ -122,8 +124,11 @@ struct SortDev {                    // everything the sort kernels need, by valu
     unsigned long long* alive;      // bit j: the request in queue slot j survives at the smallest possible cost
     unsigned long long* keepm;      // bit j: the request in queue slot j is kept (zeroed with the counters)
     uint32_t* wkept;                // [word w]: kept requests of the queue that owns slot 64w, in its slots before 64w
-    uint2* tile_tot;                // [tile of kConsTile slots]: (a queue starts in it, minimum since the last start)
-    int32_t* carry;                 // [tile]: minimum over the slots before the tile since the last queue start
+    uint2* tile_tot;                // [tile of kConsTile slots]: (a queue starts, minimum since the last start) over the
+                                    // slots before the tile inside its workgroup's range of tiles
+    uint2* range_tot;               // [range]: the same pair over the whole range
+    int32_t* carry;                 // [range]: minimum over the slots before the range since the last queue start
+    int32_t cons_ranges;            // ranges (= workgroups of the prepare and finish kernels)
 };
 
 __global__ void zero_kernel(uint4* p, int64_t count16) {
@@ -914,8 +919,8 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
 //   High budget first:  c_i never rises; the kept requests are exactly the leading ones that the
 //   plain rule (position = i) keeps, so  a_i = min(i, first i' < i with i' >= c_i').
 // Both are segmented exclusive prefix minima over the queue slots: per-tile totals from the
-// prepare kernel, one small scan over the tiles, and the finish kernel redoes the scan inside
-// its tile.  c_i has a closed form (positions_in_time).
+// prepare kernel (whose workgroups each own a range of tiles and carry the scan across it), one
+// small scan over the ranges, and the finish kernel redoes the scan inside its tile.  c_i has a closed form (positions_in_time).
 //
 // Any other queue (arrival order, or a latency table that falls somewhere) is walked:
 //   prepare   also leaves one bit per slot that says whether the request could be kept at all,
@@ -991,7 +996,12 @@ __global__ __launch_bounds__(kConsTile) void consistent_prepare_kernel(SortDev A
     const uint32_t umin = ~A.params->inv_min;
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
-    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+    const int64_t per = (tiles + A.cons_ranges - 1) / A.cons_ranges;      // this workgroup's range of tiles
+    const int64_t t_lo = blockIdx.x * per < tiles ? blockIdx.x * per : tiles;
+    const int64_t t_hi = t_lo + per < tiles ? t_lo + per : tiles;
+    uint32_t range_f = 0;                                // thread 0: the scan's total over the range so far
+    int32_t range_v = kNoMin;
+    for (int64_t t = t_lo; t < t_hi; ++t) {
         const int64_t j = t * kConsTile + tid;
         const bool ok = j < A.n;
         bool can = false;
@@ -1037,53 +1047,58 @@ __global__ __launch_bounds__(kConsTile) void consistent_prepare_kernel(SortDev A
                 seg_min_combine(tf, tv, wf, wv);
                 tf = wf; tv = wv;
             }
-            A.tile_tot[t] = make_uint2(tf, (uint32_t)tv);
+            A.tile_tot[t] = make_uint2(range_f, (uint32_t)range_v);      // what lies before this tile inside the range
+            seg_min_combine(range_f, range_v, tf, tv);
+            range_f = tf; range_v = tv;
         }
         __syncthreads();
     }
+    if (tid == 0) A.range_tot[blockIdx.x] = make_uint2(range_f, (uint32_t)range_v);
 }
 
-// carry[t] = minimum over the slots before tile t since the last queue start (one workgroup:
-// every wave scans a contiguous range of tiles 64 at a time, then the ranges are stitched)
-__global__ __launch_bounds__(1024) void consistent_tile_scan_kernel(SortDev A) {
-    __shared__ uint32_t range_f[16];
-    __shared__ int32_t range_v[16];
+// carry[r] = minimum over the slots before range r since the last queue start: one workgroup
+// scans the ranges' totals (a few per thread, then across the workgroup).
+__global__ __launch_bounds__(1024) void consistent_range_scan_kernel(SortDev A) {
+    __shared__ uint32_t wave_f[16];
+    __shared__ int32_t wave_v[16];
+    constexpr int kPer = kConsRanges / 1024;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
-    const int64_t per = ((tiles + 15) / 16 + 63) / 64 * 64;      // tiles per wave, a multiple of 64
-    const int64_t t_lo = wave * per, t_hi = t_lo + per < tiles ? t_lo + per : tiles;
-    for (int pass = 0; pass < 2; ++pass) {
-        // pass 0: the range's total; pass 1: the carries, starting from what the earlier ranges leave
-        uint32_t run_f = 0;
-        int32_t run_v = kNoMin;
-        if (pass == 1)
-            for (int w = 0; w < wave; ++w) {
-                uint32_t wf = range_f[w];
-                int32_t wv = range_v[w];
-                seg_min_combine(run_f, run_v, wf, wv);
-                run_f = wf; run_v = wv;
-            }
-        for (int64_t t0 = t_lo; t0 < t_hi; t0 += 64) {
-            const int64_t t = t0 + lane;
-            uint32_t f = 0;
-            int32_t v = kNoMin;
-            if (t < t_hi) { const uint2 x = A.tile_tot[t]; f = x.x; v = (int32_t)x.y; }
-            seg_min_wave_scan(f, v, lane);                        // inclusive over the 64 tiles
-            seg_min_combine(run_f, run_v, f, v);                  // ... and everything before them
-            if (pass == 1) {
-                uint32_t pf = __shfl_up(f, 1);
-                int32_t pv = __shfl_up(v, 1);
-                if (lane == 0) { pf = run_f; pv = run_v; }
-                if (t < t_hi) A.carry[t] = pv;                    // exclusive: what lies before tile t
-                (void)pf;
-            }
-            run_f = __shfl(f, 63);
-            run_v = __shfl(v, 63);
+    uint2 x[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i)
+        x[i] = tid * kPer + i < A.cons_ranges ? A.range_tot[tid * kPer + i] : make_uint2(0u, (uint32_t)kNoMin);
+    uint32_t f = 0;
+    int32_t v = kNoMin;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        uint32_t xf = x[i].x;
+        int32_t xv = (int32_t)x[i].y;
+        seg_min_combine(f, v, xf, xv);
+        f = xf; v = xv;
+    }
+    seg_min_wave_scan(f, v, lane);
+    if (lane == 63) { wave_f[wave] = f; wave_v[wave] = v; }
+    uint32_t ef = __shfl_up(f, 1);
+    int32_t ev = __shfl_up(v, 1);
+    if (lane == 0) { ef = 0u; ev = kNoMin; }
+    __syncthreads();
+    {
+        uint32_t rf = 0u;
+        int32_t rv = kNoMin;
+        for (int w = 0; w < wave; ++w) {
+            uint32_t wf = wave_f[w];
+            int32_t wv = wave_v[w];
+            seg_min_combine(rf, rv, wf, wv);
+            rf = wf; rv = wv;
         }
-        if (pass == 0) {
-            if (lane == 0) { range_f[wave] = run_f; range_v[wave] = run_v; }
-            __syncthreads();
-        }
+        seg_min_combine(rf, rv, ef, ev);
+    }
+    int32_t run = ev;                                    // everything before this thread's ranges
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        if (tid * kPer + i < A.cons_ranges) A.carry[tid * kPer + i] = run;
+        const int32_t xv = (int32_t)x[i].y;
+        run = x[i].x ? xv : (run < xv ? run : xv);
     }
 }
 
@@ -1206,7 +1221,11 @@ __global__ __launch_bounds__(kConsTile) void consistent_finish_kernel(SortDev A)
     uint32_t* packed = A.key[last ^ 1];
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     const int64_t tiles = (A.n + kConsTile - 1) / kConsTile;
-    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+    const int64_t per = (tiles + A.cons_ranges - 1) / A.cons_ranges;      // the same ranges as in the prepare kernel
+    const int64_t t_lo = blockIdx.x * per < tiles ? blockIdx.x * per : tiles;
+    const int64_t t_hi = t_lo + per < tiles ? t_lo + per : tiles;
+    const int32_t range_carry = A.carry[blockIdx.x];
+    for (int64_t t = t_lo; t < t_hi; ++t) {
         const int64_t j = t * kConsTile + tid;
         const bool ok = j < A.n;
         EpiSeg q{};
@@ -1232,8 +1251,9 @@ __global__ __launch_bounds__(kConsTile) void consistent_finish_kernel(SortDev A)
         int32_t ev = __shfl_up(v, 1);
         if (lane == 0) { ef = 0; ev = kNoMin; }
         {
-            uint32_t run_f = 0;
-            int32_t run_v = A.carry[t];
+            const uint2 pre = A.tile_tot[t];                   // before the tile: inside the range, and before the range
+            uint32_t run_f = pre.x;
+            int32_t run_v = pre.x ? (int32_t)pre.y : (range_carry < (int32_t)pre.y ? range_carry : (int32_t)pre.y);
             for (int w = 0; w < wave; ++w) {
                 uint32_t wf = wave_f[w];
                 int32_t wv = wave_v[w];
@@ -1302,6 +1322,7 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.keepm = reinterpret_cast<unsigned long long*>(ws + L.keepm);
     D.wkept = reinterpret_cast<uint32_t*>(ws + L.wkept);
     D.tile_tot = reinterpret_cast<uint2*>(ws + L.tile_tot);
+    D.range_tot = reinterpret_cast<uint2*>(ws + L.range_tot);
     D.carry = reinterpret_cast<int32_t*>(ws + L.carry);
     D.tiles = L.tiles;
     D.idx_bits = L.idx_bits;
@@ -1354,8 +1375,10 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
         if (a.consistent) {
             int64_t pg = (a.n + kConsTile - 1) / kConsTile;
             if (pg > 16 * (int64_t)a.num_cus) pg = 16 * (int64_t)a.num_cus;
+            if (pg > kConsRanges) pg = kConsRanges;
+            D.cons_ranges = (int32_t)pg;
             consistent_prepare_kernel<<<(unsigned)pg, kConsTile, 0, stream>>>(D);
-            consistent_tile_scan_kernel<<<1, 1024, 0, stream>>>(D);
+            consistent_range_scan_kernel<<<1, 1024, 0, stream>>>(D);
             consistent_chain_kernel<<<(unsigned)((int64_t)a.plan.K * a.plan.S), 64, 0, stream>>>(D);
             consistent_finish_kernel<<<(unsigned)pg, kConsTile, 0, stream>>>(D);
         } else {
