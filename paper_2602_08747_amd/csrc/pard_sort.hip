@@ -31,7 +31,6 @@ constexpr int kSortThreads = 512;
 constexpr int kSortItems = 16;
 constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
 constexpr int kSortWaves = kSortThreads / kWave;
-constexpr int kMaxPasses = 8;
 constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 constexpr int kConsTile = 256;                         // queue slots per workgroup in the consistent-dropping kernels
@@ -146,17 +145,6 @@ __device__ __forceinline__ int32_t snapshot_of(const int32_t* snap_ptr, int32_t 
         if ((int64_t)snap_ptr[mid] <= r) lo = mid; else hi = mid;
     }
     return lo;
-}
-
-__device__ __forceinline__ void request_segment_key(const SortDev& A, int64_t r, uint32_t& seg, uint32_t& key) {
-    const PlanDev& P = A.plan;
-    const int32_t u = snapshot_of(A.snap_ptr, P.K, r);
-    const int32_t s = clamp_stage(A.stage[r], P.S);
-    const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
-                                             : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
-    const int32_t arr = (P.any_fcfs && mode == PARD_ORDER_FCFS) ? A.arrival[r] : 0;
-    seg = (uint32_t)u * (uint32_t)P.S + (uint32_t)s;
-    key = order_key(mode, A.deadline[r], arr);
 }
 
 // ---- streaming reads shared by the count and histogram kernels -------------------------

@@ -1,0 +1,59 @@
+"""Randomised differential test: many small random plans and snapshots through every variant of the
+estimate (plain, given downstream latency, sequentially consistent) on both kernel paths, C-ABI vs the
+CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_2602_08747_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+FORCE_SORT = 1 << 20
+KEYS = ("est", "drop", "order", "seg_ptr", "surv_idx", "surv_ptr")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU and the built libpard.so")
+    from paper_2602_08747_amd import binding
+    binding.load_library()
+    return binding
+
+
+def draw_case(seed):
+    rng = np.random.default_rng([4711, seed])
+    K = int(rng.integers(1, 10))
+    S = int(rng.integers(1, 17))
+    per = int(rng.choice([0, 1, 7, 64, 300, 1500, 4000, 9000]))
+    modes = [(wl.MODE_LBF,), (wl.MODE_HBF,), (wl.MODE_LBF, wl.MODE_HBF), (wl.MODE_LBF, wl.MODE_HBF, wl.MODE_FCFS)][int(rng.integers(0, 4))]
+    w = wl.random_workload(9000 + seed, K=K, S=S, n_per_snapshot=per, monotone=bool(rng.integers(0, 2)),
+                           tie_heavy=bool(rng.integers(0, 4) == 0), modes=modes,
+                           time_span=int(rng.choice([1, 1000, 50_000, 5_000_000])),
+                           slo_choices=tuple(int(x) for x in rng.choice([0, 2000, 30_000, 400_000, 9_000_000], size=3)),
+                           max_batch=int(rng.choice([1, 4, 64])), max_workers=int(rng.choice([1, 16, 1 << 20])))
+    if rng.integers(0, 3) == 0 and w.n:
+        w.deadline[rng.integers(0, w.n, size=max(1, w.n // 10))] = 2**31 - 1
+    if rng.integers(0, 3) == 0 and w.n:
+        w.stage[rng.integers(0, w.n, size=max(1, w.n // 20))] = rng.integers(-5, S + 5)
+    sub = None
+    if rng.integers(0, 2):
+        sub = rng.choice([0, 1, 5000, 90_000, 1 << 33, 1 << 45], size=K * S).astype(np.int64)
+    return w, sub
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_case(gpu, oracle_mod, seed):
+    import torch
+    w, sub = draw_case(seed)
+    print("case", seed, w.name, "n", w.n, "K", w.K, "S", w.S, "sub", sub is not None, flush=True)
+    for consistent in (False, True):
+        ref = oracle_mod.run(w, threads=8, sub=sub, consistent=consistent)
+        for max_snap in (None, FORCE_SORT):
+            s = gpu.Session(w, max_snapshot_requests=None if max_snap is None else max(max_snap, w.max_snapshot_requests))
+            s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=consistent)
+            got = s.results()
+            for k in KEYS:
+                assert np.array_equal(got[k], ref[k]), (seed, consistent, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
+            assert s.status_word() == 0
