@@ -222,6 +222,8 @@ int pard_queue_lengths(const pard_plan_t* plan, int64_t n, const int32_t* d_stag
  *   d_sub                  device out int64[K*S], microseconds, saturated at 2^40
  * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE (variant, lambda outside [0,1], sample count),
  * PARD_E_UNSUPPORTED (PARD_SUB_FULL with a latency entry above PARD_MAX_WAIT_LATENCY), PARD_E_HIP.
+ * Enqueues on `stream`, allocates nothing; the sampled variant stages the drawn arrivals in
+ * scratch memory the plan owns, so two such calls on one plan must not run at the same time.
  */
 int pard_sub_latency(const pard_plan_t* plan, const int32_t* d_qlen, int32_t variant,
                      int64_t lambda_num, int64_t lambda_den, int32_t num_samples,

@@ -10,6 +10,7 @@ struct pard_plan {
     HostPlan host;
     PlanDev dev;
     void* blob = nullptr;      // one device allocation holding every plan table
+    uint32_t* drawn = nullptr; // inside blob: scratch of pard_sub_latency, PARD_MAX_WAIT_SAMPLES * S words
     int device = 0;
     int num_cus = 1;
     int compact_resident = 1;  // co-resident workgroups of the look-back kernels on this device
@@ -66,7 +67,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     const int64_t b_est = align256((int64_t)h.entry_stage.size() * 4 + 4);
     const int64_t b_een = align256((int64_t)h.entry_end.size() * 4 + 4);
     const int64_t b_edg = align256((int64_t)h.entry_dag.size() * 4 + 4);
-    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een + b_edg;
+    const int64_t b_drw = align256((int64_t)PARD_MAX_WAIT_SAMPLES * h.S * 4);
+    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een + b_edg + b_drw;
     if (hipGetDevice(&p->device) != hipSuccess || hipMalloc(&p->blob, (size_t)total) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -86,6 +88,7 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     char* d_est = put(h.entry_stage.data(), h.entry_stage.size() * 4, b_est);
     char* d_een = put(h.entry_end.data(), h.entry_end.size() * 4, b_een);
     char* d_edg = put(h.entry_dag.data(), h.entry_dag.size() * 4, b_edg);
+    p->drawn = reinterpret_cast<uint32_t*>(base + off);
     if (!d_recs || !d_lat || !d_dep || !d_est || !d_een || !d_edg) {
         (void)hipGetLastError();
         (void)hipFree(p->blob);
@@ -248,6 +251,7 @@ static int sub_latency_impl(const pard_plan_t* plan, const int32_t* d_qlen, cons
             a.num_samples = num_samples;
             a.samples = d_samples;
             a.picks = d_picks;
+            a.drawn = plan->drawn;
         }
     }
     hipError_t e = launch_sub_latency(a, static_cast<hipStream_t>(stream));

@@ -169,6 +169,7 @@ struct SubArgs {
     int32_t num_samples;
     const int32_t* samples;            // [num_samples]
     const uint32_t* picks;             // [num_samples * S]
+    uint32_t* drawn;                   // [S][num_samples] scratch: the arrival each (sample, stage) pair draws
     unsigned long long* sub;           // [K*S] out
 };
 hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream);

@@ -136,8 +136,21 @@ __global__ __launch_bounds__(256) void sub_simple_kernel(SubArgs A, int64_t item
     if (v) atomicMax(&A.sub[(int64_t)u * P.S + k], (unsigned long long)v);
 }
 
+// The arrival every (sample, stage) pair draws depends on neither the snapshot nor the path:
+// gather them once per call, stage-major, so that the per-path kernel below reads them with
+// unit stride instead of chasing two dependent random loads per pair.
+__global__ __launch_bounds__(256) void drawn_arrivals_kernel(int32_t S, uint32_t M, const int32_t* samples, const uint32_t* picks,
+                                                             uint32_t m_mul, uint32_t m_shf, uint32_t* drawn) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;       // t = j * S + i, the layout of picks
+    if (t >= (int64_t)M * S) return;
+    const uint32_t pick = picks[t];
+    const int32_t a = samples[pick - magic_div_dev(pick, m_mul, m_shf) * M];
+    const uint32_t j = (uint32_t)(t / S), i = (uint32_t)(t - (int64_t)j * S);
+    drawn[(int64_t)i * M + j] = a > 0 ? (uint32_t)a : 0u;
+}
+
 // The sampled variant: one workgroup per (snapshot, path entry).
-constexpr int kWThreads = 256;
+constexpr int kWThreads = 512;
 constexpr int kWWaves = kWThreads / kWave;
 constexpr int kWUnroll = 8;                            // samples a thread works on at once
 constexpr int kSelBits = 11;                            // radix-select digits: 11 + 11 + 10 bits
@@ -153,7 +166,7 @@ struct WaitLds {
     uint32_t sel_bin, sel_before;
 };
 
-__global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint32_t m_mul, uint32_t m_shf) {
+__global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A) {
     extern __shared__ __align__(16) uint32_t totals[];          // [num_samples]
     __shared__ WaitLds L;
     const PlanDev& P = A.plan;
@@ -183,7 +196,7 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
         L.dur[tid] = d; L.mul[tid] = mul; L.shf[tid] = shf; L.stg[tid] = i;
     }
     __syncthreads();
-    // kWUnroll samples per thread and trip, so that their dependent loads (draw, then arrival) overlap
+    // kWUnroll samples per thread and trip, so that their loads overlap
     for (uint32_t j0 = tid; j0 < M; j0 += kWUnroll * kWThreads) {
         uint32_t total[kWUnroll];
 #pragma unroll
@@ -192,20 +205,16 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A, uint
             const uint32_t d = L.dur[l];
             if (d == 0) continue;
             const uint32_t mul = L.mul[l], shf = L.shf[l];
-            const int32_t col = L.stg[l];
-            uint32_t pick[kWUnroll];
-            int32_t a[kWUnroll];
+            const uint32_t* col = A.drawn + (int64_t)L.stg[l] * M;
+            uint32_t a[kWUnroll];
 #pragma unroll
             for (int x = 0; x < kWUnroll; ++x) {
                 const uint32_t j = j0 + x * kWThreads;
-                pick[x] = A.picks[(int64_t)(j < M ? j : j0) * P.S + col];
+                a[x] = col[j < M ? j : j0];
             }
 #pragma unroll
-            for (int x = 0; x < kWUnroll; ++x) a[x] = A.samples[pick[x] - magic_div_dev(pick[x], m_mul, m_shf) * M];
-#pragma unroll
             for (int x = 0; x < kWUnroll; ++x) {
-                const uint32_t au = a[x] > 0 ? (uint32_t)a[x] : 0u;
-                const uint32_t rem = au - magic_div_dev(au, mul, shf) * d;
+                const uint32_t rem = a[x] - magic_div_dev(a[x], mul, shf) * d;
                 total[x] += rem ? d - rem : 0u;
             }
         }
@@ -486,7 +495,10 @@ hipError_t launch_sub_latency(const SubArgs& a, hipStream_t stream) {
         sub_simple_kernel<<<(unsigned)((items + 255) / 256), 256, 0, stream>>>(a, items);
     } else {
         const Magic32 mm = magic_u32((uint32_t)a.num_samples);
-        sub_quantile_kernel<<<(unsigned)items, kWThreads, (size_t)a.num_samples * 4, stream>>>(a, mm.m, mm.sh);
+        const int64_t pairs = (int64_t)a.num_samples * P.S;
+        drawn_arrivals_kernel<<<(unsigned)((pairs + 255) / 256), 256, 0, stream>>>(P.S, (uint32_t)a.num_samples, a.samples, a.picks,
+                                                                                  mm.m, mm.sh, a.drawn);
+        sub_quantile_kernel<<<(unsigned)items, kWThreads, (size_t)a.num_samples * 4, stream>>>(a);
     }
     return hipGetLastError();
 }
