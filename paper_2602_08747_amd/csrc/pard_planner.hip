@@ -284,8 +284,8 @@ __device__ __forceinline__ unsigned __int128 mul_64_64(uint64_t a, uint64_t b) {
     return ((unsigned __int128)__umul64hi(a, b) << 64) | (unsigned __int128)(a * b);
 }
 
-__global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, int32_t T, int32_t window, const int32_t* rate,
-                                                                   const int32_t* prev_mode, int32_t* mode_out) {
+__global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, int32_t T, int32_t window, uint32_t w_mul, uint32_t w_shf,
+                                                                   const int32_t* rate, const int32_t* prev_mode, int32_t* mode_out) {
     const int lane = threadIdx.x & 63;
     const int64_t series = (int64_t)P.K * P.S;
     const int64_t wave_id = ((int64_t)blockIdx.x * kPThreads + threadIdx.x) >> 6;
@@ -312,7 +312,9 @@ __global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, in
             carry += __shfl(inc, 63);
             if (ok) {
                 const int64_t cnt = t + 1 < window ? t + 1 : window;
-                const int64_t ts = win / cnt;
+                // floor of the window mean; a full window whose sum fits 32 bits divides by multiplication
+                const int64_t ts = (cnt == window && ((uint64_t)win >> 32) == 0ull) ? (int64_t)magic_div_dev((uint32_t)win, w_mul, w_shf)
+                                                                                   : win / cnt;
                 const int64_t d = x - ts;
                 dev += (uint64_t)(d < 0 ? -d : d);
                 sum += (uint64_t)x;
@@ -451,7 +453,8 @@ hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_
     const int64_t series = (int64_t)plan.K * plan.S;
     int64_t grid = (series + 3) / 4;
     if (grid > 4096) grid = 4096;
-    priority_modes_kernel<<<(unsigned)grid, kPThreads, 0, stream>>>(plan, series_len, window, rate, prev_mode, mode_out);
+    const Magic32 mw = magic_u32((uint32_t)window);
+    priority_modes_kernel<<<(unsigned)grid, kPThreads, 0, stream>>>(plan, series_len, window, mw.m, mw.sh, rate, prev_mode, mode_out);
     return hipGetLastError();
 }
 
