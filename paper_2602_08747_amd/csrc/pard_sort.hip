@@ -128,6 +128,7 @@ struct SortDev {                    // everything the sort kernels need, by valu
     uint2* range_tot;               // [range]: the same pair over the whole range
     int32_t* carry;                 // [range]: minimum over the slots before the range since the last queue start
     int32_t cons_ranges;            // ranges (= workgroups of the prepare and finish kernels)
+    int32_t consistent;             // sequentially consistent dropping asked for
 };
 
 __global__ void zero_kernel(uint4* p, int64_t count16) {
@@ -145,6 +146,16 @@ __device__ __forceinline__ int32_t snapshot_of(const int32_t* snap_ptr, int32_t 
         if ((int64_t)snap_ptr[mid] <= r) lo = mid; else hi = mid;
     }
     return lo;
+}
+
+// the same among the snapshots lo..hi (r is known to lie in one of them)
+__device__ __forceinline__ int32_t snapshot_between(const int32_t* snap_ptr, int32_t lo, int32_t hi, int64_t r) {
+    int32_t a = lo, b = hi + 1;                   // answer in [a, b)
+    while (b - a > 1) {
+        const int32_t mid = (a + b) >> 1;
+        if ((int64_t)snap_ptr[mid] <= r) a = mid; else b = mid;
+    }
+    return a;
 }
 
 // ---- streaming reads shared by the count and histogram kernels -------------------------
@@ -174,12 +185,13 @@ __device__ __forceinline__ void load_chunk(const SortDev& A, int64_t base, int t
                 st[c] = r0 + c < A.n ? A.stage[r0 + c] : 0;
             }
         }
+        int32_t u = r0 < A.n ? snapshot_of(A.snap_ptr, P.K, r0) : 0;        // then forward: the four are consecutive
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int i = g * 4 + c;
             const int64_t r = r0 + c;
             ok[i] = r < A.n;
-            const int32_t u = ok[i] ? snapshot_of(A.snap_ptr, P.K, r) : 0;
+            while (ok[i] && u + 1 < P.K && r >= (int64_t)A.snap_ptr[u + 1]) ++u;
             const int32_t sidx = clamp_stage(st[c], P.S);
             const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
                                                      : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + sidx].mode & 0xFF);
@@ -350,7 +362,8 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
                                 P.lat + rec * PARD_LAT_ENTRIES);
     }
     // smallest execution latency of every queue: lat[min(B, a + 1)] over all positions a
-    for (int64_t g = tid; g < segs; g += 1024) {
+    // (consistent dropping only)
+    for (int64_t g = tid; g < segs && A.consistent; g += 1024) {
         const int64_t rec = P.shared ? g % P.S : g;
         const int32_t* row = P.lat + rec * PARD_LAT_ENTRIES;
         const int32_t B = P.recs[rec].B;
@@ -373,15 +386,16 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         }
         return;
     }
-    for (int32_t u = 0; u < P.K; ++u) {
-        const int32_t dag = P.shared ? 0 : u;
-        const int32_t e_lo = P.dag_entry_ptr[dag], e_hi = P.dag_entry_ptr[dag + 1];
-        for (int32_t e = e_lo + tid; e < e_hi; e += 1024) {
-            const int32_t end = P.entry_end[e];
-            unsigned long long sum = 0;
-            for (int32_t t = e + 1; t < end; ++t) sum += A.cfull[(int64_t)u * P.S + P.entry_stage[t]];
-            atomicMax(&A.down[(int64_t)u * P.S + P.entry_stage[e]], sum);
-        }
+    const int64_t per_dag = P.dag_entry_ptr[1];                              // entries of the one shared DAG
+    const int64_t items = P.shared ? per_dag * P.K : P.total_entries;        // (snapshot, path entry) pairs
+    for (int64_t b = tid; b < items; b += 1024) {
+        int32_t u, e;
+        if (P.shared) { u = (int32_t)(b / per_dag); e = (int32_t)(b - (int64_t)u * per_dag); }
+        else { e = (int32_t)b; u = P.entry_dag[e]; }
+        const int32_t end = P.entry_end[e];
+        unsigned long long sum = 0;
+        for (int32_t t = e + 1; t < end; ++t) sum += A.cfull[(int64_t)u * P.S + P.entry_stage[t]];
+        atomicMax(&A.down[(int64_t)u * P.S + P.entry_stage[e]], sum);
     }
 }
 
@@ -438,7 +452,7 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
             const int e = wave * (kWave * kSortItems) + i * kWave + lane;
             const int64_t r = tile_base + e;
             const bool ok = e < valid;
-            const int32_t u = (ok && u_first != u_last) ? snapshot_of(A.snap_ptr, P.K, r) : u_first;
+            const int32_t u = (ok && u_first != u_last) ? snapshot_between(A.snap_ptr, u_first, u_last, r) : u_first;
             const int32_t s = clamp_stage(st[i], P.S);
             const int32_t mode = P.uniform_mode >= 0 ? P.uniform_mode
                                                      : (P.recs[(P.shared ? 0 : (int64_t)u * P.S) + s].mode & 0xFF);
@@ -799,7 +813,7 @@ __device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t se
     q.start = A.seg_ptr[seg]; q.now = A.now[u];
     q.first = A.snap_ptr[u];
     q.len = A.seg_ptr[seg + 1] - q.start;
-    q.aux = A.min_lat[seg];
+    q.aux = A.consistent ? A.min_lat[seg] : 0u;
     q.pad = 0;
     q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
     return q;
@@ -1291,6 +1305,7 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.snap_ptr = a.snap_ptr; D.now = a.now;
     D.est = a.est; D.drop = a.drop; D.order = a.order; D.seg_ptr = a.seg_ptr;
     D.sub = a.sub;
+    D.consistent = a.consistent;
     D.status_word = a.status;
     D.params = reinterpret_cast<SortParams*>(ws + L.params);
     D.seg_count = reinterpret_cast<uint32_t*>(ws + L.seg_count);
