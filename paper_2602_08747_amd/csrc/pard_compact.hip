@@ -31,6 +31,8 @@
 // but atomics on one address cost ~11 ns each here (~95 us for 8192 tiles); 16 counters on
 // separate cache lines run in parallel.  The first workgroup of pool 0 to arrive becomes the
 // helper.
+#include <type_traits>
+
 #include "pard_device.hpp"
 
 namespace pard {
@@ -387,10 +389,11 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
 // tiles.  A first kernel counts them per snapshot; the main kernel gives every snapshot to
 // one workgroup, which adds up the counts of the snapshots before it and then works alone.
 // =====================================================================================
-constexpr int kLThreads = 512;
-constexpr int kLWaves = kLThreads / kWave;
-constexpr int kLCap = kLThreads * 16;                  // queue slots one workgroup handles
-constexpr int kDirectSumSnapshots = 8192;              // up to here every workgroup adds up the counts before it itself
+// The workgroup has THREADS threads and handles up to 16 * THREADS queue slots; the launcher picks
+// the smallest one that covers the promised snapshot bound (a 512-thread workgroup spends most of
+// its time on fixed costs when a snapshot holds a few hundred requests).
+constexpr int kLThreadsMax = 512;
+constexpr int kLCap = kLThreadsMax * 16;               // queue slots the largest workgroup handles
 static_assert(kLCap == PARD_FUSED_SNAPSHOT_CAPACITY, "per-snapshot compaction covers the on-chip snapshot size");
 
 // number of zero bytes in a word
@@ -400,20 +403,21 @@ __device__ __forceinline__ uint32_t zero_bytes(uint32_t w) {
 }
 
 // Slot range of snapshot u; false when it breaks the promised bound or the array limits.
-__device__ __forceinline__ bool snapshot_range(const int32_t* seg_ptr, int64_t u, int32_t stages, int64_t n,
+__device__ __forceinline__ bool snapshot_range(const int32_t* seg_ptr, int64_t u, int32_t stages, int64_t n, int64_t cap,
                                                int64_t& a, int64_t& b) {
     a = seg_ptr[u * stages];
     b = seg_ptr[(u + 1) * stages];
-    return a >= 0 && b >= a && b <= n && b - a <= kLCap;
+    return a >= 0 && b >= a && b <= n && b - a <= cap;
 }
 
-__global__ __launch_bounds__(256) void snapshot_kept_kernel(const int32_t* seg_ptr, int32_t stages, int64_t n,
-                                                            const uint8_t* drop, uint32_t* kept, uint32_t* status_word) {
-    __shared__ uint32_t part[4];
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void snapshot_kept_kernel(const int32_t* seg_ptr, int32_t stages, int64_t n, int64_t cap,
+                                                                const uint8_t* drop, uint32_t* kept, uint32_t* status_word) {
+    __shared__ uint32_t part[THREADS / kWave];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t u = blockIdx.x;
     int64_t a, b;
-    if (!snapshot_range(seg_ptr, u, stages, n, a, b)) {
+    if (!snapshot_range(seg_ptr, u, stages, n, cap, a, b)) {
         if (tid == 0) { atomicOr(status_word, kStatusSnapshotTooLarge); kept[u] = 0; }
         return;
     }
@@ -421,7 +425,7 @@ __global__ __launch_bounds__(256) void snapshot_kept_kernel(const int32_t* seg_p
     const uintptr_t win = lo & ~(uintptr_t)15;
     const uint32_t chunks = (uint32_t)((hi - win + 15) >> 4);
     uint32_t cnt = 0;
-    for (uint32_t c = tid; c < chunks; c += 256) {
+    for (uint32_t c = tid; c < chunks; c += THREADS) {
         const uintptr_t at = win + 16u * (uintptr_t)c;
         if (at >= lo && at + 16 <= hi) {
             const uint4 v = *reinterpret_cast<const uint4*>(at);
@@ -435,7 +439,11 @@ __global__ __launch_bounds__(256) void snapshot_kept_kernel(const int32_t* seg_p
     for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
     if (lane == 0) part[wave] = cnt;
     __syncthreads();
-    if (tid == 0) kept[u] = part[0] + part[1] + part[2] + part[3];
+    if (tid == 0) {
+        uint32_t sum = 0;
+        for (int w = 0; w < THREADS / kWave; ++w) sum += part[w];
+        kept[u] = sum;
+    }
 }
 
 // Exclusive scan of kept[0..count) by one workgroup (only for very many snapshots).
@@ -459,19 +467,22 @@ __global__ __launch_bounds__(1024) void snapshot_offsets_kernel(const uint32_t* 
     for (int64_t i = lo; i < hi; ++i) { snap_off[i] = run; run += kept[i]; }
 }
 
+template <int THREADS>
 struct LocalLds {
-    uint32_t group[kLCap / 4];          // per group of 4 slots: kept slots of the snapshot before it | keep bits << 13
-    __align__(16) uint8_t drop[kLCap + 32];
-    uint32_t wave_tot[kLWaves];
-    uint32_t wave_off[kLWaves];
+    uint32_t group[THREADS * 4];        // per group of 4 slots: kept slots of the snapshot before it | keep bits << 13
+    __align__(16) uint8_t drop[THREADS * 16 + 32];
+    uint32_t wave_tot[THREADS / kWave];
+    uint32_t wave_off[THREADS / kWave];
 };
 
-__global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs A, const uint32_t* kept, const uint32_t* snap_off) {
-    __shared__ LocalLds L;
+template <int THREADS>
+__global__ __launch_bounds__(THREADS, 4) void compact_local_kernel(CompactArgs A, const uint32_t* kept, const uint32_t* snap_off) {
+    constexpr int kLThreads = THREADS, kLWaves = THREADS / kWave;
+    __shared__ LocalLds<THREADS> L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t u = blockIdx.x;
     int64_t a, b;
-    if (!snapshot_range(A.seg_ptr, u, A.stages, A.n, a, b)) return;     // reported by the counting kernel
+    if (!snapshot_range(A.seg_ptr, u, A.stages, A.n, (int64_t)THREADS * 16, a, b)) return;     // reported by the counting kernel
     const int size = (int)(b - a);
     // a snapshot without survivors (its slice of drop[] has no zero byte) only owes its queue offsets:
     // neither its slots nor its drop bytes are read
@@ -515,15 +526,14 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
     }
     // the offsets of this snapshot's queues (the last snapshot also owns the end offset), fetched early
     const int owned = A.stages + (u + 1 == gridDim.x ? 1 : 0);
-    static_assert(PARD_MAX_STAGES + 1 <= kLThreads, "one thread per queue offset");
+    static_assert(PARD_MAX_STAGES + 1 <= 2 * kLThreads, "at most two queue offsets per thread");
     const int64_t my_slot = tid < owned ? (int64_t)A.seg_ptr[u * A.stages + tid] - a : 0;
     // survivors of the snapshots before this one
     uint32_t before_me = 0;
     if (snap_off) {
         before_me = tid == 0 ? snap_off[u] : 0u;
     } else {
-        static_assert(kDirectSumSnapshots == 16 * kLThreads, "sixteen counts per thread");
-        uint32_t x[16];                 // all loads in flight at once
+        uint32_t x[16];                 // sixteen counts per thread (the launcher scans first when there are more): all loads in flight at once
 #pragma unroll
         for (int i = 0; i < 16; ++i) x[i] = (int64_t)(tid + i * kLThreads) < u ? kept[tid + i * kLThreads] : 0u;
 #pragma unroll
@@ -597,14 +607,15 @@ __global__ __launch_bounds__(kLThreads, 4) void compact_local_kernel(CompactArgs
             if (keep[k] & (1u << c)) { A.surv_idx[o] = ids[k][c]; ++o; }
     }
     __syncthreads();
-    if (tid < owned) {
-        int64_t p = my_slot < 0 ? 0 : my_slot;
+    for (int q = tid; q < owned; q += kLThreads) {          // the smallest workgroup may own more offsets than it has threads
+        const int64_t slot = q == tid ? my_slot : (int64_t)A.seg_ptr[u * A.stages + q] - a;
+        const int64_t p = slot < 0 ? 0 : slot;
         uint32_t before = total;
         if (p < size) {
             const uint32_t v = L.group[p >> 2];
             before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
         }
-        A.surv_ptr[u * A.stages + tid] = (int32_t)(off0 + before);
+        A.surv_ptr[u * A.stages + q] = (int32_t)(off0 + before);
     }
 }
 
@@ -637,9 +648,19 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
         const int64_t K = a.num_segments / a.stages;
         uint32_t* kept = static_cast<uint32_t*>(a.workspace);
         uint32_t* snap_off = kept + ((K * 4 + 255) & ~(int64_t)255) / 4;
-        snapshot_kept_kernel<<<(unsigned)K, 256, 0, stream>>>(a.seg_ptr, a.stages, a.n, a.drop, kept, a.status);
-        if (K > kDirectSumSnapshots) snapshot_offsets_kernel<<<1, 1024, 0, stream>>>(kept, K, snap_off);
-        compact_local_kernel<<<(unsigned)K, kLThreads, 0, stream>>>(a, kept, K > kDirectSumSnapshots ? snap_off : nullptr);
+        // the smallest workgroup that covers the promised snapshot bound; up to 16 * THREADS snapshots every
+        // workgroup adds up the counts before it itself, beyond that one workgroup scans them first
+        auto run = [&](auto threads_tag, auto count_tag) {
+            constexpr int THREADS = decltype(threads_tag)::value, COUNT = decltype(count_tag)::value;
+            const bool scan = K > 16 * THREADS;
+            snapshot_kept_kernel<COUNT><<<(unsigned)K, COUNT, 0, stream>>>(a.seg_ptr, a.stages, a.n, (int64_t)THREADS * 16, a.drop, kept, a.status);
+            if (scan) snapshot_offsets_kernel<<<1, 1024, 0, stream>>>(kept, K, snap_off);
+            compact_local_kernel<THREADS><<<(unsigned)K, THREADS, 0, stream>>>(a, kept, scan ? snap_off : nullptr);
+        };
+        if (a.max_snapshot <= 1024) run(std::integral_constant<int, 64>{}, std::integral_constant<int, 64>{});
+        else if (a.max_snapshot <= 2048) run(std::integral_constant<int, 128>{}, std::integral_constant<int, 64>{});
+        else if (a.max_snapshot <= 4096) run(std::integral_constant<int, 256>{}, std::integral_constant<int, 128>{});
+        else run(std::integral_constant<int, 512>{}, std::integral_constant<int, 256>{});
         return hipGetLastError();
     }
     uint32_t* pool_ctr = static_cast<uint32_t*>(a.workspace);

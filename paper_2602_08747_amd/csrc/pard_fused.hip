@@ -30,18 +30,19 @@ namespace pard {
 
 namespace {
 
-constexpr int kCap = PARD_FUSED_SNAPSHOT_CAPACITY;   // requests per snapshot, at most
-constexpr int kIdxBits = 13;                         // 8192 = 2^13 local indices
-constexpr int kBuckets = 12288;                      // 16-bit counters, two per LDS word
-constexpr int kCntWords = kBuckets / 2;
+// Capacity CAP (a power of two, at most PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (at least one wave): a
+// workgroup sized for 8192 requests spends most of its time on fixed costs when a snapshot holds a
+// few hundred, so smaller snapshots get smaller workgroups (and more of them per compute unit).
+constexpr int kAuxMin = PARD_MAX_STAGES * PARD_LAT_ENTRIES + 256;   // words: every stage's latency table + path entries
 
-static_assert(kCap == (1 << kIdxBits), "local index width");
-
+template <int CAP>
 struct SnapshotLds {
+    static constexpr int kCntWords = CAP * 3 / 4;    // 1.5 * CAP 16-bit counters, two per LDS word
+    static constexpr int kAuxWords = CAP / 2 > kAuxMin ? CAP / 2 : kAuxMin;
     __align__(16) uint32_t cnt32[kCntWords + 4];     // bucket counters, then bucket starts; later the queue order
-    __align__(16) uint32_t low[kCap + 4];            // per queue slot: low bits of key.index (or the whole key)
-    __align__(16) uint16_t idx[kCap];                // per queue slot: local index (wide keys only); otherwise
-                                                     // 4096 words of cache: latency tables, then path entries
+    __align__(16) uint32_t low[CAP + 4];             // per queue slot: low bits of key.index (or the whole key)
+    __align__(16) uint16_t idx[2 * kAuxWords];       // per queue slot: local index (wide keys only); otherwise
+                                                     // a cache: latency tables, then path entries
     StageRec recs[PARD_MAX_STAGES];
     unsigned long long cfull[PARD_MAX_STAGES];
     unsigned long long down[PARD_MAX_STAGES];
@@ -52,14 +53,22 @@ struct SnapshotLds {
     uint32_t red[2];
 };
 
+constexpr int log2_of(int x) { return x <= 1 ? 0 : 1 + log2_of(x / 2); }
+
 // FULL: the snapshot holds exactly kCap requests and every array is 16-byte aligned at its
 // start, so no per-request bounds test is needed.
-template <int T, bool FULL, bool CONSISTENT>
-__device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L, const int u, const int64_t lo,
+template <int T, int CAP, bool FULL, bool CONSISTENT>
+__device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CAP>& L, const int u, const int64_t lo,
                                               const int m, const bool aligned) {
+    constexpr int kCap = CAP;
+    constexpr int kIdxBits = log2_of(CAP);                 // bits of a local index
+    constexpr int kCntWords = SnapshotLds<CAP>::kCntWords;
+    constexpr int kBuckets = 2 * kCntWords;                // 16-bit counters
+    constexpr int kAuxWords = SnapshotLds<CAP>::kAuxWords;
     constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
     constexpr int CW = kCntWords / T;       // counter words scanned per thread
-    static_assert(G >= 1 && CW >= 2 && CW % 2 == 0 && kCntWords % T == 0, "shape");
+    static_assert(kCap == (1 << kIdxBits) && kCap <= PARD_FUSED_SNAPSHOT_CAPACITY, "capacity");
+    static_assert(G >= 1 && CW >= 2 && CW % 2 == 0 && kCntWords % T == 0 && T % kWave == 0 && T / kWave <= 16, "shape");
 
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x;
@@ -69,9 +78,9 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     const int dag = P.shared ? 0 : u;
     const int32_t* lat_dag = P.lat + (int64_t)dag * S * PARD_LAT_ENTRIES;
     auto live = [&](int idx) { return FULL || idx < m; };
-    uint32_t* aux = reinterpret_cast<uint32_t*>(L.idx);           // kCap / 2 words
+    uint32_t* aux = reinterpret_cast<uint32_t*>(L.idx);           // kAuxWords words
     const int e_lo = P.dag_entry_ptr[dag], n_entries = P.dag_entry_ptr[dag + 1] - e_lo;
-    const bool entries_cached = S * PARD_LAT_ENTRIES + n_entries <= kCap / 2;
+    const bool entries_cached = S * PARD_LAT_ENTRIES + n_entries <= kAuxWords;
     const int32_t now = A.now[u];
 
     // ---- 1. loads (issued first), LDS initialisation meanwhile ---------------
@@ -458,9 +467,10 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds& L
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
 }
 
-template <int T, bool CONSISTENT>
+template <int T, int CAP, bool CONSISTENT>
 __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
-    __shared__ SnapshotLds L;
+    constexpr int kCap = CAP;
+    __shared__ SnapshotLds<CAP> L;
     const int u = blockIdx.x;
     const int64_t n = A.n;
     // snapshot bounds, made safe whatever snap_ptr holds
@@ -480,16 +490,25 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
                            reinterpret_cast<uintptr_t>(A.est) | reinterpret_cast<uintptr_t>(A.order) |
                            (reinterpret_cast<uintptr_t>(A.drop) << 2);
     const bool aligned = (lo & 3) == 0 && (bits & 15) == 0;
-    if (m == kCap && aligned) snapshot_body<T, true, CONSISTENT>(A, L, u, lo, m, true);
-    else snapshot_body<T, false, CONSISTENT>(A, L, u, lo, m, aligned);
+    if (m == kCap && aligned) snapshot_body<T, CAP, true, CONSISTENT>(A, L, u, lo, m, true);
+    else snapshot_body<T, CAP, false, CONSISTENT>(A, L, u, lo, m, aligned);
+}
+
+template <int CAP, int T>
+void launch_capacity(const FusedArgs& a, hipStream_t stream) {
+    if (a.consistent) fused_snapshot_kernel<T, CAP, true><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    else fused_snapshot_kernel<T, CAP, false><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
 }
 
 }  // namespace
 
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
-    constexpr int T = 512;
-    if (a.consistent) fused_snapshot_kernel<T, true><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
-    else fused_snapshot_kernel<T, false><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    // the smallest workgroup whose capacity covers the promised snapshot size
+    if (a.cap <= 512) launch_capacity<512, 64>(a, stream);
+    else if (a.cap <= 1024) launch_capacity<1024, 64>(a, stream);
+    else if (a.cap <= 2048) launch_capacity<2048, 128>(a, stream);
+    else if (a.cap <= 4096) launch_capacity<4096, 256>(a, stream);
+    else launch_capacity<PARD_FUSED_SNAPSHOT_CAPACITY, 512>(a, stream);
     return hipGetLastError();
 }
 

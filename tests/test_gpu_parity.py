@@ -100,6 +100,56 @@ def test_snapshot_sizes_on_chip(gpu, oracle_mod, m):
     check(gpu, oracle_mod, w)
 
 
+@pytest.mark.parametrize("cap", [512, 1024, 2048, 4096, 8192])
+def test_every_workgroup_capacity(gpu, oracle_mod, cap):
+    """The on-chip kernel comes in several capacities, picked from the promised snapshot bound: snapshots that
+    fill a capacity exactly (the path without bounds tests), fall one short of it, or mix sizes below it; the
+    same snapshots under a larger promise (a larger workgroup) must give the same result."""
+    for per, permute in ((cap, True), (cap, False), (cap - 1, True), (cap // 2 + 3, True)):
+        w = wl.make_workload(5, n_snapshots=5, per_snapshot=per, permute=permute)
+        check(gpu, oracle_mod, w)
+        if cap < 8192:
+            check(gpu, oracle_mod, w, max_snap=2 * cap)
+    w = wl.random_workload(600 + cap, K=9, S=7, n_per_snapshot=cap // 2, dag_shared=0)     # ragged sizes up to cap
+    assert w.max_snapshot_requests <= cap
+    check(gpu, oracle_mod, w, max_snap=cap)
+    ref = oracle_mod.run(w, threads=8, consistent=True)
+    s = gpu.Session(w, max_snapshot_requests=cap)
+    s.run(consistent=True)
+    got = s.results()
+    for k in KEYS:
+        assert np.array_equal(got[k], ref[k]), (cap, k)
+
+
+@pytest.mark.parametrize("per", [40, 700, 3000, 8000])
+def test_sixty_four_stages(gpu, oracle_mod, per):
+    """The largest stage count: a chain of 64 stages plus a few shortcuts, every workgroup capacity, both paths."""
+    S, K = 64, 4
+    rng = np.random.default_rng(6400 + per)
+    rp, col = wl.csr_from_edges(S, wl.chain_edges(S) + [(3, 40), (10, 63), (20, 51)])
+    sizes = rng.integers(per // 2, per + 1, size=K)
+    snap_ptr = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(snap_ptr[-1])
+    arrival = rng.integers(0, 200_000, n).astype(np.int32)
+    w = wl.Workload(name=f"chain64-{per}", K=K, S=S, dag_shared=1, dag_row_ptr=rp, dag_col=col,
+                    batch=rng.integers(1, 65, S).astype(np.int32), workers=rng.integers(1, 9, S).astype(np.int32),
+                    lat_us=np.ascontiguousarray(wl.monotone_tables(rng, S).reshape(-1) // 20, np.int32),
+                    order_mode=rng.integers(0, 3, S).astype(np.int32), arrival=arrival,
+                    deadline=(arrival + rng.choice([100_000, 900_000, 4_000_000], n)).astype(np.int32),
+                    stage=rng.integers(0, S, n).astype(np.int32), snap_ptr=snap_ptr,
+                    now=np.full(K, 150_000, np.int32))
+    _, ref = check(gpu, oracle_mod, w)
+    assert 0.02 < ref["drop"].mean() < 0.98, ref["drop"].mean()
+    check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+    for max_snap in (None, FORCE_SORT):
+        ref = oracle_mod.run(w, threads=8, consistent=True)
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
+        s.run(consistent=True)
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (per, max_snap, k)
+
+
 @pytest.mark.parametrize("n", [0, 1, 2, 255, 4096, 4097, 8193, 12289, 70001])
 def test_sizes_sort_path(gpu, oracle_mod, n):
     w = wl.make_workload(3, n_requests=n, permute=True)
