@@ -43,6 +43,13 @@
  * force with exact rationals (tests/test_oracle_priority.py); the paper prints no value for it
  * and its algorithm listing is absent, so parity with the paper is unpinned for this function.
  *
+ * Ranked downstream positions (pard_oracle_estimate_drop_ranked): the snapshot form above lets a
+ * request join the back of every later queue; the paper's queues are kept in budget order
+ * (Section 3.3), so this variant counts, in a later queue, only the requests that order would
+ * serve before the newcomer.  A reading, not a formula of the paper: parity with the paper is
+ * unpinned; pinned by a brute force and by the cases in which it must equal the plain estimate
+ * or differ from it by a known amount (tests/test_oracle_ranked.py).
+ *
  * Monitored queueing delay (Section 3.2, State Planner, first item and its footnote: a sliding
  * window over the recent queueing delays, 5 s and linearly weighted by default):
  * pard_oracle_queue_delay() gives q_i per (snapshot, stage) from time-stamped delay samples,
@@ -224,7 +231,7 @@ static int estimate_drop_impl(
         const int32_t* row_ptr, const int32_t* col,
         const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
         int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
-        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub, int consistent,
+        const int32_t* snap_ptr, const int32_t* now, const int64_t* sub, int consistent, int ranked,
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     (void)n;
@@ -283,13 +290,29 @@ static int estimate_drop_impl(
          * Sequentially consistent: the Request Broker takes the requests of a queue in queue
          * order and a dropped request never takes a batch slot (Section 4.1, the broker's
          * drop-or-infer step), so the position is the number of requests ahead that were
-         * KEPT; each queue is then a chain of decisions, taken in order. */
+         * KEPT; each queue is then a chain of decisions, taken in order.
+         * Ranked: in a downstream queue the request does not join the back; it takes the place its
+         * budget gives it among the requests queued there now (the queue is kept in budget order,
+         * Section 3.3), so the requests ahead of it at stage i are those that queue's order puts
+         * before a newcomer with its deadline: deadline <= its own under low budget first (the
+         * ones already there win ties), deadline >= its own under high budget first, everybody
+         * in arrival order. */
         int64_t* kept = (int64_t*)calloc((size_t)S, sizeof(int64_t));
         #pragma omp parallel for schedule(static) num_threads(nthreads) if (!consistent)
         for (int64_t j = 0; j < m; ++j) {
             int32_t r = q[j].idx;
             int k = clamp_stage(stage[r], S);
             int64_t pos = consistent ? kept[k] : j - qstart[k];   /* requests ahead of r in its own queue */
+            int64_t ahead[64];                                    /* S <= 64: requests ahead of r in every other queue */
+            for (int i = 0; i < S; ++i) {
+                ahead[i] = qlen[i];
+                if (!ranked || M[i] == MODE_FCFS) continue;
+                ahead[i] = 0;
+                for (int64_t t = qstart[i]; t < qstart[i + 1]; ++t) {
+                    int32_t other = deadline[q[t].idx];
+                    if (M[i] == MODE_HBF ? other >= deadline[r] : other <= deadline[r]) ahead[i] += 1;
+                }
+            }
             wide_t best = -1;
             if (sub) {
                 /* Eq.(4): the Request Broker's own part plus the State Planner's L_sub */
@@ -303,7 +326,7 @@ static int estimate_drop_impl(
                 wide_t sum = stage_cost(L + (int64_t)k * LAT_ENTRIES, B[k], Wk[k], pos);
                 for (int32_t t = at + 1; t < b; ++t) {
                     int32_t i = ps.stage[t];
-                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);
+                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], ahead[i]);
                 }
                 if (sum > best) best = sum;
             }
@@ -335,7 +358,7 @@ int pard_oracle_estimate_drop(
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
-                              snap_ptr, now, NULL, 0, est, drop, order, seg_ptr, nthreads);
+                              snap_ptr, now, NULL, 0, 0, est, drop, order, seg_ptr, nthreads);
 }
 
 /* The same with the downstream part given: est = own-stage cost at the queue position
@@ -349,7 +372,7 @@ int pard_oracle_estimate_drop_sub(
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
-                              snap_ptr, now, sub, 0, est, drop, order, seg_ptr, nthreads);
+                              snap_ptr, now, sub, 0, 0, est, drop, order, seg_ptr, nthreads);
 }
 
 /* Sequentially consistent dropping: as above (sub may be NULL), but a request's position is
@@ -363,7 +386,23 @@ int pard_oracle_estimate_drop_consistent(
         int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
         int32_t nthreads) {
     return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
-                              snap_ptr, now, sub, 1, est, drop, order, seg_ptr, nthreads);
+                              snap_ptr, now, sub, 1, 0, est, drop, order, seg_ptr, nthreads);
+}
+
+/* Ranked downstream positions: as pard_oracle_estimate_drop, but in every later queue the request
+ * counts only the requests that queue's order would serve before it (see the comment in the
+ * implementation), not the whole queue. */
+int pard_oracle_estimate_drop_ranked(
+        int32_t K, int32_t S, int32_t dag_shared,
+        const int32_t* row_ptr, const int32_t* col,
+        const int32_t* batch, const int32_t* workers, const int32_t* lat, const int32_t* mode,
+        int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+        const int32_t* snap_ptr, const int32_t* now,
+        int32_t* est, uint8_t* drop, int32_t* order, int32_t* seg_ptr,
+        int32_t nthreads) {
+    if (S > 64) return 4;
+    return estimate_drop_impl(K, S, dag_shared, row_ptr, col, batch, workers, lat, mode, n, arrival, deadline, stage,
+                              snap_ptr, now, NULL, 0, 1, est, drop, order, seg_ptr, nthreads);
 }
 
 /*

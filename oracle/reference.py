@@ -43,6 +43,8 @@ def _load() -> ctypes.CDLL:
             _i32p, _i32p, _i32p, _i32p, _i32p, _i32p,
             ctypes.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p,
             _i32p, _u8p, _i32p, _i32p, ctypes.c_int32]
+        lib.pard_oracle_estimate_drop_ranked.restype = ctypes.c_int
+        lib.pard_oracle_estimate_drop_ranked.argtypes = lib.pard_oracle_estimate_drop.argtypes
         lib.pard_oracle_estimate_drop_sub.restype = ctypes.c_int
         lib.pard_oracle_estimate_drop_sub.argtypes = [
             ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -150,10 +152,12 @@ def priority_modes(K, S, dag_shared, batch, workers, lat_us, rate, window, prev_
 
 
 def estimate_drop(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us, order_mode,
-                  arrival, deadline, stage, snap_ptr, now, threads: int = 1, sub=None, consistent: bool = False):
+                  arrival, deadline, stage, snap_ptr, now, threads: int = 1, sub=None, consistent: bool = False,
+                  ranked: bool = False):
     """Returns (est int32[n], drop uint8[n], order int32[n], seg_ptr int32[K*S+1]).
     With `sub` (int64[K*S]) the downstream part of every estimate is taken from it.
-    `consistent`: positions count only the kept requests ahead (sequentially consistent dropping)."""
+    `consistent`: positions count only the kept requests ahead (sequentially consistent dropping).
+    `ranked`: in later queues a request counts only the requests their order serves before it."""
     lib = _load()
     rp, cl, B, W, L, M = map(_i32, (dag_row_ptr, dag_col, batch, workers, lat_us, order_mode))
     if cl.size == 0:
@@ -165,7 +169,13 @@ def estimate_drop(K, S, dag_shared, dag_row_ptr, dag_col, batch, workers, lat_us
     order = np.zeros(max(n, 1), np.int32)
     seg_ptr = np.zeros(K * S + 1, np.int32)
     pad = lambda a: a if a.size else np.zeros(1, np.int32)  # noqa: E731
-    if consistent:
+    if ranked:
+        assert sub is None and not consistent
+        rc = lib.pard_oracle_estimate_drop_ranked(
+            K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(M),
+            n, _p32(pad(arr)), _p32(pad(ddl)), _p32(pad(stg)), _p32(sp), _p32(pad(nw)),
+            _p32(est), drop.ctypes.data_as(_u8p), _p32(order), _p32(seg_ptr), int(threads))
+    elif consistent:
         sb = None if sub is None else np.ascontiguousarray(sub, dtype=np.int64)
         rc = lib.pard_oracle_estimate_drop_consistent(
             K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(W), _p32(L), _p32(M),
@@ -231,10 +241,11 @@ def stage_cost(lat64, B: int, W: int, a: int) -> int:
     return int(lib.pard_oracle_stage_cost(_p32(L), int(B), int(W), int(a)))
 
 
-def run(w, threads: int = 1, sub=None, consistent: bool = False):
+def run(w, threads: int = 1, sub=None, consistent: bool = False, ranked: bool = False):
     """Whole path on a workloads.Workload: dict of est, drop, order, seg_ptr, surv_idx, surv_ptr."""
     est, drop, order, seg_ptr = estimate_drop(
         w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, w.order_mode,
-        w.arrival, w.deadline, w.stage, w.snap_ptr, w.now, threads=threads, sub=sub, consistent=consistent)
+        w.arrival, w.deadline, w.stage, w.snap_ptr, w.now, threads=threads, sub=sub, consistent=consistent,
+        ranked=ranked)
     surv_idx, surv_ptr = compact(w.K, w.S, order, seg_ptr, drop)
     return dict(est=est, drop=drop, order=order, seg_ptr=seg_ptr, surv_idx=surv_idx, surv_ptr=surv_ptr)

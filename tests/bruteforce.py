@@ -21,9 +21,12 @@ def cost(lat, B, W, a):
     return wait + int(lat[min(B, a + 1) - 1])
 
 
-def brute(w, consistent=False):
+def brute(w, consistent=False, ranked=False):
     """est, drop, pos for every request of workload w (any K).  consistent: a request's position
-    counts only the requests ahead of it that were kept, decided one after the other in queue order."""
+    counts only the requests ahead of it that were kept, decided one after the other in queue order.
+    ranked: in a later queue the request is put where that queue's order puts a newcomer with its
+    deadline (behind the requests already there when keys tie, at the very back in arrival order),
+    and the requests ahead of it are the ones in front of that place."""
     n = w.n
     est = [0] * n
     drop = [0] * n
@@ -51,10 +54,22 @@ def brute(w, consistent=False):
                 return int(w.arrival[lo + i])
             return int(w.deadline[lo + i])
 
-        def downstream(s):           # worst total cost of everything after stage s
+        def place(t, i):             # requests in front of request i once it has joined the queue of stage t
+            if not ranked:
+                return qlen[t]
+            newcomer = hi - lo           # an index after everybody's: loses every tie
+            if M[t] == 2:
+                rows = [(int(w.arrival[lo + j]), j) for j in range(hi - lo) if stage[j] == t] + [(math.inf, newcomer)]
+            else:
+                sign = -1 if M[t] == 1 else 1
+                rows = [(sign * int(w.deadline[lo + j]), j) for j in range(hi - lo) if stage[j] == t]
+                rows.append((sign * int(w.deadline[lo + i]), newcomer))
+            return sorted(rows).index(rows[-1])
+
+        def downstream(s, i=None):   # worst total cost of everything after stage s (for request i when ranked)
             best = 0
             for t in succ[s]:
-                best = max(best, cost(L[t], int(B[t]), int(W[t]), qlen[t]) + downstream(t))
+                best = max(best, cost(L[t], int(B[t]), int(W[t]), place(t, i)) + downstream(t, i))
             return best
 
         if not consistent:
@@ -62,7 +77,7 @@ def brute(w, consistent=False):
                 k = stage[i]
                 ahead = sum(1 for j in range(hi - lo)
                             if stage[j] == k and (key(j), j) < (key(i), i))
-                e = cost(L[k], int(B[k]), int(W[k]), ahead) + downstream(k)
+                e = cost(L[k], int(B[k]), int(W[k]), ahead) + downstream(k, i)
                 pos[lo + i] = ahead
                 est[lo + i] = min(e, INT32_MAX)
                 finish = min(int(w.now[u]) + e, INT32_MAX)

@@ -11,6 +11,7 @@ import pytest
 from tests import test_oracle_consistent as pins_consistent
 from tests import test_oracle_pins as pins
 from tests import test_oracle_priority as pins_priority
+from tests import test_oracle_ranked as pins_ranked
 from tests import test_oracle_sub as pins_sub
 from tests import test_oracle_window as pins_window
 
@@ -30,10 +31,10 @@ MUTATIONS = [
     ("FCFS keyed by deadline", "else if (M[s] == MODE_FCFS) key = (int64_t)arrival[r];", "else if (M[s] == MODE_FCFS) key = (int64_t)deadline[r];", "core"),
     ("minimum over paths", "                if (sum > best) best = sum;\n            }\n            wide_t cap = (wide_t)INT32_MAX;",
      "                if (best < 0 || sum < best) best = sum;\n            }\n            wide_t cap = (wide_t)INT32_MAX;", "core"),
-    ("downstream stage at the request's own position", "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
+    ("downstream stage at the request's own position", "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], ahead[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
      "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], pos);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap", "core"),
-    ("current stage counted twice", "for (int32_t t = at + 1; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
-     "for (int32_t t = at; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap", "core"),
+    ("current stage counted twice", "for (int32_t t = at + 1; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], ahead[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap",
+     "for (int32_t t = at; t < b; ++t) {\n                    int32_t i = ps.stage[t];\n                    sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], ahead[i]);\n                }\n                if (sum > best) best = sum;\n            }\n            wide_t cap", "core"),
     ("now not added", "wide_t finish = (wide_t)now[u] + best;", "wide_t finish = best;", "core"),
     ("drop at equality", "drop[r] = (uint8_t)(finish > (wide_t)deadline[r]);", "drop[r] = (uint8_t)(finish >= (wide_t)deadline[r]);", "core"),
     ("compaction keeps the dropped", "if (!drop[r]) surv_idx[out++] = r;", "if (drop[r]) surv_idx[out++] = r;", "core"),
@@ -53,6 +54,13 @@ MUTATIONS = [
      "hi = W * B * 1000000 * sum;\n                lo = W * B * 1000000 * sum;", "priority"),
     ("throughput ignores the worker count", "hi = W * B * 1000000 * (sum + dev);", "hi = B * 1000000 * (sum + dev);", "priority"),
     ("previous priority ignored", "int32_t mode = prev_mode ? prev_mode[g] : MODE_LBF;", "int32_t mode = MODE_LBF;", "priority"),
+    ("ties in a later queue go to the newcomer", "if (M[i] == MODE_HBF ? other >= deadline[r] : other <= deadline[r]) ahead[i] += 1;",
+     "if (M[i] == MODE_HBF ? other > deadline[r] : other < deadline[r]) ahead[i] += 1;", "ranked"),
+    ("later high-budget-first queues ranked like low-budget-first ones", "if (M[i] == MODE_HBF ? other >= deadline[r] : other <= deadline[r]) ahead[i] += 1;",
+     "if (other <= deadline[r]) ahead[i] += 1;", "ranked"),
+    ("later arrival-order queues ranked by deadline", "if (!ranked || M[i] == MODE_FCFS) continue;", "if (!ranked) continue;", "ranked"),
+    ("ranked places ignored", "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], ahead[i]);",
+     "sum += stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], qlen[i]);", "ranked"),
     ("old samples weigh most", "wide_t w = window - age;", "wide_t w = age + 1;", "window"),
     ("plain mean inside the window", "wide_t w = window - age;", "wide_t w = 1;", "window"),
     ("samples later than now counted", "if (age < 0 || age >= window) continue;", "if (age >= window) continue;", "window"),
@@ -127,7 +135,15 @@ def window_pins(m):
     pins_window.test_monitored_delay_replaces_the_queue_term(m)
 
 
-GROUPS = {"core": core_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins,
+def ranked_pins(m):
+    pins_ranked.test_hand_worked_two_stages(m)
+    for seed in range(24):
+        pins_ranked.test_bruteforce_small_random(m, seed)
+    pins_ranked.test_equals_the_plain_estimate_when_it_must(m)
+    pins_ranked.test_never_above_the_plain_estimate_with_rising_tables(m)
+
+
+GROUPS = {"core": core_pins, "ranked": ranked_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins,
           "window": window_pins}
 
 
