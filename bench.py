@@ -261,7 +261,9 @@ def main():
     ap.add_argument("--permute", action="store_true", help="shuffle request order inside every snapshot")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--consistent", action="store_true",
-                    help="sequentially consistent dropping (positions count kept requests only; on-chip path only)")
+                    help="sequentially consistent dropping (positions count kept requests only)")
+    ap.add_argument("--ranked", action="store_true",
+                    help="ranked positions in the later queues (a request takes the place its budget gives it there)")
     ap.add_argument("--workload", choices=["hot-path", "planner", "priority", "queue-delay"], default="hot-path",
                     help="hot-path: estimate+drop+compact (default); planner: queue lengths + downstream latency "
                          "with the sampled batch-wait quantile on the same snapshots; priority: adaptive priority "
@@ -270,6 +272,9 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.ranked and args.consistent:
+        print("bench.py: --ranked and --consistent are separate variants", file=sys.stderr)
+        sys.exit(2)
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU only (snapshots would shard across GPUs with no "
               "communication); run with --gpus 1", file=sys.stderr)
@@ -310,7 +315,7 @@ def main():
         del src, dst
 
     for _ in range(max(args.warmup, 1)):
-        s.run(consistent=args.consistent)
+        s.run(consistent=args.consistent, ranked=args.ranked)
     torch.cuda.synchronize()
 
     # timed region: exactly --steps passes of the whole path
@@ -320,7 +325,7 @@ def main():
     t0 = time.perf_counter()
     for a, b, c in ev:
         a.record()
-        s.estimate_drop(consistent=args.consistent)
+        s.estimate_drop(consistent=args.consistent, ranked=args.ranked)
         b.record()
         s.compact()
         c.record()
@@ -347,7 +352,7 @@ def main():
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
     traffic = (recorded_traffic(args.config, "fused_snapshot_kernel", "pard_fused.hip")
-               if fused and not args.permute and not args.consistent else None)
+               if fused and not args.permute and not args.consistent and not args.ranked else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4)}
@@ -360,7 +365,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": w.name + ("+consistent" if args.consistent else ""), "requests": n, "snapshots": w.K,
+        "config": {"workload": w.name + ("+consistent" if args.consistent else "") + ("+ranked" if args.ranked else ""), "requests": n, "snapshots": w.K,
                    "stages": w.S, "path": "on-chip" if fused else "radix-sort", "radix_passes": passes,
                    "drop_fraction": round(drop_frac, 4), "status_word": status,
                    "estimate_drop_ms": round(est_ms, 4), "compact_ms": round(cmp_ms, 4),
@@ -374,9 +379,17 @@ def main():
         # the oracle finishes the whole workload in seconds, so the sample is the whole workload
         sub = w
         sample = f"whole workload ({n} requests), 1 run"
+        if args.ranked:
+            # the oracle counts the requests ahead in every later queue one by one (quadratic in the snapshot size)
+            if w.K > 1:
+                sub = workloads.make_workload(args.config, n_snapshots=min(w.K, 64), permute=args.permute)
+                sample = f"first {sub.K} of {w.K} snapshots ({sub.n} requests), 1 run"
+            else:
+                sub = workloads.make_workload(args.config, n_requests=min(n, 200_000), permute=args.permute)
+                sample = f"the same workload at {sub.n} requests, 1 run"
         oracle.build_oracle()
         t0 = time.perf_counter()
-        oracle.run(sub, threads=threads, consistent=args.consistent)
+        oracle.run(sub, threads=threads, consistent=args.consistent, ranked=args.ranked)
         cpu_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(sub.n / cpu_s, 1), "unit": "requests/s", "cores": threads,
                                "kind": "oracle", "sample": sample, "seconds": round(cpu_s, 3)}

@@ -286,6 +286,23 @@ int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t ma
                                   void* d_workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * Ranked downstream positions: pard_estimate_drop, except that in a later queue a request does
+ * not join the back but takes the place its budget gives it.  The queues are kept in
+ * remaining-budget order (Section 3.3), so at a later stage i the requests ahead of a newcomer
+ * with deadline d are those that order serves first - deadline <= d under PARD_ORDER_LBF (the
+ * requests already there win ties), deadline >= d under PARD_ORDER_HBF, the whole queue under
+ * PARD_ORDER_FCFS - and
+ *   est = cost_k(pos) + max over the paths through k of sum over later stages i of cost_i(ahead_i(d)).
+ * d_order and d_seg_ptr are the same as in pard_estimate_drop; d_est and d_drop differ.
+ * Arguments, workspace and errors as for pard_estimate_drop; both snapshot sizes are served.
+ */
+int pard_estimate_drop_ranked(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                              const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                              const int32_t* d_snap_ptr, const int32_t* d_now,
+                              int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                              void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Adaptive request priority with delayed transition (Section 3.3).  Per (snapshot u, stage s), from
  * the series d_rate[(u*S + s)*series_len + t] of the module's monitored input workload T_in
  * (requests per second, >= 0):

@@ -25,6 +25,7 @@ STATUS_NAMES = {
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
+           "pard_estimate_drop_ranked",
            "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
            "pard_sub_latency", "pard_sub_latency_q", "pard_queue_delay", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
@@ -59,6 +60,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_plan_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i32)]
     lib.pard_workspace_bytes.argtypes = [vp, i64, i64, ctypes.POINTER(i64)]
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
+    lib.pard_estimate_drop_ranked.argtypes = lib.pard_estimate_drop.argtypes
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
@@ -160,6 +162,18 @@ def pard_estimate_drop(plan: Plan, n: int, max_snapshot_requests: int, arrival, 
         _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_estimate_drop")
+    return rc
+
+
+def pard_estimate_drop_ranked(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now,
+                              est, drop, order, seg_ptr, workspace, stream=None, check: bool = True) -> int:
+    """pard_estimate_drop with ranked positions in the later queues."""
+    rc = load_library().pard_estimate_drop_ranked(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage),
+        _ptr(snap_ptr), _ptr(now), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop_ranked")
     return rc
 
 
@@ -282,8 +296,11 @@ class Session:
         self.workspace = torch.zeros(self.ws_bytes // 4 + 64, dtype=torch.int32, device=self.dev)
         assert self.workspace.data_ptr() % 256 == 0
 
-    def estimate_drop(self, stream=None, sub=None, consistent=False):
-        if consistent:
+    def estimate_drop(self, stream=None, sub=None, consistent=False, ranked=False):
+        if ranked:
+            pard_estimate_drop_ranked(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
+                                      self.now, self.est, self.drop, self.order, self.seg_ptr, self.workspace, stream)
+        elif consistent:
             pard_estimate_drop_consistent(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage,
                                           self.snap_ptr, self.now, sub, self.est, self.drop, self.order, self.seg_ptr,
                                           self.workspace, stream)
@@ -314,8 +331,8 @@ class Session:
         pard_compact(self.plan, self.n, self.max_snap, self.order, self.seg_ptr, self.drop, self.surv_idx, self.surv_ptr,
                      self.workspace, stream)
 
-    def run(self, stream=None, sub=None, consistent=False):
-        self.estimate_drop(stream, sub, consistent)
+    def run(self, stream=None, sub=None, consistent=False, ranked=False):
+        self.estimate_drop(stream, sub, consistent, ranked)
         self.compact(stream)
 
     def status_word(self) -> int:

@@ -217,6 +217,24 @@ int pard_estimate_drop_consistent(const pard_plan_t* plan, int64_t n, int64_t ma
                               d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
 }
 
+int pard_estimate_drop_ranked(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                              const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                              const int32_t* d_snap_ptr, const int32_t* d_now,
+                              int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                              void* d_workspace, int64_t workspace_bytes, void* stream) {
+    const int rc = estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr,
+                                      false, d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
+    if (rc != PARD_OK) return rc;
+    RankedArgs a{};
+    a.plan = plan->dev;
+    a.n = n;
+    a.deadline = d_deadline; a.now = d_now;
+    a.order = d_order; a.seg_ptr = d_seg_ptr;
+    a.est = d_est; a.drop = d_drop;
+    a.num_cus = plan->num_cus;
+    return launch_ranked(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PARD_OK : PARD_E_HIP;
+}
+
 int pard_queue_lengths(const pard_plan_t* plan, int64_t n, const int32_t* d_stage, const int32_t* d_snap_ptr,
                        int32_t* d_qlen, void* stream) {
     if (!plan || !d_snap_ptr || !d_qlen) return PARD_E_NULL;

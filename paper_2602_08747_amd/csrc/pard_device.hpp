@@ -138,6 +138,17 @@ int64_t sort_workspace_bytes(int32_t K, int32_t S, int64_t n);
 bool sort_supported(int32_t K, int32_t S, int64_t n, int64_t max_snapshot);
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream);
 
+struct RankedArgs {
+    PlanDev plan;
+    int64_t n;
+    const int32_t *deadline, *now;
+    const int32_t *order, *seg_ptr;    // the plain call's queues
+    int32_t* est;                      // rewritten
+    uint8_t* drop;
+    int32_t num_cus;
+};
+hipError_t launch_ranked(const RankedArgs& a, hipStream_t stream);
+
 struct CompactArgs {
     int32_t num_segments;              // K*S
     int32_t stages;                    // S

@@ -470,3 +470,71 @@ def test_monitored_delay_feeds_the_estimate(gpu, oracle_mod, max_snap):
             for k in KEYS:
                 assert np.array_equal(got[k], ref[k]), (w.name, variant, k)
             assert 0 < drop.mean() < 1, drop.mean()
+
+
+# ---- ranked positions in the later queues --------------------------------------------------------------
+
+def ranked_cases():
+    w = wl.make_workload(5, n_snapshots=6, per_snapshot=8192, permute=True)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 250000).astype(np.int32)
+    yield w
+    w = wl.make_workload(5, n_snapshots=7, per_snapshot=3000, permute=True, order_mode=None)
+    w.order_mode[:] = np.arange(w.order_mode.size) % 3
+    w.deadline[::5] = w.deadline[1::5][: w.deadline[::5].size]                     # ties across queues
+    yield w
+    yield wl.make_workload(1)
+    for seed in range(6):
+        yield wl.random_workload(900 + seed, K=1 + seed, S=1 + (seed * 5) % 9, n_per_snapshot=150 + 211 * seed,
+                                 monotone=(seed % 2 == 0), tie_heavy=(seed % 3 == 1), dag_shared=seed % 2)
+    yield wl.make_workload(4, n_requests=20_001, permute=True)                      # 12 stages, 16 paths, high budget first
+    w = wl.make_workload(3, n_requests=15_000)                                      # arrival order, three SLOs
+    w.now[:] = int(np.median(w.arrival))
+    yield w
+    w = wl.make_workload(2, n_requests=9000, permute=True)                          # extreme values
+    w.deadline[::7] = 2**31 - 1
+    w.deadline[3::11] = -2**31
+    w.workers[:] = [1 << 20, 1, 3, 1, 999]
+    yield w
+
+
+def test_ranked_positions(gpu, oracle_mod):
+    differs = 0
+    for w in ranked_cases():
+        print("case", w.name, w.n, w.K, w.S, flush=True)
+        ref = oracle_mod.run(w, threads=8, ranked=True)
+        for max_snap in (None, FORCE_SORT):
+            s = gpu.Session(w, max_snapshot_requests=None if max_snap is None else max(max_snap, w.max_snapshot_requests))
+            s.run(ranked=True)
+            got = s.results()
+            for k in KEYS:
+                assert np.array_equal(got[k], ref[k]), (w.name, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
+            assert s.status_word() == 0
+        differs += int(not np.array_equal(oracle_mod.run(w, threads=8)["drop"], ref["drop"]))
+    assert differs >= 6                      # the variant really decides differently on most of them
+
+
+def test_ranked_many_stages_and_errors(gpu, oracle_mod):
+    S, K = 64, 3
+    rng = np.random.default_rng(77)
+    rp, col = wl.csr_from_edges(S, wl.chain_edges(S) + [(5, 30), (12, 63)])
+    sizes = rng.integers(500, 2500, size=K)
+    snap_ptr = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(snap_ptr[-1])
+    arrival = rng.integers(0, 200_000, n).astype(np.int32)
+    w = wl.Workload(name="chain64-ranked", K=K, S=S, dag_shared=1, dag_row_ptr=rp, dag_col=col,
+                    batch=rng.integers(1, 65, S).astype(np.int32), workers=rng.integers(1, 9, S).astype(np.int32),
+                    lat_us=np.ascontiguousarray(wl.monotone_tables(rng, S).reshape(-1) // 20, np.int32),
+                    order_mode=rng.integers(0, 3, S).astype(np.int32), arrival=arrival,
+                    deadline=(arrival + rng.choice([100_000, 900_000, 4_000_000], n)).astype(np.int32),
+                    stage=rng.integers(0, S, n).astype(np.int32), snap_ptr=snap_ptr, now=np.full(K, 150_000, np.int32))
+    ref = oracle_mod.run(w, threads=8, ranked=True)
+    for max_snap in (None, FORCE_SORT):
+        s = gpu.Session(w, max_snapshot_requests=max_snap)
+        s.run(ranked=True)
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (max_snap, k)
+    assert gpu.pard_estimate_drop_ranked(s.plan, -1, s.max_snap, s.arrival, s.deadline, s.stage, s.snap_ptr, s.now, s.est, s.drop,
+                                         s.order, s.seg_ptr, s.workspace, check=False) == -2
+    assert gpu.pard_estimate_drop_ranked(s.plan, s.n, s.max_snap, s.arrival, None, s.stage, s.snap_ptr, s.now, s.est, s.drop,
+                                         s.order, s.seg_ptr, s.workspace, check=False) == -1
