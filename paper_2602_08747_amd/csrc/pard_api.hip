@@ -231,6 +231,7 @@ int pard_estimate_drop_ranked(const pard_plan_t* plan, int64_t n, int64_t max_sn
     a.deadline = d_deadline; a.now = d_now;
     a.order = d_order; a.seg_ptr = d_seg_ptr;
     a.est = d_est; a.drop = d_drop;
+    a.max_snapshot = max_snapshot_requests;
     a.num_cus = plan->num_cus;
     return launch_ranked(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PARD_OK : PARD_E_HIP;
 }

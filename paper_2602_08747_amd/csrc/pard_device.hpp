@@ -145,6 +145,7 @@ struct RankedArgs {
     const int32_t *order, *seg_ptr;    // the plain call's queues
     int32_t* est;                      // rewritten
     uint8_t* drop;
+    int64_t max_snapshot;              // promised bound on a snapshot's size
     int32_t num_cus;
 };
 hipError_t launch_ranked(const RankedArgs& a, hipStream_t stream);
