@@ -1,5 +1,5 @@
 """Randomised differential test: many small random plans and snapshots through every variant of the
-estimate (plain, given downstream latency, sequentially consistent) on both kernel paths, C-ABI vs the
+estimate (plain, given downstream latency, sequentially consistent, ranked) on both kernel paths, C-ABI vs the
 CPU oracle, bit for bit."""
 import numpy as np
 import pytest
@@ -48,12 +48,15 @@ def test_random_case(gpu, oracle_mod, seed):
     import torch
     w, sub = draw_case(seed)
     print("case", seed, w.name, "n", w.n, "K", w.K, "S", w.S, "sub", sub is not None, flush=True)
-    for consistent in (False, True):
-        ref = oracle_mod.run(w, threads=8, sub=sub, consistent=consistent)
+    for variant in ("plain", "consistent", "ranked"):
+        if variant == "ranked" and sub is not None:
+            continue                                   # the ranked variant computes the downstream part itself
+        consistent, ranked = variant == "consistent", variant == "ranked"
+        ref = oracle_mod.run(w, threads=8, sub=sub, consistent=consistent, ranked=ranked)
         for max_snap in (None, FORCE_SORT):
             s = gpu.Session(w, max_snapshot_requests=None if max_snap is None else max(max_snap, w.max_snapshot_requests))
-            s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=consistent)
+            s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=consistent, ranked=ranked)
             got = s.results()
             for k in KEYS:
-                assert np.array_equal(got[k], ref[k]), (seed, consistent, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
+                assert np.array_equal(got[k], ref[k]), (seed, variant, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
             assert s.status_word() == 0
