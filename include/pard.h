@@ -30,8 +30,10 @@
  *     valid until the work queued on `stream` has completed.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The two
  *     hot calls only enqueue kernels: they do not allocate, free or synchronise.
- *   - A plan is immutable after creation and may be used from several streams at
- *     once, provided each concurrent call has its own workspace.
+ *   - A plan changes only through pard_plan_set_modes.  It may be used from several
+ *     streams at once, provided each concurrent call has its own workspace; the one
+ *     exception is the sampled variant of pard_sub_latency, which stages its draws in
+ *     scratch memory the plan owns (see there).
  */
 #ifndef PARD_H_
 #define PARD_H_
@@ -133,9 +135,12 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
  *
  *   n                      total requests, 0 <= n < 2^30
  *   max_snapshot_requests  caller's upper bound on snap_ptr[u+1]-snap_ptr[u]; selects the
- *                          on-chip path when <= PARD_FUSED_SNAPSHOT_CAPACITY.  A snapshot
- *                          larger than the promised bound is truncated to the bound
- *                          (memory safe, results for that snapshot unspecified).
+ *                          on-chip path when <= PARD_FUSED_SNAPSHOT_CAPACITY, and there the
+ *                          size of the workgroup that takes a snapshot (a tight bound is
+ *                          faster: 512, 1024, 2048, 4096, 8192 are the steps).  A snapshot
+ *                          larger than the promised bound is truncated to the bound and
+ *                          raises bit 0 of the status word (memory safe, results for that
+ *                          snapshot unspecified).
  *   d_arrival, d_deadline, d_stage   device int32[n], request order.  d_arrival may be
  *                          NULL when no stage of the plan uses PARD_ORDER_FCFS.
  *   d_snap_ptr             device int32[K+1], non-decreasing, snap_ptr[0]=0, snap_ptr[K]=n;
@@ -164,9 +169,11 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
  *   max_snapshot_requests  promised upper bound on the requests of one snapshot, as for
  *                          pard_estimate_drop: up to PARD_FUSED_SNAPSHOT_CAPACITY every
  *                          snapshot is compacted by one workgroup, above it the queues are
- *                          compacted as one stream.  A snapshot that breaks a promised
- *                          bound of at most PARD_FUSED_SNAPSHOT_CAPACITY raises bit 0 of the
- *                          status word; the outputs are then unspecified (never out of bounds)
+ *                          compacted as one stream.  A snapshot larger than the workgroup
+ *                          chosen for a promised bound of at most PARD_FUSED_SNAPSHOT_CAPACITY
+ *                          can hold (the bound rounded up to 1024, 2048, 4096 or 8192) raises
+ *                          bit 0 of the status word; the outputs are then unspecified (never
+ *                          out of bounds)
  *   d_order, d_seg_ptr     as written by pard_estimate_drop
  *   d_drop                 device uint8[n], request order; zero = keep, anything else = drop
  *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests
