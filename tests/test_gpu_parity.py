@@ -315,6 +315,38 @@ def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw, max_snap):
         assert (sb[:off_idx] == -7).all() and (sb[off_idx + want_ptr[-1]:] == -7).all()   # nothing written outside
 
 
+@pytest.mark.parametrize("case", ["on-chip", "sorted", "sorted-consistent", "on-chip-ranked"])
+def test_graph_capture_and_replay(gpu, oracle_mod, case):
+    """The hot calls only enqueue kernels (no allocation, no synchronisation, no memset nodes), so they can be
+    recorded into a HIP graph.  Every replay, with different inputs in the same buffers and eager work in
+    between, must match the oracle."""
+    import torch
+    if case.startswith("on-chip"):
+        w = wl.make_workload(5, n_snapshots=12, per_snapshot=6000, permute=True)
+    else:
+        w = wl.make_workload(3, n_requests=120_000, permute=True)
+    consistent, ranked = case.endswith("consistent"), case.endswith("ranked")
+    s = gpu.Session(w)
+    s.run(consistent=consistent, ranked=ranked)                 # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s.run(consistent=consistent, ranked=ranked)
+    base_now = w.now.copy()
+    for shift in (0, -150_000, -400_000, 0):
+        w.now[:] = np.maximum(-2**31, base_now.astype(np.int64) + shift).astype(np.int32)
+        s.now.copy_(torch.from_numpy(w.now).to(s.dev))
+        s.est.zero_(); s.drop.zero_(); s.order.zero_(); s.surv_idx.zero_()      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = s.results()
+        ref = oracle_mod.run(w, threads=8, consistent=consistent, ranked=ranked)
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (case, shift, k)
+        assert s.status_word() == 0
+
+
 def test_repeatable_and_stream(gpu, oracle_mod):
     import torch
     w = wl.make_workload(4, n_requests=300000, permute=True)
