@@ -488,19 +488,25 @@ __global__ __launch_bounds__(THREADS, 4) void compact_local_kernel(CompactArgs A
     // neither its slots nor its drop bytes are read
     const int load_size = kept[u] == 0 ? 0 : size;
 
-    // this snapshot's slots: wave w owns [w*1024, (w+1)*1024), load k covers 256 of them, 4 per lane
-    const int32_t* slots = A.order + a;
+    // this snapshot's slots: wave w owns [w*1024, (w+1)*1024), load k covers 256 of them, 4 per lane.
+    // Slot q of the snapshot is element q + off of that layout, off = a mod 4 when order[] allows 16-byte
+    // loads, so that a lane's four slots sit on a 16-byte boundary whatever the snapshot's first slot is
+    // (the off elements before the snapshot are masked out).
+    const int shift = (int)(a & 3);
+    const int off = ((reinterpret_cast<uintptr_t>(A.order) & 15) == 0 && size + shift <= kLThreads * 16) ? shift : 0;
+    const int32_t* slots = A.order + a - off;
     const bool vec = (reinterpret_cast<uintptr_t>(slots) & 15) == 0;
     int32_t ids[4][4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int e = wave * 1024 + k * 256 + lane * 4;
-        if (vec && e + 3 < load_size) {
+        if (vec && e + 3 < load_size + off) {
             const int4 v = *reinterpret_cast<const int4*>(slots + e);
-            ids[k][0] = v.x; ids[k][1] = v.y; ids[k][2] = v.z; ids[k][3] = v.w;
+            ids[k][0] = e + 0 >= off ? v.x : -1; ids[k][1] = e + 1 >= off ? v.y : -1;
+            ids[k][2] = e + 2 >= off ? v.z : -1; ids[k][3] = v.w;
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) ids[k][c] = e + c < load_size ? slots[e + c] : -1;
+            for (int c = 0; c < 4; ++c) ids[k][c] = (e + c >= off && e + c < load_size + off) ? slots[e + c] : -1;
         }
     }
     // its slice of drop[]: 16-byte chunks at 16-byte aligned addresses from just below drop[a]
@@ -612,8 +618,9 @@ __global__ __launch_bounds__(THREADS, 4) void compact_local_kernel(CompactArgs A
         const int64_t p = slot < 0 ? 0 : slot;
         uint32_t before = total;
         if (p < size) {
-            const uint32_t v = L.group[p >> 2];
-            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
+            const int64_t ps = p + off;                  // the slot's place in the shifted layout
+            const uint32_t v = L.group[ps >> 2];
+            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (ps & 3)) - 1u));
         }
         A.surv_ptr[u * A.stages + q] = (int32_t)(off0 + before);
     }

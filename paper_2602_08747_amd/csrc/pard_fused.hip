@@ -59,7 +59,7 @@ constexpr int log2_of(int x) { return x <= 1 ? 0 : 1 + log2_of(x / 2); }
 // start, so no per-request bounds test is needed.
 template <int T, int CAP, bool FULL, bool CONSISTENT>
 __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CAP>& L, const int u, const int64_t lo,
-                                              const int m, const bool aligned) {
+                                              const int m, const bool aligned, const int off) {
     constexpr int kCap = CAP;
     constexpr int kIdxBits = log2_of(CAP);                 // bits of a local index
     constexpr int kCntWords = SnapshotLds<CAP>::kCntWords;
@@ -77,7 +77,14 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     const int S = P.S;
     const int dag = P.shared ? 0 : u;
     const int32_t* lat_dag = P.lat + (int64_t)dag * S * PARD_LAT_ENTRIES;
-    auto live = [&](int idx) { return FULL || idx < m; };
+    // Local indices: request lo + i has local index i + off, where off = lo mod 4 when the arrays allow
+    // 16-byte accesses (0 otherwise).  A thread's groups of four then sit on 16-byte boundaries of the
+    // request arrays whatever the snapshot's first request is; the `off` slots before the snapshot
+    // and the ones behind its end are simply not live.
+    const int64_t lo_s = lo - off;
+    const int m_s = m + off;
+    auto live = [&](int idx) { return FULL || (idx >= off && idx < m_s); };
+    auto whole = [&](int base) { return FULL || (aligned && base >= off && base + 3 < m_s); };   // four live requests, 16-byte access
     uint32_t* aux = reinterpret_cast<uint32_t*>(L.idx);           // kAuxWords words
     const int e_lo = P.dag_entry_ptr[dag], n_entries = P.dag_entry_ptr[dag + 1] - e_lo;
     const bool entries_cached = S * PARD_LAT_ENTRIES + n_entries <= kAuxWords;
@@ -88,17 +95,17 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
-        if (FULL || (aligned && base + 3 < m)) {
-            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo + base);
-            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + lo + base);
+        if (FULL || (aligned && base < m_s && lo_s + base + 3 < A.n)) {      // neighbours' values may ride along: they are not live
+            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo_s + base);
+            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + lo_s + base);
             dl[g][0] = d4.x; dl[g][1] = d4.y; dl[g][2] = d4.z; dl[g][3] = d4.w;
             st[g][0] = s4.x; st[g][1] = s4.y; st[g][2] = s4.z; st[g][3] = s4.w;
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const bool ok = base + c < m;
-                dl[g][c] = ok ? A.deadline[lo + base + c] : 0;
-                st[g][c] = ok ? A.stage[lo + base + c] : 0;
+                const bool ok = live(base + c);
+                dl[g][c] = ok ? A.deadline[lo_s + base + c] : 0;
+                st[g][c] = ok ? A.stage[lo_s + base + c] : 0;
             }
         }
     }
@@ -135,7 +142,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
             else {
                 const int mode = P.uniform_mode >= 0 ? P.uniform_mode : (L.recs[s].mode & 0xFF);
                 int32_t arr = 0;
-                if (mode == PARD_ORDER_FCFS && ok) arr = A.arrival[lo + base + c];
+                if (mode == PARD_ORDER_FCFS && ok) arr = A.arrival[lo_s + base + c];
                 k = order_key(mode, dl[g][c], arr);
             }
             uk[g][c] = k;
@@ -386,14 +393,14 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
                 est[c] = (int32_t)(v & 0x7FFFFFFFu);
                 drp[c] = (uint8_t)(v >> 31);
             }
-            if (FULL || (aligned && base + 3 < m)) {
-                *reinterpret_cast<int4*>(A.est + lo + base) = make_int4(est[0], est[1], est[2], est[3]);
-                *reinterpret_cast<uint32_t*>(A.drop + lo + base) =
+            if (whole(base)) {
+                *reinterpret_cast<int4*>(A.est + lo_s + base) = make_int4(est[0], est[1], est[2], est[3]);
+                *reinterpret_cast<uint32_t*>(A.drop + lo_s + base) =
                     (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
-                    if (base + c < m) { A.est[lo + base + c] = est[c]; A.drop[lo + base + c] = drp[c]; }
+                    if (live(base + c)) { A.est[lo_s + base + c] = est[c]; A.drop[lo_s + base + c] = drp[c]; }
             }
         }
     }
@@ -435,14 +442,14 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
                 }
             }
         }
-        if (FULL || (aligned && base + 3 < m)) {
-            *reinterpret_cast<int4*>(A.est + lo + base) = make_int4(est[0], est[1], est[2], est[3]);
-            *reinterpret_cast<uint32_t*>(A.drop + lo + base) =
+        if (whole(base)) {
+            *reinterpret_cast<int4*>(A.est + lo_s + base) = make_int4(est[0], est[1], est[2], est[3]);
+            *reinterpret_cast<uint32_t*>(A.drop + lo_s + base) =
                 (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (base + c < m) { A.est[lo + base + c] = est[c]; A.drop[lo + base + c] = drp[c]; }
+                if (live(base + c)) { A.est[lo_s + base + c] = est[c]; A.drop[lo_s + base + c] = drp[c]; }
         }
     }
     __syncthreads();
@@ -451,16 +458,24 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const int base = (g * T + tid) * 4;
-        if (FULL || (aligned && base + 3 < m)) {
-            const uint2 o = *reinterpret_cast<const uint2*>(ord_l + base);
-            const int32_t b32 = (int32_t)lo;
-            *reinterpret_cast<int4*>(A.order + lo + base) =
-                make_int4(b32 + (int32_t)(o.x & 0xFFFFu), b32 + (int32_t)(o.x >> 16),
-                          b32 + (int32_t)(o.y & 0xFFFFu), b32 + (int32_t)(o.y >> 16));
+        // queue slot q sits at order[lo + q] = order[lo_s + (q + off)]: the same shifted groups of four;
+        // its entry is the request with local index ord_l[q], i.e. request lo_s + ord_l[q]
+        const int32_t b32 = (int32_t)lo_s;
+        if (whole(base)) {
+            int32_t r4[4];
+            if (off == 0) {
+                const uint2 o = *reinterpret_cast<const uint2*>(ord_l + base);
+                r4[0] = (int32_t)(o.x & 0xFFFFu); r4[1] = (int32_t)(o.x >> 16);
+                r4[2] = (int32_t)(o.y & 0xFFFFu); r4[3] = (int32_t)(o.y >> 16);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) r4[c] = (int32_t)ord_l[base - off + c];
+            }
+            *reinterpret_cast<int4*>(A.order + lo_s + base) = make_int4(b32 + r4[0], b32 + r4[1], b32 + r4[2], b32 + r4[3]);
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (base + c < m) A.order[lo + base + c] = (int32_t)lo + (int32_t)ord_l[base + c];
+                if (live(base + c)) A.order[lo_s + base + c] = b32 + (int32_t)ord_l[base - off + c];
         }
     }
     if (tid < S) A.seg_ptr[(int64_t)u * S + tid] = (int32_t)lo + L.seg_start[tid];
@@ -489,9 +504,13 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     const uintptr_t bits = reinterpret_cast<uintptr_t>(A.deadline) | reinterpret_cast<uintptr_t>(A.stage) |
                            reinterpret_cast<uintptr_t>(A.est) | reinterpret_cast<uintptr_t>(A.order) |
                            (reinterpret_cast<uintptr_t>(A.drop) << 2);
-    const bool aligned = (lo & 3) == 0 && (bits & 15) == 0;
-    if (m == kCap && aligned) snapshot_body<T, CAP, true, CONSISTENT>(A, L, u, lo, m, true);
-    else snapshot_body<T, CAP, false, CONSISTENT>(A, L, u, lo, m, aligned);
+    // 16-byte accesses need aligned arrays; the snapshot's own start is taken care of by shifting the
+    // local indices by lo mod 4, as long as the shifted snapshot still fits the capacity
+    const int shift = (int)(lo & 3);
+    const bool aligned = (bits & 15) == 0 && m + shift <= kCap;
+    const int off = aligned ? shift : 0;
+    if (m == kCap && aligned && off == 0) snapshot_body<T, CAP, true, CONSISTENT>(A, L, u, lo, m, true, 0);
+    else snapshot_body<T, CAP, false, CONSISTENT>(A, L, u, lo, m, aligned, off);
 }
 
 template <int CAP, int T>
