@@ -33,21 +33,27 @@ namespace {
 // Capacity CAP (a power of two, at most PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (at least one wave): a
 // workgroup sized for 8192 requests spends most of its time on fixed costs when a snapshot holds a
 // few hundred, so smaller snapshots get smaller workgroups (and more of them per compute unit).
-constexpr int kAuxMin = PARD_MAX_STAGES * PARD_LAT_ENTRIES + 256;   // words: every stage's latency table + path entries
+//
+// SCAP is the number of stages the per-stage arrays and the latency-table cache are sized for.  Sized
+// for PARD_MAX_STAGES they cost about 24 KB per workgroup, more than everything else a small
+// capacity needs, and that alone would hold a compute unit to a few one-wave workgroups; pipelines
+// of at most kFewStages stages (the usual case) therefore get a variant that carries a tenth of that.
+constexpr int kFewStages = 8;
 
-template <int CAP>
+template <int CAP, int SCAP>
 struct SnapshotLds {
     static constexpr int kCntWords = CAP * 3 / 4;    // 1.5 * CAP 16-bit counters, two per LDS word
+    static constexpr int kAuxMin = SCAP * PARD_LAT_ENTRIES + 256;   // words: every stage's latency table + path entries
     static constexpr int kAuxWords = CAP / 2 > kAuxMin ? CAP / 2 : kAuxMin;
     __align__(16) uint32_t cnt32[kCntWords + 4];     // bucket counters, then bucket starts; later the queue order
     __align__(16) uint32_t low[CAP + 4];             // per queue slot: low bits of key.index (or the whole key)
     __align__(16) uint16_t idx[2 * kAuxWords];       // per queue slot: local index (wide keys only); otherwise
                                                      // a cache: latency tables, then path entries
-    StageRec recs[PARD_MAX_STAGES];
-    unsigned long long cfull[PARD_MAX_STAGES];
-    unsigned long long down[PARD_MAX_STAGES];
-    int32_t seg_start[PARD_MAX_STAGES + 1];
-    __align__(16) uint32_t quick[PARD_MAX_STAGES][8];   // per stage: B-1, 1/B, 1/W, aW, bW, queue start (short-queue form)
+    StageRec recs[SCAP];
+    unsigned long long cfull[SCAP];
+    unsigned long long down[SCAP];
+    int32_t seg_start[SCAP + 1];
+    __align__(16) uint32_t quick[SCAP][8];   // per stage: B-1, 1/B, 1/W, aW, bW, queue start (short-queue form)
     uint32_t slow_stages;                            // set when some stage cannot use the short-queue form
     uint32_t wave_tot[16];
     uint32_t red[2];
@@ -57,14 +63,14 @@ constexpr int log2_of(int x) { return x <= 1 ? 0 : 1 + log2_of(x / 2); }
 
 // FULL: the snapshot holds exactly kCap requests and every array is 16-byte aligned at its
 // start, so no per-request bounds test is needed.
-template <int T, int CAP, bool FULL, bool CONSISTENT>
-__device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CAP>& L, const int u, const int64_t lo,
+template <int T, int CAP, int SCAP, bool FULL, bool CONSISTENT>
+__device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CAP, SCAP>& L, const int u, const int64_t lo,
                                               const int m, const bool aligned, const int off) {
     constexpr int kCap = CAP;
     constexpr int kIdxBits = log2_of(CAP);                 // bits of a local index
-    constexpr int kCntWords = SnapshotLds<CAP>::kCntWords;
+    constexpr int kCntWords = SnapshotLds<CAP, SCAP>::kCntWords;
     constexpr int kBuckets = 2 * kCntWords;                // 16-bit counters
-    constexpr int kAuxWords = SnapshotLds<CAP>::kAuxWords;
+    constexpr int kAuxWords = SnapshotLds<CAP, SCAP>::kAuxWords;
     constexpr int G = kCap / (4 * T);       // groups of 4 consecutive requests per thread
     constexpr int CW = kCntWords / T;       // counter words scanned per thread
     static_assert(kCap == (1 << kIdxBits) && kCap <= PARD_FUSED_SNAPSHOT_CAPACITY, "capacity");
@@ -115,7 +121,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         const uint32_t* src = reinterpret_cast<const uint32_t*>(P.recs + (int64_t)dag * S);
         uint32_t* dst = reinterpret_cast<uint32_t*>(L.recs);
         for (int i = tid; i < S * (int)(sizeof(StageRec) / 4); i += T) dst[i] = src[i];
-        if (tid < PARD_MAX_STAGES) L.down[tid] = 0;
+        for (int i = tid; i < SCAP; i += T) L.down[i] = 0;
         if (tid == 0) { L.red[0] = 0xFFFFFFFFu; L.red[1] = 0u; L.slow_stages = 0u; }
         // cache in the (so far unused) index array: the DAG's latency tables and path entries
         for (int i = tid; i < S * PARD_LAT_ENTRIES; i += T) aux[i] = (uint32_t)lat_dag[i];
@@ -482,10 +488,10 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
 }
 
-template <int T, int CAP, bool CONSISTENT>
+template <int T, int CAP, int SCAP, bool CONSISTENT>
 __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     constexpr int kCap = CAP;
-    __shared__ SnapshotLds<CAP> L;
+    __shared__ SnapshotLds<CAP, SCAP> L;
     const int u = blockIdx.x;
     const int64_t n = A.n;
     // snapshot bounds, made safe whatever snap_ptr holds
@@ -509,14 +515,23 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     const int shift = (int)(lo & 3);
     const bool aligned = (bits & 15) == 0 && m + shift <= kCap;
     const int off = aligned ? shift : 0;
-    if (m == kCap && aligned && off == 0) snapshot_body<T, CAP, true, CONSISTENT>(A, L, u, lo, m, true, 0);
-    else snapshot_body<T, CAP, false, CONSISTENT>(A, L, u, lo, m, aligned, off);
+    if (m == kCap && aligned && off == 0) snapshot_body<T, CAP, SCAP, true, CONSISTENT>(A, L, u, lo, m, true, 0);
+    else snapshot_body<T, CAP, SCAP, false, CONSISTENT>(A, L, u, lo, m, aligned, off);
+}
+
+template <int CAP, int T, int SCAP>
+void launch_stages(const FusedArgs& a, hipStream_t stream) {
+    if (a.consistent) fused_snapshot_kernel<T, CAP, SCAP, true><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    else fused_snapshot_kernel<T, CAP, SCAP, false><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
 }
 
 template <int CAP, int T>
 void launch_capacity(const FusedArgs& a, hipStream_t stream) {
-    if (a.consistent) fused_snapshot_kernel<T, CAP, true><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
-    else fused_snapshot_kernel<T, CAP, false><<<dim3((unsigned)a.plan.K), dim3(T), 0, stream>>>(a);
+    // at the full capacity the request arrays dominate the LDS and two workgroups fit either way
+    if constexpr (CAP < PARD_FUSED_SNAPSHOT_CAPACITY) {
+        if (a.plan.S <= kFewStages) return launch_stages<CAP, T, kFewStages>(a, stream);
+    }
+    launch_stages<CAP, T, PARD_MAX_STAGES>(a, stream);
 }
 
 }  // namespace

@@ -110,18 +110,20 @@ def test_every_workgroup_capacity(gpu, oracle_mod, cap):
         check(gpu, oracle_mod, w)
         if cap < 8192:
             check(gpu, oracle_mod, w, max_snap=2 * cap)
-    w = wl.random_workload(600 + cap, K=9, S=7, n_per_snapshot=cap // 2, dag_shared=0)     # ragged sizes up to cap
-    assert w.max_snapshot_requests <= cap
-    check(gpu, oracle_mod, w, max_snap=cap)
-    ref = oracle_mod.run(w, threads=8, consistent=True)
-    s = gpu.Session(w, max_snapshot_requests=cap)
-    s.run(consistent=True)
-    got = s.results()
-    for k in KEYS:
-        assert np.array_equal(got[k], ref[k]), (cap, k)
+    # ragged sizes up to cap; each capacity has a variant for pipelines of at most 8 stages and one for more
+    for S in (7, 8, 9, 13):
+        w = wl.random_workload(600 + cap + S, K=9, S=S, n_per_snapshot=cap // 2, dag_shared=0)
+        assert w.max_snapshot_requests <= cap
+        check(gpu, oracle_mod, w, max_snap=cap)
+        ref = oracle_mod.run(w, threads=8, consistent=True)
+        s = gpu.Session(w, max_snapshot_requests=cap)
+        s.run(consistent=True)
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (cap, S, k)
 
 
-@pytest.mark.parametrize("per", [40, 700, 3000, 8000])
+@pytest.mark.parametrize("per", [40, 700, 1500, 3000, 8000])
 def test_sixty_four_stages(gpu, oracle_mod, per):
     """The largest stage count: a chain of 64 stages plus a few shortcuts, every workgroup capacity, both paths."""
     S, K = 64, 4
