@@ -167,13 +167,13 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
  * the Request Broker keeps or drops each request; kept requests form the next batches).
  *
  *   max_snapshot_requests  promised upper bound on the requests of one snapshot, as for
- *                          pard_estimate_drop: up to PARD_FUSED_SNAPSHOT_CAPACITY every
- *                          snapshot is compacted by one workgroup, above it the queues are
- *                          compacted as one stream.  A snapshot larger than the workgroup
- *                          chosen for a promised bound of at most PARD_FUSED_SNAPSHOT_CAPACITY
- *                          can hold (the bound rounded up to 1024, 2048, 4096 or 8192) raises
- *                          bit 0 of the status word; the outputs are then unspecified (never
- *                          out of bounds)
+ *                          pard_estimate_drop: from 2049 to PARD_FUSED_SNAPSHOT_CAPACITY every
+ *                          snapshot is compacted by one workgroup, below and above that the
+ *                          queues are compacted as one stream (where the bound plays no
+ *                          further role).  A snapshot larger than the workgroup chosen for
+ *                          such a bound can hold (the bound rounded up to 4096 or 8192)
+ *                          raises bit 0 of the status word; the outputs are then unspecified
+ *                          (never out of bounds)
  *   d_order, d_seg_ptr     as written by pard_estimate_drop
  *   d_drop                 device uint8[n], request order; zero = keep, anything else = drop
  *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests
