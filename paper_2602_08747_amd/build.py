@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libpard.so")
-SOURCES = ["pard_api.hip", "pard_fused.hip", "pard_sort.hip", "pard_compact.hip", "pard_planner.hip", "pard_ranked.hip"]
+SOURCES = ["pard_api.hip", "pard_fused.hip", "pard_sort.hip", "pard_compact.hip", "pard_planner.hip", "pard_ranked.hip", "pard_wave.hip"]
 HEADERS = ["pard_host.hpp", "pard_device.hpp"]
 
 

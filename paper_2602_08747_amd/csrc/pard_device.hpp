@@ -119,6 +119,9 @@ struct FusedArgs {
     int64_t n;                         // total requests (bounds every index derived from snap_ptr)
 };
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream);
+// Snapshots of at most 128 requests, one wave each (launch_fused hands these over itself).
+bool wave_path_covers(const FusedArgs& a);
+hipError_t launch_wave(const FusedArgs& a, hipStream_t stream);
 
 struct SortArgs {
     PlanDev plan;

@@ -537,6 +537,7 @@ void launch_capacity(const FusedArgs& a, hipStream_t stream) {
 }  // namespace
 
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
+    if (wave_path_covers(a)) return launch_wave(a, stream);      // a few dozen requests per snapshot: one wave each
     // the smallest workgroup whose capacity covers the promised snapshot size
     if (a.cap <= 512) launch_capacity<512, 64>(a, stream);
     else if (a.cap <= 1024) launch_capacity<1024, 64>(a, stream);

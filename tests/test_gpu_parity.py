@@ -100,6 +100,48 @@ def test_snapshot_sizes_on_chip(gpu, oracle_mod, m):
     check(gpu, oracle_mod, w)
 
 
+@pytest.mark.parametrize("per", [1, 31, 64, 65, 100, 127, 128])
+def test_one_wave_per_snapshot(gpu, oracle_mod, per):
+    """Promised bounds up to 128 requests take the path that gives a snapshot to a single wave (64 or 128
+    sorted in registers): snapshots that fill the wave exactly or not, ragged mixes with empty ones, every
+    order mode and heavy ties, own and shared DAGs, few and many stages, the downstream latency given
+    from outside, and the same snapshots under a larger promise (the workgroup path)."""
+    for permute in (True, False):
+        w = wl.make_workload(5, n_snapshots=9, per_snapshot=per, permute=permute)
+        check(gpu, oracle_mod, w)
+        check(gpu, oracle_mod, w, max_snap=128)
+        check(gpu, oracle_mod, w, max_snap=512)
+    half = max(per // 2, 1)
+    for i, kw in enumerate((dict(S=5, dag_shared=0), dict(S=8, dag_shared=1), dict(S=9, dag_shared=0, tie_heavy=True),
+                            dict(S=12, dag_shared=1), dict(S=3, dag_shared=0, modes=(wl.MODE_FCFS,)),
+                            dict(S=4, dag_shared=1, modes=(wl.MODE_HBF,), tie_heavy=True))):
+        for attempt in range(20):           # a random DAG of a dozen stages may expand to more paths than a plan takes
+            w = wl.random_workload(9000 + 10 * per + i + 1000 * attempt, K=41, n_per_snapshot=half, **kw)
+            rows = w.dag_row_ptr.reshape(-1, w.S + 1)
+            cols = np.split(w.dag_col, np.cumsum(rows[:, -1])[:-1])
+            if max(wl.count_paths_any_order(w.S, rows[d], cols[d]) * w.S for d in range(len(rows))) <= 4096:
+                break
+        assert w.max_snapshot_requests <= 128
+        s, ref = check(gpu, oracle_mod, w)
+        rng = np.random.default_rng(per + i)
+        sub = rng.integers(0, 60_000, size=w.K * w.S).astype(np.int64)
+        want = oracle_mod.run(w, threads=8, sub=sub)
+        import torch
+        s.run(sub=torch.from_numpy(sub).to(s.dev))
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], want[k]), (per, i, k)
+
+
+def test_one_wave_per_snapshot_many_snapshots(gpu, oracle_mod):
+    w = wl.make_workload(5, n_snapshots=20000, per_snapshot=61, permute=True)
+    _, ref = check(gpu, oracle_mod, w, threads=16)
+    assert 0 < ref["drop"].mean() < 1
+    w = wl.random_workload(31337, K=3000, S=6, n_per_snapshot=64, dag_shared=0)
+    assert w.max_snapshot_requests <= 128
+    check(gpu, oracle_mod, w, threads=16)
+
+
 @pytest.mark.parametrize("cap", [512, 1024, 2048, 4096, 8192])
 def test_every_workgroup_capacity(gpu, oracle_mod, cap):
     """The on-chip kernel comes in several capacities, picked from the promised snapshot bound: snapshots that
