@@ -259,6 +259,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="benchmark configuration 1..5 (default: the largest)")
     ap.add_argument("--permute", action="store_true", help="shuffle request order inside every snapshot")
+    ap.add_argument("--snapshots", type=int, default=None,
+                    help="configuration 5 only: this many snapshots instead of 4,096 (other shapes of the same sweep)")
+    ap.add_argument("--per-snapshot", type=int, default=None,
+                    help="configuration 5 only: this many requests per snapshot instead of 8,192")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--consistent", action="store_true",
                     help="sequentially consistent dropping (positions count kept requests only)")
@@ -290,7 +294,16 @@ def main():
     binding.load_library()
 
     t0 = time.time()
-    w = workloads.make_workload(args.config, permute=args.permute)
+    reshaped = args.snapshots is not None or args.per_snapshot is not None
+    if reshaped and args.config != 5:
+        print("bench.py: --snapshots/--per-snapshot reshape configuration 5 only", file=sys.stderr)
+        sys.exit(2)
+    shape = {}
+    if args.snapshots is not None:
+        shape["n_snapshots"] = args.snapshots
+    if args.per_snapshot is not None:
+        shape["per_snapshot"] = args.per_snapshot
+    w = workloads.make_workload(args.config, permute=args.permute, **shape)
     gen_s = time.time() - t0
     s = binding.Session(w)
     fused = s.max_snap <= binding.PARD_FUSED_SNAPSHOT_CAPACITY
@@ -342,7 +355,8 @@ def main():
     # roofline of the dominant kernel
     fcfs = bool((w.order_mode == workloads.MODE_FCFS).any())
     if fused:
-        kernel = "fused_snapshot_kernel (whole pard_estimate_drop call: one launch)"
+        small = s.max_snap <= 128
+        kernel = ("wave_snapshot_kernel" if small else "fused_snapshot_kernel") + " (whole pard_estimate_drop call: one launch)"
         passes = 0
     else:
         kernel = "pard_estimate_drop call (count, setup, histogram, radix passes, epilogue)"
@@ -352,7 +366,7 @@ def main():
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
     traffic = (recorded_traffic(args.config, "fused_snapshot_kernel", "pard_fused.hip")
-               if fused and not args.permute and not args.consistent and not args.ranked else None)
+               if fused and not args.permute and not args.consistent and not args.ranked and not reshaped else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4)}

@@ -15,6 +15,11 @@
 //   5. per queue slot: own-stage cost at its position + downstream maximum, drop decision;
 //      the queue order leaves coalesced, estimate and decision return to request order
 //      through LDS and leave coalesced as well.
+//      Sequentially consistent variant (the position counts only the kept requests ahead,
+//      Section 4.1): every queue is a chain of decisions.  Guess that everybody is kept, evaluate
+//      every slot at the position the guess implies, take the decisions as the next guess: after
+//      t rounds the first t slots of every queue are final, and a guess that reproduces itself
+//      is the in-order result.  The guess is a lane mask, a position a population count.
 // The workgroup is a single wave, so its barriers cost next to nothing and up to 32 snapshots
 // are in flight per compute unit.  (Measured on 131,072 snapshots of 64 requests: 0.13 ms against
 // 0.33 ms for the workgroup path; letting each wave loop over snapshots, with the next snapshot's
@@ -67,7 +72,17 @@ constexpr int kStageShift = 40, kKeyShift = 8;            // word = stage << 40 
 // LDS words (4 bytes) a snapshot of up to 64 * R requests and S stages needs.
 __host__ __device__ constexpr int wave_lds_words(int R, int S) { return kWave * R + 17 * S + 2; }
 
-template <int R>
+// Lanes l of slot row r (slots r * 64 + l) with first <= r * 64 + l < end.
+__device__ __forceinline__ unsigned long long row_mask(int r, int first, int end) {
+    int a = first - r * kWave, b = end - r * kWave;
+    a = a < 0 ? 0 : a;
+    b = b > kWave ? kWave : b;
+    if (b <= a) return 0ull;
+    const unsigned long long below_b = b == kWave ? ~0ull : (1ull << b) - 1ull;
+    return below_b & ~((1ull << a) - 1ull);
+}
+
+template <int R, bool CONSISTENT>
 __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
     constexpr int N = kWave * R;
     extern __shared__ __align__(16) uint32_t lds[];
@@ -170,17 +185,63 @@ __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
     __syncthreads();
 
     // ---- 5. estimate and decision per queue slot; back to request order through LDS ----------
+    int32_t est[R];
+    uint8_t drp[R];
+    if (CONSISTENT) {
+        unsigned long long keep[R];
+        int q0[R];
+        unsigned long long dn[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool ok = r * kWave + lane < m;
+            keep[r] = __ballot(ok);
+            q0[r] = ok ? seg_start[sp[r]] : 0;
+            dn[r] = ok ? down[sp[r]] : 0ull;
+            est[r] = 0;
+            drp[r] = 0;
+        }
+        for (int round = 0; round <= N; ++round) {
+            unsigned long long next[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int p = r * kWave + lane;
+                const bool ok = p < m;
+                if (ok) {
+                    uint32_t ahead = 0;
+#pragma unroll
+                    for (int r2 = 0; r2 <= r; ++r2) ahead += (uint32_t)__popcll(keep[r2] & row_mask(r2, q0[r], p));
+                    finish_request(stage_cost_short(recs[sp[r]], ahead, lat_dag + sp[r] * PARD_LAT_ENTRIES) + dn[r], now, dq[r],
+                                   est[r], drp[r]);
+                }
+                next[r] = __ballot(ok && drp[r] == 0);
+            }
+            bool same = true;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                same = same && next[r] == keep[r];
+                keep[r] = next[r];
+            }
+            if (same) break;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int p = r * kWave + lane;
+            est[r] = 0;
+            drp[r] = 0;
+            if (p < m) {
+                const int k = sp[r];
+                const uint32_t pos = (uint32_t)(p - seg_start[k]);
+                finish_request(stage_cost_short(recs[k], pos, lat_dag + k * PARD_LAT_ENTRIES) + down[k], now, dq[r], est[r], drp[r]);
+            }
+        }
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int p = r * kWave + lane;
         if (p < m) {
-            const int k = sp[r];
             const uint32_t id = (uint32_t)c[r] & (N - 1);
-            const uint32_t pos = (uint32_t)(p - seg_start[k]);
-            int32_t est;
-            uint8_t drp;
-            finish_request(stage_cost_short(recs[k], pos, lat_dag + k * PARD_LAT_ENTRIES) + down[k], now, dq[r], est, drp);
-            by_id[id] = (uint32_t)est | ((uint32_t)drp << 31);
+            by_id[id] = (uint32_t)est[r] | ((uint32_t)drp[r] << 31);
             A.order[lo + p] = (int32_t)(lo + id);
         }
     }
@@ -200,13 +261,19 @@ __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
 
 }  // namespace
 
-bool wave_path_covers(const FusedArgs& a) { return !a.consistent && a.cap <= 2 * kWave; }
+bool wave_path_covers(const FusedArgs& a) { return a.cap <= 2 * kWave; }
+
+template <int R>
+static void launch_rows(const FusedArgs& a, size_t bytes, hipStream_t stream) {
+    if (a.consistent) wave_snapshot_kernel<R, true><<<dim3((unsigned)a.plan.K), dim3(kWave), bytes, stream>>>(a);
+    else wave_snapshot_kernel<R, false><<<dim3((unsigned)a.plan.K), dim3(kWave), bytes, stream>>>(a);
+}
 
 hipError_t launch_wave(const FusedArgs& a, hipStream_t stream) {
     const int R = a.cap <= kWave ? 1 : 2;
     const size_t bytes = (size_t)wave_lds_words(R, a.plan.S) * 4;
-    if (R == 1) wave_snapshot_kernel<1><<<dim3((unsigned)a.plan.K), dim3(kWave), bytes, stream>>>(a);
-    else wave_snapshot_kernel<2><<<dim3((unsigned)a.plan.K), dim3(kWave), bytes, stream>>>(a);
+    if (R == 1) launch_rows<1>(a, bytes, stream);
+    else launch_rows<2>(a, bytes, stream);
     return hipGetLastError();
 }
 

@@ -131,6 +131,13 @@ def test_one_wave_per_snapshot(gpu, oracle_mod, per):
         got = s.results()
         for k in KEYS:
             assert np.array_equal(got[k], want[k]), (per, i, k)
+        # sequentially consistent dropping, with modest downstream latencies so that queues are cut in the middle
+        for given in (None, sub // 8):
+            want = oracle_mod.run(w, threads=8, sub=given, consistent=True)
+            s.run(sub=None if given is None else torch.from_numpy(given).to(s.dev), consistent=True)
+            got = s.results()
+            for k in KEYS:
+                assert np.array_equal(got[k], want[k]), (per, i, "consistent", given is None, k)
 
 
 def test_one_wave_per_snapshot_many_snapshots(gpu, oracle_mod):
@@ -139,7 +146,14 @@ def test_one_wave_per_snapshot_many_snapshots(gpu, oracle_mod):
     assert 0 < ref["drop"].mean() < 1
     w = wl.random_workload(31337, K=3000, S=6, n_per_snapshot=64, dag_shared=0)
     assert w.max_snapshot_requests <= 128
-    check(gpu, oracle_mod, w, threads=16)
+    s, _ = check(gpu, oracle_mod, w, threads=16)
+    plain = s.results()
+    want = oracle_mod.run(w, threads=16, consistent=True)
+    s.run(consistent=True)
+    got = s.results()
+    for k in KEYS:
+        assert np.array_equal(got[k], want[k]), k
+    assert not np.array_equal(got["drop"], plain["drop"])          # the variant is not vacuous on this input
 
 
 @pytest.mark.parametrize("cap", [512, 1024, 2048, 4096, 8192])
