@@ -30,7 +30,8 @@ namespace pard {
 
 namespace {
 
-// Capacity CAP (a power of two, at most PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (at least one wave): a
+// Capacity CAP (a power of two, at most PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (CAP / 8 at 512 and
+// 1024, where that measured faster or is what one wave needs): a
 // workgroup sized for 8192 requests spends most of its time on fixed costs when a snapshot holds a
 // few hundred, so smaller snapshots get smaller workgroups (and more of them per compute unit).
 //
@@ -540,7 +541,7 @@ hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
     if (wave_path_covers(a)) return launch_wave(a, stream);      // a few dozen requests per snapshot: one wave each
     // the smallest workgroup whose capacity covers the promised snapshot size
     if (a.cap <= 512) launch_capacity<512, 64>(a, stream);
-    else if (a.cap <= 1024) launch_capacity<1024, 64>(a, stream);
+    else if (a.cap <= 1024) launch_capacity<1024, 128>(a, stream);
     else if (a.cap <= 2048) launch_capacity<2048, 128>(a, stream);
     else if (a.cap <= 4096) launch_capacity<4096, 256>(a, stream);
     else launch_capacity<PARD_FUSED_SNAPSHOT_CAPACITY, 512>(a, stream);
