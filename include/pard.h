@@ -137,7 +137,7 @@ int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
  *   max_snapshot_requests  caller's upper bound on snap_ptr[u+1]-snap_ptr[u]; selects the
  *                          on-chip path when <= PARD_FUSED_SNAPSHOT_CAPACITY, and there the
  *                          size of the workgroup that takes a snapshot (a tight bound is
- *                          faster: 64, 128, 512, 1024, 2048, 4096, 8192 are the steps; up to
+ *                          faster: 64, 128, 256, 512, 1024, 2048, 4096, 8192 are the steps; up to
  *                          128 a single wave sorts the snapshot in registers).  A snapshot
  *                          larger than the promised bound is truncated to the bound and
  *                          raises bit 0 of the status word (memory safe, results for that

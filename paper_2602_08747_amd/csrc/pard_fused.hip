@@ -30,8 +30,8 @@ namespace pard {
 
 namespace {
 
-// Capacity CAP (a power of two, at most PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (CAP / 8 at 512 and
-// 1024, where that measured faster or is what one wave needs): a
+// Capacity CAP (a power of two from 256 to PARD_FUSED_SNAPSHOT_CAPACITY) with CAP / 16 threads (more at 256, 512
+// and 1024, where that measured faster or is what one wave needs): a
 // workgroup sized for 8192 requests spends most of its time on fixed costs when a snapshot holds a
 // few hundred, so smaller snapshots get smaller workgroups (and more of them per compute unit).
 //
@@ -43,7 +43,8 @@ constexpr int kFewStages = 8;
 
 template <int CAP, int SCAP>
 struct SnapshotLds {
-    static constexpr int kCntWords = CAP * 3 / 4;    // 1.5 * CAP 16-bit counters, two per LDS word
+    // 1.5 * CAP 16-bit counters, two per LDS word (2 * CAP at the smallest capacity: a thread scans an even number of words)
+    static constexpr int kCntWords = CAP == 256 ? CAP : CAP * 3 / 4;
     static constexpr int kAuxMin = SCAP * PARD_LAT_ENTRIES + 256;   // words: every stage's latency table + path entries
     static constexpr int kAuxWords = CAP / 2 > kAuxMin ? CAP / 2 : kAuxMin;
     __align__(16) uint32_t cnt32[kCntWords + 4];     // bucket counters, then bucket starts; later the queue order
@@ -540,7 +541,8 @@ void launch_capacity(const FusedArgs& a, hipStream_t stream) {
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
     if (wave_path_covers(a)) return launch_wave(a, stream);      // a few dozen requests per snapshot: one wave each
     // the smallest workgroup whose capacity covers the promised snapshot size
-    if (a.cap <= 512) launch_capacity<512, 64>(a, stream);
+    if (a.cap <= 256) launch_capacity<256, 64>(a, stream);
+    else if (a.cap <= 512) launch_capacity<512, 64>(a, stream);
     else if (a.cap <= 1024) launch_capacity<1024, 128>(a, stream);
     else if (a.cap <= 2048) launch_capacity<2048, 128>(a, stream);
     else if (a.cap <= 4096) launch_capacity<4096, 256>(a, stream);

@@ -110,6 +110,7 @@ def test_one_wave_per_snapshot(gpu, oracle_mod, per):
         w = wl.make_workload(5, n_snapshots=9, per_snapshot=per, permute=permute)
         check(gpu, oracle_mod, w)
         check(gpu, oracle_mod, w, max_snap=128)
+        check(gpu, oracle_mod, w, max_snap=256)
         check(gpu, oracle_mod, w, max_snap=512)
     half = max(per // 2, 1)
     for i, kw in enumerate((dict(S=5, dag_shared=0), dict(S=8, dag_shared=1), dict(S=9, dag_shared=0, tie_heavy=True),
@@ -156,7 +157,7 @@ def test_one_wave_per_snapshot_many_snapshots(gpu, oracle_mod):
     assert not np.array_equal(got["drop"], plain["drop"])          # the variant is not vacuous on this input
 
 
-@pytest.mark.parametrize("cap", [512, 1024, 2048, 4096, 8192])
+@pytest.mark.parametrize("cap", [256, 512, 1024, 2048, 4096, 8192])
 def test_every_workgroup_capacity(gpu, oracle_mod, cap):
     """The on-chip kernel comes in several capacities, picked from the promised snapshot bound: snapshots that
     fill a capacity exactly (the path without bounds tests), fall one short of it, or mix sizes below it; the

@@ -54,8 +54,8 @@ def test_random_case(gpu, oracle_mod, seed):
         consistent, ranked = variant == "consistent", variant == "ranked"
         ref = oracle_mod.run(w, threads=8, sub=sub, consistent=consistent, ranked=ranked)
         # the tight promise picks the one-wave kernel for snapshots of at most 128: those also run under a
-        # promise of 512 (the smallest workgroup kernel)
-        promises = (None, FORCE_SORT) + ((512,) if w.max_snapshot_requests <= 128 else ())
+        # promise of 256 and of 512 (the smallest workgroup kernels)
+        promises = (None, FORCE_SORT) + ((256, 512) if w.max_snapshot_requests <= 128 else ())
         for max_snap in promises:
             s = gpu.Session(w, max_snapshot_requests=None if max_snap is None else max(max_snap, w.max_snapshot_requests))
             s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=consistent, ranked=ranked)
