@@ -93,6 +93,9 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     const int m_s = m + off;
     auto live = [&](int idx) { return FULL || (idx >= off && idx < m_s); };
     auto whole = [&](int base) { return FULL || (aligned && base >= off && base + 3 < m_s); };   // four live requests, 16-byte access
+    // a thread's g-th group of four lies in slots [g * 4T, (g + 1) * 4T): a snapshot that ends before them leaves
+    // the whole workgroup nothing to do for that g, in any phase
+    auto dead_group = [&](int g) { return !FULL && g * T * 4 >= m_s; };
     uint32_t* aux = reinterpret_cast<uint32_t*>(L.idx);           // kAuxWords words
     const int e_lo = P.dag_entry_ptr[dag], n_entries = P.dag_entry_ptr[dag + 1] - e_lo;
     const bool entries_cached = S * PARD_LAT_ENTRIES + n_entries <= kAuxWords;
@@ -102,6 +105,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     int32_t dl[G][4], st[G][4];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
         if (FULL || (aligned && base < m_s && lo_s + base + 3 < A.n)) {      // neighbours' values may ride along: they are not live
             const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo_s + base);
@@ -138,6 +142,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -182,6 +187,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     uint32_t bs[G][4];                       // bucket | slot << 16
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -258,6 +264,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     uint32_t se[G][4];                       // bucket start (13 bits) | bucket size - 1 (13 bits) | stage << 26
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
@@ -302,6 +309,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         // overlap; reads past the end of a short bucket are masked), longer buckets after that
 #pragma unroll
         for (int g = 0; g < G; ++g) {
+            if (dead_group(g)) continue;
             uint32_t part[4];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -326,6 +334,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         const int base0 = tid * 4;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
+            if (dead_group(g)) continue;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (live(g * T * 4 + base0 + c)) {
@@ -345,6 +354,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     uint16_t* ord_l = reinterpret_cast<uint16_t*>(L.cnt32);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -356,6 +366,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         // deadlines by queue slot (L.low is free: every read of the rank phase is behind the barrier above)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
+            if (dead_group(g)) continue;
             const int base = (g * T + tid) * 4;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
@@ -392,6 +403,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         __syncthreads();
 #pragma unroll
         for (int g = 0; g < G; ++g) {
+            if (dead_group(g)) continue;
             const int base = (g * T + tid) * 4;
             int32_t est[4];
             uint8_t drp[4];
@@ -417,6 +429,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     const bool quick = !wide && L.slow_stages == 0u;          // every stage admits the exact short-queue form
 #pragma unroll
     for (int g = 0; g < (CONSISTENT ? 0 : G); ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
         int32_t est[4];
         uint8_t drp[4];
@@ -465,6 +478,7 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     // ---- queue order and queue offsets out ----------------------------------------------
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
         // queue slot q sits at order[lo + q] = order[lo_s + (q + off)]: the same shifted groups of four;
         // its entry is the request with local index ord_l[q], i.e. request lo_s + ord_l[q]
