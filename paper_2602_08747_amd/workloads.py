@@ -17,6 +17,8 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import List, Optional, Sequence
 
+import dataclasses
+
 import numpy as np
 
 BASE_SEED = 20260208
@@ -363,6 +365,18 @@ def make_workload(cfg: int, n_requests: Optional[int] = None, n_snapshots: Optio
 # --------------------------------------------------------------------------
 # small random cases for brute-force pins and adversarial parity tests
 # --------------------------------------------------------------------------
+
+def with_snapshot_sizes(w: Workload, sizes) -> Workload:
+    """The same plan with snapshot u cut down to its first sizes[u] requests (ragged batches)."""
+    have = np.diff(w.snap_ptr.astype(np.int64))
+    sizes = np.minimum(np.asarray(sizes, np.int64), have)
+    keep = (np.concatenate([np.arange(w.snap_ptr[u], w.snap_ptr[u] + sizes[u]) for u in range(w.K)])
+            if w.K else np.zeros(0, np.int64)).astype(np.int64)
+    snap_ptr = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    return dataclasses.replace(w, name=w.name + "-ragged", arrival=np.ascontiguousarray(w.arrival[keep]),
+                               deadline=np.ascontiguousarray(w.deadline[keep]),
+                               stage=np.ascontiguousarray(w.stage[keep]), snap_ptr=snap_ptr)
+
 
 def random_dag(rng: np.random.Generator, S: int, p_edge: float = 0.35):
     """Random DAG on S stages: edge a->b only for a<b under a random relabelling."""

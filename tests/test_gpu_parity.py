@@ -157,6 +157,34 @@ def test_one_wave_per_snapshot_many_snapshots(gpu, oracle_mod):
     assert not np.array_equal(got["drop"], plain["drop"])          # the variant is not vacuous on this input
 
 
+@pytest.mark.parametrize("mix", ["uniform", "mostly-small", "geometric", "all-empty", "steps"])
+def test_mixed_snapshot_sizes(gpu, oracle_mod, mix):
+    """Batches whose snapshots differ widely in size under one promise (the workgroup of a call is sized for the
+    largest): snapshots that end before some of a thread's request groups, empty ones, sizes at every capacity step."""
+    import torch
+    K = 700
+    rng = np.random.default_rng(sum(map(ord, mix)))
+    base = wl.make_workload(5, n_snapshots=K, per_snapshot=8192, permute=True)
+    sizes = {"uniform": rng.integers(0, 8193, K),
+             "mostly-small": np.where(rng.random(K) < 0.9, rng.integers(0, 257, K), rng.integers(4000, 8193, K)),
+             "geometric": np.minimum(rng.geometric(1 / 600, K), 8192),
+             "all-empty": np.zeros(K, np.int64),
+             "steps": rng.choice([0, 1, 63, 64, 65, 128, 129, 256, 257, 512, 513, 1024, 1025, 2048, 2049, 4096, 4097, 8192], K)}[mix]
+    w = wl.with_snapshot_sizes(base, sizes)
+    for max_snap in (None, 8192, 5000, 9000):          # 9000: the large-snapshot path
+        if max_snap is not None and max_snap < w.max_snapshot_requests:
+            continue
+        s, ref = check(gpu, oracle_mod, w, max_snap=max_snap)
+        sub = rng.integers(0, 300_000, size=w.K * w.S).astype(np.int64)
+        for given, consistent in ((sub, False), (None, True), (sub // 16, True)):
+            want = oracle_mod.run(w, threads=8, sub=given, consistent=consistent)
+            s.run(sub=None if given is None else torch.from_numpy(given).to(s.dev), consistent=consistent)
+            got = s.results()
+            for k in KEYS:
+                assert np.array_equal(got[k], want[k]), (mix, max_snap, given is None, consistent, k)
+            assert s.status_word() == 0
+
+
 @pytest.mark.parametrize("cap", [256, 512, 1024, 2048, 4096, 8192])
 def test_every_workgroup_capacity(gpu, oracle_mod, cap):
     """The on-chip kernel comes in several capacities, picked from the promised snapshot bound: snapshots that
