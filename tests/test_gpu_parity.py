@@ -402,6 +402,59 @@ def test_compact_unaligned_buffers(gpu, oracle_mod, cfg, kw, max_snap):
         assert (sb[:off_idx] == -7).all() and (sb[off_idx + want_ptr[-1]:] == -7).all()   # nothing written outside
 
 
+@pytest.mark.parametrize("shape", ["wave", "workgroup-small", "workgroup-full", "workgroup-ragged", "sorted"])
+def test_estimate_unaligned_buffers(gpu, oracle_mod, shape):
+    """Request arrays and outputs that start at odd offsets (views into larger allocations): the 16-byte accesses
+    of every kernel path fall back or shift, the results stay the same and nothing is written outside the views."""
+    import torch
+    if shape == "wave":
+        w = wl.make_workload(5, n_snapshots=300, per_snapshot=61, permute=True)
+    elif shape == "workgroup-small":
+        w = wl.make_workload(5, n_snapshots=40, per_snapshot=700, permute=True)
+    elif shape == "workgroup-full":
+        w = wl.make_workload(5, n_snapshots=6, per_snapshot=8192, permute=True)
+    elif shape == "workgroup-ragged":
+        w = wl.with_snapshot_sizes(wl.make_workload(5, n_snapshots=30, per_snapshot=8192, permute=True),
+                                   np.random.default_rng(3).integers(0, 8193, 30))
+    else:
+        w = wl.make_workload(3, n_requests=90_001, permute=True)
+    s, ref = check(gpu, oracle_mod, w)
+    want_c = oracle_mod.run(w, threads=8, consistent=True)
+    n = w.n
+    for o32, o8 in ((1, 1), (2, 6), (3, 3), (4, 16)):
+        def view32(src):
+            big = torch.full((n + 32,), -7, dtype=torch.int32, device=s.dev)
+            v = big[o32:o32 + n]
+            if src is not None:
+                v.copy_(src)
+            return big, v
+        _, arrival = view32(s.arrival)
+        _, deadline = view32(s.deadline)
+        _, stage = view32(s.stage)
+        est_big, est = view32(None)
+        order_big, order = view32(None)
+        drop_big = torch.full((n + 64,), 9, dtype=torch.uint8, device=s.dev)
+        drop = drop_big[o8:o8 + n]
+        for consistent, want in ((False, ref), (True, want_c)):
+            if consistent:
+                gpu.pard_estimate_drop_consistent(s.plan, n, s.max_snap, arrival, deadline, stage, s.snap_ptr, s.now, None,
+                                                  est, drop, order, s.seg_ptr, s.workspace)
+            else:
+                gpu.pard_estimate_drop(s.plan, n, s.max_snap, arrival, deadline, stage, s.snap_ptr, s.now,
+                                       est, drop, order, s.seg_ptr, s.workspace)
+            torch.cuda.synchronize()
+            assert np.array_equal(est.cpu().numpy(), want["est"]), (shape, o32, consistent)
+            assert np.array_equal(drop.cpu().numpy(), want["drop"]), (shape, o8, consistent)
+            assert np.array_equal(order.cpu().numpy(), want["order"]), (shape, o32, consistent)
+            assert np.array_equal(s.seg_ptr.cpu().numpy(), want["seg_ptr"]), (shape, consistent)
+            for big, off in ((est_big, o32), (order_big, o32)):
+                h = big.cpu().numpy()
+                assert (h[:off] == -7).all() and (h[off + n:] == -7).all()
+            h = drop_big.cpu().numpy()
+            assert (h[:o8] == 9).all() and (h[o8 + n:] == 9).all()
+        assert s.status_word() == 0
+
+
 @pytest.mark.parametrize("case", ["on-chip", "sorted", "sorted-consistent", "on-chip-ranked"])
 def test_graph_capture_and_replay(gpu, oracle_mod, case):
     """The hot calls only enqueue kernels (no allocation, no synchronisation, no memset nodes), so they can be
