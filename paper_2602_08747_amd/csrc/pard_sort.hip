@@ -35,7 +35,7 @@ constexpr int kDies = 8;                               // accelerator dies (XCDs
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 constexpr int kConsTile = 256;                         // queue slots per workgroup in the consistent-dropping kernels
 constexpr int kConsRanges = 8192;                      // workgroups of those kernels at most (each owns a range of tiles)
-constexpr int kFusedScanChunks = 32;                   // up to here every chunk scans the chunk totals itself
+constexpr int kFusedScanChunks = 64;                   // up to here every chunk scans the chunk totals itself
 
 constexpr uint32_t kSegScan = 1u << 31;                // queue flag: consistent positions by prefix minimum (see below)
 
