@@ -819,8 +819,18 @@ __device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t se
     return q;
 }
 
+// Order of the work.  Walking the queue slots front to back writes the packed results of one queue at a
+// time, and the requests of a queue are spread over the whole request range: every cache line of packed[]
+// is then written a few bytes at a time, as many times as there are queues, long after one another.  When
+// the requests arrive roughly in key order (arrival-ordered input), the f-th fraction of every queue holds
+// the requests of the same stretch of the request range.  So a workgroup takes one small share of EVERY queue
+// at a time (share phi of `shares`: groups [L*phi/shares, L*(phi+1)/shares) of a queue that owns L groups of
+// four slots): what it writes then falls into one stretch of packed[] and meets in its L2.
 __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
     __shared__ EpiSeg tab[kEpiSegs];
+    __shared__ int32_t gfirst[kEpiSegs + 1];     // first group of four slots a queue owns (the group's first slot is the queue's)
+    __shared__ int32_t cum[kEpiSegs + 1];        // this share: groups of the queues before q
+    __shared__ int32_t from[kEpiSegs];           // this share: its first group of queue q
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x;
     const int64_t segs = (int64_t)P.K * P.S;
@@ -835,8 +845,7 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     const bool vec = (reinterpret_cast<uintptr_t>(A.order) & 15) == 0;     // the workspace buffers are 256-byte aligned
     const int64_t groups = (A.n + 3) / 4;
-    const int64_t stride = (int64_t)gridDim.x * kEpiThreads;
-    for (int64_t g = (int64_t)blockIdx.x * kEpiThreads + tid; g < groups; g += stride) {
+    auto one_group = [&](const int64_t g) {
         const int64_t j0 = g * 4;
         uint32_t k4[4], p4[4];
         if (j0 + 3 < A.n) {
@@ -882,6 +891,45 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
             if (j0 + c < A.n && (int64_t)r4[c] < A.n) packed[r4[c]] = out[c];
+    };
+    if (!cached || segs < 2) {
+        const int64_t stride = (int64_t)gridDim.x * kEpiThreads;
+        for (int64_t g = (int64_t)blockIdx.x * kEpiThreads + tid; g < groups; g += stride) one_group(g);
+        return;
+    }
+    if (tid <= segs) gfirst[tid] = tid < segs ? (int32_t)(((int64_t)tab[tid].start + 3) / 4) : (int32_t)groups;
+    __syncthreads();
+    const int64_t shares = (groups + kEpiThreads - kEpiSegs - 1) / (kEpiThreads - kEpiSegs);     // at most kEpiThreads groups each
+    const int nseg = (int)segs;
+    for (int64_t phi = blockIdx.x; phi < shares; phi += gridDim.x) {
+        if (tid < kWave) {
+            int32_t c = 0, f0 = 0;
+            if (tid < nseg) {
+                const int64_t L = gfirst[tid + 1] - gfirst[tid];
+                const int64_t a0 = L * phi / shares, a1 = L * (phi + 1) / shares;
+                c = (int32_t)(a1 - a0);
+                f0 = gfirst[tid] + (int32_t)a0;
+            }
+            int32_t inc = c;
+#pragma unroll
+            for (int off = 1; off < kWave; off <<= 1) {
+                const int32_t t = __shfl_up(inc, off);
+                if (tid >= off) inc += t;
+            }
+            if (tid < nseg) { cum[tid] = inc - c; from[tid] = f0; }
+            if (tid == nseg - 1) cum[nseg] = inc;
+        }
+        __syncthreads();
+        const int total = cum[nseg];
+        for (int x = tid; x < total; x += kEpiThreads) {
+            int lo = 0, hi = nseg;                       // the last queue with cum[q] <= x holds x
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (cum[mid] <= x) lo = mid; else hi = mid;
+            }
+            one_group((int64_t)from[lo] + (x - cum[lo]));
+        }
+        __syncthreads();
     }
 }
 
