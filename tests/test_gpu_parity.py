@@ -195,9 +195,15 @@ def test_every_workgroup_capacity(gpu, oracle_mod, cap):
         check(gpu, oracle_mod, w)
         if cap < 8192:
             check(gpu, oracle_mod, w, max_snap=2 * cap)
-    # ragged sizes up to cap; each capacity has a variant for pipelines of at most 8 stages and one for more
-    for S in (7, 8, 9, 13):
-        w = wl.random_workload(600 + cap + S, K=9, S=S, n_per_snapshot=cap // 2, dag_shared=0)
+    # ragged sizes up to cap; each capacity has variants for pipelines of at most 8, at most 16 and more stages
+    for S in (7, 8, 9, 13, 16, 17):
+        for attempt in range(40):           # a random DAG of many stages may expand to more paths than a plan takes
+            w = wl.random_workload(600 + cap + S + 1000 * attempt, K=9, S=S, n_per_snapshot=cap // 2,
+                                   dag_shared=0 if S < 16 else 1)
+            rows = w.dag_row_ptr.reshape(-1, w.S + 1)
+            cols = np.split(w.dag_col, np.cumsum(rows[:, -1])[:-1])
+            if max(wl.count_paths_any_order(w.S, rows[d], cols[d]) * w.S for d in range(len(rows))) <= 4096:
+                break
         assert w.max_snapshot_requests <= cap
         check(gpu, oracle_mod, w, max_snap=cap)
         ref = oracle_mod.run(w, threads=8, consistent=True)
