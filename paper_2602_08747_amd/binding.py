@@ -45,13 +45,14 @@ class PlanDesc(ctypes.Structure):
 
 
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
-    """Loads the built library; builds it first only when no built library exists."""
+    """Loads the built library.  The in-tree library is rebuilt first when it is missing or was built
+    from other sources than the ones in the tree (a stale binary is never loaded silently)."""
     global _lib
     if _lib is not None and path is None:
         return _lib
     p = path or os.environ.get("PARD_LIBRARY") or _build.LIB_PATH
-    if p == _build.LIB_PATH and not os.path.exists(p):
-        _build.build_library()
+    if p == _build.LIB_PATH and _build.is_stale():
+        _build.build_library(incremental=True)
     lib = ctypes.CDLL(p)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     lib.pard_plan_check.argtypes = [ctypes.POINTER(PlanDesc), ctypes.POINTER(i64), ctypes.POINTER(i32)]

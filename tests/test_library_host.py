@@ -148,3 +148,20 @@ def test_short_queue_float_reciprocals_are_exact():
         assert p.max() < 2**21
         got = ((p.astype(f32) + f32(0.5)) * (f32(1.0) / f32(W))).astype(np.int64)
         assert np.array_equal(got, p // W), W
+
+
+def test_stale_library_is_detected(tmp_path, monkeypatch):
+    """The digest written beside the library at build time covers every source, header and flag: a tree whose
+    sources differ from the ones the library was built from is reported stale whatever the file times say."""
+    from paper_2602_08747_amd import build
+    binding.load_library()                       # builds when needed
+    assert not build.is_stale()
+    assert set(os.path.basename(d) for d in build.dependencies()) >= {"pard_api.hip", "pard_device.hpp", "pard.h"}
+    recorded = open(build.HASH_PATH).read().strip()
+    assert recorded == build.source_hash()
+    fake = tmp_path / "libpard.srchash"
+    fake.write_text("0" * 64 + "\n")
+    monkeypatch.setattr(build, "HASH_PATH", str(fake))
+    assert build.is_stale()
+    monkeypatch.setattr(build, "HASH_PATH", str(tmp_path / "missing"))
+    assert build.is_stale()
