@@ -34,6 +34,37 @@ def estimate_drop_bytes_per_request(fused: bool, passes: int, fcfs: bool) -> flo
     return float(io + 16 * (passes - 1) + 8)
 
 
+def usable_cores() -> int:
+    """Host cores this process may use: its affinity mask, and no more than the share the machine's
+    own thread-count setting (OMP_NUM_THREADS) grants a one-GPU job."""
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        cores = os.cpu_count() or 1
+    share = os.environ.get("OMP_NUM_THREADS", "")
+    if share.isdigit() and int(share) > 0:
+        cores = min(cores, int(share))
+    return max(1, cores)
+
+
+def copy_calibration(torch, nbytes: int, reps: int = 5) -> float:
+    """GB/s (bytes read + bytes written) of a plain device-to-device copy that moves `nbytes` in total."""
+    half = max(int(nbytes) // 2, 1 << 20)
+    src = torch.ones(half, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    del src, dst
+    return 2.0 * half / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+
+
 def recorded_traffic(workload_cfg: int, kernel: str, source: str):
     """HBM bytes per launch of `kernel` taken from the committed rocprofv3 counter summary,
     or None when there is none for this workload or the kernel source changed since."""
@@ -129,7 +160,7 @@ def bench_planner(args, w, s, gen_s):
     }
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(os.cpu_count() or 1, 16)
+        threads = usable_cores()
         oracle.build_oracle()
         Ks = w.K if w.dag_shared else min(w.K, 64)      # bounded sample: the first snapshots
         qlen = s.qlen.cpu().numpy()
@@ -263,6 +294,10 @@ def main():
                     help="configuration 5 only: this many snapshots instead of 4,096 (other shapes of the same sweep)")
     ap.add_argument("--per-snapshot", type=int, default=None,
                     help="configuration 5 only: this many requests per snapshot instead of 8,192")
+    ap.add_argument("--half-survivors", action="store_true",
+                    help="configurations 2-4 only: a labelled variant that is NOT one of the five configurations "
+                         "(SLO = half the arrival span, latencies scaled down) so that about half of every queue "
+                         "survives")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--consistent", action="store_true",
                     help="sequentially consistent dropping (positions count kept requests only)")
@@ -304,8 +339,20 @@ def main():
     if args.per_snapshot is not None:
         shape["per_snapshot"] = args.per_snapshot
     w = workloads.make_workload(args.config, permute=args.permute, **shape)
+    if args.half_survivors:
+        if args.config not in (2, 3, 4):
+            print("bench.py: --half-survivors is a variant of configurations 2-4", file=sys.stderr)
+            sys.exit(2)
+        w = workloads.half_survivors(w)
     gen_s = time.time() - t0
     s = binding.Session(w)
+    # host-to-device time of the request arrays (outside every timed region; the boundary takes device buffers)
+    torch.cuda.synchronize()
+    t_up = time.perf_counter()
+    for host in (w.arrival, w.deadline, w.stage):
+        torch.from_numpy(host).to(s.dev)
+    torch.cuda.synchronize()
+    h2d_ms = (time.perf_counter() - t_up) * 1e3
     fused = s.max_snap <= binding.PARD_FUSED_SNAPSHOT_CAPACITY
     n = w.n
 
@@ -369,7 +416,11 @@ def main():
                if fused and not args.permute and not args.consistent and not args.ranked and not reshaped else None)
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4)}
+                "traffic_source": (f"profiles/hbm_traffic_cfg{args.config}.txt (rocprofv3 counters, valid for the "
+                                   "kernel source it names)") if traffic is not None else None,
+                "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4),
+                # a plain device copy moving the same number of bytes, timed in this run
+                "copy_calibration_gbs": round(copy_calibration(torch, int(alg_bytes)), 1)}
 
     out = {
         "metric": "requests evaluated/sec (estimate+drop+compact)",
@@ -383,13 +434,13 @@ def main():
                    "stages": w.S, "path": "on-chip" if fused else "radix-sort", "radix_passes": passes,
                    "drop_fraction": round(drop_frac, 4), "status_word": status,
                    "estimate_drop_ms": round(est_ms, 4), "compact_ms": round(cmp_ms, 4),
-                   "generate_s": round(gen_s, 2)},
+                   "h2d_ms": round(h2d_ms, 2), "generate_s": round(gen_s, 2)},
         "roofline": roofline,
     }
 
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(os.cpu_count() or 1, 16)
+        threads = usable_cores()
         # the oracle finishes the whole workload in seconds, so the sample is the whole workload
         sub = w
         sample = f"whole workload ({n} requests), 1 run"
@@ -405,8 +456,16 @@ def main():
         t0 = time.perf_counter()
         oracle.run(sub, threads=threads, consistent=args.consistent, ranked=args.ranked)
         cpu_s = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.run(sub, threads=1, consistent=args.consistent, ranked=args.ranked)
+        cpu1_s = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(sub.n / cpu_s, 1), "unit": "requests/s", "cores": threads,
-                               "kind": "oracle", "sample": sample, "seconds": round(cpu_s, 3)}
+                               "kind": "oracle", "sample": sample, "seconds": round(cpu_s, 3),
+                               "single_thread": {"value": round(sub.n / cpu1_s, 1), "unit": "requests/s", "cores": 1,
+                                                 "seconds": round(cpu1_s, 3)},
+                               "host_cores": os.cpu_count(),
+                               "cores_note": "cores = every host core this job may use (affinity mask, capped by the "
+                                             "machine's OMP_NUM_THREADS share)"}
     print(json.dumps(out))
 
 

@@ -362,6 +362,19 @@ def make_workload(cfg: int, n_requests: Optional[int] = None, n_snapshots: Optio
         stage=np.ascontiguousarray(stage, np.int32), snap_ptr=snap_ptr, now=now.astype(np.int32), notes=notes)
 
 
+def half_survivors(w: Workload) -> Workload:
+    """A labelled variant of a single-snapshot workload (not one of the five configurations): the SLO is
+    half the arrival span, `now` sits in the middle of it and the latency tables are scaled down by 200,
+    so that roughly half of the queue is still in time and the drop mask is mixed.  The deep-overload
+    snapshots of configurations 2-4 drop nearly everything; this one exercises estimates below the
+    saturation value and a compaction that keeps a large part of every queue."""
+    span = int(w.arrival.max()) if w.n else 0
+    deadline = (w.arrival.astype(np.int64) + span // 2).astype(np.int32)
+    return dataclasses.replace(w, name=w.name + "-half-survivors", deadline=deadline,
+                               now=np.full_like(w.now, span // 2),
+                               lat_us=np.maximum(1, w.lat_us // 200).astype(np.int32))
+
+
 # --------------------------------------------------------------------------
 # small random cases for brute-force pins and adversarial parity tests
 # --------------------------------------------------------------------------

@@ -61,14 +61,23 @@ def test_config_shapes_permuted(gpu, oracle_mod, cfg, kw):
     assert 0 < ref["drop"].mean() < 1
 
 
-def test_config4_half_survivors(gpu, oracle_mod):
-    """Bursty DAG with an SLO of half the arrival span: compaction with roughly half the queue surviving."""
-    w = wl.make_workload(4, n_requests=1 << 20, permute=True)
-    span = int(w.arrival.max())
-    w.deadline[:] = w.arrival + span // 2
-    w.now[:] = span // 2
-    w.lat_us[:] = np.maximum(1, w.lat_us // 200)
-    s, ref = check(gpu, oracle_mod, w)
+@pytest.mark.parametrize("n,permute", [(1 << 20, True), (None, False), (None, True)])
+def test_config4_half_survivors(gpu, oracle_mod, n, permute):
+    """Bursty DAG with an SLO of half the arrival span (a labelled variant, not one of the five configurations):
+    compaction with roughly half the queue surviving and estimates below the saturation value, at one million
+    requests and at the configuration's full 16.8 million, in arrival order and shuffled."""
+    w = wl.half_survivors(wl.make_workload(4, n_requests=n, permute=permute))
+    s, ref = check(gpu, oracle_mod, w, threads=16)
+    assert 0.1 < ref["drop"].mean() < 0.9
+    assert (ref["est"] < INT32_MAX).mean() > 0.5
+
+
+def test_large_path_beyond_64_chunks(gpu, oracle_mod):
+    """More than 2^24 requests in one snapshot: the radix passes then scan their chunk totals in a kernel of
+    their own (up to 64 chunks every chunk workgroup scans them itself).  Configuration 4's shape, shuffled,
+    with latencies scaled so that the drop mask is mixed."""
+    w = wl.half_survivors(wl.make_workload(4, n_requests=(1 << 24) + 8193, permute=True))
+    s, ref = check(gpu, oracle_mod, w, threads=16)
     assert 0.1 < ref["drop"].mean() < 0.9
 
 
