@@ -64,7 +64,9 @@ typedef enum {
     PARD_E_WORKSPACE = -8,       /* workspace NULL, misaligned or too small               */
     PARD_E_HIP = -9,             /* a HIP runtime call failed                             */
     PARD_E_BAD_MODE = -10,       /* order mode not one of PARD_ORDER_*                    */
-    PARD_E_UNSUPPORTED = -11     /* shape or value range not supported (see the calls)    */
+    PARD_E_UNSUPPORTED = -11,    /* shape or value range not supported (see the calls)    */
+    PARD_E_SCRATCH = -12         /* the call needs more than PARD_STATIC_SCRATCH_BYTES of the
+                                    library's built-in scratch buffer                      */
 } pard_status;
 
 enum { PARD_ORDER_LBF = 0,       /* ascending deadline  (low remaining budget first)      */
@@ -162,6 +164,33 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
                        const int32_t* d_snap_ptr, const int32_t* d_now,
                        int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
                        void* d_workspace, int64_t workspace_bytes, void* stream);
+
+/*
+ * pard_estimate_drop for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * kernels are the ones pard_estimate_drop launches; their workspace is a buffer of
+ * PARD_STATIC_SCRATCH_BYTES that is part of the library's device image (each GPU the library
+ * runs on holds its own copy until the process ends).  The call allocates and frees nothing.
+ *
+ *   d_status               device out uint32[1], may be NULL: receives the status bits the buffer has
+ *                          accumulated since they were last taken (meaning as for the workspace's
+ *                          first word); copied on `stream` after the kernels, then cleared
+ *   everything else        as for pard_estimate_drop
+ *
+ * Snapshots up to PARD_FUSED_SNAPSHOT_CAPACITY need a few bytes of the buffer, so any n is
+ * served; larger snapshots need what pard_workspace_bytes reports, and the call returns
+ * PARD_E_SCRATCH when that exceeds PARD_STATIC_SCRATCH_BYTES (about 1.8 million requests).
+ * All calls on one GPU share that GPU's buffer: two such calls that overlap in time on one GPU
+ * (different streams) race; calls on one stream are ordered and safe.  The first call on a
+ * device looks up the buffer's address (no allocation); make it outside a stream capture.
+ * Errors: as pard_estimate_drop, plus PARD_E_SCRATCH.
+ */
+#define PARD_STATIC_SCRATCH_BYTES (32 << 20)
+int pard_estimate_drop_static(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                              const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                              const int32_t* d_snap_ptr, const int32_t* d_now,
+                              int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                              uint32_t* d_status, void* stream);
 
 /*
  * Drop-mask stream compaction: the survivor queues that go on to batching (Section 4.1,

@@ -21,11 +21,11 @@ PARD_FUSED_SNAPSHOT_CAPACITY = 8192
 STATUS_NAMES = {
     0: "PARD_OK", -1: "PARD_E_NULL", -2: "PARD_E_BAD_SHAPE", -3: "PARD_E_BAD_BATCH", -4: "PARD_E_BAD_WORKERS",
     -5: "PARD_E_BAD_LATENCY", -6: "PARD_E_BAD_DAG", -7: "PARD_E_TOO_MANY_PATHS", -8: "PARD_E_WORKSPACE",
-    -9: "PARD_E_HIP", -10: "PARD_E_BAD_MODE", -11: "PARD_E_UNSUPPORTED",
+    -9: "PARD_E_HIP", -10: "PARD_E_BAD_MODE", -11: "PARD_E_UNSUPPORTED", -12: "PARD_E_SCRATCH",
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
-           "pard_estimate_drop_ranked",
+           "pard_estimate_drop_ranked", "pard_estimate_drop_static",
            "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
            "pard_sub_latency", "pard_sub_latency_q", "pard_queue_delay", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
@@ -62,6 +62,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_workspace_bytes.argtypes = [vp, i64, i64, ctypes.POINTER(i64)]
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
     lib.pard_estimate_drop_ranked.argtypes = lib.pard_estimate_drop.argtypes
+    lib.pard_estimate_drop_static.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, vp]
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
@@ -163,6 +164,18 @@ def pard_estimate_drop(plan: Plan, n: int, max_snapshot_requests: int, arrival, 
         _ptr(workspace), int(workspace.numel() * workspace.element_size()), _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_estimate_drop")
+    return rc
+
+
+def pard_estimate_drop_static(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now,
+                              est, drop, order, seg_ptr, status=None, stream=None, check: bool = True) -> int:
+    """pard_estimate_drop on the library's built-in scratch buffer (no workspace, nothing allocated)."""
+    rc = load_library().pard_estimate_drop_static(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage),
+        _ptr(snap_ptr), _ptr(now), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr), _ptr(status),
+        _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop_static")
     return rc
 
 

@@ -1,5 +1,6 @@
 // C-ABI of libpard (see include/pard.h): argument checks, plan upload, kernel launches.
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "pard_device.hpp"
@@ -22,6 +23,40 @@ constexpr int64_t kHeaderBytes = 256;      // workspace header: word 0 = status 
 
 int64_t align256(int64_t x) { return (x + 255) & ~(int64_t)255; }
 
+// Built-in scratch buffer of pard_estimate_drop_static.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[PARD_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of the current device's copy of the scratch buffer (nullptr on failure).
+void* static_scratch_for_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return nullptr; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// Hands the accumulated status bits to the caller and starts the next call from zero.
+__global__ void take_status_kernel(uint32_t* __restrict__ src, uint32_t* __restrict__ dst) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) { *dst = *src; *src = 0u; }
+}
+
+// What the estimate calls themselves use of a workspace: the header alone on the on-chip path, header and
+// sort buffers for larger snapshots.
+int64_t estimate_need(const pard_plan* p, int64_t n, int64_t max_snap) {
+    if (max_snap <= PARD_FUSED_SNAPSHOT_CAPACITY) return kHeaderBytes;
+    return kHeaderBytes + sort_workspace_bytes(p->host.K, p->host.S, n);
+}
+
+// What pard_workspace_bytes reports: enough for the estimate calls and for pard_compact.
 int64_t workspace_need(const pard_plan* p, int64_t n, int64_t max_snap) {
     int64_t need = compact_workspace_bytes(n, p->host.K);
     if (max_snap > PARD_FUSED_SNAPSHOT_CAPACITY) {
@@ -147,7 +182,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
                               const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
                               const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub, bool consistent,
                               int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
-                              void* d_workspace, int64_t workspace_bytes, void* stream) {
+                              void* d_workspace, int64_t workspace_bytes, void* stream, bool own_buffer = false) {
     if (!plan || !d_snap_ptr || !d_now || !d_seg_ptr) return PARD_E_NULL;
     if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
@@ -155,7 +190,10 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
     const bool fused = max_snapshot_requests <= PARD_FUSED_SNAPSHOT_CAPACITY;
     if (!fused && !sort_supported(plan->host.K, plan->host.S, n, max_snapshot_requests)) return PARD_E_UNSUPPORTED;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
-        workspace_bytes < workspace_need(plan, n, max_snapshot_requests)) return PARD_E_WORKSPACE;
+        // a caller's workspace must be the size pard_workspace_bytes reports (it also serves pard_compact); the
+        // library's own buffer only has to hold what this call uses
+        workspace_bytes < (own_buffer ? estimate_need(plan, n, max_snapshot_requests)
+                                      : workspace_need(plan, n, max_snapshot_requests))) return PARD_E_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint32_t* status = static_cast<uint32_t*>(d_workspace);
     hipError_t e;
@@ -196,6 +234,29 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
                        void* d_workspace, int64_t workspace_bytes, void* stream) {
     return estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr, false,
                               d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream);
+}
+
+int pard_estimate_drop_static(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                              const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                              const int32_t* d_snap_ptr, const int32_t* d_now,
+                              int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                              uint32_t* d_status, void* stream) {
+    if (!plan) return PARD_E_NULL;
+    if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
+    // what the call will use of the buffer: the header alone on the on-chip path, header + sort buffers above it
+    if (max_snapshot_requests > PARD_FUSED_SNAPSHOT_CAPACITY &&
+        !sort_supported(plan->host.K, plan->host.S, n, max_snapshot_requests)) return PARD_E_UNSUPPORTED;
+    if (estimate_need(plan, n, max_snapshot_requests) > (int64_t)PARD_STATIC_SCRATCH_BYTES) return PARD_E_SCRATCH;
+    void* ptr = static_scratch_for_current_device();
+    if (!ptr) return PARD_E_HIP;
+    const int rc = estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr,
+                                      false, d_est, d_drop, d_order, d_seg_ptr, ptr, (int64_t)PARD_STATIC_SCRATCH_BYTES, stream, true);
+    if (rc != PARD_OK) return rc;
+    if (d_status) {
+        take_status_kernel<<<1, 64, 0, static_cast<hipStream_t>(stream)>>>(static_cast<uint32_t*>(ptr), d_status);
+        if (hipGetLastError() != hipSuccess) return PARD_E_HIP;
+    }
+    return PARD_OK;
 }
 
 int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
@@ -355,6 +416,7 @@ const char* pard_strerror(int status) {
         case PARD_E_WORKSPACE: return "workspace missing, misaligned or too small";
         case PARD_E_HIP: return "HIP runtime error";
         case PARD_E_BAD_MODE: return "unknown order mode";
+        case PARD_E_SCRATCH: return "the call needs more than the library's built-in scratch buffer holds (PARD_STATIC_SCRATCH_BYTES)";
         case PARD_E_UNSUPPORTED: return "not supported: bits of the snapshot bound plus bits of the queue count above 32 on the large-snapshot path, or a latency above 2^25 us for the sampled batch wait";
         default: return "unknown status";
     }
