@@ -51,9 +51,13 @@ __global__ void take_status_kernel(uint32_t* __restrict__ src, uint32_t* __restr
 
 // What the estimate calls themselves use of a workspace: the header alone on the on-chip path, header and
 // sort buffers for larger snapshots.
+// Layout of a workspace: header | one word per snapshot (marks of the on-chip path) | what the large-snapshot
+// path or pard_compact keep there.
+int64_t marks_bytes(const pard_plan* p) { return align256((int64_t)p->host.K * 4); }
+
 int64_t estimate_need(const pard_plan* p, int64_t n, int64_t max_snap) {
-    if (max_snap <= PARD_FUSED_SNAPSHOT_CAPACITY) return kHeaderBytes;
-    return kHeaderBytes + sort_workspace_bytes(p->host.K, p->host.S, n);
+    if (max_snap <= PARD_FUSED_SNAPSHOT_CAPACITY) return kHeaderBytes + marks_bytes(p);
+    return kHeaderBytes + marks_bytes(p) + sort_workspace_bytes(p->host.K, p->host.S, n);
 }
 
 // What pard_workspace_bytes reports: enough for the estimate calls and for pard_compact.
@@ -63,7 +67,7 @@ int64_t workspace_need(const pard_plan* p, int64_t n, int64_t max_snap) {
         int64_t s = sort_workspace_bytes(p->host.K, p->host.S, n);
         if (s > need) need = s;
     }
-    return kHeaderBytes + need;
+    return kHeaderBytes + marks_bytes(p) + need;
 }
 
 }  // namespace
@@ -142,6 +146,7 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     d.K = h.K; d.S = h.S; d.shared = h.shared; d.any_fcfs = h.any_fcfs ? 1 : 0;
     d.uniform_mode = h.uniform_mode;
     d.max_entries_per_dag = h.max_entries_per_dag;
+    d.presorted_ok = h.short_form_everywhere ? 1 : 0;
     d.recs = reinterpret_cast<const StageRec*>(d_recs);
     d.lat = reinterpret_cast<const int32_t*>(d_lat);
     d.dag_entry_ptr = reinterpret_cast<const int32_t*>(d_dep);
@@ -205,6 +210,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         a.est = d_est; a.drop = d_drop; a.order = d_order; a.seg_ptr = d_seg_ptr;
         a.sub = d_sub;
         a.status = status;
+        a.todo = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + kHeaderBytes);
         a.cap = (int32_t)max_snapshot_requests;
         a.consistent = consistent ? 1 : 0;
         a.n = n;
@@ -220,7 +226,7 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         a.sub = d_sub;
         a.consistent = consistent ? 1 : 0;
         a.status = status;
-        a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+        a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes + marks_bytes(plan);
         a.num_cus = plan->num_cus;
         e = launch_sort_path(a, s);
     }
@@ -388,7 +394,7 @@ int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_reques
     if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (n > 0 && (!d_order || !d_drop || !d_surv_idx)) return PARD_E_NULL;
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 255) != 0 ||
-        workspace_bytes < kHeaderBytes + compact_workspace_bytes(n, plan->host.K)) return PARD_E_WORKSPACE;
+        workspace_bytes < kHeaderBytes + marks_bytes(plan) + compact_workspace_bytes(n, plan->host.K)) return PARD_E_WORKSPACE;
     CompactArgs a{};
     a.num_segments = plan->host.K * plan->host.S;
     a.stages = plan->host.S;
@@ -397,7 +403,7 @@ int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_reques
     a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
     a.status = static_cast<uint32_t*>(d_workspace);
-    a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes;
+    a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes + marks_bytes(plan);
     a.resident_blocks = plan->compact_resident;
     hipError_t e = launch_compact(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;

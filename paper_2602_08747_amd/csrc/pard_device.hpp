@@ -17,6 +17,7 @@ struct PlanDev {
     int32_t K, S, shared, any_fcfs;
     int32_t uniform_mode;              // >= 0 when all stages share one order mode
     int32_t max_entries_per_dag;
+    int32_t presorted_ok;              // every stage admits the 32-bit short-queue form (see HostPlan)
     const StageRec* recs;              // [D*S]
     const int32_t* lat;                // [D*S*64]
     const int32_t* dag_entry_ptr;      // [D+1]
@@ -114,11 +115,17 @@ struct FusedArgs {
     int32_t *order, *seg_ptr;
     const int64_t* sub;                // [K*S] downstream latency per (snapshot, stage), or null: walk the paths
     uint32_t* status;
+    uint32_t* todo;                    // [K] scratch, or null: snapshots left to the general kernel by the one for
+                                       // snapshots that come in queue order
     int32_t cap;                       // promised bound on a snapshot's size
     int32_t consistent;                // positions count only the kept requests ahead
     int64_t n;                         // total requests (bounds every index derived from snap_ptr)
 };
 hipError_t launch_fused(const FusedArgs& a, hipStream_t stream);
+// Snapshots whose requests already come in queue order (launch_fused tries this first when it applies).
+constexpr int kPresortedMaxStages = 6;
+bool presorted_path_covers(const FusedArgs& a);
+hipError_t launch_presorted(const FusedArgs& a, hipStream_t stream);
 // Snapshots of at most 128 requests, one wave each (launch_fused hands these over itself).
 bool wave_path_covers(const FusedArgs& a);
 hipError_t launch_wave(const FusedArgs& a, hipStream_t stream);

@@ -512,6 +512,7 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     constexpr int kCap = CAP;
     __shared__ SnapshotLds<CAP, SCAP> L;
     const int u = blockIdx.x;
+    if (A.todo && A.todo[u] == 0u) return;       // already done by the kernel for snapshots that come in queue order
     const int64_t n = A.n;
     // snapshot bounds, made safe whatever snap_ptr holds
     int64_t lo = A.snap_ptr[u], hi = A.snap_ptr[u + 1];
@@ -556,8 +557,17 @@ void launch_capacity(const FusedArgs& a, hipStream_t stream) {
 
 }  // namespace
 
-hipError_t launch_fused(const FusedArgs& a, hipStream_t stream) {
-    if (wave_path_covers(a)) return launch_wave(a, stream);      // a few dozen requests per snapshot: one wave each
+hipError_t launch_fused(const FusedArgs& args, hipStream_t stream) {
+    FusedArgs a = args;
+    if (wave_path_covers(a)) { a.todo = nullptr; return launch_wave(a, stream); }      // a few dozen requests per snapshot: one wave each
+    // Snapshots in queue order are finished by the kernel made for them; it marks the others in todo[],
+    // and the general kernel below then works on the marked ones only (every other workgroup returns at once).
+    if (presorted_path_covers(a)) {
+        const hipError_t e = launch_presorted(a, stream);
+        if (e != hipSuccess) return e;
+    } else {
+        a.todo = nullptr;
+    }
     // the smallest workgroup whose capacity covers the promised snapshot size
     if (a.cap <= 256) launch_capacity<256, 64>(a, stream);
     else if (a.cap <= 512) launch_capacity<512, 64>(a, stream);

@@ -77,6 +77,8 @@ struct HostPlan {
     std::vector<int32_t> entry_end;         // [E]     one past the last entry of the entry's path
     std::vector<int32_t> entry_dag;         // [E]     the DAG an entry belongs to
     int32_t max_lat = 0;                    // largest latency-table entry
+    bool short_form_everywhere = true;      // every stage is kStageFast with latB / W < 2^17: wait + execution of a
+                                            // short queue fit 32 bits without a carry
 };
 
 // Validates one DAG and appends its source-to-sink paths.  Returns a pard_status.
@@ -173,6 +175,7 @@ inline int build_host_plan(const pard_plan_desc_t* d, HostPlan& hp) {
         const int32_t latB = d->lat_us[i * PARD_LAT_ENTRIES + B - 1];
         const uint32_t aW = (uint32_t)latB / (uint32_t)W, bW = (uint32_t)latB % (uint32_t)W;
         const int32_t fast = (W <= 256 && aW < (1u << 18)) ? kStageFast : 0;
+        if (!fast || aW >= (1u << 17)) hp.short_form_everywhere = false;
         hp.recs[(size_t)i] = StageRec{B, W, latB, M | fast, kb.m, kb.sh, kw.m, kw.sh,
                                       1.0f / (float)B, 1.0f / (float)W, aW, bW};
     }

@@ -362,6 +362,16 @@ def make_workload(cfg: int, n_requests: Optional[int] = None, n_snapshots: Optio
         stage=np.ascontiguousarray(stage, np.int32), snap_ptr=snap_ptr, now=now.astype(np.int32), notes=notes)
 
 
+def in_deadline_order(w: Workload) -> Workload:
+    """The same snapshots with the requests of every snapshot arranged by rising deadline (what a queue
+    snapshot taken in arrival order looks like when the pipeline has one SLO)."""
+    idx = np.arange(w.n, dtype=np.int64)
+    snap = np.repeat(np.arange(w.K, dtype=np.int64), np.diff(w.snap_ptr.astype(np.int64)))
+    perm = np.lexsort((idx, w.deadline, snap))
+    return dataclasses.replace(w, name=w.name + "-by-deadline", arrival=np.ascontiguousarray(w.arrival[perm]),
+                               deadline=np.ascontiguousarray(w.deadline[perm]), stage=np.ascontiguousarray(w.stage[perm]))
+
+
 def half_survivors(w: Workload) -> Workload:
     """A labelled variant of a single-snapshot workload (not one of the five configurations): the SLO is
     half the arrival span, `now` sits in the middle of it and the latency tables are scaled down by 200,
