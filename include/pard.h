@@ -218,6 +218,29 @@ int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_reques
                  int32_t* d_surv_idx, int32_t* d_surv_ptr,
                  void* d_workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * The whole path in one call: pard_estimate_drop followed by pard_compact, with the same outputs
+ * (Section 3.2 Eq.(1),(2),(4) for the estimate, Section 3.3 for the order, Section 4.1 for the kept
+ * requests that go on to batching).  Where the estimate kernels see a snapshot's queues complete in
+ * on-chip memory (promised bounds from 2049 to PARD_FUSED_SNAPSHOT_CAPACITY) they also count and stage
+ * its survivors, so that the compaction step neither counts nor reads d_order and d_drop again; for
+ * every other shape the call is the two calls one after the other.
+ *
+ *   d_surv_idx, d_surv_ptr   as for pard_compact
+ *   between_event            NULL, or a hipEvent_t that the call records on `stream` between the kernels of
+ *                            the estimate step and those of the compaction step (lets a caller time the steps)
+ *   everything else          as for pard_estimate_drop; the workspace must have the size pard_workspace_bytes
+ *                            reports (it holds one staged survivor slot per request on top of what the two
+ *                            separate calls need)
+ * Errors: those of pard_estimate_drop and pard_compact.
+ */
+int pard_estimate_drop_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                               const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                               const int32_t* d_snap_ptr, const int32_t* d_now,
+                               int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                               int32_t* d_surv_idx, int32_t* d_surv_ptr,
+                               void* d_workspace, int64_t workspace_bytes, void* between_event, void* stream);
+
 /* Variants of the downstream latency (Section 5.1 baseline table; Section 5.3 ablations). */
 enum { PARD_SUB_FULL = 0,        /* sum q_i + sum d_i + w, w = sampled lambda-quantile of the batch wait */
        PARD_SUB_LOWER = 1,       /* batch wait assumed 0            (the "-lower" ablation)                */

@@ -25,7 +25,7 @@ STATUS_NAMES = {
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
-           "pard_estimate_drop_ranked", "pard_estimate_drop_static",
+           "pard_estimate_drop_ranked", "pard_estimate_drop_static", "pard_estimate_drop_compact",
            "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
            "pard_sub_latency", "pard_sub_latency_q", "pard_queue_delay", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
@@ -63,6 +63,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_estimate_drop.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, i64, vp]
     lib.pard_estimate_drop_ranked.argtypes = lib.pard_estimate_drop.argtypes
     lib.pard_estimate_drop_static.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, vp]
+    lib.pard_estimate_drop_compact.argtypes = [vp, i64, i64] + [vp] * 11 + [vp, i64, vp, vp]
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
@@ -176,6 +177,21 @@ def pard_estimate_drop_static(plan: Plan, n: int, max_snapshot_requests: int, ar
         _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_estimate_drop_static")
+    return rc
+
+
+def pard_estimate_drop_compact(plan: Plan, n: int, max_snapshot_requests: int, arrival, deadline, stage, snap_ptr, now,
+                               est, drop, order, seg_ptr, surv_idx, surv_ptr, workspace, between_event=None, stream=None,
+                               check: bool = True) -> int:
+    """The whole path in one call (estimate, drop decision, survivor queues).  between_event: a raw hipEvent_t
+    handle (int) recorded between the two steps, or None."""
+    rc = load_library().pard_estimate_drop_compact(
+        plan.handle, int(n), int(max_snapshot_requests), _ptr(arrival), _ptr(deadline), _ptr(stage),
+        _ptr(snap_ptr), _ptr(now), _ptr(est), _ptr(drop), _ptr(order), _ptr(seg_ptr), _ptr(surv_idx), _ptr(surv_ptr),
+        _ptr(workspace), int(workspace.numel() * workspace.element_size()),
+        ctypes.c_void_p(between_event) if between_event else ctypes.c_void_p(None), _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_estimate_drop_compact")
     return rc
 
 
@@ -348,6 +364,12 @@ class Session:
     def run(self, stream=None, sub=None, consistent=False, ranked=False):
         self.estimate_drop(stream, sub, consistent, ranked)
         self.compact(stream)
+
+    def run_one_call(self, stream=None, between_event=None):
+        """The whole path through pard_estimate_drop_compact."""
+        pard_estimate_drop_compact(self.plan, self.n, self.max_snap, self.arrival, self.deadline, self.stage, self.snap_ptr,
+                                   self.now, self.est, self.drop, self.order, self.seg_ptr, self.surv_idx, self.surv_ptr,
+                                   self.workspace, between_event, stream)
 
     def status_word(self) -> int:
         return int(self.workspace[0].item())

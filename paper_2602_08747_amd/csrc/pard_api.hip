@@ -60,9 +60,16 @@ int64_t estimate_need(const pard_plan* p, int64_t n, int64_t max_snap) {
     return kHeaderBytes + marks_bytes(p) + sort_workspace_bytes(p->host.K, p->host.S, n);
 }
 
-// What pard_workspace_bytes reports: enough for the estimate calls and for pard_compact.
+// Behind the compaction's own region: what pard_estimate_drop_compact stages for it (survivors of the snapshot
+// before each of its queues, one survivor slot per request).
+int64_t staging_bytes(const pard_plan* p, int64_t n, int64_t max_snap) {
+    if (!compact_per_snapshot(max_snap)) return 0;
+    return align256((int64_t)p->host.K * p->host.S * 4) + align256(n * 4);
+}
+
+// What pard_workspace_bytes reports: enough for the estimate calls, for pard_compact and for the call that does both.
 int64_t workspace_need(const pard_plan* p, int64_t n, int64_t max_snap) {
-    int64_t need = compact_workspace_bytes(n, p->host.K);
+    int64_t need = compact_workspace_bytes(n, p->host.K) + staging_bytes(p, n, max_snap);
     if (max_snap > PARD_FUSED_SNAPSHOT_CAPACITY) {
         int64_t s = sort_workspace_bytes(p->host.K, p->host.S, n);
         if (s > need) need = s;
@@ -187,7 +194,8 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
                               const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
                               const int32_t* d_snap_ptr, const int32_t* d_now, const int64_t* d_sub, bool consistent,
                               int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
-                              void* d_workspace, int64_t workspace_bytes, void* stream, bool own_buffer = false) {
+                              void* d_workspace, int64_t workspace_bytes, void* stream, bool own_buffer = false,
+                              bool stage_survivors = false) {
     if (!plan || !d_snap_ptr || !d_now || !d_seg_ptr) return PARD_E_NULL;
     if (n < 0 || n >= ((int64_t)1 << 30) || max_snapshot_requests < 0) return PARD_E_BAD_SHAPE;
     if (n > 0 && (!d_deadline || !d_stage || !d_est || !d_drop || !d_order)) return PARD_E_NULL;
@@ -211,6 +219,14 @@ static int estimate_drop_impl(const pard_plan_t* plan, int64_t n, int64_t max_sn
         a.sub = d_sub;
         a.status = status;
         a.todo = reinterpret_cast<uint32_t*>(static_cast<char*>(d_workspace) + kHeaderBytes);
+        if (stage_survivors) {
+            // the compaction's region starts with its per-snapshot counts; the staging arrays follow the region
+            char* region = static_cast<char*>(d_workspace) + kHeaderBytes + marks_bytes(plan);
+            char* stage = region + compact_workspace_bytes(n, plan->host.K);
+            a.kept = reinterpret_cast<uint32_t*>(region);
+            a.loc_ptr = reinterpret_cast<int32_t*>(stage);
+            a.staged = reinterpret_cast<int32_t*>(stage + align256((int64_t)plan->host.K * plan->host.S * 4));
+        }
         a.cap = (int32_t)max_snapshot_requests;
         a.consistent = consistent ? 1 : 0;
         a.n = n;
@@ -263,6 +279,44 @@ int pard_estimate_drop_static(const pard_plan_t* plan, int64_t n, int64_t max_sn
         if (hipGetLastError() != hipSuccess) return PARD_E_HIP;
     }
     return PARD_OK;
+}
+
+int pard_estimate_drop_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,
+                               const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                               const int32_t* d_snap_ptr, const int32_t* d_now,
+                               int32_t* d_est, uint8_t* d_drop, int32_t* d_order, int32_t* d_seg_ptr,
+                               int32_t* d_surv_idx, int32_t* d_surv_ptr,
+                               void* d_workspace, int64_t workspace_bytes, void* between_event, void* stream) {
+    if (!plan || !d_surv_ptr) return PARD_E_NULL;
+    if (n > 0 && !d_surv_idx) return PARD_E_NULL;
+    const bool prepared = n > 0 && max_snapshot_requests >= 0 && compact_per_snapshot(max_snapshot_requests);
+    int rc = estimate_drop_impl(plan, n, max_snapshot_requests, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, nullptr, false,
+                                d_est, d_drop, d_order, d_seg_ptr, d_workspace, workspace_bytes, stream, false, prepared);
+    if (rc != PARD_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (between_event && hipEventRecord(static_cast<hipEvent_t>(between_event), s) != hipSuccess) {
+        (void)hipGetLastError();
+        return PARD_E_HIP;
+    }
+    if (!prepared)
+        return pard_compact(plan, n, max_snapshot_requests, d_order, d_seg_ptr, d_drop, d_surv_idx, d_surv_ptr, d_workspace,
+                            workspace_bytes, stream);
+    char* region = static_cast<char*>(d_workspace) + kHeaderBytes + marks_bytes(plan);
+    char* stage = region + compact_workspace_bytes(n, plan->host.K);
+    CompactArgs a{};
+    a.num_segments = plan->host.K * plan->host.S;
+    a.stages = plan->host.S;
+    a.max_snapshot = max_snapshot_requests;
+    a.n = n;
+    a.order = d_order; a.seg_ptr = d_seg_ptr; a.drop = d_drop;
+    a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
+    a.status = static_cast<uint32_t*>(d_workspace);
+    a.workspace = region;
+    a.resident_blocks = plan->compact_resident;
+    a.kept = reinterpret_cast<const uint32_t*>(region);
+    a.loc_ptr = reinterpret_cast<const int32_t*>(stage);
+    a.staged = reinterpret_cast<const int32_t*>(stage + align256((int64_t)plan->host.K * plan->host.S * 4));
+    return launch_compact(a, s) == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
 int pard_estimate_drop_sub(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,

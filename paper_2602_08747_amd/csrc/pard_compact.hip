@@ -631,7 +631,37 @@ __global__ __launch_bounds__(THREADS, 4) void compact_local_kernel(CompactArgs A
     }
 }
 
+// After an estimate call that staged every snapshot's survivors (in queue order, from the snapshot's first
+// request's place on) and a scan of the per-snapshot counts: one wave per snapshot moves its survivors and queue
+// offsets to their final place.  Everything a wave needs first comes from one round of independent loads, the
+// survivors from a second one.  (Measured alternatives for 4096 snapshots: every wave adding up all earlier
+// counts itself 22 us - all waves of the device read the same few cache lines at once; 64 workgroups that add
+// them up once and move 64 snapshots each 52 us - too few, too long chains of dependent loads.)
+__global__ __launch_bounds__(kWave) void move_staged_kernel(CompactArgs A, const uint32_t* snap_off) {
+    const int lane = threadIdx.x;
+    const int64_t u = blockIdx.x, K = A.num_segments / A.stages;
+    const int64_t a = A.seg_ptr[u * A.stages], b = A.seg_ptr[(u + 1) * A.stages];
+    const uint32_t mine = A.kept[u], first = snap_off[u];
+    const uint32_t loc = lane < A.stages ? (uint32_t)A.loc_ptr[u * A.stages + lane] : 0u;
+    if (a < 0 || b > A.n || b - a < (int64_t)mine || b - a > (int64_t)PARD_FUSED_SNAPSHOT_CAPACITY ||
+        (int64_t)first + mine > A.n) return;                                            // only after a broken promise
+    const int32_t* __restrict__ src = A.staged + a + staging_shift(u, (uint32_t)(b - a), mine);
+    int32_t* __restrict__ dst = A.surv_idx;
+    for (uint32_t i0 = 0; i0 < mine; i0 += 16 * kWave) {
+        int32_t v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = i0 + i * kWave + lane < mine ? src[i0 + i * kWave + lane] : 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (i0 + i * kWave + lane < mine) dst[first + i0 + i * kWave + lane] = v[i];
+    }
+    if (lane < A.stages) A.surv_ptr[u * A.stages + lane] = (int32_t)(first + loc);
+    if (u + 1 == K && lane == 0) A.surv_ptr[K * A.stages] = (int32_t)(first + mine);
+}
+
 }  // namespace
+
+bool compact_per_snapshot(int64_t max_snapshot) { return max_snapshot > kLocalMin && max_snapshot <= kLCap; }
 
 int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots) {
     const int64_t tiles = (n + kCTile - 1) / kCTile;
@@ -656,10 +686,15 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
         compact_empty_kernel<<<(a.num_segments + 256) / 256, 256, 0, stream>>>(a.surv_ptr, a.num_segments);
         return hipGetLastError();
     }
-    if (a.max_snapshot > kLocalMin && a.max_snapshot <= kLCap) {      // every snapshot fits one workgroup
+    if (compact_per_snapshot(a.max_snapshot)) {      // every snapshot fits one workgroup
         const int64_t K = a.num_segments / a.stages;
         uint32_t* kept = static_cast<uint32_t*>(a.workspace);
         uint32_t* snap_off = kept + ((K * 4 + 255) & ~(int64_t)255) / 4;
+        if (a.staged) {                              // counted and staged by the estimate kernels: only the move is left
+            snapshot_offsets_kernel<<<1, 1024, 0, stream>>>(a.kept, K, snap_off);
+            move_staged_kernel<<<(unsigned)K, kWave, 0, stream>>>(a, snap_off);
+            return hipGetLastError();
+        }
         // the smaller workgroup that covers the promised snapshot bound; up to 16 * THREADS snapshots every
         // workgroup adds up the counts before it itself, beyond that one workgroup scans them first
         auto run = [&](auto threads_tag, auto count_tag) {

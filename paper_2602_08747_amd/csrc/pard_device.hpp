@@ -105,6 +105,27 @@ __device__ __forceinline__ uint32_t lane_id() {
     return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
 }
 
+// Inclusive prefix sum across the 64 lanes of a wave, on the vector ALU's data-parallel
+// primitives: four shifts inside each row of 16 lanes, then the last lane of rows 0 and 2 is
+// added to rows 1 and 3, and lane 31 to the upper half.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);    // row_shr:1
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);    // row_shr:2
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);    // row_shr:4
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);    // row_shr:8
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);    // row_bcast:15 into rows 1, 3
+    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);    // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// Where a snapshot's staged survivors start inside the snapshot's own stretch of the staging array.  Snapshots
+// of equal size start at equal distances; if every one staged its few survivors at its very start, they would
+// all fall into the same few memory channels (measured: the kernel that moves them ran at an eighth of the
+// bandwidth).  Eight consecutive snapshots therefore start at eight different eighths of the free room.
+__host__ __device__ __forceinline__ uint32_t staging_shift(int64_t u, uint32_t requests, uint32_t survivors) {
+    return ((uint32_t)(u & 7) * ((requests - survivors) >> 3)) & ~15u;
+}
+
 // ---- launchers implemented in the .hip files (host functions) ----------------
 
 struct FusedArgs {
@@ -117,6 +138,10 @@ struct FusedArgs {
     uint32_t* status;
     uint32_t* todo;                    // [K] scratch, or null: snapshots left to the general kernel by the one for
                                        // snapshots that come in queue order
+    // survivor compaction in the same pass (all three null otherwise):
+    uint32_t* kept;                    // [K] out: survivors of every snapshot
+    int32_t* staged;                   // [n] out: a snapshot's survivors in queue order from its first request's place on
+    int32_t* loc_ptr;                  // [K*S] out: survivors of the snapshot before each of its queues
     int32_t cap;                       // promised bound on a snapshot's size
     int32_t consistent;                // positions count only the kept requests ahead
     int64_t n;                         // total requests (bounds every index derived from snap_ptr)
@@ -171,7 +196,14 @@ struct CompactArgs {
     uint32_t* status;
     void* workspace;
     int32_t resident_blocks;           // workgroups of the compaction kernel the device holds at once
+    // after an estimate call that counted and staged the survivors along the way (all three null otherwise):
+    const uint32_t* kept;              // [K] survivors per snapshot
+    const int32_t* staged;             // [n] a snapshot's survivors in queue order, from its first request's place on
+    const int32_t* loc_ptr;            // [K*S] survivors of the snapshot before each of its queues
 };
+// True when pard_compact gives every snapshot to one workgroup for this promised bound (the form the
+// estimate kernels can prepare).
+bool compact_per_snapshot(int64_t max_snapshot);
 int compact_blocks_per_cu();
 int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);

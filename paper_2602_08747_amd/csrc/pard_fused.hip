@@ -61,6 +61,7 @@ struct SnapshotLds {
     __align__(16) uint32_t quick[SCAP][8];   // per stage: B-1, 1/B, 1/W, aW, bW, queue start (short-queue form)
     uint32_t slow_stages;                            // set when some stage cannot use the short-queue form
     uint32_t wave_tot[16];
+    uint32_t kept_tot[16][2];                        // survivor staging: kept slots per wave and group of loads
     uint32_t red[2];
 };
 
@@ -466,6 +467,11 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
                 }
             }
         }
+        if (A.kept) {                        // survivor staging below: a dropped request's queue slot carries the decision
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (live(base + c) && drp[c]) ord_l[se[g][c] & 0x1FFFu] = (uint16_t)((uint32_t)(base + c) | 0x8000u);
+        }
         if (whole(base)) {
             *reinterpret_cast<int4*>(A.est + lo_s + base) = make_int4(est[0], est[1], est[2], est[3]);
             *reinterpret_cast<uint32_t*>(A.drop + lo_s + base) =
@@ -479,32 +485,92 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
     __syncthreads();
 
     // ---- queue order and queue offsets out ----------------------------------------------
+    // (an entry of ord_l[] is local index | drop << 15; the drop bit is only set when survivors are staged)
+    uint32_t ent[G][4];
+    const int32_t b32 = (int32_t)lo_s;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ent[g][c] = 0x8000u;         // not a slot: counts as dropped below
         if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
         // queue slot q sits at order[lo + q] = order[lo_s + (q + off)]: the same shifted groups of four;
         // its entry is the request with local index ord_l[q], i.e. request lo_s + ord_l[q]
-        const int32_t b32 = (int32_t)lo_s;
         if (whole(base)) {
-            int32_t r4[4];
             if (off == 0) {
                 const uint2 o = *reinterpret_cast<const uint2*>(ord_l + base);
-                r4[0] = (int32_t)(o.x & 0xFFFFu); r4[1] = (int32_t)(o.x >> 16);
-                r4[2] = (int32_t)(o.y & 0xFFFFu); r4[3] = (int32_t)(o.y >> 16);
+                ent[g][0] = o.x & 0xFFFFu; ent[g][1] = o.x >> 16;
+                ent[g][2] = o.y & 0xFFFFu; ent[g][3] = o.y >> 16;
             } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) r4[c] = (int32_t)ord_l[base - off + c];
+                for (int c = 0; c < 4; ++c) ent[g][c] = ord_l[base - off + c];
             }
-            *reinterpret_cast<int4*>(A.order + lo_s + base) = make_int4(b32 + r4[0], b32 + r4[1], b32 + r4[2], b32 + r4[3]);
+            *reinterpret_cast<int4*>(A.order + lo_s + base) =
+                make_int4(b32 + (int32_t)(ent[g][0] & 0x7FFFu), b32 + (int32_t)(ent[g][1] & 0x7FFFu),
+                          b32 + (int32_t)(ent[g][2] & 0x7FFFu), b32 + (int32_t)(ent[g][3] & 0x7FFFu));
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                if (live(base + c)) A.order[lo_s + base + c] = b32 + (int32_t)ord_l[base - off + c];
+                if (live(base + c)) {
+                    ent[g][c] = ord_l[base - off + c];
+                    A.order[lo_s + base + c] = b32 + (int32_t)(ent[g][c] & 0x7FFFu);
+                }
         }
     }
     if (tid < S) A.seg_ptr[(int64_t)u * S + tid] = (int32_t)lo + L.seg_start[tid];
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
+    if (CONSISTENT || !A.kept) return;
+
+    // ---- survivors of this snapshot in queue order, staged at the snapshot's own place ----------
+    // (the compaction's last kernel moves them to their final place once the counts of all snapshots are known)
+    // Queue slots run group-major here: group g of thread t holds the shifted slots [(g T + t) 4, +4).
+    static_assert(G <= 4, "two words of two 16-bit counts");
+    uint32_t keep[G];
+    uint32_t c01 = 0, c23 = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        keep[g] = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) keep[g] |= ((ent[g][c] >> 15) ^ 1u) << c;
+        const uint32_t cnt = (uint32_t)__popc(keep[g]);
+        if (g < 2) c01 |= cnt << (16 * g); else c23 |= cnt << (16 * (g - 2));
+    }
+    const uint32_t i01 = wave_inclusive_sum(c01), i23 = wave_inclusive_sum(c23);
+    if (lane == kWave - 1) { L.kept_tot[wave][0] = i01; L.kept_tot[wave][1] = i23; }
+    __syncthreads();
+    uint32_t tot01 = 0, tot23 = 0, bef01 = 0, bef23 = 0;       // all waves / the waves before this one
+#pragma unroll
+    for (int w = 0; w < T / kWave; ++w) {
+        const uint32_t a = L.kept_tot[w][0], b = L.kept_tot[w][1];
+        tot01 += a; tot23 += b;
+        if (w < wave) { bef01 += a; bef23 += b; }
+    }
+    const uint32_t gt[4] = {tot01 & 0xFFFFu, tot01 >> 16, tot23 & 0xFFFFu, tot23 >> 16};
+    const uint32_t total = gt[0] + gt[1] + gt[2] + gt[3];
+    const uint32_t x01 = bef01 + i01 - c01, x23 = bef23 + i23 - c23;
+    int32_t* stage_at = A.staged + lo + staging_shift(u, (uint32_t)m, total);
+    uint32_t* grp = L.low;                   // free by now: per group of four slots the kept slots before it | keep bits << 14
+    uint32_t groups_before = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        uint32_t o = groups_before + (g < 2 ? (x01 >> (16 * g)) & 0xFFFFu : (x23 >> (16 * (g - 2))) & 0xFFFFu);
+        groups_before += gt[g];
+        grp[g * T + tid] = o | (keep[g] << 14);
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep[g] & (1u << c)) { stage_at[o] = b32 + (int32_t)(ent[g][c] & 0x7FFFu); ++o; }
+    }
+    __syncthreads();
+    for (int k = tid; k < S; k += T) {
+        const int ps = L.seg_start[k] + off;             // the queue's first slot in this layout
+        uint32_t before = total;
+        if (ps < m_s) {
+            const uint32_t v = grp[ps >> 2];
+            before = (v & 0x3FFFu) + (uint32_t)__popc((v >> 14) & ((1u << (ps & 3)) - 1u));
+        }
+        A.loc_ptr[(int64_t)u * S + k] = (int32_t)before;
+    }
+    if (tid == 0) A.kept[u] = total;
 }
 
 template <int T, int CAP, int SCAP, bool CONSISTENT>

@@ -71,21 +71,9 @@ struct PresortedLds {
     unsigned long long down[kPsStages];
     int32_t seg_start[kPsStages + 1];
     uint32_t disorder[T / kWave];                             // per wave: it saw a deadline fall
+    uint32_t ktot[SUB];                                       // kept slots per sub-block
     uint32_t verdict;                                         // 0: in order and finished here, 1: left to the general kernel
 };
-
-// Inclusive prefix sum across the 64 lanes of a wave, on the vector ALU's data-parallel
-// primitives: four shifts inside each row of 16 lanes, then the last lane of rows 0 and 2 is
-// added to rows 1 and 3, and lane 31 to the upper half.
-__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);    // row_shr:1
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);    // row_shr:2
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);    // row_shr:4
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);    // row_shr:8
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);    // row_bcast:15 into rows 1, 3
-    v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);    // row_bcast:31 into rows 2, 3
-    return v;
-}
 
 // Value of the previous lane (lane 0 keeps `own`).
 __device__ __forceinline__ int32_t from_previous_lane(int32_t v, int32_t own) {
@@ -139,6 +127,7 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
         uint32_t* dst = reinterpret_cast<uint32_t*>(L.recs);
         for (int i = tid; i < S * (int)(sizeof(StageRec) / 4); i += T) dst[i] = src[i];
         if (tid < kPsStages) L.down[tid] = 0;
+        if (tid < SUB) L.ktot[tid] = 0;
         if (tid >= S && tid < 8) *reinterpret_cast<uint4*>(&L.quick[tid][0]) = *reinterpret_cast<uint4*>(&L.quick[tid][4]) = make_uint4(0, 0, 0, 0);
     }
 
@@ -275,7 +264,6 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
         for (int c = 0; c < 4; ++c) {
             const uint32_t k = (sr[j] >> (8 * c)) & 7u;     // slots that are not live compute on the zeroed rows of stage 7 and are discarded
             const uint32_t slot = (uint32_t)fs[k] + ((uint32_t)(before >> (k * 10u)) & 1023u) + ((sr[j] >> (8 * c + 3)) & 7u);
-            if (live(base + c)) L.ord[slot] = (uint16_t)(base + c);
             const uint4 qa = *reinterpret_cast<const uint4*>(&L.quick[k][0]);     // B-1, 1/B, 1/W, aW
             const uint4 qb = *reinterpret_cast<const uint4*>(&L.quick[k][4]);     // bW, queue start, downstream
             const uint32_t pos = slot - qb.y;
@@ -286,6 +274,10 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
             const uint64_t dn = (uint64_t)qb.z | ((uint64_t)qb.w << 32);
             const uint64_t e64 = (uint64_t)wait + L.lat[k * PARD_LAT_ENTRIES + seen] + dn;
             finish_request(e64, now, dl[j][c], est[c], drp[c]);
+            if (live(base + c)) {
+                L.ord[slot] = (uint16_t)((uint32_t)(base + c) | ((uint32_t)drp[c] << 15));   // local index < 2^13
+                if (A.kept && !drp[c]) atomicAdd(&L.ktot[(slot + (uint32_t)off) >> 8], 1u);     // kept slots per sub-block of the slot layout
+            }
         }
         if (whole(base)) {
             out_store(reinterpret_cast<int4*>(A.est + lo_s + base), make_int4(est[0], est[1], est[2], est[3]));
@@ -300,30 +292,80 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
     __syncthreads();
 
     // ---- queue order and queue offsets out --------------------------------------------------------
+    // (an entry of ord[] is local index | drop << 15)
     const int32_t b32 = (int32_t)lo_s;
+    uint32_t entry[4][4];                    // this thread's sixteen queue slots (slot = local index - off)
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int base = wbase + j * 256;
         // queue slot q sits at order[lo + q] = order[lo_s + (q + off)]
         if (whole(base)) {
-            int32_t r4[4];
             if (off == 0) {
                 const uint2 o = *reinterpret_cast<const uint2*>(L.ord + base);
-                r4[0] = (int32_t)(o.x & 0xFFFFu); r4[1] = (int32_t)(o.x >> 16);
-                r4[2] = (int32_t)(o.y & 0xFFFFu); r4[3] = (int32_t)(o.y >> 16);
+                entry[j][0] = o.x & 0xFFFFu; entry[j][1] = o.x >> 16;
+                entry[j][2] = o.y & 0xFFFFu; entry[j][3] = o.y >> 16;
             } else {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) r4[c] = (int32_t)L.ord[base - off + c];
+                for (int c = 0; c < 4; ++c) entry[j][c] = L.ord[base - off + c];
             }
-            out_store(reinterpret_cast<int4*>(A.order + lo_s + base), make_int4(b32 + r4[0], b32 + r4[1], b32 + r4[2], b32 + r4[3]));
+            out_store(reinterpret_cast<int4*>(A.order + lo_s + base),
+                      make_int4(b32 + (int32_t)(entry[j][0] & 0x7FFFu), b32 + (int32_t)(entry[j][1] & 0x7FFFu),
+                                b32 + (int32_t)(entry[j][2] & 0x7FFFu), b32 + (int32_t)(entry[j][3] & 0x7FFFu)));
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
-                if (live(base + c)) A.order[lo_s + base + c] = b32 + (int32_t)L.ord[base - off + c];
+            for (int c = 0; c < 4; ++c) {
+                entry[j][c] = 0x8000u;       // not a slot: counts as dropped below
+                if (live(base + c)) {
+                    entry[j][c] = L.ord[base - off + c];
+                    A.order[lo_s + base + c] = b32 + (int32_t)(entry[j][c] & 0x7FFFu);
+                }
+            }
         }
     }
     if (tid < S) A.seg_ptr[(int64_t)u * S + tid] = (int32_t)lo + L.seg_start[tid];
     if (u == P.K - 1 && tid == 0) A.seg_ptr[(int64_t)P.K * S] = (int32_t)(lo + m);
+    if (!A.kept) return;
+
+    // ---- survivors of this snapshot in queue order, staged at the snapshot's own place ----------------
+    // (the compaction's last kernel moves them to their final place once the counts of all snapshots are known)
+    uint32_t keep[4];
+    uint32_t c0 = 0, c1 = 0;                 // kept slots per sub-block: three 10-bit fields, and the fourth
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        keep[j] = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) keep[j] |= ((entry[j][c] >> 15) ^ 1u) << c;
+        const uint32_t cnt = (uint32_t)__popc(keep[j]);
+        if (j < 3) c0 |= cnt << (10 * j); else c1 = cnt;
+    }
+    const uint32_t i0 = wave_inclusive_sum(c0), i1 = wave_inclusive_sum(c1);
+    // kept slots in earlier sub-blocks: every wave scans the sub-block totals itself
+    const uint32_t tk = lane < SUB ? L.ktot[lane] : 0u;
+    const uint32_t ik = wave_inclusive_sum(tk);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)ik, kWave - 1);
+    const uint32_t xk = ik - tk;
+    const uint32_t e0 = i0 - c0, e1 = i1 - c1;
+    int32_t* stage_at = A.staged + lo + staging_shift(u, (uint32_t)m, total);
+    // a queue's first slot, in this layout, for the threads that happen to hold it
+    int qs[kPsStages];
+#pragma unroll
+    for (int k = 0; k < kPsStages; ++k) qs[k] = L.seg_start[k] + off;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int base = wbase + j * 256;
+        const uint32_t sub_before = (uint32_t)__builtin_amdgcn_readlane((int)xk, wave * 4 + j);
+        uint32_t o = sub_before + (j < 3 ? (e0 >> (10 * j)) & 1023u : e1);
+        // survivors of the snapshot before each queue: written by whoever holds the queue's first slot
+#pragma unroll
+        for (int k = 0; k < kPsStages; ++k)
+            if (k < S && (qs[k] >> 2) == (base >> 2) && qs[k] < m_s)
+                A.loc_ptr[(int64_t)u * S + k] = (int32_t)(o + (uint32_t)__popc(keep[j] & ((1u << (qs[k] & 3)) - 1u)));
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (keep[j] & (1u << c)) { stage_at[o] = b32 + (int32_t)(entry[j][c] & 0x7FFFu); ++o; }
+    }
+    if (tid < S && L.seg_start[tid] + off >= m_s) A.loc_ptr[(int64_t)u * S + tid] = (int32_t)total;   // queues that start at the end
+    if (tid == 0) A.kept[u] = total;
 }
 
 // Six waves per SIMD (three workgroups of 512 per compute unit): measured faster than four (128 registers) and

@@ -38,6 +38,14 @@ def check(gpu, oracle_mod, w, max_snap=None, threads=8):
                                  f"first bad {None if bad is None else bad[:8]}; "
                                  f"got {None if bad is None else got[k][bad[:8]]} want {None if bad is None else ref[k][bad[:8]]}")
     assert s.status_word() == 0
+    # the whole path in one call leaves the same outputs
+    for t in (s.est, s.drop, s.order, s.seg_ptr, s.surv_idx, s.surv_ptr):
+        t.fill_(0x55)
+    s.run_one_call()
+    got = s.results()
+    for k in KEYS:
+        assert np.array_equal(got[k], ref[k]), (w.name, "one call", k)
+    assert s.status_word() == 0
     return s, ref
 
 
