@@ -58,6 +58,15 @@
  * are hand-worked windows, the closed form of a linearly weighted mean over equally spaced
  * samples, and an exact-rational brute force (tests/test_oracle_window.py).
  *
+ * Reactive baselines on the same snapshot (Section 5.1 "Baselines"): pard_oracle_nexus_drop() is the
+ * reactive policy the paper describes for Nexus (scan the queue in arrival order with a window of one
+ * batch, stop at the first window whose requests can all still finish the current module, drop everything
+ * before it); pard_oracle_clipper_drop() is Clipper++ (the end-to-end SLO divided among the modules in
+ * proportion to their execution durations, a request is dropped once it has used up the budget of the
+ * modules up to and including its own).  The paper prints no value for either, and a snapshot has to read
+ * both rules (see the comments at the functions): parity with the paper is unpinned; the pins are
+ * hand-worked queues, closed forms and independent Python brute forces (tests/test_oracle_reactive.py).
+ *
  * Parity status: no value in the paper pins the estimate/drop path (it prints none for it).
  * The pins are brute force on tiny inputs, closed forms, invariants and a hand-worked
  * vector (tests/test_oracle_*.py).
@@ -643,4 +652,108 @@ int pard_oracle_compact(int32_t K, int32_t S, int64_t n,
     }
     surv_ptr[(int64_t)K * S] = (int32_t)out;
     return 0;
+}
+
+
+/* ---- reactive baselines (Section 5.1, "Baselines") ------------------------------------------
+ *
+ * Nexus.  "scans the queue in arrival order with a sliding window equal to the batch size, stopping at the
+ * first position where all requests in the window can meet the current module's latency budget and
+ * dropping all earlier ones".  On a snapshot: the queues are given in the order to scan (order/seg_ptr as
+ * written by the estimate call; a plan whose stages use arrival order gives the paper's baseline).  For
+ * queue (u, s) with batch size B and n requests, the window at position p holds the requests at positions
+ * p .. p + w - 1, w = min(B, n - p) (the last windows are cut off by the end of the queue); its requests run
+ * as one batch of w, which takes lat[w]; a request can meet the module's budget when that batch ends no
+ * later than its deadline, now + lat[w] <= deadline.  first_kept = the first p whose whole window can
+ * (n when no window can); the requests at positions before first_kept are dropped, all others kept.
+ * Nothing downstream is looked at (the paper: "without considering latency budget for subsequent modules").
+ */
+int pard_oracle_nexus_drop(int32_t K, int32_t S, int32_t dag_shared, const int32_t* batch, const int32_t* lat_us,
+                           int64_t n, const int32_t* deadline, const int32_t* order, const int32_t* seg_ptr,
+                           const int32_t* now, uint8_t* drop_out, int32_t* first_kept_out) {
+    if (K < 1 || S < 1 || n < 0) return 1;
+    for (int32_t u = 0; u < K; ++u)
+        for (int32_t s = 0; s < S; ++s) {
+            const int64_t g = (int64_t)u * S + s;
+            const int64_t rec = dag_shared ? s : g;
+            const int32_t B = batch[rec];
+            const int32_t* lat = lat_us + rec * LAT_ENTRIES;
+            const int64_t a = seg_ptr[g], len = (int64_t)seg_ptr[g + 1] - a;
+            int64_t first = len;
+            for (int64_t p = 0; p < len && first == len; ++p) {
+                const int64_t w = len - p < B ? len - p : B;
+                const wide_t batch_end = (wide_t)now[u] + (wide_t)lat[w - 1];
+                int all_meet = 1;
+                for (int64_t i = 0; i < w; ++i)
+                    if (batch_end > (wide_t)deadline[order[a + p + i]]) all_meet = 0;
+                if (all_meet) first = p;
+            }
+            first_kept_out[g] = (int32_t)first;
+            for (int64_t j = 0; j < len; ++j) drop_out[order[a + j]] = j < first ? 1 : 0;
+        }
+    return 0;
+}
+
+/* Clipper++.  "proportionally dividing the end-to-end SLO among modules based on their execution durations,
+ * SLO_k = SLO * d_k / sum_i d_i, and making drop decisions based on these per-module budgets"; Clipper itself
+ * "drops requests only if they already exceed the latency objective before inference".  On a snapshot a
+ * request carries the time it was sent (arrival) and its deadline, so SLO = deadline - arrival, and what it
+ * has used so far is now - arrival; the time it entered its current module is not known.  The budgets of
+ * the modules up to and including the current one add up to SLO * P_k / T_k, where d_i = lat_i[B_i] is a
+ * module's execution duration at its batch size, P_k the summed durations from a source to k (k included)
+ * and T_k the summed durations of a whole source-to-sink path through k; for a DAG both are taken along the
+ * longest such path (P_k = longest way in, T_k = P_k + longest way out).  The request is dropped when it has
+ * already used more than that:  now - arrival > SLO * P_k / T_k  (exactly, as rationals: no rounding), which
+ * for one module is Clipper's own rule, now > deadline.  T_k = 0 (all durations zero) reads as P_k / T_k = 1.
+ */
+int pard_oracle_clipper_drop(int32_t K, int32_t S, int32_t dag_shared, const int32_t* dag_row_ptr, const int32_t* dag_col,
+                             const int32_t* batch, const int32_t* lat_us, int64_t n, const int32_t* arrival,
+                             const int32_t* deadline, const int32_t* stage, const int32_t* snap_ptr, const int32_t* now,
+                             uint8_t* drop_out) {
+    if (K < 1 || S < 1 || n < 0) return 1;
+    const int D = dag_shared ? 1 : K;
+    wide_t* way_in = (wide_t*)malloc(sizeof(wide_t) * (size_t)D * (size_t)S);     /* P_k */
+    wide_t* whole = (wide_t*)malloc(sizeof(wide_t) * (size_t)D * (size_t)S);      /* T_k */
+    int64_t col_base = 0;
+    int err = 0;
+    for (int d = 0; d < D && !err; ++d) {
+        const int32_t* rp = dag_row_ptr + (int64_t)d * (S + 1);
+        paths_t ps;
+        if (enumerate_paths(S, rp, dag_col + col_base, &ps)) { err = 2; paths_free(&ps); break; }
+        col_base += rp[S];
+        for (int k = 0; k < S; ++k) {
+            wide_t longest_in = -1, longest_out = -1;
+            for (int64_t q = 0; q < ps.P; ++q) {
+                for (int32_t e = ps.ptr[q]; e < ps.ptr[q + 1]; ++e) {
+                    if (ps.stage[e] != k) continue;
+                    wide_t in = 0, out = 0;
+                    for (int32_t t = ps.ptr[q]; t <= e; ++t) {
+                        const int64_t rec = (int64_t)d * S + ps.stage[t];
+                        in += lat_us[rec * LAT_ENTRIES + batch[rec] - 1];
+                    }
+                    for (int32_t t = e + 1; t < ps.ptr[q + 1]; ++t) {
+                        const int64_t rec = (int64_t)d * S + ps.stage[t];
+                        out += lat_us[rec * LAT_ENTRIES + batch[rec] - 1];
+                    }
+                    if (in > longest_in) longest_in = in;
+                    if (out > longest_out) longest_out = out;
+                }
+            }
+            way_in[(int64_t)d * S + k] = longest_in;
+            whole[(int64_t)d * S + k] = longest_in + longest_out;
+        }
+        paths_free(&ps);
+    }
+    for (int32_t u = 0; u < K && !err; ++u)
+        for (int64_t r = snap_ptr[u]; r < snap_ptr[u + 1]; ++r) {
+            const int k = clamp_stage(stage[r], S);
+            const int64_t rec = (int64_t)(dag_shared ? 0 : u) * S + k;
+            const wide_t used = (wide_t)now[u] - (wide_t)arrival[r];
+            const wide_t slo = (wide_t)deadline[r] - (wide_t)arrival[r];
+            if (whole[rec] == 0) drop_out[r] = used > slo ? 1 : 0;
+            else drop_out[r] = used * whole[rec] > slo * way_in[rec] ? 1 : 0;
+        }
+    free(way_in);
+    free(whole);
+    return err;
 }

@@ -69,6 +69,12 @@ def _load() -> ctypes.CDLL:
         lib.pard_oracle_compact.restype = ctypes.c_int
         lib.pard_oracle_compact.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64,
                                             _i32p, _i32p, _u8p, _i32p, _i32p]
+        lib.pard_oracle_nexus_drop.restype = ctypes.c_int
+        lib.pard_oracle_nexus_drop.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, ctypes.c_int64,
+                                               _i32p, _i32p, _i32p, _i32p, _u8p, _i32p]
+        lib.pard_oracle_clipper_drop.restype = ctypes.c_int
+        lib.pard_oracle_clipper_drop.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _i32p, _i32p, _i32p, _i32p,
+                                                 ctypes.c_int64, _i32p, _i32p, _i32p, _i32p, _i32p, _u8p]
         lib.pard_oracle_paths.restype = ctypes.c_int
         lib.pard_oracle_paths.argtypes = [ctypes.c_int32, _i32p, _i32p, _i64p, _i64p,
                                           _i32p, ctypes.c_int64, _i32p, ctypes.c_int64]
@@ -213,6 +219,38 @@ def compact(K, S, order, seg_ptr, drop):
     lib.pard_oracle_compact(K, S, n, _p32(o), _p32(seg_ptr), d.ctypes.data_as(_u8p),
                             _p32(surv), _p32(surv_ptr))
     return surv[:int(surv_ptr[-1])], surv_ptr
+
+
+def nexus_drop(K, S, dag_shared, batch, lat_us, deadline, order, seg_ptr, now):
+    """Reactive window scan over the given queues: (drop uint8[n], first_kept int32[K*S])."""
+    lib = _load()
+    B, L, ddl, od, sp, nw = map(_i32, (batch, lat_us, deadline, order, seg_ptr, now))
+    n = int(ddl.shape[0])
+    drop = np.zeros(max(n, 1), np.uint8)
+    first = np.zeros(K * S, np.int32)
+    pad = lambda a: a if a.size else np.zeros(1, np.int32)  # noqa: E731
+    rc = lib.pard_oracle_nexus_drop(K, S, int(dag_shared), _p32(B), _p32(L), n, _p32(pad(ddl)), _p32(pad(od)), _p32(sp),
+                                    _p32(nw), drop.ctypes.data_as(_u8p), _p32(first))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return drop[:n], first
+
+
+def clipper_drop(K, S, dag_shared, dag_row_ptr, dag_col, batch, lat_us, arrival, deadline, stage, snap_ptr, now):
+    """Per-module SLO split: drop uint8[n]."""
+    lib = _load()
+    rp, cl, B, L = map(_i32, (dag_row_ptr, dag_col, batch, lat_us))
+    if cl.size == 0:
+        cl = np.zeros(1, np.int32)
+    arr, ddl, stg, sp, nw = map(_i32, (arrival, deadline, stage, snap_ptr, now))
+    n = int(arr.shape[0])
+    drop = np.zeros(max(n, 1), np.uint8)
+    pad = lambda a: a if a.size else np.zeros(1, np.int32)  # noqa: E731
+    rc = lib.pard_oracle_clipper_drop(K, S, int(dag_shared), _p32(rp), _p32(cl), _p32(B), _p32(L), n, _p32(pad(arr)),
+                                      _p32(pad(ddl)), _p32(pad(stg)), _p32(sp), _p32(nw), drop.ctypes.data_as(_u8p))
+    if rc != 0:
+        raise ValueError(f"oracle rejected the arguments (code {rc})")
+    return drop[:n]
 
 
 def expand_paths(S, dag_row_ptr, dag_col):

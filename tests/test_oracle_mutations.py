@@ -12,6 +12,7 @@ from tests import test_oracle_consistent as pins_consistent
 from tests import test_oracle_pins as pins
 from tests import test_oracle_priority as pins_priority
 from tests import test_oracle_ranked as pins_ranked
+from tests import test_oracle_reactive as pins_reactive
 from tests import test_oracle_sub as pins_sub
 from tests import test_oracle_window as pins_window
 
@@ -71,6 +72,23 @@ MUTATIONS = [
     ("monitored delay on top of the queue-length term", "sum_qd += (q_i > 0 ? q_i : 0) + d_i;",
      "sum_qd += (q_i > 0 ? q_i : 0) + stage_cost(L + (int64_t)i * LAT_ENTRIES, B[i], Wk[i], nq[i]);", "window"),
     ("monitored delay without the execution duration", "sum_qd += (q_i > 0 ? q_i : 0) + d_i;", "sum_qd += (q_i > 0 ? q_i : 0);", "window"),
+    ("window scan: every window takes the full batch's latency", "const wide_t batch_end = (wide_t)now[u] + (wide_t)lat[w - 1];",
+     "const wide_t batch_end = (wide_t)now[u] + (wide_t)lat[B - 1];", "reactive"),
+    ("window scan: a request on its deadline is late", "if (batch_end > (wide_t)deadline[order[a + p + i]]) all_meet = 0;",
+     "if (batch_end >= (wide_t)deadline[order[a + p + i]]) all_meet = 0;", "reactive"),
+    ("window scan: only the window's first request is looked at", "for (int64_t i = 0; i < w; ++i)\n                    if (batch_end >",
+     "for (int64_t i = 0; i < 1; ++i)\n                    if (batch_end >", "reactive"),
+    ("window scan: the window itself is dropped too", "drop_out[order[a + j]] = j < first ? 1 : 0;", "drop_out[order[a + j]] = j <= first ? 1 : 0;", "reactive"),
+    ("window scan: the queue is read by request index", "if (batch_end > (wide_t)deadline[order[a + p + i]]) all_meet = 0;",
+     "if (batch_end > (wide_t)deadline[a + p + i]) all_meet = 0;", "reactive"),
+    ("window scan: now left out", "const wide_t batch_end = (wide_t)now[u] + (wide_t)lat[w - 1];", "const wide_t batch_end = (wide_t)lat[w - 1];", "reactive"),
+    ("SLO split: the current module's own budget left out", "for (int32_t t = ps.ptr[q]; t <= e; ++t) {", "for (int32_t t = ps.ptr[q]; t < e; ++t) {", "reactive"),
+    ("SLO split: shortest way in instead of the longest", "if (in > longest_in) longest_in = in;", "if (longest_in < 0 || in < longest_in) longest_in = in;", "reactive"),
+    ("SLO split: durations at batch size one", "in += lat_us[rec * LAT_ENTRIES + batch[rec] - 1];", "in += lat_us[rec * LAT_ENTRIES];", "reactive"),
+    ("SLO split: the whole SLO at every module", "else drop_out[r] = used * whole[rec] > slo * way_in[rec] ? 1 : 0;", "else drop_out[r] = used > slo ? 1 : 0;", "reactive"),
+    ("SLO split: dropped already when the budget is just used up", "else drop_out[r] = used * whole[rec] > slo * way_in[rec] ? 1 : 0;",
+     "else drop_out[r] = used * whole[rec] >= slo * way_in[rec] ? 1 : 0;", "reactive"),
+    ("SLO split: the deadline taken for the SLO", "const wide_t slo = (wide_t)deadline[r] - (wide_t)arrival[r];", "const wide_t slo = (wide_t)deadline[r];", "reactive"),
 ]
 
 
@@ -143,7 +161,19 @@ def ranked_pins(m):
     pins_ranked.test_never_above_the_plain_estimate_with_rising_tables(m)
 
 
-GROUPS = {"core": core_pins, "ranked": ranked_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins,
+def reactive_pins(m):
+    pins_reactive.test_nexus_hand_worked_queues(m)
+    pins_reactive.test_nexus_closed_forms(m)
+    for seed in range(16):
+        pins_reactive.test_nexus_brute_force(m, seed)
+    pins_reactive.test_nexus_invariants(m)
+    pins_reactive.test_clipper_hand_worked(m)
+    pins_reactive.test_clipper_single_module_is_the_plain_rule(m)
+    for seed in range(16):
+        pins_reactive.test_clipper_brute_force(m, seed)
+
+
+GROUPS = {"core": core_pins, "reactive": reactive_pins, "ranked": ranked_pins, "consistent": consistent_pins, "sub": sub_pins, "priority": priority_pins,
           "window": window_pins}
 
 
