@@ -283,6 +283,85 @@ def bench_queue_delay(args, w, s, gen_s):
     return out
 
 
+def bench_reactive(args, w, gen_s):
+    """The reactive policies of Section 5.1 on the same snapshots: window scan over the queues in arrival order
+    and per-module SLO split, timed per call, and how their drop sets differ from the proactive estimate's."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2602_08747_amd import binding, workloads
+    s = binding.Session(w)                                      # the plan's own queue order: the proactive estimate
+    s.estimate_drop()
+    proactive = s.drop[:w.n].clone()
+    wf = dataclasses.replace(w, order_mode=np.full_like(w.order_mode, workloads.MODE_FCFS))
+    f = binding.Session(wf)                                     # the same snapshots, queues in arrival order
+    f.estimate_drop()
+    scan = torch.empty(max(w.n, 1), dtype=torch.uint8, device=f.dev)
+    split = torch.empty_like(scan)
+    first = torch.empty(w.K * w.S, dtype=torch.int32, device=f.dev)
+
+    def window_scan():
+        binding.pard_reactive_drop(f.plan, binding.REACTIVE_WINDOW_SCAN, w.n, None, f.deadline, None, None, f.now, f.order, f.seg_ptr,
+                                   scan, first)
+
+    def slo_split():
+        binding.pard_reactive_drop(f.plan, binding.REACTIVE_SLO_SPLIT, w.n, f.arrival, f.deadline, f.stage, f.snap_ptr, f.now, None, None,
+                                   split, None)
+
+    for _ in range(max(args.warmup, 1)):
+        window_scan()
+        slo_split()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b, c in ev:
+        a.record()
+        window_scan()
+        b.record()
+        slo_split()
+        c.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    scan_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in ev]))
+    split_ms = float(np.mean([b.elapsed_time(c) for _, b, c in ev]))
+    n = max(w.n, 1)
+    frac = lambda t: round(float(t.float().sum().item()) / n, 4)          # noqa: E731
+    p, a, b = proactive[:w.n].bool(), scan[:w.n].bool(), split[:w.n].bool()
+    alg_bytes = 9.0 * w.n                                         # order 4 + the deadline it points at 4 + the drop byte 1
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9 if scan_ms > 0 else 0.0
+    out = {
+        "metric": "requests decided/sec by the reactive policies (window scan + per-module SLO split)",
+        "value": round(w.n / (ms_per_step * 1e-3), 1), "unit": "requests/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": w.name + "+reactive", "requests": w.n, "snapshots": w.K, "stages": w.S,
+                   "window_scan_ms": round(scan_ms, 4), "slo_split_ms": round(split_ms, 4),
+                   "drop_fraction": {"proactive": frac(p), "window_scan": frac(a), "slo_split": frac(b)},
+                   # how the drop sets differ: requests only the one or only the other policy drops, as fractions of all
+                   "dropped_only_by_proactive_vs_window_scan": frac(p & ~a), "dropped_only_by_window_scan": frac(a & ~p),
+                   "dropped_only_by_proactive_vs_slo_split": frac(p & ~b), "dropped_only_by_slo_split": frac(b & ~p),
+                   "generate_s": round(gen_s, 2)},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": "the window-scan call (window_scan_kernel, window_tail_kernel, window_mask_kernel)",
+                     "bytes_per_request": 9.0, "launch_ms": round(scan_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build_oracle()
+        order, seg_ptr = f.order[:w.n].cpu().numpy(), f.seg_ptr.cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.nexus_drop(w.K, w.S, w.dag_shared, w.batch, w.lat_us, w.deadline, order, seg_ptr, w.now)
+        oracle.clipper_drop(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.lat_us, w.arrival, w.deadline, w.stage,
+                            w.snap_ptr, w.now)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(w.n / cpu_s, 1), "unit": "requests/s", "cores": 1, "kind": "oracle",
+                               "sample": f"whole workload ({w.n} requests), both policies, 1 run", "seconds": round(cpu_s, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -306,11 +385,12 @@ def main():
                     help="sequentially consistent dropping (positions count kept requests only)")
     ap.add_argument("--ranked", action="store_true",
                     help="ranked positions in the later queues (a request takes the place its budget gives it there)")
-    ap.add_argument("--workload", choices=["hot-path", "planner", "priority", "queue-delay"], default="hot-path",
+    ap.add_argument("--workload", choices=["hot-path", "planner", "priority", "queue-delay", "reactive"], default="hot-path",
                     help="hot-path: estimate+drop+compact (default); planner: queue lengths + downstream latency "
                          "with the sampled batch-wait quantile on the same snapshots; priority: adaptive priority "
                          "from a rate series per (snapshot, stage); queue-delay: the sliding-window queueing delay "
-                         "from delay samples per (snapshot, stage)")
+                         "from delay samples per (snapshot, stage); reactive: the window-scan and SLO-split policies the "
+                         "paper compares with, and how their drop sets differ from the proactive estimate's")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -348,6 +428,9 @@ def main():
             sys.exit(2)
         w = workloads.half_survivors(w)
     gen_s = time.time() - t0
+    if args.workload == "reactive":
+        print(json.dumps(bench_reactive(args, w, gen_s)))
+        return
     s = binding.Session(w)
     # host-to-device time of the request arrays (outside every timed region; the boundary takes device buffers)
     torch.cuda.synchronize()

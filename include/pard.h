@@ -388,6 +388,37 @@ int pard_priority_modes(const pard_plan_t* plan, int32_t series_len, int32_t win
  */
 int pard_plan_set_modes(pard_plan_t* plan, const int32_t* d_mode, void* stream);
 
+/*
+ * Reactive dropping policies on the same snapshot (Section 5.1, "Baselines"): what the proactive estimate is
+ * compared with.  Both write a drop mask in request order like pard_estimate_drop; neither looks at the modules
+ * after the current one.
+ *
+ * PARD_REACTIVE_WINDOW_SCAN - the policy the paper describes for Nexus: every queue is scanned in the order
+ *   given (d_order/d_seg_ptr as written by pard_estimate_drop; a plan whose stages use PARD_ORDER_FCFS gives
+ *   the paper's arrival order) with a window of one batch.  With n requests in the queue the window at position
+ *   p holds w = min(B, n - p) requests, runs as one batch of w and ends at now + lat[w]; it fits when no
+ *   deadline in it is earlier.  d_first_kept[u*S + s] = the first position whose window fits (n when none
+ *   does); the requests before it are dropped, all others kept.
+ *     reads d_deadline, d_now, d_order, d_seg_ptr; d_arrival, d_stage, d_snap_ptr may be NULL
+ * PARD_REACTIVE_SLO_SPLIT - Clipper++: the end-to-end SLO (deadline - arrival) is divided among the modules in
+ *   proportion to their execution durations d_i = lat_i[B_i], SLO_k = SLO d_k / sum d_i; a request at module k
+ *   is dropped once the time since it was sent exceeds the budgets of the modules up to and including k:
+ *   now - arrival > SLO P_k / T_k (exactly, no rounding), P_k = summed durations along the longest way from a
+ *   source to k, T_k = P_k + the longest way from k to a sink.  For one module this is Clipper's own rule,
+ *   now > deadline; T_k = 0 reads as P_k / T_k = 1.
+ *     reads d_arrival, d_deadline, d_stage, d_snap_ptr, d_now; d_order, d_seg_ptr, d_first_kept may be NULL
+ *
+ *   d_drop        device out uint8[n], 1 = drop, request order
+ *   d_first_kept  device out int32[K*S] (window scan only)
+ * Errors: PARD_E_NULL, PARD_E_BAD_SHAPE (policy, n), PARD_E_UNSUPPORTED (SLO split with a path whose summed
+ * durations reach 2^30 microseconds), PARD_E_HIP.  Enqueues on `stream`, allocates nothing.
+ */
+enum { PARD_REACTIVE_WINDOW_SCAN = 0, PARD_REACTIVE_SLO_SPLIT = 1 };
+int pard_reactive_drop(const pard_plan_t* plan, int32_t policy, int64_t n,
+                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                       const int32_t* d_snap_ptr, const int32_t* d_now, const int32_t* d_order, const int32_t* d_seg_ptr,
+                       uint8_t* d_drop, int32_t* d_first_kept, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* pard_strerror(int status);
 

@@ -25,10 +25,11 @@ STATUS_NAMES = {
 }
 EXPORTS = ["pard_plan_check", "pard_plan_create", "pard_plan_destroy", "pard_plan_info",
            "pard_workspace_bytes", "pard_estimate_drop", "pard_estimate_drop_sub", "pard_estimate_drop_consistent",
-           "pard_estimate_drop_ranked", "pard_estimate_drop_static", "pard_estimate_drop_compact",
+           "pard_estimate_drop_ranked", "pard_estimate_drop_static", "pard_estimate_drop_compact", "pard_reactive_drop",
            "pard_queue_lengths", "pard_priority_modes", "pard_plan_set_modes",
            "pard_sub_latency", "pard_sub_latency_q", "pard_queue_delay", "pard_compact", "pard_strerror"]
 SUB_FULL, SUB_LOWER, SUB_UPPER, SUB_SF, SUB_BACK = range(5)
+REACTIVE_WINDOW_SCAN, REACTIVE_SLO_SPLIT = 0, 1
 
 
 class PardError(RuntimeError):
@@ -65,6 +66,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.pard_estimate_drop_static.argtypes = [vp, i64, i64] + [vp] * 9 + [vp, vp]
     lib.pard_estimate_drop_compact.argtypes = [vp, i64, i64] + [vp] * 11 + [vp, i64, vp, vp]
     lib.pard_compact.argtypes = [vp, i64, i64] + [vp] * 5 + [vp, i64, vp]
+    lib.pard_reactive_drop.argtypes = [vp, i32, i64] + [vp] * 10
     lib.pard_estimate_drop_sub.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_estimate_drop_consistent.argtypes = [vp, i64, i64] + [vp] * 10 + [vp, i64, vp]
     lib.pard_queue_lengths.argtypes = [vp, i64, vp, vp, vp, vp]
@@ -284,6 +286,17 @@ def pard_queue_delay(plan: Plan, series_len: int, window_us: int, time, delay, n
                                          _ptr(q), _stream_handle(stream))
     if check and rc != PARD_OK:
         raise PardError(rc, "pard_queue_delay")
+    return rc
+
+
+def pard_reactive_drop(plan: Plan, policy: int, n: int, arrival, deadline, stage, snap_ptr, now, order, seg_ptr, drop,
+                       first_kept, stream=None, check: bool = True) -> int:
+    """Enqueues a reactive dropping policy (window scan or per-module SLO split) on `stream`."""
+    rc = load_library().pard_reactive_drop(plan.handle, int(policy), int(n), _ptr(arrival), _ptr(deadline), _ptr(stage),
+                                           _ptr(snap_ptr), _ptr(now), _ptr(order), _ptr(seg_ptr), _ptr(drop), _ptr(first_kept),
+                                           _stream_handle(stream))
+    if check and rc != PARD_OK:
+        raise PardError(rc, "pard_reactive_drop")
     return rc
 
 

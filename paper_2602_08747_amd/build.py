@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libpard.so")
 HASH_PATH = os.path.join(HERE, "libpard.srchash")
-SOURCES = ["pard_api.hip", "pard_fused.hip", "pard_presorted.hip", "pard_sort.hip", "pard_compact.hip", "pard_planner.hip", "pard_ranked.hip", "pard_wave.hip"]
+SOURCES = ["pard_api.hip", "pard_fused.hip", "pard_presorted.hip", "pard_sort.hip", "pard_compact.hip", "pard_planner.hip", "pard_ranked.hip", "pard_reactive.hip", "pard_wave.hip"]
 HEADERS = ["pard_host.hpp", "pard_device.hpp"]
 
 

@@ -114,7 +114,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     const int64_t b_een = align256((int64_t)h.entry_end.size() * 4 + 4);
     const int64_t b_edg = align256((int64_t)h.entry_dag.size() * 4 + 4);
     const int64_t b_drw = align256((int64_t)PARD_MAX_WAIT_SAMPLES * h.S * 4);
-    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een + b_edg + b_drw;
+    const int64_t b_spl = align256((int64_t)h.split_in.size() * 8);
+    const int64_t total = b_recs + b_lat + b_dep + b_est + b_een + b_edg + 2 * b_spl + b_drw;
     if (hipGetDevice(&p->device) != hipSuccess || hipMalloc(&p->blob, (size_t)total) != hipSuccess) {
         (void)hipGetLastError();
         delete p;
@@ -134,8 +135,10 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     char* d_est = put(h.entry_stage.data(), h.entry_stage.size() * 4, b_est);
     char* d_een = put(h.entry_end.data(), h.entry_end.size() * 4, b_een);
     char* d_edg = put(h.entry_dag.data(), h.entry_dag.size() * 4, b_edg);
+    char* d_spi = put(h.split_in.data(), h.split_in.size() * 8, b_spl);
+    char* d_spw = put(h.split_whole.data(), h.split_whole.size() * 8, b_spl);
     p->drawn = reinterpret_cast<uint32_t*>(base + off);
-    if (!d_recs || !d_lat || !d_dep || !d_est || !d_een || !d_edg) {
+    if (!d_recs || !d_lat || !d_dep || !d_est || !d_een || !d_edg || !d_spi || !d_spw) {
         (void)hipGetLastError();
         (void)hipFree(p->blob);
         delete p;
@@ -160,6 +163,8 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
     d.entry_stage = reinterpret_cast<const int32_t*>(d_est);
     d.entry_end = reinterpret_cast<const int32_t*>(d_een);
     d.entry_dag = reinterpret_cast<const int32_t*>(d_edg);
+    d.split_in = reinterpret_cast<const int64_t*>(d_spi);
+    d.split_whole = reinterpret_cast<const int64_t*>(d_spw);
     d.total_entries = (int64_t)h.entry_stage.size();
     *out = p;
     return PARD_OK;
@@ -438,6 +443,27 @@ int pard_plan_set_modes(pard_plan_t* plan, const int32_t* d_mode, void* stream) 
     plan->host.uniform_mode = -1;          // the stages' modes now live on the device only
     plan->dev.uniform_mode = -1;
     return PARD_OK;
+}
+
+int pard_reactive_drop(const pard_plan_t* plan, int32_t policy, int64_t n,
+                       const int32_t* d_arrival, const int32_t* d_deadline, const int32_t* d_stage,
+                       const int32_t* d_snap_ptr, const int32_t* d_now, const int32_t* d_order, const int32_t* d_seg_ptr,
+                       uint8_t* d_drop, int32_t* d_first_kept, void* stream) {
+    if (!plan || !d_now) return PARD_E_NULL;
+    if (n < 0 || n >= ((int64_t)1 << 30) || (policy != PARD_REACTIVE_WINDOW_SCAN && policy != PARD_REACTIVE_SLO_SPLIT))
+        return PARD_E_BAD_SHAPE;
+    if (n > 0 && (!d_deadline || !d_drop)) return PARD_E_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (policy == PARD_REACTIVE_WINDOW_SCAN) {
+        if (!d_seg_ptr || !d_first_kept || (n > 0 && !d_order)) return PARD_E_NULL;
+        e = launch_window_scan(plan->dev, n, d_deadline, d_order, d_seg_ptr, d_now, d_drop, d_first_kept, s);
+    } else {
+        if (!d_snap_ptr || (n > 0 && (!d_arrival || !d_stage))) return PARD_E_NULL;
+        if (!plan->host.split_fits) return PARD_E_UNSUPPORTED;
+        e = launch_slo_split(plan->dev, n, d_arrival, d_deadline, d_stage, d_snap_ptr, d_now, d_drop, s);
+    }
+    return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }
 
 int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_requests,

@@ -24,6 +24,8 @@ struct PlanDev {
     const int32_t* entry_stage;        // [E]
     const int32_t* entry_end;          // [E]
     const int32_t* entry_dag;          // [E]
+    const int64_t* split_in;           // [D*S] per-module SLO split: longest way in (see HostPlan)
+    const int64_t* split_whole;        // [D*S] longest whole path through the stage
     int64_t total_entries;             // E
 };
 
@@ -232,5 +234,11 @@ hipError_t launch_priority_modes(const PlanDev& plan, int32_t series_len, int32_
 hipError_t launch_queue_delay(int32_t K, int32_t S, int32_t len, uint32_t window, const int32_t* time, const int32_t* delay,
                               const int32_t* now, int32_t* q, hipStream_t stream);
 hipError_t launch_set_modes(StageRec* recs, const int32_t* modes, int64_t count, hipStream_t stream);
+
+// ---- reactive policies (pard_reactive.hip) --------------------------------------------
+hipError_t launch_window_scan(const PlanDev& plan, int64_t n, const int32_t* deadline, const int32_t* order, const int32_t* seg_ptr,
+                              const int32_t* now, uint8_t* drop, int32_t* first, hipStream_t stream);
+hipError_t launch_slo_split(const PlanDev& plan, int64_t n, const int32_t* arrival, const int32_t* deadline, const int32_t* stage,
+                            const int32_t* snap_ptr, const int32_t* now, uint8_t* drop, hipStream_t stream);
 
 }  // namespace pard

@@ -77,6 +77,10 @@ struct HostPlan {
     std::vector<int32_t> entry_end;         // [E]     one past the last entry of the entry's path
     std::vector<int32_t> entry_dag;         // [E]     the DAG an entry belongs to
     int32_t max_lat = 0;                    // largest latency-table entry
+    // Per-module SLO split (Section 5.1, Clipper++): summed execution durations lat[B] along the longest way from a
+    // source to a stage (the stage included) and along the longest whole path through it.
+    std::vector<int64_t> split_in, split_whole;   // [D*S]
+    bool split_fits = true;                 // every such sum is below 2^30 (products with 33-bit times fit 64 bits)
     bool short_form_everywhere = true;      // every stage is kStageFast with latB / W < 2^17: wait + execution of a
                                             // short queue fit 32 bits without a carry
 };
@@ -190,6 +194,29 @@ inline int build_host_plan(const pard_plan_desc_t* d, HostPlan& hp) {
         int rc = expand_dag(S, rp, d->dag_col ? d->dag_col + col_base : nullptr, hp);
         if (rc != PARD_OK) return rc;
         col_base += rp[S];
+        {
+            // longest way in and out of every stage, over the paths just listed (every stage lies on one)
+            std::vector<int64_t> in(S, 0), out(S, 0);
+            const size_t e0 = (size_t)hp.dag_entry_ptr.back(), e1 = hp.entry_stage.size();
+            for (size_t first = e0; first < e1;) {
+                const size_t end = (size_t)hp.entry_end[first];
+                int64_t total = 0;
+                for (size_t e = first; e < end; ++e) total += hp.recs[(size_t)g * S + hp.entry_stage[e]].latB;
+                int64_t run = 0;
+                for (size_t e = first; e < end; ++e) {
+                    const int32_t v = hp.entry_stage[e];
+                    run += hp.recs[(size_t)g * S + v].latB;
+                    if (run > in[v]) in[v] = run;
+                    if (total - run > out[v]) out[v] = total - run;
+                }
+                first = end;
+            }
+            for (int32_t v = 0; v < S; ++v) {
+                hp.split_in.push_back(in[v]);
+                hp.split_whole.push_back(in[v] + out[v]);
+                if (in[v] + out[v] >= ((int64_t)1 << 30)) hp.split_fits = false;
+            }
+        }
         hp.dag_path_ptr.push_back((int32_t)(hp.path_ptr.size() - 1));
         hp.dag_entry_ptr.push_back((int32_t)hp.entry_stage.size());
         hp.entry_dag.resize(hp.entry_stage.size(), g);
