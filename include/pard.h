@@ -31,9 +31,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The two
  *     hot calls only enqueue kernels: they do not allocate, free or synchronise.
  *   - A plan changes only through pard_plan_set_modes.  It may be used from several
- *     streams at once, provided each concurrent call has its own workspace; the one
- *     exception is the sampled variant of pard_sub_latency, which stages its draws in
- *     scratch memory the plan owns (see there).
+ *     streams at once, provided each concurrent call has its own workspace.  Two
+ *     exceptions: the sampled variant of pard_sub_latency, which stages its draws in
+ *     scratch memory the plan owns (see there), and pard_compact where it compacts the
+ *     queues as one stream (see there): its workgroups wait for each other and need the
+ *     device's compute units to themselves.
  */
 #ifndef PARD_H_
 #define PARD_H_
@@ -204,6 +206,16 @@ int pard_estimate_drop_static(const pard_plan_t* plan, int64_t n, int64_t max_sn
  *                          such a bound can hold (the bound rounded up to 4096 or 8192)
  *                          raises bit 0 of the status word; the outputs are then unspecified
  *                          (never out of bounds)
+ *                          Where the queues are compacted as one stream, the kernel's workgroups
+ *                          (as many as the device holds at once, counted when the plan was made)
+ *                          hand tile offsets to each other and wait for them: such a call must have
+ *                          the device's compute units to itself while it runs - no second such call,
+ *                          and no other kernel that occupies them, on another stream at the same
+ *                          time.  A wait that does not end (the grid was not resident as a whole)
+ *                          gives up after a bounded number of polls, every kernel still runs to its
+ *                          end, bit 1 of the status word is raised and d_surv_idx / d_surv_ptr of that
+ *                          call are invalid (never out of bounds).  The per-snapshot form has no
+ *                          such waits.
  *   d_order, d_seg_ptr     as written by pard_estimate_drop
  *   d_drop                 device uint8[n], request order; zero = keep, anything else = drop
  *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests

@@ -45,7 +45,12 @@ constexpr int kCTile = kCThreads * kCItems;            // 4096 queue slots per t
 constexpr int kCWaves = kCThreads / kWave;
 constexpr uint32_t kFlagReady = 1u << 31;              // word has been published
 constexpr uint32_t kValueMask = (1u << 30) - 1;
-constexpr uint32_t kSpinLimit = 1u << 22;
+// Polls a waiting workgroup makes before it gives up (status bit 1).  A test build of the library sets it to a
+// handful, so that the give-up path can be exercised from the host with every kernel still running to its end.
+#ifndef PARD_COMPACT_SPIN_LIMIT
+#define PARD_COMPACT_SPIN_LIMIT (1u << 22)
+#endif
+constexpr uint32_t kSpinLimit = PARD_COMPACT_SPIN_LIMIT;
 constexpr int kPools = 16;                             // tile pools (see above)
 constexpr int kLook = 8;                               // groups of 64 tile counts the scan service requests per step
 constexpr int kPoolStride = 64;                        // counters 256 bytes apart

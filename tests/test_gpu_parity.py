@@ -546,3 +546,40 @@ def test_error_codes_with_device(gpu):
                                   s.drop, s.order, s.seg_ptr, s.workspace, check=False) == -1
     assert gpu.pard_compact(s.plan, s.n, s.max_snap, s.order, s.seg_ptr, s.drop, s.surv_idx, s.surv_ptr, tiny[:8], check=False) == -8
     assert gpu.pard_plan_info(s.plan) == (1, 3)
+
+
+def test_streamed_compaction_gives_up_cleanly(gpu, oracle_mod):
+    """The streamed compaction's workgroups wait for tile offsets from each other.  A build of the library whose waits
+    give up after two polls shows the give-up path from the host: every kernel runs to its end, status bit 1 is
+    raised, nothing is written outside the outputs; the regular library on the same inputs is unaffected."""
+    import ctypes
+    import torch
+    from paper_2602_08747_amd import build
+    w = wl.make_workload(4, n_requests=3_000_001, permute=True)
+    w.lat_us[:] = np.maximum(1, w.lat_us // 400)
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 280000).astype(np.int32)
+    s, ref = check(gpu, oracle_mod, w)
+    test_lib = gpu.load_library(build.SPINTEST_LIB_PATH)
+    vp = ctypes.c_void_p
+    n = w.n
+    surv_big = torch.full((n + 64,), -7, dtype=torch.int32, device=s.dev)
+    surv = surv_big[32:32 + n]
+    ptr = torch.full((w.K * w.S + 1,), -7, dtype=torch.int32, device=s.dev)
+    ws = torch.zeros_like(s.workspace)
+    plan2 = vp(None)                                   # a plan of the test library's own
+    d, keep = gpu._desc(w.K, w.S, w.dag_shared, w.dag_row_ptr, w.dag_col, w.batch, w.workers, w.lat_us, w.order_mode)
+    assert test_lib.pard_plan_create(ctypes.byref(plan2), ctypes.byref(d)) == 0
+    rc = test_lib.pard_compact(plan2, n, s.max_snap, vp(s.order.data_ptr()), vp(s.seg_ptr.data_ptr()), vp(s.drop.data_ptr()),
+                               vp(surv.data_ptr()), vp(ptr.data_ptr()), vp(ws.data_ptr()), ws.numel() * 4,
+                               vp(torch.cuda.current_stream().cuda_stream))
+    assert rc == 0
+    torch.cuda.synchronize()                           # every kernel has ended
+    assert int(ws[0].item()) & 2, "the cut-down waits were expected to give up"
+    h = surv_big.cpu().numpy()
+    assert (h[:32] == -7).all() and (h[32 + n:] == -7).all()
+    test_lib.pard_plan_destroy(plan2)
+    # the regular library, same inputs, right after
+    s.compact()
+    got = s.results()
+    assert np.array_equal(got["surv_idx"], ref["surv_idx"]) and np.array_equal(got["surv_ptr"], ref["surv_ptr"])
+    assert s.status_word() == 0
