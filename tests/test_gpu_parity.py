@@ -583,3 +583,28 @@ def test_streamed_compaction_gives_up_cleanly(gpu, oracle_mod):
     got = s.results()
     assert np.array_equal(got["surv_idx"], ref["surv_idx"]) and np.array_equal(got["surv_ptr"], ref["surv_ptr"])
     assert s.status_word() == 0
+
+
+@pytest.mark.parametrize("permute", [True, False])
+def test_hundred_repeats_are_identical(gpu, oracle_mod, permute):
+    """Configuration 5 at full size, a hundred runs of the whole path (through the two calls and through the one call
+    in turn): every output of every run is bit for bit the first run's, which is the oracle's."""
+    import torch
+    w = wl.make_workload(5, permute=permute)
+    s, ref = check(gpu, oracle_mod, w, threads=16)
+    names = ("est", "drop", "order", "seg_ptr", "surv_idx", "surv_ptr")
+    total = int(ref["surv_ptr"][-1])
+    want = {k: getattr(s, k).clone() for k in names}
+    for i in range(100):
+        for k in names:
+            getattr(s, k).fill_(0x33)
+        if i % 2:
+            s.run_one_call()
+        else:
+            s.run()
+        for k in names:
+            a, b = getattr(s, k), want[k]
+            if k == "surv_idx":
+                a, b = a[:total], b[:total]
+            assert torch.equal(a, b), (i, k)
+    assert s.status_word() == 0

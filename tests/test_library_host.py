@@ -165,3 +165,156 @@ def test_stale_library_is_detected(tmp_path, monkeypatch):
     assert build.is_stale()
     monkeypatch.setattr(build, "HASH_PATH", str(tmp_path / "missing"))
     assert build.is_stale()
+
+
+SANITIZE = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan"]
+SAN_ENV = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1", UBSAN_OPTIONS="halt_on_error=1")
+SAN_ENV.pop("LD_PRELOAD", None)
+
+
+def _run_sanitized(exe):
+    res = subprocess.run([str(exe)], env=SAN_ENV, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
+    assert res.returncode == 0, res.stdout[-3000:]
+    assert "ERROR: AddressSanitizer" not in res.stdout and "runtime error" not in res.stdout, res.stdout[-3000:]
+    return res.stdout
+
+
+def test_oracle_under_address_and_undefined_sanitizers(tmp_path):
+    """The oracle's C source built with AddressSanitizer and UndefinedBehaviorSanitizer and driven through every entry
+    point on small random pipelines (including out-of-range stages, empty snapshots and extreme times)."""
+    driver = tmp_path / "driver.c"
+    driver.write_text(r'''
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+int pard_oracle_estimate_drop(int32_t, int32_t, int32_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*,
+    const int32_t*, int64_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, int32_t*, uint8_t*, int32_t*,
+    int32_t*, int32_t);
+int pard_oracle_estimate_drop_consistent(int32_t, int32_t, int32_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*,
+    const int32_t*, const int32_t*, int64_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int64_t*,
+    int32_t*, uint8_t*, int32_t*, int32_t*, int32_t);
+int pard_oracle_estimate_drop_ranked(int32_t, int32_t, int32_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*,
+    const int32_t*, int64_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, int32_t*, uint8_t*, int32_t*,
+    int32_t*, int32_t);
+int pard_oracle_compact(int32_t, int32_t, int64_t, const int32_t*, const int32_t*, const uint8_t*, int32_t*, int32_t*);
+int pard_oracle_nexus_drop(int32_t, int32_t, int32_t, const int32_t*, const int32_t*, int64_t, const int32_t*, const int32_t*, const int32_t*,
+    const int32_t*, uint8_t*, int32_t*);
+int pard_oracle_clipper_drop(int32_t, int32_t, int32_t, const int32_t*, const int32_t*, const int32_t*, const int32_t*, int64_t,
+    const int32_t*, const int32_t*, const int32_t*, const int32_t*, const int32_t*, uint8_t*);
+static uint64_t state = 88172645463325252ull;
+static uint32_t rnd(void) { state ^= state << 13; state ^= state >> 7; state ^= state << 17; return (uint32_t)(state >> 16); }
+int main(void) {
+    for (int round = 0; round < 40; ++round) {
+        const int K = 1 + rnd() % 4, S = 1 + rnd() % 6;
+        /* a diamond-ish DAG: stage s -> s+1 and sometimes s -> s+2 */
+        int32_t* rp = calloc((size_t)K * (S + 1), 4); int32_t* col = calloc((size_t)K * 2 * S + 1, 4);
+        int32_t* B = malloc((size_t)K * S * 4); int32_t* W = malloc((size_t)K * S * 4); int32_t* M = malloc((size_t)K * S * 4);
+        int32_t* L = malloc((size_t)K * S * 64 * 4);
+        int nc = 0;
+        for (int u = 0; u < K; ++u) {
+            int local = 0;
+            for (int s = 0; s < S; ++s) {
+                rp[u * (S + 1) + s] = local;
+                if (s + 1 < S) { col[nc++] = s + 1; ++local; }
+                if (s + 2 < S && rnd() % 2) { col[nc++] = s + 2; ++local; }
+            }
+            rp[u * (S + 1) + S] = local;
+        }
+        for (int i = 0; i < K * S; ++i) {
+            B[i] = 1 + rnd() % 64; W[i] = 1 + rnd() % 9; M[i] = rnd() % 3;
+            for (int b = 0; b < 64; ++b) L[i * 64 + b] = round % 5 == 4 ? 2147483647 : (int32_t)(rnd() % 20000);
+        }
+        int32_t* sp = malloc((size_t)(K + 1) * 4); sp[0] = 0;
+        for (int u = 0; u < K; ++u) sp[u + 1] = sp[u] + (rnd() % 3 == 0 ? 0 : (int32_t)(rnd() % 300));
+        const int64_t n = sp[K];
+        int32_t* arr = malloc((size_t)(n + 1) * 4); int32_t* dl = malloc((size_t)(n + 1) * 4); int32_t* st = malloc((size_t)(n + 1) * 4);
+        int32_t* now = malloc((size_t)K * 4);
+        for (int64_t r = 0; r < n; ++r) {
+            arr[r] = (int32_t)(rnd() % 100000) - 500; dl[r] = rnd() % 7 == 0 ? 2147483647 : arr[r] + (int32_t)(rnd() % 90000);
+            st[r] = (int32_t)(rnd() % (S + 2)) - 1;
+        }
+        for (int u = 0; u < K; ++u) now[u] = round % 7 == 6 ? -2147483647 - 1 : (int32_t)(rnd() % 120000);
+        int32_t* est = malloc((size_t)(n + 1) * 4); uint8_t* drop = malloc((size_t)n + 1); int32_t* order = malloc((size_t)(n + 1) * 4);
+        int32_t* seg = malloc((size_t)(K * S + 1) * 4); int32_t* surv = malloc((size_t)(n + 1) * 4); int32_t* sptr = malloc((size_t)(K * S + 1) * 4);
+        int32_t* first = malloc((size_t)K * S * 4);
+        if (pard_oracle_estimate_drop(K, S, 0, rp, col, B, W, L, M, n, arr, dl, st, sp, now, est, drop, order, seg, 2)) return 2;
+        if (pard_oracle_compact(K, S, n, order, seg, drop, surv, sptr)) return 3;
+        if (pard_oracle_estimate_drop_consistent(K, S, 0, rp, col, B, W, L, M, n, arr, dl, st, sp, now, NULL, est, drop, order, seg, 1)) return 4;
+        if (pard_oracle_estimate_drop_ranked(K, S, 0, rp, col, B, W, L, M, n, arr, dl, st, sp, now, est, drop, order, seg, 1)) return 5;
+        if (pard_oracle_nexus_drop(K, S, 0, B, L, n, dl, order, seg, now, drop, first)) return 6;
+        if (pard_oracle_clipper_drop(K, S, 0, rp, col, B, L, n, arr, dl, st, sp, now, drop)) return 7;
+        free(rp); free(col); free(B); free(W); free(M); free(L); free(sp); free(arr); free(dl); free(st); free(now); free(est); free(drop);
+        free(order); free(seg); free(surv); free(sptr); free(first);
+    }
+    puts("oracle driver done");
+    return 0;
+}
+''')
+    exe = tmp_path / "oracle_san"
+    subprocess.run(["gcc", "-std=gnu99", *SANITIZE, "-fopenmp", os.path.join(ROOT, "oracle", "pard_oracle.c"), str(driver), "-o", str(exe)],
+                   check=True)
+    assert "oracle driver done" in _run_sanitized(exe)
+
+
+def test_host_plan_builder_under_address_and_undefined_sanitizers(tmp_path):
+    """The library's host-side plan builder (validation, path expansion, constants) built on its own with the sanitizers and
+    fed valid, malformed and exploding pipeline descriptions."""
+    driver = tmp_path / "driver.cpp"
+    driver.write_text(r'''
+#include <cstdio>
+#include <vector>
+#include "paper_2602_08747_amd/csrc/pard_host.hpp"
+static unsigned long long state = 88172645463325252ull;
+static unsigned rnd() { state ^= state << 13; state ^= state >> 7; state ^= state << 17; return (unsigned)(state >> 16); }
+int main() {
+    int ok = 0, rejected = 0;
+    for (int round = 0; round < 400; ++round) {
+        const int K = 1 + rnd() % 3, S = 1 + rnd() % 12, shared = rnd() % 2, D = shared ? 1 : K;
+        std::vector<int32_t> rp, col, B(D * S), W(D * S), M(D * S), L((size_t)D * S * 64);
+        for (int d = 0; d < D; ++d) {
+            int local = 0;
+            for (int s = 0; s < S; ++s) {
+                rp.push_back(local);
+                for (int t = s + 1; t < S; ++t)
+                    if (rnd() % 3 == 0) { col.push_back(round % 11 == 10 && rnd() % 9 == 0 ? (int)(rnd() % (S + 2)) - 1 : t); ++local; }
+            }
+            rp.push_back(local);
+        }
+        for (int i = 0; i < D * S; ++i) {
+            B[i] = round % 13 == 12 ? (int)(rnd() % 70) : 1 + rnd() % 64;
+            W[i] = round % 17 == 16 ? (int)(rnd() % 3) : 1 + rnd() % 300;
+            M[i] = round % 19 == 18 ? (int)(rnd() % 5) : rnd() % 3;
+            for (int b = 0; b < 64; ++b) L[(size_t)i * 64 + b] = round % 23 == 22 ? -(int)(rnd() % 3) : (int)(rnd() % 2000000);
+        }
+        pard_plan_desc_t d{K, S, shared, rp.data(), col.empty() ? nullptr : col.data(), B.data(), W.data(), L.data(), M.data()};
+        pard::HostPlan hp;
+        const int rc = pard::build_host_plan(&d, hp);
+        if (rc == PARD_OK) {
+            ++ok;
+            if (hp.split_in.size() != (size_t)D * S || hp.entry_end.size() != hp.entry_stage.size()) return 2;
+        } else {
+            ++rejected;
+        }
+    }
+    // twelve diamonds in series: 4096 paths, refused
+    {
+        const int S = 37;
+        std::vector<int32_t> rp(S + 1, 0), col, one(S, 1), zero(S, 0), L((size_t)S * 64, 5);
+        for (int s = 0; s < S; ++s) {
+            rp[s] = (int32_t)col.size();
+            if (s % 3 == 0 && s + 3 < S) { col.push_back(s + 1); col.push_back(s + 2); }
+            else if (s % 3 == 1 && s + 2 < S) col.push_back(s + 2);
+            else if (s % 3 == 2 && s + 1 < S) col.push_back(s + 1);
+        }
+        rp[S] = (int32_t)col.size();
+        pard_plan_desc_t d{1, S, 1, rp.data(), col.data(), one.data(), one.data(), L.data(), zero.data()};
+        pard::HostPlan hp;
+        if (pard::build_host_plan(&d, hp) != PARD_E_TOO_MANY_PATHS) return 3;
+    }
+    std::printf("host driver done: %d accepted, %d rejected\n", ok, rejected);
+    return ok > 50 && rejected > 20 ? 0 : 4;
+}
+''')
+    exe = tmp_path / "host_san"
+    subprocess.run(["g++", "-std=c++17", *SANITIZE, "-I", ROOT, str(driver), "-o", str(exe)], check=True)
+    assert "host driver done" in _run_sanitized(exe)
