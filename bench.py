@@ -34,6 +34,33 @@ def estimate_drop_bytes_per_request(fused: bool, passes: int, fcfs: bool) -> flo
     return float(io + 16 * (passes - 1) + 8)
 
 
+def arrives_in_deadline_order(w, consistent: bool) -> bool:
+    """Whether the large-snapshot path finds the requests in deadline order and finishes with a stable split by stage
+    instead of sorting (the library decides this on the device; this is the same rule on the host, for the label and
+    the byte count of the roofline only): every stage orders by deadline the same way, at most 64 queues, no deadline
+    below its predecessor inside a snapshot, and under high budget first no long run of equal deadlines."""
+    import numpy as np
+    from paper_2602_08747_amd import workloads
+    n = w.n
+    if consistent or n == 0 or w.K * w.S > 64:
+        return False
+    modes = np.unique(w.order_mode)
+    if len(modes) != 1 or int(modes[0]) == workloads.MODE_FCFS:
+        return False
+    d = w.deadline.astype(np.int64)
+    falls = np.diff(d) < 0
+    inner = np.asarray(w.snap_ptr[1:-1], dtype=np.int64)
+    inner = inner[(inner > 0) & (inner < n)]
+    falls[inner - 1] = False                       # the order may restart where a snapshot starts
+    if falls.any():
+        return False
+    if int(modes[0]) == workloads.MODE_HBF:
+        r = np.arange(32, n, 4)
+        if (d[r] == d[r - 32]).any():
+            return False
+    return True
+
+
 def usable_cores() -> int:
     """Host cores this process may use: its affinity mask, and no more than the share the machine's
     own thread-count setting (OMP_NUM_THREADS) grants a one-GPU job."""
@@ -509,17 +536,22 @@ def main():
 
     # roofline of the dominant kernel
     fcfs = bool((w.order_mode == workloads.MODE_FCFS).any())
+    in_order = not fused and not args.ranked and arrives_in_deadline_order(w, args.consistent)
     if fused:
         small = s.max_snap <= 128
         kernel = ("wave_snapshot_kernel (the estimate step: one launch)" if small else
                   "the estimate step: presorted_snapshot_kernel for snapshots in queue order, then fused_snapshot_kernel "
                   "for the others (both launches are inside the timed interval)")
         passes = 0
+    elif in_order:
+        kernel = ("pard_estimate_drop call: count_kernel (which finds the requests in deadline order), setup_kernel, "
+                  "split_kernel; the radix launches that follow find nothing to do")
+        passes = 0
     else:
         kernel = "pard_estimate_drop call (count, setup, histogram, radix passes, epilogue)"
         span = int(w.deadline.max()) - int(w.deadline.min()) if n else 0
         passes = max(1, -(-(max(span, 0).bit_length() + max(w.K * w.S - 1, 0).bit_length()) // 8))
-    bpr = estimate_drop_bytes_per_request(fused, passes, fcfs)
+    bpr = estimate_drop_bytes_per_request(fused or in_order, passes, fcfs)
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
     traffic = (recorded_traffic(args.config, "presorted_snapshot_kernel", "pard_presorted.hip")
@@ -541,7 +573,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": w.name + ("+consistent" if args.consistent else "") + ("+ranked" if args.ranked else ""), "requests": n, "snapshots": w.K,
-                   "stages": w.S, "path": "on-chip" if fused else "radix-sort", "radix_passes": passes,
+                   "stages": w.S, "path": "on-chip" if fused else ("deadline-order split" if in_order else "radix-sort"), "radix_passes": passes,
                    "calls": "pard_estimate_drop_compact" if one_call else "pard_estimate_drop + pard_compact",
                    ("two_calls_ms_per_step" if one_call else "one_call_ms_per_step"): None if other_ms is None else round(other_ms, 4),
                    "drop_fraction": round(drop_frac, 4), "status_word": status,

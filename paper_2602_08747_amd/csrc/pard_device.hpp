@@ -58,16 +58,18 @@ static __device__ __noinline__ uint64_t wide_div(uint64_t x, uint32_t d) { retur
 
 // Eq.(2) in snapshot form with `a` requests ahead (0 <= a < 2^31):
 //   floor(ceil(a/B) * lat[B] / W) + lat[min(B, a+1)]
-// clamped to 2^40.  Clamping every term at 2^40 keeps 64-bit sums of up to 65 terms
+// clamped to 2^40.  With lat[B] = aW * W + bW (bW < W) and q batches ahead, floor(q * lat[B] / W) is
+// q * aW + floor(q * bW / W): what is left to divide fits 32 bits unless W is huge, while q * lat[B] itself
+// passes 2^32 as soon as a queue is long.  Clamping every term at 2^40 keeps 64-bit sums of up to 65 terms
 // exact-or-saturated: any sum that reaches the clamp is far above INT32_MAX even after
 // adding the most negative `now`, so the reported estimate and the drop decision are
 // the same as with unbounded integers.
 __device__ __forceinline__ uint64_t stage_cost(const StageRec& r, uint32_t a, const int32_t* lat_row) {
     uint32_t q = magic_div_dev(a + (uint32_t)r.B - 1u, r.mB, r.shB);
-    uint64_t x = (uint64_t)q * (uint32_t)r.latB;
-    uint64_t wait;
-    if ((x >> 32) == 0) wait = magic_div_dev((uint32_t)x, r.mW, r.shW);
-    else wait = wide_div(x, (uint32_t)r.W);
+    const uint64_t p = (uint64_t)q * r.bW;
+    uint64_t wait = (uint64_t)q * r.aW;
+    if ((p >> 32) == 0) wait += magic_div_dev((uint32_t)p, r.mW, r.shW);
+    else wait += wide_div(p, (uint32_t)r.W);
     uint32_t ex = (a + 1u >= (uint32_t)r.B) ? (uint32_t)r.latB : (uint32_t)lat_row[a];
     uint64_t c = wait + ex;
     return c < kCostCap ? c : kCostCap;

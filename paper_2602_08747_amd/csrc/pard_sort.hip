@@ -45,13 +45,14 @@ struct SortParams {                 // lives in device memory, written by the se
     uint32_t kb;                    // bits of (max key - min key)
     uint32_t passes;                // radix passes actually needed
     uint32_t total_bits;            // bits of the virtual sort key
+    uint32_t split;                 // the requests come in deadline order: the queues are a stable split by stage (no sort)
 };
 
 constexpr int kStreamBlocksMax = 1024;                 // upper bound on the grid of the streaming kernels
 constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
 
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, key[2], pay[2],
+    int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
             min_lat, alive, wkept, tile_tot, range_tot, carry, total;
     int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits;
@@ -81,6 +82,8 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.tile_hist = off;  off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
     L.part_minmax = off; off = align256(off + (int64_t)kStreamBlocksMax * 8);
     L.part_cnt = off;    off = align256(off + (int64_t)kStreamBlocksMax * kPartialSegs * 4);
+    L.part_flag = off;   off = align256(off + (int64_t)kStreamBlocksMax * 4);
+    L.wave_cnt = off;    off = align256(off + (int64_t)kStreamBlocksMax * 16 * kPartialSegs * 4);
     for (int b = 0; b < 2; ++b) {
         L.key[b] = off; off = align256(off + n * 4);
         L.pay[b] = off; off = align256(off + n * 4);
@@ -112,7 +115,10 @@ struct SortDev {                    // everything the sort kernels need, by valu
     uint32_t* tile_hist;            // [max_passes][tiles][256] digit counts per tile, then each tile's first output slots
     int64_t chunks;
     uint32_t* part_minmax;          // [stream_blocks][2]  per-workgroup (~min key, max key)
-    uint32_t* part_cnt;             // [stream_blocks][kPartialSegs] per-workgroup queue lengths
+    uint32_t* part_cnt;             // [stream_blocks][kPartialSegs] per-workgroup queue lengths (then, for the split, the
+                                    // queue lengths of all workgroups before)
+    uint32_t* part_flag;            // [stream_blocks] what a workgroup saw of the order of the deadlines (kSaw*)
+    uint32_t* wave_cnt;             // [stream_blocks][16][kPartialSegs] queue lengths of every wave's stretch of the array
     int32_t stream_blocks;
     uint32_t* key[2];
     uint32_t* pay[2];
@@ -163,15 +169,36 @@ constexpr int kScanThreads = 1024;
 constexpr int kScanItems = 8;                          // requests per thread per chunk
 constexpr int kChunk = kScanThreads * kScanItems;      // 8192 requests per chunk
 
-// The 8 requests of thread `tid` in the chunk starting at request `base`: two groups of 4
-// consecutive requests (16-byte loads when the arrays allow it).
-__device__ __forceinline__ void load_chunk(const SortDev& A, int64_t base, int tid, bool vec,
+// A wave walks a contiguous stretch of the request array kWaveChunk requests at a time; a lane holds 8 consecutive
+// requests of it (two 16-byte loads per array when the arrays allow it).
+constexpr int kWaveChunk = kWave * kScanItems;         // 512 requests
+
+// first request of the g-th group of four of a lane
+__device__ __forceinline__ int64_t lane_first(int64_t base, int lane, int g) { return base + lane * kScanItems + g * 4; }
+
+// The wave chunks [first, last) of wave `wave` of workgroup `block`: the workgroups cut the array into contiguous
+// ranges, the waves of a workgroup cut its range into contiguous ranges (the count and the split must agree on this).
+__device__ __forceinline__ void wave_range(int64_t n, int blocks, int block, int wave, int64_t& first, int64_t& last) {
+    const int64_t total = (n + kWaveChunk - 1) / kWaveChunk;
+    const int64_t per_block = (total + blocks - 1) / blocks;
+    const int64_t per_wave = (per_block + (kScanThreads / kWave) - 1) / (kScanThreads / kWave);
+    const int64_t block_first = (int64_t)block * per_block;
+    int64_t block_last = block_first + per_block;
+    if (block_last > total) block_last = total;
+    first = block_first + (int64_t)wave * per_wave;
+    last = first + per_wave;
+    if (first > block_last) first = block_last;
+    if (last > block_last) last = block_last;
+}
+
+// The 8 requests of lane `lane` in the wave chunk starting at request `base`.
+__device__ __forceinline__ void load_chunk(const SortDev& A, int64_t base, int lane, bool vec,
                                            uint32_t (&seg)[kScanItems], uint32_t (&key)[kScanItems],
                                            bool (&ok)[kScanItems]) {
     const PlanDev& P = A.plan;
 #pragma unroll
     for (int g = 0; g < kScanItems / 4; ++g) {
-        const int64_t r0 = base + (int64_t)g * (kScanThreads * 4) + tid * 4;
+        const int64_t r0 = lane_first(base, lane, g);
         int32_t d[4], st[4];
         if (vec && r0 + 3 < A.n) {
             const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0);
@@ -206,31 +233,138 @@ __device__ __forceinline__ bool arrays_vectorizable(const SortDev& A) {
     return ((reinterpret_cast<uintptr_t>(A.deadline) | reinterpret_cast<uintptr_t>(A.stage)) & 15) == 0;
 }
 
+// The same for a plan whose stages all order by deadline (MODE: low or high budget first) and that has at most
+// 64 snapshots, without anything the general form needs only for other plans.  `bound` holds the snapshot
+// boundaries across the lanes: lane k (1 <= k < K) has snap_ptr[k], every other lane INT32_MAX.
+__device__ __forceinline__ int32_t snapshot_bound(const SortDev& A, int lane) {
+    return lane >= 1 && lane < A.plan.K ? A.snap_ptr[lane] : kInt32Max;
+}
+
+template <int MODE>
+__device__ __forceinline__ void load_chunk_by_deadline(const SortDev& A, int64_t base, int lane, bool vec, int32_t bound,
+                                                       uint32_t (&snap)[kScanItems], uint32_t (&seg)[kScanItems],
+                                                       uint32_t (&key)[kScanItems], bool (&ok)[kScanItems]) {
+    const PlanDev& P = A.plan;
+    const int64_t r0 = lane_first(base, lane, 0);
+    int32_t d[kScanItems], st[kScanItems];
+    if (vec && base + kWaveChunk <= A.n) {
+#pragma unroll
+        for (int g = 0; g < kScanItems / 4; ++g) {
+            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0 + g * 4);
+            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + r0 + g * 4);
+            d[g * 4] = d4.x; d[g * 4 + 1] = d4.y; d[g * 4 + 2] = d4.z; d[g * 4 + 3] = d4.w;
+            st[g * 4] = s4.x; st[g * 4 + 1] = s4.y; st[g * 4 + 2] = s4.z; st[g * 4 + 3] = s4.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            d[i] = r0 + i < A.n ? A.deadline[r0 + i] : 0;
+            st[i] = r0 + i < A.n ? A.stage[r0 + i] : 0;
+        }
+    }
+    // snapshot of the chunk's first request: the boundaries at or before it; then one step up per boundary inside
+    const int32_t lo = (int32_t)base, hi = (int32_t)(base + kWaveChunk < A.n ? base + kWaveChunk : A.n);
+    const uint32_t u_base = (uint32_t)__popcll(__ballot(bound <= lo));
+    unsigned long long inside = __ballot(bound > lo && bound < hi);
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) snap[i] = u_base;
+    while (inside) {
+        const int32_t b = __builtin_amdgcn_readlane(bound, __builtin_ctzll(inside));
+        inside &= inside - 1ull;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) snap[i] += (int32_t)(r0 + i) >= b ? 1u : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kScanItems; ++i) {
+        ok[i] = r0 + i < A.n;
+        seg[i] = snap[i] * (uint32_t)P.S + (uint32_t)clamp_stage(st[i], P.S);
+        key[i] = order_key(MODE, d[i], 0);
+    }
+}
+
 // ---- count: queue lengths and key range ------------------------------------------
 // No atomics on a shared global word here: every workgroup leaves its partial results in
 // its own slot and the setup kernel adds them up.  (Same-address global atomics cost ~11 ns
 // each on this chip and serialise.)
+constexpr uint32_t kSawFall = 1u, kSawLongTie = 2u;
+constexpr int kTieReach = 32;
 constexpr int kCountLds = 16384;
 constexpr int kCountPrivate = kCountLds / kScanThreads;    // up to 16 queues: one counter column per thread
-__global__ __launch_bounds__(kScanThreads) void count_kernel(SortDev A) {
+// MODE: PARD_ORDER_LBF or PARD_ORDER_HBF when every stage orders that way, nothing is dropped consistently and
+// there are at most kPartialSegs queues (then the order of the deadlines is watched); -1 otherwise.
+template <int MODE>
+__global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
     __shared__ uint32_t h[kCountLds];
     __shared__ uint32_t red[2 * (kScanThreads / kWave)];
+    __shared__ uint32_t saw_by_wave[kScanThreads / kWave];
+    __shared__ uint32_t block_tot[kPartialSegs];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)A.plan.K * A.plan.S;
     const bool priv = segs <= kCountPrivate;            // h[seg * 1024 + tid]: no two lanes share a counter
+    const bool rows = !priv && segs <= kPartialSegs;    // h[wave * 64 + seg]: one row of counters per wave
     const bool use_lds = segs <= kCountLds;             // h[seg]: LDS atomics
     for (int i = tid; i < kCountLds; i += kScanThreads) h[i] = 0;
+    if (tid < kPartialSegs) block_tot[tid] = 0;
     __syncthreads();
     const bool vec = arrays_vectorizable(A);
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-    for (int64_t base = (int64_t)blockIdx.x * kChunk; base < A.n; base += (int64_t)gridDim.x * kChunk) {
+    // Does every snapshot come in deadline order (then its queues are a stable split by stage and nothing has to be
+    // sorted)?  Only looked at when all stages order by deadline.  kSawFall: a deadline lower than the one before
+    // it; kSawLongTie: more than kTieReach equal deadlines in a row (high budget first has to find the ends of a
+    // run of equal deadlines, and looks no further than that).
+    constexpr bool watch = MODE >= 0;
+    const int32_t bound = watch ? snapshot_bound(A, lane) : 0;
+    uint32_t saw = 0;
+    int64_t first, last;
+    wave_range(A.n, gridDim.x, blockIdx.x, wave, first, last);
+    for (int64_t chunk = first; chunk < last; ++chunk) {
+        const int64_t base = chunk * kWaveChunk;
         uint32_t seg[kScanItems], key[kScanItems];
         bool ok[kScanItems];
-        load_chunk(A, base, tid, vec, seg, key, ok);
+        if constexpr (!watch) load_chunk(A, base, lane, vec, seg, key, ok);
+        if constexpr (watch) {
+            uint32_t snap[kScanItems];
+            load_chunk_by_deadline<MODE>(A, base, lane, vec, bound, snap, seg, key, ok);
+            // the request before this lane's eight: the last of the lane below (lane 0: from memory)
+            uint32_t before = __shfl_up(key[kScanItems - 1], 1), before_snap = __shfl_up(snap[kScanItems - 1], 1);
+            if (lane == 0) {
+                before = key[0];
+                before_snap = snap[0];
+                if (base > 0 && base < A.n) {
+                    before = order_key(MODE, A.deadline[base - 1], 0);
+                    before_snap = (uint32_t)snapshot_of(A.snap_ptr, A.plan.K, base - 1);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kScanItems; ++i) {
+                if (!ok[i]) continue;
+                const uint32_t prev = i == 0 ? before : key[i - 1];
+                const uint32_t prev_snap = i == 0 ? before_snap : snap[i - 1];
+                // the key rises with the deadline under low budget first and falls with it under high budget first
+                if (snap[i] == prev_snap && (MODE == PARD_ORDER_LBF ? key[i] < prev : key[i] > prev)) saw |= kSawFall;
+            }
+            if constexpr (MODE == PARD_ORDER_HBF) {
+                // in sorted order, equal values kTieReach apart mean a run longer than that (a run of kTieReach + 4 or
+                // more holds the first request of a group of four together with the one kTieReach before it); that
+                // request is the same one of the lane kTieReach / 8 below (lowest lanes: from memory)
+                static_assert(kTieReach % kScanItems == 0, "the far request sits in a whole lane's distance");
+#pragma unroll
+                for (int g = 0; g < kScanItems / 4; ++g) {
+                    uint32_t far = __shfl_up(key[g * 4], kTieReach / kScanItems);
+                    if (lane < kTieReach / kScanItems) {
+                        const int64_t r = lane_first(base, lane, g) - kTieReach;
+                        far = ~key[g * 4];
+                        if (r >= 0 && r + kTieReach < A.n) far = order_key(MODE, A.deadline[r], 0);
+                    }
+                    if (ok[g * 4] && key[g * 4] == far) saw |= kSawLongTie;
+                }
+            }
+        }
 #pragma unroll
         for (int i = 0; i < kScanItems; ++i) {
             if (ok[i]) {
                 if (priv) atomicAdd(&h[seg[i] * kScanThreads + tid], 1u);
+                else if (rows) atomicAdd(&h[wave * kPartialSegs + seg[i]], 1u);
                 else if (use_lds) atomicAdd(&h[seg[i]], 1u);
                 else atomicAdd(&A.seg_count[seg[i]], 1u);
                 kmin = key[i] < kmin ? key[i] : kmin;
@@ -245,26 +379,37 @@ __global__ __launch_bounds__(kScanThreads) void count_kernel(SortDev A) {
         kmax = b > kmax ? b : kmax;
     }
     if (lane == 0) { red[2 * wave] = ~kmin; red[2 * wave + 1] = kmax; }
+    const uint32_t wave_saw = (__ballot(saw & kSawFall) ? kSawFall : 0u) | (__ballot(saw & kSawLongTie) ? kSawLongTie : 0u);
+    if (lane == 0) saw_by_wave[wave] = wave_saw;
+    // queue lengths of this wave's stretch, and of the workgroup's
+    if (priv || rows) {
+        uint32_t* mine = A.wave_cnt + ((int64_t)blockIdx.x * (kScanThreads / kWave) + wave) * kPartialSegs;
+        if (priv) {
+            for (int64_t g = 0; g < segs; ++g) {
+                uint32_t v = h[g * kScanThreads + tid];
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+                if (lane == 0) { mine[g] = v; if (v) atomicAdd(&block_tot[g], v); }
+            }
+        } else {
+            const uint32_t v = lane < segs ? h[wave * kPartialSegs + lane] : 0u;
+            if (lane < segs) { mine[lane] = v; if (v) atomicAdd(&block_tot[lane], v); }
+        }
+    }
     __syncthreads();
     if (tid == 0) {
-        uint32_t a = 0, b = 0;
+        uint32_t a = 0, b = 0, f = watch ? 0u : kSawFall;
         for (int w = 0; w < kScanThreads / kWave; ++w) {
             a = red[2 * w] > a ? red[2 * w] : a;
             b = red[2 * w + 1] > b ? red[2 * w + 1] : b;
+            f |= saw_by_wave[w];
         }
         A.part_minmax[2 * blockIdx.x] = a;
         A.part_minmax[2 * blockIdx.x + 1] = b;
+        A.part_flag[blockIdx.x] = f;
     }
-    if (priv) {
-        for (int64_t g = wave; g < segs; g += kScanThreads / kWave) {
-            uint32_t v = 0;
-            for (int j = lane; j < kScanThreads; j += kWave) v += h[g * kScanThreads + j];
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
-            if (lane == 0) A.part_cnt[(int64_t)blockIdx.x * kPartialSegs + g] = v;
-        }
-    } else if (segs <= kPartialSegs) {
-        if (tid < segs) A.part_cnt[(int64_t)blockIdx.x * kPartialSegs + tid] = h[tid];
+    if (priv || rows) {
+        if (tid < segs) A.part_cnt[(int64_t)blockIdx.x * kPartialSegs + tid] = block_tot[tid];
     } else if (use_lds) {
         for (int i = tid; i < segs; i += kScanThreads)
             if (h[i]) atomicAdd(&A.seg_count[i], h[i]);
@@ -273,8 +418,10 @@ __global__ __launch_bounds__(kScanThreads) void count_kernel(SortDev A) {
 
 // ---- setup: one workgroup --------------------------------------------------------
 __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
+    constexpr int kSlices = 1024 / kPartialSegs;
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t carry;
+    __shared__ uint32_t slice_tot[kSlices][kPartialSegs];
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)P.K * P.S;
@@ -295,22 +442,19 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         }
         if (lane == 0) { mm[0][wave] = a; mm[1][wave] = b; }
         if (segs <= kPartialSegs) {
-            // thread t: queue t % 64, workgroups t / 64, t / 64 + 16, ...; four loads in flight
-            const int g = tid & (kPartialSegs - 1);
-            uint32_t v0 = 0, v1 = 0, v2 = 0, v3 = 0;
-            if (g < segs) {
-                const int step = 1024 / kPartialSegs;
-                int i = tid / kPartialSegs;
-                for (; i + 3 * step < A.stream_blocks; i += 4 * step) {
-                    v0 += A.part_cnt[(int64_t)i * kPartialSegs + g];
-                    v1 += A.part_cnt[(int64_t)(i + step) * kPartialSegs + g];
-                    v2 += A.part_cnt[(int64_t)(i + 2 * step) * kPartialSegs + g];
-                    v3 += A.part_cnt[(int64_t)(i + 3 * step) * kPartialSegs + g];
-                }
-                for (; i < A.stream_blocks; i += step) v0 += A.part_cnt[(int64_t)i * kPartialSegs + g];
+            // thread (slice, g) adds up queue g over the workgroups [slice * len, (slice + 1) * len), eight loads in flight
+            const int g = tid & (kPartialSegs - 1), slice = tid / kPartialSegs;
+            const int len = (A.stream_blocks + kSlices - 1) / kSlices;
+            const int b0 = slice * len, b1 = b0 + len < A.stream_blocks ? b0 + len : A.stream_blocks;
+            uint32_t sum = 0;
+            for (int b = b0; b < b1; b += 8) {
+                uint32_t v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] : 0u;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sum += v[k];
             }
-            const uint32_t v = v0 + v1 + v2 + v3;
-            if (g < segs && v) atomicAdd(&A.seg_count[g], v);
+            slice_tot[slice][g] = sum;
         }
         __syncthreads();
         if (tid == 0) {
@@ -320,6 +464,11 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
             }
             A.params->inv_min = mm[0][0];
             A.params->max_key = mm[1][0];
+        }
+        if (segs <= kPartialSegs && tid < segs) {
+            uint32_t v = 0;
+            for (int sl = 0; sl < kSlices; ++sl) v += slice_tot[sl][tid];
+            A.seg_count[tid] = v;
         }
         __threadfence();
         __syncthreads();
@@ -334,6 +483,47 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         A.params->total_bits = total;
         A.params->passes = passes < 1 ? 1 : passes;
         carry = 0;
+    }
+    // Requests in deadline order: the queues are a stable split by stage, done by split_kernel; the radix passes, the
+    // epilogue and the unpacking then find nothing to do (passes = 0).
+    {
+        __shared__ uint32_t seen;
+        if (tid == 0) seen = 0;
+        __syncthreads();
+        uint32_t f = 0;
+        for (int i = tid; i < A.stream_blocks; i += 1024) f |= A.part_flag[i];
+        if (f) atomicOr(&seen, f);
+        __syncthreads();
+        const bool hbf = P.uniform_mode == PARD_ORDER_HBF;
+        const bool split = A.n > 0 && !A.consistent && segs <= kPartialSegs && !(seen & kSawFall) && !(hbf && (seen & kSawLongTie));
+        if (tid == 0) {
+            A.params->split = split ? 1u : 0u;
+            if (split) A.params->passes = 0;
+        }
+        if (split) {
+            // a snapshot beyond the promised bound is flagged as the radix passes would flag it (their payload word
+            // holds idx_bits of index); the split itself has no such limit
+            for (int u = tid; u < P.K; u += 1024) {
+                const int64_t size = (int64_t)A.snap_ptr[u + 1] - (int64_t)A.snap_ptr[u];
+                if (A.idx_bits < 32 && size > ((int64_t)1 << A.idx_bits)) atomicOr(A.status_word, kStatusSnapshotTooLarge);
+            }
+            // part_cnt[b][g] becomes the number of requests of queue g in the workgroups before b
+            const int g = tid & (kPartialSegs - 1), slice = tid / kPartialSegs;
+            const int len = (A.stream_blocks + kSlices - 1) / kSlices;
+            const int b0 = slice * len, b1 = b0 + len < A.stream_blocks ? b0 + len : A.stream_blocks;
+            uint32_t run = 0;
+            for (int sl = 0; sl < slice; ++sl) run += slice_tot[sl][g];
+            for (int b = b0; b < b1; b += 8) {
+                uint32_t v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] : 0u;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    if (b + k < b1) A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] = run;
+                    run += v[k];
+                }
+            }
+        }
     }
     __syncthreads();
     // queue offsets: exclusive scan of the queue lengths, 1024 at a time
@@ -758,7 +948,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
 constexpr int kEpiSegs = 64;
 constexpr int kEpiThreads = 256;
 
-struct EpiSeg {                     // 64 bytes
+struct EpiSeg {                     // 80 bytes
     uint32_t B, W, latB, mode;
     uint32_t mB, shB, mW, shW;
     int32_t start, now;
@@ -766,17 +956,19 @@ struct EpiSeg {                     // 64 bytes
     int32_t first;                  // first request of the queue's snapshot
     int32_t len;                    // queue length
     uint32_t aux;                   // smallest execution latency | kSegScan << 31
-    int32_t pad;
+    int32_t rec;                    // the queue's stage record and latency row in the plan
+    uint32_t aW, bW;                // latB = aW * W + bW
+    uint32_t pad[2];
 };
 
 // own-stage cost at queue position pos plus the downstream maximum: stage_cost() with the record
 // held in registers
 __device__ __forceinline__ uint64_t epilogue_estimate(const EpiSeg& q, const int32_t* lat_row, uint32_t pos) {
     const uint32_t batches = magic_div_dev(pos + q.B - 1u, q.mB, q.shB);
-    const uint64_t x = (uint64_t)batches * q.latB;
-    uint64_t wait;
-    if ((x >> 32) == 0) wait = magic_div_dev((uint32_t)x, q.mW, q.shW);
-    else wait = wide_div(x, q.W);
+    const uint64_t p = (uint64_t)batches * q.bW;
+    uint64_t wait = (uint64_t)batches * q.aW;
+    if ((p >> 32) == 0) wait += magic_div_dev((uint32_t)p, q.mW, q.shW);
+    else wait += wide_div(p, q.W);
     uint32_t ex = q.latB;
     if (pos + 1u < q.B) ex = (uint32_t)lat_row[pos];             // only the first B-1 requests of a queue
     uint64_t c = wait + ex;
@@ -814,7 +1006,8 @@ __device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t se
     q.first = A.snap_ptr[u];
     q.len = A.seg_ptr[seg + 1] - q.start;
     q.aux = A.consistent ? A.min_lat[seg] : 0u;
-    q.pad = 0;
+    q.rec = (int32_t)(P.shared ? k : seg);
+    q.aW = sr.aW; q.bW = sr.bW; q.pad[0] = q.pad[1] = 0;
     q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
     return q;
 }
@@ -831,6 +1024,7 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
     __shared__ int32_t gfirst[kEpiSegs + 1];     // first group of four slots a queue owns (the group's first slot is the queue's)
     __shared__ int32_t cum[kEpiSegs + 1];        // this share: groups of the queues before q
     __shared__ int32_t from[kEpiSegs];           // this share: its first group of queue q
+    if (A.params->split) return;                 // the split kernel has written everything
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x;
     const int64_t segs = (int64_t)P.K * P.S;
@@ -934,6 +1128,7 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
 }
 
 __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
+    if (A.params->split) return;
     const uint32_t* packed = A.key[(((int)A.params->passes - 1) & 1) ^ 1];
     const bool vec = ((reinterpret_cast<uintptr_t>(A.est) & 15) | (reinterpret_cast<uintptr_t>(A.drop) & 3)) == 0;
     const int64_t groups = (A.n + 3) / 4;
@@ -951,6 +1146,214 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
                 A.est[r] = (int32_t)(v & 0x7FFFFFFFu);
                 A.drop[r] = (uint8_t)(v >> 31);
             }
+        }
+    }
+}
+
+// ---- split: snapshots whose requests come in deadline order ----------------------------------
+// When the deadlines never fall along the request array (a queue snapshot taken in arrival order, one SLO), the
+// queue order needs no sort.  Low budget first: a queue holds its requests in request order, so a request's
+// position is the number of earlier requests of its stage.  High budget first: the reverse, except that requests
+// with equal deadlines keep their request order: with j earlier requests of the stage, `before` of them and
+// `after` later ones sharing the deadline, the position is (queue length - 1 - j) - after + before.  Equal
+// deadlines are neighbours in the array, so before and after come from looking left and right as long as the
+// deadline stays the same (the count kernel has ruled out runs longer than kTieSearch).
+// Every wave takes the same contiguous stretch of the array as in the count kernel and works on its own: lane g
+// starts from the number of requests of queue g before the stretch (workgroups before: left by the setup kernel;
+// waves before in the workgroup: the count kernel's per-wave counts) and carries it along.  Estimates and
+// decisions leave in request order (coalesced); only the queue order is scattered, as one ascending or
+// descending stream per queue.  Under high budget first a wave keeps the keys and queues of its 512 requests,
+// and of kTieSearch requests on either side, in its own piece of LDS for the look to the left and right.
+constexpr int kTieSearch = 40;
+constexpr int kSplitWaves = kScanThreads / kWave;      // waves per workgroup of the count kernel
+constexpr int kSplitThreads = 256;                     // the split's own workgroups: a quarter of those waves each
+constexpr int kSplitPerCount = kScanThreads / kSplitThreads;
+constexpr int kHaloSpan = kWaveChunk + 2 * kTieSearch;
+
+// OR over the 64 lanes of a wave (the result is the same in every lane's copy of the return value)
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xF, 0xF, false);    // row_shr:1
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xF, 0xF, false);    // row_shr:2
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, false);    // row_shr:4
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, false);    // row_shr:8
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false);    // row_bcast:15 into rows 1, 3
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false);    // row_bcast:31 into rows 2, 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Queues are counted three to a 32-bit word, ten bits each: a wave chunk holds 512 requests, so no field of an
+// exclusive prefix passes 504, and a field of the inclusive prefix that reaches 512 and spills into the next one
+// is put right again when the lane's own word is subtracted.
+constexpr uint32_t kFieldBits = 10, kFieldMask = (1u << kFieldBits) - 1u;
+constexpr uint32_t kNoWord = 31;
+
+template <bool HBF>
+__global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
+    if (!A.params->split) return;
+    __shared__ EpiSeg tab[kPartialSegs];
+    __shared__ __align__(16) uint32_t halo_key[HBF ? kSplitThreads / kWave : 1][HBF ? kHaloSpan : 4];
+    __shared__ __align__(16) uint8_t halo_seg[HBF ? kSplitThreads / kWave : 1][HBF ? kHaloSpan : 16];
+    const PlanDev& P = A.plan;
+    const int tid = threadIdx.x, lane = tid & 63, own = tid >> 6;
+    // which workgroup and wave of the count kernel this wave follows
+    const int block = blockIdx.x / kSplitPerCount, wave = (blockIdx.x % kSplitPerCount) * (kSplitThreads / kWave) + own;
+    const int blocks = gridDim.x / kSplitPerCount;
+    const int segs = P.K * P.S;
+    if (tid < segs) tab[tid] = epilogue_segment(A, (uint32_t)tid);
+    // lane g: requests of queue g before this wave's stretch
+    uint32_t run = 0;
+    if (lane < segs) {
+        run = A.part_cnt[(int64_t)block * kPartialSegs + lane];
+        const uint32_t* rows = A.wave_cnt + (int64_t)block * kSplitWaves * kPartialSegs + lane;
+        uint32_t v[kSplitWaves - 1];
+#pragma unroll
+        for (int w = 0; w < kSplitWaves - 1; ++w) v[w] = w < wave ? rows[w * kPartialSegs] : 0u;
+#pragma unroll
+        for (int w = 0; w < kSplitWaves - 1; ++w) run += v[w];
+    }
+    const uint32_t lane_word = ((uint32_t)lane * 43u) >> 7;             // lane / 3 (exact below 128)
+    const uint32_t lane_shift = kFieldBits * ((uint32_t)lane - 3u * lane_word);
+    const bool vec = arrays_vectorizable(A);
+    const bool vec_out = ((reinterpret_cast<uintptr_t>(A.est) & 15) | (reinterpret_cast<uintptr_t>(A.drop) & 3)) == 0;
+    const int32_t bound = snapshot_bound(A, lane);
+    int64_t first, last;
+    wave_range(A.n, blocks, block, wave, first, last);
+    __syncthreads();
+    for (int64_t chunk = first; chunk < last; ++chunk) {
+        const int64_t base = chunk * kWaveChunk;
+        uint32_t snap[kScanItems], seg[kScanItems], key[kScanItems], j[kScanItems];
+        bool ok[kScanItems];
+        load_chunk_by_deadline<HBF ? PARD_ORDER_HBF : PARD_ORDER_LBF>(A, base, lane, vec, bound, snap, seg, key, ok);
+        // need a look to the left or right: an equal key next to the request
+        uint32_t tie_left = 0, tie_right = 0;                  // one bit per request of the lane
+        uint64_t ties_before = 0, ties_after = 0;              // one byte per request: same queue, same deadline, to the left / right
+        if constexpr (HBF) {
+            // the neighbours on either side of the wave chunk (two loads per lane at most), then the chunk itself
+            uint32_t* hk = halo_key[own];
+            uint8_t* hs = halo_seg[own];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int h = lane + t * kWave;                                   // 0 .. 127, of which 2 * kTieSearch used
+                if (h < 2 * kTieSearch) {
+                    const bool left = h < kTieSearch;
+                    const int64_t r = left ? base - kTieSearch + h : base + kWaveChunk + (h - kTieSearch);
+                    const int at = left ? h : kTieSearch + kWaveChunk + (h - kTieSearch);
+                    uint32_t k = 0, sg = 0xFFu;
+                    if (r >= 0 && r < A.n) {
+                        k = order_key(PARD_ORDER_HBF, A.deadline[r], 0);
+                        const uint32_t u = P.K == 1 ? 0u : (uint32_t)snapshot_of(A.snap_ptr, P.K, r);
+                        sg = u * (uint32_t)P.S + (uint32_t)clamp_stage(A.stage[r], P.S);
+                    }
+                    hk[at] = k;
+                    hs[at] = (uint8_t)sg;
+                }
+            }
+            const int at0 = kTieSearch + lane * kScanItems;
+            static_assert(kTieSearch % 8 == 0, "a lane's eight keys sit on a 16-byte boundary");
+            *reinterpret_cast<uint4*>(hk + at0) = make_uint4(key[0], key[1], key[2], key[3]);
+            *reinterpret_cast<uint4*>(hk + at0 + 4) = make_uint4(key[4], key[5], key[6], key[7]);
+            uint32_t s_lo = 0, s_hi = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                s_lo |= (ok[c] ? seg[c] : 0xFFu) << (8 * c);
+                s_hi |= (ok[4 + c] ? seg[4 + c] : 0xFFu) << (8 * c);
+            }
+            *reinterpret_cast<uint2*>(hs + at0) = make_uint2(s_lo, s_hi);
+            // the wave's own LDS traffic runs in order; this only keeps the compiler from moving reads above the writes
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const uint32_t left_key = hk[at0 - 1], right_key = hk[at0 + kScanItems];
+#pragma unroll
+            for (int i = 0; i < kScanItems; ++i) {
+                tie_left |= ((i == 0 ? left_key : key[i - 1]) == key[i] ? 1u : 0u) << i;
+                tie_right |= ((i == kScanItems - 1 ? right_key : key[i + 1]) == key[i] ? 1u : 0u) << i;
+            }
+            // one look at a time (rare: deadlines are in microseconds), a byte of the result per request
+            uint32_t looks = tie_left | (tie_right << kScanItems);
+            while (looks) {
+                const int b = __builtin_ctz(looks);
+                looks &= looks - 1u;
+                const int i = b & (kScanItems - 1), step = b < kScanItems ? -1 : 1;
+                const int at = at0 + i;
+                const uint32_t uk = hk[at];
+                const uint8_t sg = hs[at];
+                uint32_t same = 0;
+                for (int t = 1; t <= kTieSearch; ++t) {
+                    if (hk[at + step * t] != uk) break;
+                    same += hs[at + step * t] == sg ? 1u : 0u;
+                }
+                if (step < 0) ties_before |= (uint64_t)same << (8 * i);
+                else ties_after |= (uint64_t)same << (8 * i);
+            }
+        }
+        // j: requests of the same queue ahead in the array.  First those before the chunk ...
+        uint32_t word[kScanItems], shift[kScanItems], present = 0;
+#pragma unroll
+        for (int i = 0; i < kScanItems; ++i) {
+            j[i] = (uint32_t)__shfl((int)run, (int)(seg[i] & 63u));
+            const uint32_t w = (seg[i] * 43u) >> 7;                      // seg / 3
+            shift[i] = kFieldBits * (seg[i] - 3u * w);
+            word[i] = ok[i] ? w : kNoWord;
+            present |= 1u << word[i];
+        }
+        // ... then, word by word of three queues, those in lower lanes and earlier in this lane
+        uint32_t words = wave_or(present) & ~(1u << kNoWord);
+        while (words) {
+            const uint32_t w = (uint32_t)__builtin_ctz(words);
+            words &= words - 1u;
+            uint32_t partial[kScanItems + 1];
+            partial[0] = 0;
+#pragma unroll
+            for (int i = 0; i < kScanItems; ++i) partial[i + 1] = partial[i] + (word[i] == w ? 1u << shift[i] : 0u);
+            const uint32_t inclusive = wave_inclusive_sum(partial[kScanItems]);
+            const uint32_t below = inclusive - partial[kScanItems];
+            const uint32_t last_below = (uint32_t)__builtin_amdgcn_readlane((int)below, 63);
+            const uint32_t last_own = (uint32_t)__builtin_amdgcn_readlane((int)partial[kScanItems], 63);
+#pragma unroll
+            for (int i = 0; i < kScanItems; ++i)
+                if (word[i] == w) j[i] += ((below + partial[i]) >> shift[i]) & kFieldMask;
+            if (lane_word == w) run += ((last_below >> lane_shift) & kFieldMask) + ((last_own >> lane_shift) & kFieldMask);
+        }
+#pragma unroll
+        for (int g = 0; g < kScanItems / 4; ++g) {
+            const int64_t r0 = lane_first(base, lane, g);
+            int32_t est[4];
+            uint8_t drp[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const int i = g * 4 + c;
+                est[c] = 0;
+                drp[c] = 0;
+                if (!ok[i]) continue;
+                const int64_t r = r0 + c;
+                const EpiSeg& q = tab[seg[i]];
+                const uint32_t uk = key[i];
+                const int32_t d = HBF ? (int32_t)(~uk ^ 0x80000000u) : (int32_t)(uk ^ 0x80000000u);
+                uint32_t pos = j[i];
+                if constexpr (HBF) {
+                    // requests of the same queue with the same deadline right before and right after this one
+                    const uint32_t before = (uint32_t)(ties_before >> (8 * i)) & 0xFFu;
+                    const uint32_t after = (uint32_t)(ties_after >> (8 * i)) & 0xFFu;
+                    pos = (uint32_t)q.len - 1u - j[i] - after + before;
+                }
+                const uint64_t e64 = epilogue_estimate(q, P.lat + (int64_t)q.rec * PARD_LAT_ENTRIES, pos);
+                finish_request(e64, q.now, d, est[c], drp[c]);
+                A.order[(int64_t)q.start + pos] = (int32_t)r;
+            }
+            if (vec_out && r0 + 3 < A.n) {
+                *reinterpret_cast<int4*>(A.est + r0) = make_int4(est[0], est[1], est[2], est[3]);
+                *reinterpret_cast<uint32_t*>(A.drop + r0) =
+                    (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (ok[g * 4 + c]) { A.est[r0 + c] = est[c]; A.drop[r0 + c] = drp[c]; }
+            }
+        }
+        if constexpr (HBF) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
@@ -1364,6 +1767,8 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.chunks = L.chunks;
     D.part_minmax = reinterpret_cast<uint32_t*>(ws + L.part_minmax);
     D.part_cnt = reinterpret_cast<uint32_t*>(ws + L.part_cnt);
+    D.part_flag = reinterpret_cast<uint32_t*>(ws + L.part_flag);
+    D.wave_cnt = reinterpret_cast<uint32_t*>(ws + L.wave_cnt);
     for (int b = 0; b < 2; ++b) {
         D.key[b] = reinterpret_cast<uint32_t*>(ws + L.key[b]);
         D.pay[b] = reinterpret_cast<uint32_t*>(ws + L.pay[b]);
@@ -1407,9 +1812,18 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     if (sb > kStreamBlocksMax) sb = kStreamBlocksMax;
     if (sb < 1) sb = 1;
     D.stream_blocks = sb;
-    count_kernel<<<sb, kScanThreads, 0, stream>>>(D);
+    // the split below may finish the call: then the count also watches the order of the deadlines
+    const bool may_split = a.n > 0 && !a.consistent && (int64_t)a.plan.K * a.plan.S <= kPartialSegs;
+    if (may_split && a.plan.uniform_mode == PARD_ORDER_LBF) count_kernel<PARD_ORDER_LBF><<<sb, kScanThreads, 0, stream>>>(D);
+    else if (may_split && a.plan.uniform_mode == PARD_ORDER_HBF) count_kernel<PARD_ORDER_HBF><<<sb, kScanThreads, 0, stream>>>(D);
+    else count_kernel<-1><<<sb, kScanThreads, 0, stream>>>(D);
     setup_kernel<<<1, 1024, 0, stream>>>(D);
     if (a.n > 0) {
+        // finishes the call when the requests come in deadline order; everything below then finds nothing to do
+        if (!a.consistent && (int64_t)a.plan.K * a.plan.S <= kPartialSegs) {
+            if (a.plan.uniform_mode == PARD_ORDER_HBF) split_kernel<true><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
+            else if (a.plan.uniform_mode == PARD_ORDER_LBF) split_kernel<false><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
+        }
         for (int p = 0; p < L.max_passes; ++p) {
             if (p == 0) upsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
             else upsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
