@@ -408,6 +408,9 @@ def main():
                     help="time pard_estimate_drop_compact, the one call that does both steps (same outputs; the estimate "
                          "kernels then also stage the survivors), instead of pard_estimate_drop followed by pard_compact")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-leg", action="store_true",
+                    help="do not time the other form of the call (one call / two calls) beside the timed region, so that a "
+                         "kernel trace of the run holds the timed configuration only")
     ap.add_argument("--consistent", action="store_true",
                     help="sequentially consistent dropping (positions count kept requests only)")
     ap.add_argument("--ranked", action="store_true",
@@ -520,7 +523,7 @@ def main():
 
     # the same path through the one call that does both steps, timed beside it (outside the timed region above)
     other_ms = None
-    if not (args.consistent or args.ranked):
+    if not (args.consistent or args.ranked or args.no_side_leg):
         run_other = s.run if one_call else s.run_one_call
         run_other()
         torch.cuda.synchronize()
