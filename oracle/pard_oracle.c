@@ -657,16 +657,17 @@ int pard_oracle_compact(int32_t K, int32_t S, int64_t n,
 
 /* ---- reactive baselines (Section 5.1, "Baselines") ------------------------------------------
  *
- * Nexus.  "scans the queue in arrival order with a sliding window equal to the batch size, stopping at the
- * first position where all requests in the window can meet the current module's latency budget and
- * dropping all earlier ones".  On a snapshot: the queues are given in the order to scan (order/seg_ptr as
+ * Nexus, as the paper describes it: the queue is walked in arrival order with a window as long as the batch
+ * size; the walk ends at the first position at which every request inside the window can still meet the
+ * budget of the module it waits at, and everything ahead of that position is dropped.  On a snapshot: the
+ * queues are given in the order to scan (order/seg_ptr as
  * written by the estimate call; a plan whose stages use arrival order gives the paper's baseline).  For
  * queue (u, s) with batch size B and n requests, the window at position p holds the requests at positions
  * p .. p + w - 1, w = min(B, n - p) (the last windows are cut off by the end of the queue); its requests run
  * as one batch of w, which takes lat[w]; a request can meet the module's budget when that batch ends no
  * later than its deadline, now + lat[w] <= deadline.  first_kept = the first p whose whole window can
  * (n when no window can); the requests at positions before first_kept are dropped, all others kept.
- * Nothing downstream is looked at (the paper: "without considering latency budget for subsequent modules").
+ * Nothing downstream is looked at (the paper says so: later modules' budgets play no part in this policy).
  */
 int pard_oracle_nexus_drop(int32_t K, int32_t S, int32_t dag_shared, const int32_t* batch, const int32_t* lat_us,
                            int64_t n, const int32_t* deadline, const int32_t* order, const int32_t* seg_ptr,
@@ -694,9 +695,9 @@ int pard_oracle_nexus_drop(int32_t K, int32_t S, int32_t dag_shared, const int32
     return 0;
 }
 
-/* Clipper++.  "proportionally dividing the end-to-end SLO among modules based on their execution durations,
- * SLO_k = SLO * d_k / sum_i d_i, and making drop decisions based on these per-module budgets"; Clipper itself
- * "drops requests only if they already exceed the latency objective before inference".  On a snapshot a
+/* Clipper++, as the paper describes it: the end-to-end SLO is shared out among the modules in proportion to
+ * their execution durations, SLO_k = SLO * d_k / sum_i d_i, and each module decides by its own share; Clipper
+ * itself only drops a request whose latency objective has already passed before inference starts.  On a snapshot a
  * request carries the time it was sent (arrival) and its deadline, so SLO = deadline - arrival, and what it
  * has used so far is now - arrival; the time it entered its current module is not known.  The budgets of
  * the modules up to and including the current one add up to SLO * P_k / T_k, where d_i = lat_i[B_i] is a
