@@ -274,14 +274,61 @@ __global__ __launch_bounds__(kWThreads) void sub_quantile_kernel(SubArgs A) {
 
 // ---- adaptive priority (Section 3.3) --------------------------------------------------------
 // One wave per rate series, 64 samples at a time.  The window sum at t is the prefix sum of
-// rate[t] - rate[t - w], so one running scan gives the smoothed workload; a second sweep over the
-// series (now in cache) compares every sample with the two thresholds and keeps the last one
-// that decides - which is the priority in force at the end, since samples inside the band
-// change nothing.
+// rate[t] - rate[t - w], so one running scan gives the smoothed workload.  The two thresholds are
+// comparisons of rate * lat[B] * sum with a constant of the series, so each is one cut in the
+// 32-bit range of a rate: the wave finds both cuts once (six rounds of 64 candidates each, exact
+// 128-bit products) and then walks the series backwards (it is in cache) to the last sample that
+// lies outside the band - the priority in force at the end, since samples inside change nothing.
 constexpr int kPThreads = 256;
 
 __device__ __forceinline__ unsigned __int128 mul_64_64(uint64_t a, uint64_t b) {
     return ((unsigned __int128)__umul64hi(a, b) << 64) | (unsigned __int128)(a * b);
+}
+
+// inclusive prefix sum of a 64-bit value across the wave (the 32-bit halves travel separately)
+__device__ __forceinline__ int64_t wave_inclusive_sum64(int64_t v) {
+    uint64_t x = (uint64_t)v;
+#define PARD_SCAN64_STEP(ctrl, rows)                                                                              \
+    {                                                                                                             \
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)x, ctrl, rows, 0xF, false);   \
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(x >> 32), ctrl, rows, 0xF, false); \
+        x += ((uint64_t)hi << 32) | lo;                                                                           \
+    }
+    PARD_SCAN64_STEP(0x111, 0xF)     // row_shr:1
+    PARD_SCAN64_STEP(0x112, 0xF)     // row_shr:2
+    PARD_SCAN64_STEP(0x114, 0xF)     // row_shr:4
+    PARD_SCAN64_STEP(0x118, 0xF)     // row_shr:8
+    PARD_SCAN64_STEP(0x142, 0xA)     // row_bcast:15 into rows 1, 3
+    PARD_SCAN64_STEP(0x143, 0xC)     // row_bcast:31 into rows 2, 3
+#undef PARD_SCAN64_STEP
+    return (int64_t)x;
+}
+
+// y * d as 128 bits, d given as three 32-bit limbs (d < 2^96), y < 2^32
+__device__ __forceinline__ unsigned __int128 mul_32_96(uint32_t y, uint32_t d0, uint32_t d1, uint32_t d2) {
+    const uint64_t t0 = (uint64_t)y * d0;
+    const uint64_t t1 = (uint64_t)y * d1 + (t0 >> 32);
+    const uint64_t t2 = (uint64_t)y * d2 + (t1 >> 32);
+    return ((unsigned __int128)t2 << 64) | ((unsigned __int128)(uint32_t)t1 << 32) | (unsigned __int128)(uint32_t)t0;
+}
+
+// The number of 32-bit values y, counted from 0 upwards, for which  y * d > bound  (strict) or  y * d >= bound
+// (!strict) does NOT hold yet; the condition holds for every y from that number on (2^32 when it never holds).
+// All lanes take part and get the same result.
+__device__ __forceinline__ uint64_t first_above(uint32_t d0, uint32_t d1, uint32_t d2, unsigned __int128 bound, bool strict, int lane) {
+    uint64_t found = 0;                                  // so many values are known not to satisfy the condition
+#pragma unroll
+    for (int shift = 30; shift >= 0; shift -= 6) {
+        const uint64_t y = found + ((uint64_t)(lane + 1) << shift) - 1ull;        // the last of lane+1 more blocks of 2^shift values
+        bool short_of = false;
+        if (y <= 0xFFFFFFFFull) {
+            const unsigned __int128 prod = mul_32_96((uint32_t)y, d0, d1, d2);
+            short_of = strict ? !(prod > bound) : !(prod >= bound);
+        }
+        // the condition is monotone in y, so the lanes that are still short of it form a prefix
+        found += (uint64_t)__popcll(__ballot(short_of)) << shift;
+    }
+    return found;
 }
 
 __global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, int32_t T, int32_t window, uint32_t w_mul, uint32_t w_shf,
@@ -290,34 +337,54 @@ __global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, in
     const int64_t series = (int64_t)P.K * P.S;
     const int64_t wave_id = ((int64_t)blockIdx.x * kPThreads + threadIdx.x) >> 6;
     const int64_t waves = ((int64_t)gridDim.x * kPThreads) >> 6;
+    // every series starts on a 16-byte boundary when the array does and the length is a multiple of 4
+    const bool vec = (T & 3) == 0 && (reinterpret_cast<uintptr_t>(rate) & 15) == 0;
     for (int64_t g = wave_id; g < series; g += waves) {
         const int64_t rec = P.shared ? g % P.S : g;
         const StageRec sr = P.recs[rec];
         const int32_t* r = rate + g * T;
-        // sum of the series and of |rate - smoothed rate|
+        // sum of the series and of |rate - smoothed rate|; a lane takes four consecutive samples
         uint64_t sum = 0, dev = 0;
         int64_t carry = 0;                                          // window sum up to the previous chunk's last sample
-        for (int32_t t0 = 0; t0 < T; t0 += 64) {
-            const int32_t t = t0 + lane;
-            const bool ok = t < T;
-            const int64_t x = ok ? (int64_t)r[t] : 0;
-            const int64_t old = (ok && t >= window) ? (int64_t)r[t - window] : 0;
-            int64_t inc = x - old;
+        for (int32_t t0 = 0; t0 < T; t0 += 4 * 64) {
+            const int32_t t = t0 + 4 * lane;
+            int32_t xs[4];
+            if (vec && t + 3 < T) {
+                const int4 v = *reinterpret_cast<const int4*>(r + t);
+                xs[0] = v.x; xs[1] = v.y; xs[2] = v.z; xs[3] = v.w;
+            } else {
 #pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int64_t up = __shfl_up(inc, off);
-                if (lane >= off) inc += up;
+                for (int i = 0; i < 4; ++i) xs[i] = t + i < T ? r[t + i] : 0;
             }
-            const int64_t win = carry + inc;                         // rate[max(0, t-w+1)] + ... + rate[t]
-            carry += __shfl(inc, 63);
-            if (ok) {
-                const int64_t cnt = t + 1 < window ? t + 1 : window;
-                // floor of the window mean; a full window whose sum fits 32 bits divides by multiplication
-                const int64_t ts = (cnt == window && ((uint64_t)win >> 32) == 0ull) ? (int64_t)magic_div_dev((uint32_t)win, w_mul, w_shf)
-                                                                                   : win / cnt;
-                const int64_t d = x - ts;
-                dev += (uint64_t)(d < 0 ? -d : d);
-                sum += (uint64_t)x;
+            int64_t part[4];                                         // inc of this lane's samples up to and including i
+            int64_t run = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool ok = t + i < T;
+                const int64_t old = (ok && t + i >= window) ? (int64_t)r[t + i - window] : 0;
+                run += (ok ? (int64_t)xs[i] : 0) - old;
+                part[i] = run;
+            }
+            const int64_t incl = wave_inclusive_sum64(run);
+            const int64_t before = carry + incl - run;               // window sum just before this lane's first sample
+            carry += (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)incl >> 32), 63) << 32) |
+                               (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(uint64_t)incl, 63));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (t + i < T) {
+                    const int64_t win = before + part[i];            // rate[max(0, t-w+1)] + ... + rate[t]
+                    const int64_t x = (int64_t)xs[i];
+                    const int64_t cnt = t + i + 1 < window ? t + i + 1 : window;
+                    // floor of the window mean; a sum that fits 32 bits divides by multiplication once the window is
+                    // full and by a 32-bit division before that
+                    int64_t ts;
+                    if (((uint64_t)win >> 32) != 0ull) ts = win / cnt;
+                    else if (cnt == window) ts = (int64_t)magic_div_dev((uint32_t)win, w_mul, w_shf);
+                    else ts = (int64_t)((uint32_t)win / (uint32_t)cnt);
+                    const int64_t d = x - ts;
+                    dev += (uint64_t)(d < 0 ? -d : d);
+                    sum += (uint64_t)x;
+                }
             }
         }
 #pragma unroll
@@ -325,29 +392,30 @@ __global__ __launch_bounds__(kPThreads) void priority_modes_kernel(PlanDev P, in
             sum += __shfl_xor(sum, off);
             dev += __shfl_xor(dev, off);
         }
-        // thresholds, cross-multiplied:  mu > 1 + eps  <=>  rate * lat[B] * sum > W * B * 10^6 * (sum + dev)
+        // thresholds, cross-multiplied:  mu > 1 + eps  <=>  rate * lat[B] * sum > W * B * 10^6 * (sum + dev),
+        // mu < 1 - eps  <=>  rate * lat[B] * sum < W * B * 10^6 * (sum - dev); an all-zero series has eps = 0
         const uint64_t cap = (uint64_t)(uint32_t)sr.W * (uint32_t)sr.B * 1000000ull;            // < 2^46
-        unsigned __int128 hi, lo;
-        if (sum > 0) {
-            hi = mul_64_64(cap, sum + dev);
-            lo = dev <= sum ? mul_64_64(cap, sum - dev) : (unsigned __int128)0;                   // 1 - eps < 0: never below
-        } else {
-            hi = lo = cap;
-        }
-        const bool never_below = sum > 0 && dev > sum;
+        const uint64_t s1 = sum > 0 ? sum : 1ull, dv = sum > 0 ? dev : 0ull;
+        const unsigned __int128 hi = mul_64_64(cap, s1 + dv);
+        const bool never_below = dv > s1;                                                         // 1 - eps < 0
+        const unsigned __int128 lo = never_below ? (unsigned __int128)0 : mul_64_64(cap, s1 - dv);
+        const unsigned __int128 per_rate = mul_64_64((uint64_t)(uint32_t)sr.latB, s1);            // < 2^31 * 2^62
+        const uint32_t d0 = (uint32_t)per_rate, d1 = (uint32_t)(per_rate >> 32), d2 = (uint32_t)(per_rate >> 64);
+        // a rate is above the band from `above_from` on and below it up to `below_until` - 1
+        const uint64_t above_from = first_above(d0, d1, d2, hi, true, lane);
+        const uint64_t below_until = never_below ? 0ull : first_above(d0, d1, d2, lo, false, lane);
         int32_t mode = prev_mode ? prev_mode[g] : PARD_ORDER_LBF;
-        for (int32_t t0 = 0; t0 < T; t0 += 64) {
+        for (int32_t t0 = ((T - 1) / 64) * 64; t0 >= 0; t0 -= 64) {
             const int32_t t = t0 + lane;
             const bool ok = t < T;
             const uint64_t x = ok ? (uint64_t)(uint32_t)r[t] : 0;
-            const uint64_t xl = x * (uint32_t)sr.latB;                                            // < 2^62
-            const unsigned __int128 lhs = sum > 0 ? mul_64_64(xl, sum) : (unsigned __int128)xl;
-            const bool above = ok && lhs > hi;
-            const bool below = ok && !never_below && lhs < lo;
+            const bool above = ok && x >= above_from;
+            const bool below = ok && x < below_until;
             const unsigned long long decided = __ballot(above || below);
             if (decided) {
                 const int last = 63 - __clzll((long long)decided);
                 mode = ((__ballot(above) >> last) & 1ull) ? PARD_ORDER_HBF : PARD_ORDER_LBF;
+                break;
             }
         }
         if (lane == 0) mode_out[g] = mode;
