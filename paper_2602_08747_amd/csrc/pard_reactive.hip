@@ -25,7 +25,6 @@ namespace {
 
 constexpr int kRxThreads = 256;
 constexpr int kRxChunks = 16;                            // chunks of 64 queue slots a wave walks
-constexpr int kRxTile = kRxThreads / kWave * kRxChunks * kWave;   // queue slots per workgroup
 constexpr int32_t kNoWindow = 0x7fffffff;
 
 // The queue that holds slot j: the last g in [lo, hi] with seg_ptr[g] <= j (queues may be empty).
@@ -50,38 +49,67 @@ struct WindowArgs {
     int32_t* first;
 };
 
-// Step 1.
+// What a lane keeps about the queue its slots are in; reloaded only when the queue changes along the walk.
+struct QueueView {
+    int g;
+    int32_t start, len, batch;
+    int64_t batch_end;                                      // now + lat[B]
+};
+
+__device__ __forceinline__ void look_at_queue(const WindowArgs& A, int g, QueueView& q) {
+    const int S = A.plan.S;
+    const int u = g / S;
+    const StageRec& r = A.plan.recs[A.plan.shared ? g - u * S : g];
+    q.g = g;
+    q.start = A.seg_ptr[g];
+    q.len = A.seg_ptr[g + 1] - q.start;
+    q.batch = r.B;
+    q.batch_end = (int64_t)A.now[u] + (int64_t)r.latB;
+}
+
+// Step 1.  A wave walks kRxChunks chunks of 64 slots plus one chunk of look-ahead.  All its loads are issued before
+// anything is decided: the slots' request ids first, then the deadlines they point at (two round trips to memory
+// for the whole walk instead of two per chunk).
 __global__ __launch_bounds__(kRxThreads) void window_scan_kernel(WindowArgs A) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int G = A.plan.K * A.plan.S, S = A.plan.S;
+    const int G = A.plan.K * A.plan.S;
     const int64_t t0 = ((int64_t)blockIdx.x * (kRxThreads / kWave) + wave) * (kRxChunks * kWave);
     if (t0 >= A.n) return;
     int64_t t1 = t0 + (kRxChunks + 1) * kWave;            // one chunk of look-ahead
     if (t1 > A.n) t1 = A.n;
     const int g_lo = queue_of_slot(A.seg_ptr, t0, 0, G - 1), g_hi = queue_of_slot(A.seg_ptr, t1 - 1, g_lo, G - 1);
+    int32_t req[kRxChunks + 1], dl[kRxChunks + 1];
+#pragma unroll
+    for (int c = 0; c <= kRxChunks; ++c) {
+        const int64_t j = t0 + (int64_t)c * kWave + lane;
+        req[c] = j < t1 ? A.order[j] : -1;
+    }
+#pragma unroll
+    for (int c = 0; c <= kRxChunks; ++c) dl[c] = req[c] >= 0 ? A.deadline[req[c]] : 0;
 
+    QueueView q;
+    look_at_queue(A, g_lo, q);
     // state of the previous chunk, whose windows are settled once the late bits of this chunk are known
     unsigned long long late_prev = 0;
     int g_prev = 0;
     int32_t pos_prev = 0, batch_prev = 0;
     bool start_prev = false;                                // the lane's slot starts a window of full size
+    int reported = -1;                                      // the highest queue this wave has reported a position for
+#pragma unroll
     for (int c = 0; c <= kRxChunks; ++c) {
         const int64_t j = t0 + (int64_t)c * kWave + lane;
-        const bool in = j < A.n;
-        int g = g_lo;
-        int32_t pos = 0, batch = 1;
+        const bool in = j < t1;
+        int32_t pos = 0;
         bool late = false, start = false;
         if (in) {
-            g = queue_of_slot(A.seg_ptr, j, g_lo, g_hi);
-            const int u = g / S;
-            const StageRec& r = A.plan.recs[A.plan.shared ? g - u * S : g];
-            const int32_t a = A.seg_ptr[g], len = A.seg_ptr[g + 1] - a;
-            pos = (int32_t)(j - a);
-            batch = r.B;
-            const int32_t dl = A.deadline[A.order[j]];
-            late = (int64_t)A.now[u] + (int64_t)r.latB > (int64_t)dl;
-            start = c < kRxChunks && pos + batch <= len;    // the look-ahead chunk starts no windows of this wave
+            // the slots of a lane rise along the walk, so its queue only moves forward (empty queues are stepped over)
+            while (q.g < g_hi && j >= (int64_t)q.start + q.len) look_at_queue(A, q.g + 1, q);
+            pos = (int32_t)(j - q.start);
+            late = q.batch_end > (int64_t)dl[c];
+            start = c < kRxChunks && pos + q.batch <= q.len;   // the look-ahead chunk starts no windows of this wave
         }
+        const int g = in ? q.g : g_lo;
+        const int32_t batch = in ? q.batch : 1;
         const unsigned long long late_now = __ballot(late);
         if (c > 0) {
             // the B slots from the previous chunk's lane on: bits lane.. of late_prev, then the low bits of late_now
@@ -91,10 +119,14 @@ __global__ __launch_bounds__(kRxThreads) void window_scan_kernel(WindowArgs A) {
             // the lowest fitting position of a queue inside this chunk reports it
             const int g_left = __shfl_up(g_prev, 1);
             const bool fits_left = __shfl_up((int)fits, 1) != 0;
-            if (fits && (lane == 0 || !fits_left || g_left != g_prev)) {
+            // ... once per wave: positions rise along the walk, so a queue that has reported has nothing lower to add
+            const bool reports = fits && g_prev > reported && (lane == 0 || !fits_left || g_left != g_prev);
+            if (reports) {
                 if (__hip_atomic_load(A.first + g_prev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) > pos_prev)
                     atomicMin(A.first + g_prev, pos_prev);
             }
+            const unsigned long long who = __ballot(reports);
+            if (who) reported = __builtin_amdgcn_readlane(g_prev, 63 - __clzll((long long)who));   // queues rise with the lanes
         }
         late_prev = late_now;
         g_prev = g; pos_prev = pos; batch_prev = batch; start_prev = start;
@@ -128,17 +160,31 @@ __global__ __launch_bounds__(kWave) void window_tail_kernel(WindowArgs A) {
     if (lane == 0) A.first[g] = first;
 }
 
-// Step 3.
+// Step 3.  The same walk (a wave takes kRxChunks chunks of 64 slots, request ids loaded up front).
 __global__ __launch_bounds__(kRxThreads) void window_mask_kernel(WindowArgs A) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int G = A.plan.K * A.plan.S;
-    const int64_t t0 = (int64_t)blockIdx.x * kRxTile;
-    int64_t t1 = t0 + kRxTile;
+    const int64_t t0 = ((int64_t)blockIdx.x * (kRxThreads / kWave) + wave) * (kRxChunks * kWave);
+    if (t0 >= A.n) return;
+    int64_t t1 = t0 + kRxChunks * kWave;
     if (t1 > A.n) t1 = A.n;
-    if (t0 >= t1) return;
     const int g_lo = queue_of_slot(A.seg_ptr, t0, 0, G - 1), g_hi = queue_of_slot(A.seg_ptr, t1 - 1, g_lo, G - 1);
-    for (int64_t j = t0 + threadIdx.x; j < t1; j += kRxThreads) {
-        const int g = queue_of_slot(A.seg_ptr, j, g_lo, g_hi);
-        A.drop[A.order[j]] = (int32_t)(j - A.seg_ptr[g]) < A.first[g] ? 1 : 0;
+    int32_t req[kRxChunks];
+#pragma unroll
+    for (int c = 0; c < kRxChunks; ++c) {
+        const int64_t j = t0 + (int64_t)c * kWave + lane;
+        req[c] = j < t1 ? A.order[j] : -1;
+    }
+    // the slots of a lane rise along the walk, so its queue only moves forward (empty queues are stepped over)
+    int g = g_lo;
+    int32_t start = A.seg_ptr[g_lo], end = A.seg_ptr[g_lo + 1], first = A.first[g_lo];
+#pragma unroll
+    for (int c = 0; c < kRxChunks; ++c) {
+        const int64_t j = t0 + (int64_t)c * kWave + lane;
+        if (j < t1) {
+            while (g < g_hi && j >= (int64_t)end) { ++g; start = end; end = A.seg_ptr[g + 1]; first = A.first[g]; }
+            A.drop[req[c]] = (int32_t)(j - start) < first ? 1 : 0;
+        }
     }
 }
 
@@ -158,7 +204,7 @@ __device__ __forceinline__ int snapshot_of_request(const int32_t* snap_ptr, int6
     return lo;
 }
 
-constexpr int kSplitPerThread = 4;
+constexpr int kSplitPerThread = 4;                      // consecutive requests of a thread (16-byte loads when the arrays allow it)
 __global__ __launch_bounds__(kRxThreads) void slo_split_kernel(SplitArgs A) {
     const int64_t t0 = (int64_t)blockIdx.x * (kRxThreads * kSplitPerThread);
     int64_t t1 = t0 + kRxThreads * kSplitPerThread;
@@ -166,18 +212,50 @@ __global__ __launch_bounds__(kRxThreads) void slo_split_kernel(SplitArgs A) {
     if (t0 >= t1) return;
     const int K = A.plan.K, S = A.plan.S;
     const int u_lo = snapshot_of_request(A.snap_ptr, t0, 0, K - 1), u_hi = snapshot_of_request(A.snap_ptr, t1 - 1, u_lo, K - 1);
+    const int64_t r0 = t0 + (int64_t)threadIdx.x * kSplitPerThread;
+    if (r0 >= t1) return;
+    const bool vec = ((reinterpret_cast<uintptr_t>(A.arrival) | reinterpret_cast<uintptr_t>(A.deadline) |
+                       reinterpret_cast<uintptr_t>(A.stage)) & 15) == 0 && r0 + 3 < t1;
+    int32_t arr[4], dl[4], st[4];
+    if (vec) {
+        const int4 a4 = *reinterpret_cast<const int4*>(A.arrival + r0);
+        const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0);
+        const int4 s4 = *reinterpret_cast<const int4*>(A.stage + r0);
+        arr[0] = a4.x; arr[1] = a4.y; arr[2] = a4.z; arr[3] = a4.w;
+        dl[0] = d4.x; dl[1] = d4.y; dl[2] = d4.z; dl[3] = d4.w;
+        st[0] = s4.x; st[1] = s4.y; st[2] = s4.z; st[3] = s4.w;
+    } else {
 #pragma unroll
-    for (int i = 0; i < kSplitPerThread; ++i) {
-        const int64_t r = t0 + (int64_t)i * kRxThreads + threadIdx.x;
-        if (r >= t1) continue;
-        const int u = snapshot_of_request(A.snap_ptr, r, u_lo, u_hi);
-        const int k = clamp_stage(A.stage[r], S);
+        for (int i = 0; i < 4; ++i) {
+            const bool ok = r0 + i < t1;
+            arr[i] = ok ? A.arrival[r0 + i] : 0;
+            dl[i] = ok ? A.deadline[r0 + i] : 0;
+            st[i] = ok ? A.stage[r0 + i] : 0;
+        }
+    }
+    int u = snapshot_of_request(A.snap_ptr, r0, u_lo, u_hi);              // then forward: the four are consecutive
+    int64_t now = A.now[u];
+    uint32_t bits = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t r = r0 + i;
+        if (r >= t1) break;
+        while (u < u_hi && r >= (int64_t)A.snap_ptr[u + 1]) { ++u; now = A.now[u]; }
+        const int k = clamp_stage(st[i], S);
         const int64_t rec = (int64_t)(A.plan.shared ? 0 : u) * S + k;
         const int64_t way_in = A.plan.split_in[rec], whole = A.plan.split_whole[rec];
-        const int64_t used = (int64_t)A.now[u] - (int64_t)A.arrival[r];
-        const int64_t slo = (int64_t)A.deadline[r] - (int64_t)A.arrival[r];
+        const int64_t used = now - (int64_t)arr[i];
+        const int64_t slo = (int64_t)dl[i] - (int64_t)arr[i];
         // |used|, |slo| < 2^33 and the path sums are below 2^30 (checked when the plan was made): the products fit 64 bits
-        A.drop[r] = (whole == 0 ? used > slo : used * whole > slo * way_in) ? 1 : 0;
+        const bool drop = whole == 0 ? used > slo : used * whole > slo * way_in;
+        bits |= (drop ? 1u : 0u) << (8 * i);
+    }
+    if (r0 + 3 < t1 && (reinterpret_cast<uintptr_t>(A.drop) & 3) == 0) {
+        *reinterpret_cast<uint32_t*>(A.drop + r0) = bits;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (r0 + i < t1) A.drop[r0 + i] = (uint8_t)((bits >> (8 * i)) & 1u);
     }
 }
 
@@ -193,7 +271,10 @@ hipError_t launch_window_scan(const PlanDev& plan, int64_t n, const int32_t* dea
         window_scan_kernel<<<(unsigned)((n + per_block - 1) / per_block), kRxThreads, 0, stream>>>(a);
     }
     window_tail_kernel<<<(unsigned)G, kWave, 0, stream>>>(a);
-    if (n > 0) window_mask_kernel<<<(unsigned)((n + kRxTile - 1) / kRxTile), kRxThreads, 0, stream>>>(a);
+    if (n > 0) {
+        const int64_t per_block = (int64_t)(kRxThreads / kWave) * kRxChunks * kWave;
+        window_mask_kernel<<<(unsigned)((n + per_block - 1) / per_block), kRxThreads, 0, stream>>>(a);
+    }
     return hipGetLastError();
 }
 
