@@ -161,3 +161,47 @@ def test_deadline_order_unaligned_buffers(gpu, oracle_mod, mode):
             assert (h[:off] == -7).all() and (h[off + n:] == -7).all()
         h = drop_big.cpu().numpy()
         assert (h[:o8] == 9).all() and (h[o8 + n:] == 9).all()
+
+
+@pytest.mark.parametrize("mode", [wl.MODE_LBF, wl.MODE_HBF])
+def test_graph_replays_choose_the_path_again(gpu, oracle_mod, mode):
+    """A recorded call decides on the device, at every replay, whether the requests come in deadline order: the same
+    graph is replayed on inputs in order (split), shuffled (radix passes), in order with another `now`, with one
+    falling pair, and in order again, with eager work in between; every replay must match the oracle."""
+    import torch
+    w = wl.make_workload(4, n_requests=150_001, order_mode=mode)
+    w.lat_us[:] = np.maximum(1, w.lat_us // 3000)
+    w.now[:] = int(w.deadline[w.n // 3])
+    s = gpu.Session(w, max_snapshot_requests=FORCE_SORT)
+    s.run()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s.run()
+    rng = np.random.default_rng(3)
+    ordered = (w.arrival.copy(), w.deadline.copy(), w.stage.copy())
+    perm = rng.permutation(w.n)
+    for step in ("in order", "shuffled", "later now", "one falling pair", "in order again"):
+        a, d, st = (x.copy() for x in ordered)
+        if step == "shuffled":
+            a, d, st = a[perm], d[perm], st[perm]
+        if step == "one falling pair":
+            d[70_000] = d[70_001] + 5
+        if step == "later now":
+            w.now[:] = int(ordered[1][2 * w.n // 3])
+        w.arrival[:], w.deadline[:], w.stage[:] = a, d, st
+        s.arrival.copy_(torch.from_numpy(w.arrival).to(s.dev))
+        s.deadline.copy_(torch.from_numpy(w.deadline).to(s.dev))
+        s.stage.copy_(torch.from_numpy(w.stage).to(s.dev))
+        s.now.copy_(torch.from_numpy(w.now).to(s.dev))
+        s.est.zero_(); s.drop.zero_(); s.order.zero_(); s.surv_idx.zero_()      # eager work between the replays
+        torch.cuda.synchronize()
+        print(f"replay: {step}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = s.results()
+        ref = oracle_mod.run(w, threads=8)
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (step, k)
+        assert s.status_word() == 0
+        assert 0 < ref["drop"].mean() < 1
