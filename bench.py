@@ -546,15 +546,17 @@ def main():
                   "the estimate step: presorted_snapshot_kernel for snapshots in queue order, then fused_snapshot_kernel "
                   "for the others (both launches are inside the timed interval)")
         passes = 0
-    elif in_order:
-        kernel = ("pard_estimate_drop call: count_kernel (which finds the requests in deadline order), setup_kernel, "
-                  "split_kernel; the radix launches that follow find nothing to do")
-        passes = 0
     else:
-        kernel = "pard_estimate_drop call (count, setup, histogram, radix passes, epilogue)"
+        kernel = ("pard_estimate_drop call: count_kernel (which finds the requests in deadline order), setup_kernel, "
+                  "split_kernel; the radix launches that follow find nothing to do" if in_order else
+                  "pard_estimate_drop call (count, setup, histogram, radix passes, epilogue)")
+        # The denominator for snapshots beyond the chip's LDS is the out-of-core sort model with p passes of 8 bits
+        # over the key range, also when the call exploits input that is already in order and moves less: that
+        # lowers the bytes moved, not the model (the 17 B/request I/O floor is reported beside it).
         span = int(w.deadline.max()) - int(w.deadline.min()) if n else 0
         passes = max(1, -(-(max(span, 0).bit_length() + max(w.K * w.S - 1, 0).bit_length()) // 8))
-    bpr = estimate_drop_bytes_per_request(fused or in_order, passes, fcfs)
+    bpr = estimate_drop_bytes_per_request(fused, passes, fcfs)
+    io_bpr = estimate_drop_bytes_per_request(True, 0, fcfs)
     alg_bytes = bpr * n
     achieved = alg_bytes / (est_ms * 1e-3) / 1e9 if est_ms > 0 else 0.0
     traffic = (recorded_traffic(args.config, "presorted_snapshot_kernel", "pard_presorted.hip")
@@ -564,6 +566,9 @@ def main():
                 "traffic_source": (f"profiles/hbm_traffic_cfg{args.config}.txt (rocprofv3 counters, valid for the "
                                    "kernel source it names)") if traffic is not None else None,
                 "kernel": kernel, "bytes_per_request": bpr, "launch_ms": round(est_ms, 4),
+                # the same duration against the bare inputs and outputs (8 B in, 9 B out, + 4 under arrival order)
+                "io_floor_bytes_per_request": io_bpr,
+                "io_floor_frac": round(io_bpr * n / (est_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4) if est_ms > 0 else 0.0,
                 # a plain device copy moving the same number of bytes, timed in this run
                 "copy_calibration_gbs": round(copy_calibration(torch, int(alg_bytes)), 1)}
 
@@ -577,6 +582,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": w.name + ("+consistent" if args.consistent else "") + ("+ranked" if args.ranked else ""), "requests": n, "snapshots": w.K,
                    "stages": w.S, "path": "on-chip" if fused else ("deadline-order split" if in_order else "radix-sort"), "radix_passes": passes,
+                   "radix_passes_run": 0 if (fused or in_order) else passes,
                    "calls": "pard_estimate_drop_compact" if one_call else "pard_estimate_drop + pard_compact",
                    ("two_calls_ms_per_step" if one_call else "one_call_ms_per_step"): None if other_ms is None else round(other_ms, 4),
                    "drop_fraction": round(drop_frac, 4), "status_word": status,
