@@ -169,12 +169,15 @@ constexpr int kScanThreads = 1024;
 constexpr int kScanItems = 8;                          // requests per thread per chunk
 constexpr int kChunk = kScanThreads * kScanItems;      // 8192 requests per chunk
 
-// A wave walks a contiguous stretch of the request array kWaveChunk requests at a time; a lane holds 8 consecutive
-// requests of it (two 16-byte loads per array when the arrays allow it).
+// A wave walks a contiguous stretch of the request array kWaveChunk requests at a time: two groups of 256, in each
+// of which a lane holds four consecutive requests, so that a load or store of the wave covers whole cache lines
+// (16 bytes per lane when the arrays allow it; with eight consecutive requests per lane every access touched
+// twice the lines and the two kernels below ran 15 % slower).  Order inside a chunk: group, lane, the four.
 constexpr int kWaveChunk = kWave * kScanItems;         // 512 requests
+constexpr int kGroupSpan = kWave * 4;                  // 256 requests
 
 // first request of the g-th group of four of a lane
-__device__ __forceinline__ int64_t lane_first(int64_t base, int lane, int g) { return base + lane * kScanItems + g * 4; }
+__device__ __forceinline__ int64_t lane_first(int64_t base, int lane, int g) { return base + g * kGroupSpan + lane * 4; }
 
 // The wave chunks [first, last) of wave `wave` of workgroup `block`: the workgroups cut the array into contiguous
 // ranges, the waves of a workgroup cut its range into contiguous ranges (the count and the split must agree on this).
@@ -245,21 +248,22 @@ __device__ __forceinline__ void load_chunk_by_deadline(const SortDev& A, int64_t
                                                        uint32_t (&snap)[kScanItems], uint32_t (&seg)[kScanItems],
                                                        uint32_t (&key)[kScanItems], bool (&ok)[kScanItems]) {
     const PlanDev& P = A.plan;
-    const int64_t r0 = lane_first(base, lane, 0);
     int32_t d[kScanItems], st[kScanItems];
     if (vec && base + kWaveChunk <= A.n) {
 #pragma unroll
         for (int g = 0; g < kScanItems / 4; ++g) {
-            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0 + g * 4);
-            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + r0 + g * 4);
+            const int64_t r0 = lane_first(base, lane, g);
+            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + r0);
+            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + r0);
             d[g * 4] = d4.x; d[g * 4 + 1] = d4.y; d[g * 4 + 2] = d4.z; d[g * 4 + 3] = d4.w;
             st[g * 4] = s4.x; st[g * 4 + 1] = s4.y; st[g * 4 + 2] = s4.z; st[g * 4 + 3] = s4.w;
         }
     } else {
 #pragma unroll
         for (int i = 0; i < kScanItems; ++i) {
-            d[i] = r0 + i < A.n ? A.deadline[r0 + i] : 0;
-            st[i] = r0 + i < A.n ? A.stage[r0 + i] : 0;
+            const int64_t r = lane_first(base, lane, i / 4) + (i & 3);
+            d[i] = r < A.n ? A.deadline[r] : 0;
+            st[i] = r < A.n ? A.stage[r] : 0;
         }
     }
     // snapshot of the chunk's first request: the boundaries at or before it; then one step up per boundary inside
@@ -272,11 +276,11 @@ __device__ __forceinline__ void load_chunk_by_deadline(const SortDev& A, int64_t
         const int32_t b = __builtin_amdgcn_readlane(bound, __builtin_ctzll(inside));
         inside &= inside - 1ull;
 #pragma unroll
-        for (int i = 0; i < kScanItems; ++i) snap[i] += (int32_t)(r0 + i) >= b ? 1u : 0u;
+        for (int i = 0; i < kScanItems; ++i) snap[i] += (int32_t)(lane_first(base, lane, i / 4) + (i & 3)) >= b ? 1u : 0u;
     }
 #pragma unroll
     for (int i = 0; i < kScanItems; ++i) {
-        ok[i] = r0 + i < A.n;
+        ok[i] = lane_first(base, lane, i / 4) + (i & 3) < A.n;
         seg[i] = snap[i] * (uint32_t)P.S + (uint32_t)clamp_stage(st[i], P.S);
         key[i] = order_key(MODE, d[i], 0);
     }
@@ -325,33 +329,45 @@ __global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
         if constexpr (watch) {
             uint32_t snap[kScanItems];
             load_chunk_by_deadline<MODE>(A, base, lane, vec, bound, snap, seg, key, ok);
-            // the request before this lane's eight: the last of the lane below (lane 0: from memory)
-            uint32_t before = __shfl_up(key[kScanItems - 1], 1), before_snap = __shfl_up(snap[kScanItems - 1], 1);
-            if (lane == 0) {
-                before = key[0];
-                before_snap = snap[0];
-                if (base > 0 && base < A.n) {
-                    before = order_key(MODE, A.deadline[base - 1], 0);
-                    before_snap = (uint32_t)snapshot_of(A.snap_ptr, A.plan.K, base - 1);
-                }
-            }
+            // the request before a lane's four: the last of the lane below; lane 0: the last request of the group
+            // before, or for the chunk's first group the one in memory
 #pragma unroll
-            for (int i = 0; i < kScanItems; ++i) {
-                if (!ok[i]) continue;
-                const uint32_t prev = i == 0 ? before : key[i - 1];
-                const uint32_t prev_snap = i == 0 ? before_snap : snap[i - 1];
-                // the key rises with the deadline under low budget first and falls with it under high budget first
-                if (snap[i] == prev_snap && (MODE == PARD_ORDER_LBF ? key[i] < prev : key[i] > prev)) saw |= kSawFall;
+            for (int g = 0; g < kScanItems / 4; ++g) {
+                uint32_t before = __shfl_up(key[g * 4 + 3], 1), before_snap = __shfl_up(snap[g * 4 + 3], 1);
+                if (g > 0) {
+                    const uint32_t k63 = (uint32_t)__builtin_amdgcn_readlane((int)key[g * 4 - 1], 63);
+                    const uint32_t s63 = (uint32_t)__builtin_amdgcn_readlane((int)snap[g * 4 - 1], 63);
+                    if (lane == 0) { before = k63; before_snap = s63; }
+                } else if (lane == 0) {
+                    before = key[0];
+                    before_snap = snap[0];
+                    if (base > 0 && base < A.n) {
+                        before = order_key(MODE, A.deadline[base - 1], 0);
+                        before_snap = (uint32_t)snapshot_of(A.snap_ptr, A.plan.K, base - 1);
+                    }
+                }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int i = g * 4 + c;
+                    if (!ok[i]) continue;
+                    const uint32_t prev = c == 0 ? before : key[i - 1];
+                    const uint32_t prev_snap = c == 0 ? before_snap : snap[i - 1];
+                    // the key rises with the deadline under low budget first and falls with it under high budget first
+                    if (snap[i] == prev_snap && (MODE == PARD_ORDER_LBF ? key[i] < prev : key[i] > prev)) saw |= kSawFall;
+                }
             }
             if constexpr (MODE == PARD_ORDER_HBF) {
                 // in sorted order, equal values kTieReach apart mean a run longer than that (a run of kTieReach + 4 or
                 // more holds the first request of a group of four together with the one kTieReach before it); that
-                // request is the same one of the lane kTieReach / 8 below (lowest lanes: from memory)
-                static_assert(kTieReach % kScanItems == 0, "the far request sits in a whole lane's distance");
+                // request is the first of the lane kTieReach / 4 below (lowest lanes: of the group before, or memory)
+                static_assert(kTieReach % 4 == 0 && kTieReach / 4 < kWave, "the far request is a lane's first");
 #pragma unroll
                 for (int g = 0; g < kScanItems / 4; ++g) {
-                    uint32_t far = __shfl_up(key[g * 4], kTieReach / kScanItems);
-                    if (lane < kTieReach / kScanItems) {
+                    uint32_t far = __shfl_up(key[g * 4], kTieReach / 4);
+                    if (g > 0) {
+                        const uint32_t wrapped = (uint32_t)__shfl((int)key[g * 4 - 4], lane + kWave - kTieReach / 4);
+                        if (lane < kTieReach / 4) far = wrapped;
+                    } else if (lane < kTieReach / 4) {
                         const int64_t r = lane_first(base, lane, g) - kTieReach;
                         far = ~key[g * 4];
                         if (r >= 0 && r + kTieReach < A.n) far = order_key(MODE, A.deadline[r], 0);
@@ -1181,9 +1197,7 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Queues are counted three to a 32-bit word, ten bits each: a wave chunk holds 512 requests, so no field of an
-// exclusive prefix passes 504, and a field of the inclusive prefix that reaches 512 and spills into the next one
-// is put right again when the lane's own word is subtracted.
+// Queues are counted three to a 32-bit word, ten bits each: a wave chunk holds 512 requests, so no field passes 512.
 constexpr uint32_t kFieldBits = 10, kFieldMask = (1u << kFieldBits) - 1u;
 constexpr uint32_t kNoWord = 31;
 
@@ -1248,26 +1262,30 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                     hs[at] = (uint8_t)sg;
                 }
             }
-            const int at0 = kTieSearch + lane * kScanItems;
-            static_assert(kTieSearch % 8 == 0, "a lane's eight keys sit on a 16-byte boundary");
-            *reinterpret_cast<uint4*>(hk + at0) = make_uint4(key[0], key[1], key[2], key[3]);
-            *reinterpret_cast<uint4*>(hk + at0 + 4) = make_uint4(key[4], key[5], key[6], key[7]);
-            uint32_t s_lo = 0, s_hi = 0;
+            // a lane's four keys of group g sit at kTieSearch + 256 g + 4 lane (a 16-byte boundary)
+            static_assert(kTieSearch % 4 == 0, "a lane's four keys sit on a 16-byte boundary");
+            const int at0 = kTieSearch + lane * 4;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                s_lo |= (ok[c] ? seg[c] : 0xFFu) << (8 * c);
-                s_hi |= (ok[4 + c] ? seg[4 + c] : 0xFFu) << (8 * c);
+            for (int g = 0; g < kScanItems / 4; ++g) {
+                *reinterpret_cast<uint4*>(hk + at0 + g * kGroupSpan) = make_uint4(key[g * 4], key[g * 4 + 1], key[g * 4 + 2], key[g * 4 + 3]);
+                uint32_t four = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) four |= (ok[g * 4 + c] ? seg[g * 4 + c] : 0xFFu) << (8 * c);
+                *reinterpret_cast<uint32_t*>(hs + at0 + g * kGroupSpan) = four;
             }
-            *reinterpret_cast<uint2*>(hs + at0) = make_uint2(s_lo, s_hi);
             // the wave's own LDS traffic runs in order; this only keeps the compiler from moving reads above the writes
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const uint32_t left_key = hk[at0 - 1], right_key = hk[at0 + kScanItems];
 #pragma unroll
-            for (int i = 0; i < kScanItems; ++i) {
-                tie_left |= ((i == 0 ? left_key : key[i - 1]) == key[i] ? 1u : 0u) << i;
-                tie_right |= ((i == kScanItems - 1 ? right_key : key[i + 1]) == key[i] ? 1u : 0u) << i;
+            for (int g = 0; g < kScanItems / 4; ++g) {
+                const uint32_t left_key = hk[at0 + g * kGroupSpan - 1], right_key = hk[at0 + g * kGroupSpan + 4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int i = g * 4 + c;
+                    tie_left |= ((c == 0 ? left_key : key[i - 1]) == key[i] ? 1u : 0u) << i;
+                    tie_right |= ((c == 3 ? right_key : key[i + 1]) == key[i] ? 1u : 0u) << i;
+                }
             }
             // one look at a time (rare: deadlines are in microseconds), a byte of the result per request
             uint32_t looks = tie_left | (tie_right << kScanItems);
@@ -1275,7 +1293,7 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                 const int b = __builtin_ctz(looks);
                 looks &= looks - 1u;
                 const int i = b & (kScanItems - 1), step = b < kScanItems ? -1 : 1;
-                const int at = at0 + i;
+                const int at = at0 + (i >> 2) * kGroupSpan + (i & 3);
                 const uint32_t uk = hk[at];
                 const uint8_t sg = hs[at];
                 uint32_t same = 0;
@@ -1297,23 +1315,28 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
             word[i] = ok[i] ? w : kNoWord;
             present |= 1u << word[i];
         }
-        // ... then, word by word of three queues, those in lower lanes and earlier in this lane
+        // ... then, word by word of three queues, those earlier in the chunk: the group before, lower lanes of the own
+        // group, and earlier ones among the lane's own four
         uint32_t words = wave_or(present) & ~(1u << kNoWord);
         while (words) {
             const uint32_t w = (uint32_t)__builtin_ctz(words);
             words &= words - 1u;
-            uint32_t partial[kScanItems + 1];
-            partial[0] = 0;
+            uint32_t earlier = 0;                                // the groups before, all lanes
 #pragma unroll
-            for (int i = 0; i < kScanItems; ++i) partial[i + 1] = partial[i] + (word[i] == w ? 1u << shift[i] : 0u);
-            const uint32_t inclusive = wave_inclusive_sum(partial[kScanItems]);
-            const uint32_t below = inclusive - partial[kScanItems];
-            const uint32_t last_below = (uint32_t)__builtin_amdgcn_readlane((int)below, 63);
-            const uint32_t last_own = (uint32_t)__builtin_amdgcn_readlane((int)partial[kScanItems], 63);
+            for (int g = 0; g < kScanItems / 4; ++g) {
+                uint32_t partial[5];
+                partial[0] = 0;
 #pragma unroll
-            for (int i = 0; i < kScanItems; ++i)
-                if (word[i] == w) j[i] += ((below + partial[i]) >> shift[i]) & kFieldMask;
-            if (lane_word == w) run += ((last_below >> lane_shift) & kFieldMask) + ((last_own >> lane_shift) & kFieldMask);
+                for (int c = 0; c < 4; ++c) partial[c + 1] = partial[c] + (word[g * 4 + c] == w ? 1u << shift[g * 4 + c] : 0u);
+                const uint32_t inclusive = wave_inclusive_sum(partial[4]);
+                const uint32_t below = earlier + inclusive - partial[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (word[g * 4 + c] == w) j[g * 4 + c] += ((below + partial[c]) >> shift[g * 4 + c]) & kFieldMask;
+                earlier += (uint32_t)__builtin_amdgcn_readlane((int)(inclusive - partial[4]), 63) +
+                           (uint32_t)__builtin_amdgcn_readlane((int)partial[4], 63);
+            }
+            if (lane_word == w) run += (earlier >> lane_shift) & kFieldMask;
         }
 #pragma unroll
         for (int g = 0; g < kScanItems / 4; ++g) {
