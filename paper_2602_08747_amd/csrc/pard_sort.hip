@@ -1238,9 +1238,9 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
         uint32_t snap[kScanItems], seg[kScanItems], key[kScanItems], j[kScanItems];
         bool ok[kScanItems];
         load_chunk_by_deadline<HBF ? PARD_ORDER_HBF : PARD_ORDER_LBF>(A, base, lane, vec, bound, snap, seg, key, ok);
-        // need a look to the left or right: an equal key next to the request
-        uint32_t tie_left = 0, tie_right = 0;                  // one bit per request of the lane
-        uint64_t ties_before = 0, ties_after = 0;              // one byte per request: same queue, same deadline, to the left / right
+        // same queue, same deadline, to the left / right of a request: among the lane's own four, and beyond them (a byte each)
+        uint32_t near_before[kScanItems] = {0, 0, 0, 0, 0, 0, 0, 0}, near_after[kScanItems] = {0, 0, 0, 0, 0, 0, 0, 0};
+        uint64_t ties_before = 0, ties_after = 0;
         if constexpr (HBF) {
             // the neighbours on either side of the wave chunk (two loads per lane at most), then the chunk itself
             uint32_t* hk = halo_key[own];
@@ -1277,29 +1277,41 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            // Same queue and same deadline among the lane's own four: every pair counts once to the left and once
+            // to the right (the deadlines are sorted, so equal ends mean an equal stretch).  Only a run that reaches
+            // past the lane's four needs a look into LDS, from the lane's edge outwards.
+            uint32_t looks = 0;                                  // bit i: look left for request i, bit 8 + i: right
 #pragma unroll
             for (int g = 0; g < kScanItems / 4; ++g) {
-                const uint32_t left_key = hk[at0 + g * kGroupSpan - 1], right_key = hk[at0 + g * kGroupSpan + 4];
+                const bool edge_left = hk[at0 + g * kGroupSpan - 1] == key[g * 4];
+                const bool edge_right = hk[at0 + g * kGroupSpan + 4] == key[g * 4 + 3];
+#pragma unroll
+                for (int a = 0; a < 4; ++a)
+#pragma unroll
+                    for (int b = a + 1; b < 4; ++b) {
+                        const uint32_t both = (ok[g * 4 + b] && key[g * 4 + a] == key[g * 4 + b] && seg[g * 4 + a] == seg[g * 4 + b]) ? 1u : 0u;
+                        near_before[g * 4 + b] += both;
+                        near_after[g * 4 + a] += both;
+                    }
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    const int i = g * 4 + c;
-                    tie_left |= ((c == 0 ? left_key : key[i - 1]) == key[i] ? 1u : 0u) << i;
-                    tie_right |= ((c == 3 ? right_key : key[i + 1]) == key[i] ? 1u : 0u) << i;
+                    looks |= ((edge_left && key[g * 4] == key[g * 4 + c]) ? 1u : 0u) << (g * 4 + c);
+                    looks |= ((edge_right && key[g * 4 + 3] == key[g * 4 + c]) ? 1u : 0u) << (kScanItems + g * 4 + c);
                 }
             }
             // one look at a time (rare: deadlines are in microseconds), a byte of the result per request
-            uint32_t looks = tie_left | (tie_right << kScanItems);
             while (looks) {
                 const int b = __builtin_ctz(looks);
                 looks &= looks - 1u;
                 const int i = b & (kScanItems - 1), step = b < kScanItems ? -1 : 1;
-                const int at = at0 + (i >> 2) * kGroupSpan + (i & 3);
-                const uint32_t uk = hk[at];
-                const uint8_t sg = hs[at];
+                const int mine = at0 + (i >> 2) * kGroupSpan;
+                const uint32_t uk = hk[mine + (i & 3)];
+                const uint8_t sg = hs[mine + (i & 3)];
+                const int from = step < 0 ? mine - 1 : mine + 4;    // the first request beyond the lane's four
                 uint32_t same = 0;
-                for (int t = 1; t <= kTieSearch; ++t) {
-                    if (hk[at + step * t] != uk) break;
-                    same += hs[at + step * t] == sg ? 1u : 0u;
+                for (int t = 0; t < kTieSearch; ++t) {
+                    if (hk[from + step * t] != uk) break;
+                    same += hs[from + step * t] == sg ? 1u : 0u;
                 }
                 if (step < 0) ties_before |= (uint64_t)same << (8 * i);
                 else ties_after |= (uint64_t)same << (8 * i);
@@ -1356,8 +1368,8 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                 uint32_t pos = j[i];
                 if constexpr (HBF) {
                     // requests of the same queue with the same deadline right before and right after this one
-                    const uint32_t before = (uint32_t)(ties_before >> (8 * i)) & 0xFFu;
-                    const uint32_t after = (uint32_t)(ties_after >> (8 * i)) & 0xFFu;
+                    const uint32_t before = near_before[i] + ((uint32_t)(ties_before >> (8 * i)) & 0xFFu);
+                    const uint32_t after = near_after[i] + ((uint32_t)(ties_after >> (8 * i)) & 0xFFu);
                     pos = (uint32_t)q.len - 1u - j[i] - after + before;
                 }
                 const uint64_t e64 = epilogue_estimate(q, P.lat + (int64_t)q.rec * PARD_LAT_ENTRIES, pos);
