@@ -63,3 +63,27 @@ def test_random_case(gpu, oracle_mod, seed):
             for k in KEYS:
                 assert np.array_equal(got[k], ref[k]), (seed, variant, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
             assert s.status_word() == 0
+
+
+@pytest.mark.parametrize("seed", range(64))
+def test_random_case_in_deadline_order(gpu, oracle_mod, seed):
+    """The same random cases with every snapshot arranged by rising deadline: snapshots that arrive in queue order take
+    the kernels without a sort (on chip and, under the forced promise, the split of the large-snapshot path) whenever
+    the plan qualifies, and the general kernels otherwise; plain estimate with and without a given downstream latency."""
+    import torch
+    w, sub = draw_case(seed)
+    w = wl.in_deadline_order(w)
+    print("case", seed, w.name, "n", w.n, "K", w.K, "S", w.S, "sub", sub is not None, flush=True)
+    ref = oracle_mod.run(w, threads=8, sub=sub)
+    for max_snap in (None, FORCE_SORT):
+        s = gpu.Session(w, max_snapshot_requests=None if max_snap is None else max(max_snap, w.max_snapshot_requests))
+        s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev))
+        got = s.results()
+        for k in KEYS:
+            assert np.array_equal(got[k], ref[k]), (seed, max_snap, k, np.flatnonzero(got[k] != ref[k])[:5])
+        assert s.status_word() == 0
+        if sub is None:
+            s.run_one_call()
+            again = s.results()
+            for k in KEYS:
+                assert np.array_equal(again[k], ref[k]), (seed, max_snap, "one call", k)
