@@ -69,6 +69,20 @@ constexpr int log2_of(int x) { return x <= 1 ? 0 : 1 + log2_of(x / 2); }
 
 // FULL: the snapshot holds exactly kCap requests and every array is 16-byte aligned at its
 // start, so no per-request bounds test is needed.
+// Minimum over the lanes below (INT32_MAX in lane 0), on the vector ALU's data-parallel primitives.
+__device__ __forceinline__ int32_t wave_exclusive_min(int32_t v) {
+    const int32_t inf = kInt32Max;
+    int32_t x = __builtin_amdgcn_update_dpp(inf, v, 0x138, 0xF, 0xF, false);          // wave_shr:1: the lane below's value
+    auto lower = [](int32_t a, int32_t b) { return a < b ? a : b; };
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x111, 0xF, 0xF, false));         // row_shr:1
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x112, 0xF, 0xF, false));         // row_shr:2
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x114, 0xF, 0xF, false));         // row_shr:4
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x118, 0xF, 0xF, false));         // row_shr:8
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x142, 0xA, 0xF, false));         // row_bcast:15 into rows 1, 3
+    x = lower(x, __builtin_amdgcn_update_dpp(inf, x, 0x143, 0xC, 0xF, false));         // row_bcast:31 into rows 2, 3
+    return x;
+}
+
 template <int T, int CAP, int SCAP, bool FULL, bool CONSISTENT>
 __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CAP, SCAP>& L, const int u, const int64_t lo,
                                               const int m, const bool aligned, const int off) {
@@ -380,25 +394,79 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         for (int k = wave; k < S; k += T / kWave) {            // one wave per queue
             const int s0 = L.seg_start[k], s1 = L.seg_start[k + 1];
             const unsigned long long dn = L.down[k];
-            const int32_t* lat_row = lat_dag + k * PARD_LAT_ENTRIES;
+            // the DAG's latency tables sit in LDS unless the wide case took that array back
+            const int32_t* lat_row = wide ? lat_dag + k * PARD_LAT_ENTRIES : reinterpret_cast<const int32_t*>(aux) + k * PARD_LAT_ENTRIES;
+            const int32_t order = L.recs[k].mode & 0xFF;
+            // A latency table that never falls up to the batch size makes the cost rise with the position, so the
+            // positions at which a request is still in time form a prefix; in a queue ordered by deadline the chain
+            // of decisions then has a closed form per 64 requests (below).  Anything else is iterated.
+            const bool falls = lane + 1 < L.recs[k].B && lat_row[lane + 1] < lat_row[lane];
+            const bool closed = __ballot(falls) == 0ull && order != PARD_ORDER_FCFS;
             uint32_t kept = 0;                                  // kept requests of this queue so far (same in every lane)
+            bool cut = false;                                   // high budget first: a request has been dropped already
             for (int first = s0; first < s1; first += kWave) {
                 const int j = first + lane;
                 const bool ok = j < s1;
                 const int32_t deadline = ok ? (int32_t)L.low[j] : 0;
-                // Guess that all 64 are kept, evaluate everybody at the position that guess implies,
-                // take the decisions as the next guess: after t rounds the first t lanes are final,
-                // and a guess that reproduces itself is the in-order result.
-                unsigned long long keep = __ballot(ok);
+                unsigned long long keep;
                 int32_t est = 0;
                 uint8_t drp = 0;
-                for (int round = 0; round <= kWave; ++round) {
-                    const uint32_t ahead = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(keep >> 32),
-                                                      __builtin_amdgcn_mbcnt_lo((uint32_t)keep, 0u));
-                    finish_request(stage_cost_short(L.recs[k], ahead, lat_row) + dn, now, deadline, est, drp);
-                    const unsigned long long next = __ballot(ok && drp == 0);
-                    if (next == keep) break;
-                    keep = next;
+                if (closed && order == PARD_ORDER_LBF) {
+                    // Lane l evaluates position kept + l.  Budgets rise along the queue, so does the number c of
+                    // positions (counted from `kept`) a request is in time at, and the recurrence
+                    // a' = min(a + 1, c) unrolls to a_i = min(i, i - 1 + min over i' < i of (c_i' - i')).
+                    const uint32_t at = kept + (uint32_t)lane < (uint32_t)(CAP - 1) ? kept + (uint32_t)lane : (uint32_t)(CAP - 1);
+                    const uint64_t e64 = stage_cost_short(L.recs[k], at, lat_row) + dn;
+                    const int32_t est_at = e64 > (uint64_t)kInt32Max ? kInt32Max : (int32_t)e64;
+                    const int64_t fin = (int64_t)now + (int64_t)e64;
+                    const int32_t end_at = fin > (int64_t)kInt32Max ? kInt32Max : (int32_t)fin;     // late iff end_at > deadline
+                    // c: positions kept .. kept + c - 1 are in time (c <= 64); end_at rises with the lane, so first the
+                    // blocks of eight positions that fit as a whole (their last lane's value, read as a scalar), then
+                    // three steps inside the next block
+                    int c = 0;
+#pragma unroll
+                    for (int b = 0; b < kWave / 8; ++b) c += __builtin_amdgcn_readlane(end_at, 8 * b + 7) <= deadline ? 8 : 0;
+#pragma unroll
+                    for (int step = 4; step >= 1; step >>= 1) {
+                        const int32_t probe = __shfl(end_at, (c + step - 1) & (kWave - 1));
+                        if (c < kWave && probe <= deadline) c += step;
+                    }
+                    const int32_t least = wave_exclusive_min(c - lane);        // min over lower lanes, INT32_MAX for lane 0
+                    int a = lane;
+                    if (lane > 0 && lane - 1 + (int64_t)least < (int64_t)a) a = lane - 1 + least;
+                    est = __shfl(est_at, a);
+                    drp = (ok && a < c) ? 0 : 1;
+                    keep = __ballot(ok && a < c);
+                } else if (closed) {
+                    // High budget first: budgets fall along the queue, so once a request is late at its plain
+                    // position every later one is late at that same position.
+                    const uint32_t at = kept + (cut ? 0u : (uint32_t)lane);
+                    finish_request(stage_cost_short(L.recs[k], at < (uint32_t)(CAP - 1) ? at : (uint32_t)(CAP - 1), lat_row) + dn,
+                                   now, deadline, est, drp);
+                    keep = 0ull;
+                    if (!cut) {
+                        const unsigned long long late = __ballot(ok && drp != 0);
+                        const int f = late ? __builtin_ctzll(late) : kWave;    // the first late request of the chunk
+                        keep = __ballot(ok && lane < f);
+                        const int32_t est_cut = __shfl(est, f < kWave ? f : 0);
+                        if (lane >= f) { est = est_cut; drp = 1; }
+                        cut = late != 0ull;
+                    } else {
+                        drp = 1;
+                    }
+                } else {
+                    // Guess that all 64 are kept, evaluate everybody at the position that guess implies,
+                    // take the decisions as the next guess: after t rounds the first t lanes are final,
+                    // and a guess that reproduces itself is the in-order result.
+                    keep = __ballot(ok);
+                    for (int round = 0; round <= kWave; ++round) {
+                        const uint32_t ahead = kept + __builtin_amdgcn_mbcnt_hi((uint32_t)(keep >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)keep, 0u));
+                        finish_request(stage_cost_short(L.recs[k], ahead, lat_row) + dn, now, deadline, est, drp);
+                        const unsigned long long next = __ballot(ok && drp == 0);
+                        if (next == keep) break;
+                        keep = next;
+                    }
                 }
                 if (ok) L.low[j] = (uint32_t)est | ((uint32_t)drp << 31);
                 kept += (uint32_t)__popcll(keep);
