@@ -441,111 +441,102 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     const PlanDev& P = A.plan;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t segs = (int64_t)P.K * P.S;
-    // add up what the count kernel's workgroups left behind
-    {
-        __shared__ uint32_t mm[2][16];
-        uint32_t a = 0, b = 0;
-        for (int i = tid; i < A.stream_blocks; i += 1024) {
-            const uint32_t x = A.part_minmax[2 * i], y = A.part_minmax[2 * i + 1];
-            a = x > a ? x : a;
-            b = y > b ? y : b;
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const uint32_t x = __shfl_xor(a, off), y = __shfl_xor(b, off);
-            a = x > a ? x : a;
-            b = y > b ? y : b;
-        }
-        if (lane == 0) { mm[0][wave] = a; mm[1][wave] = b; }
-        if (segs <= kPartialSegs) {
-            // thread (slice, g) adds up queue g over the workgroups [slice * len, (slice + 1) * len), eight loads in flight
-            const int g = tid & (kPartialSegs - 1), slice = tid / kPartialSegs;
-            const int len = (A.stream_blocks + kSlices - 1) / kSlices;
-            const int b0 = slice * len, b1 = b0 + len < A.stream_blocks ? b0 + len : A.stream_blocks;
-            uint32_t sum = 0;
-            for (int b = b0; b < b1; b += 8) {
-                uint32_t v[8];
-#pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] : 0u;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) sum += v[k];
-            }
-            slice_tot[slice][g] = sum;
-        }
-        __syncthreads();
-        if (tid == 0) {
-            for (int w = 1; w < 16; ++w) {
-                mm[0][0] = mm[0][w] > mm[0][0] ? mm[0][w] : mm[0][0];
-                mm[1][0] = mm[1][w] > mm[1][0] ? mm[1][w] : mm[1][0];
-            }
-            A.params->inv_min = mm[0][0];
-            A.params->max_key = mm[1][0];
-        }
-        if (segs <= kPartialSegs && tid < segs) {
-            uint32_t v = 0;
-            for (int sl = 0; sl < kSlices; ++sl) v += slice_tot[sl][tid];
-            A.seg_count[tid] = v;
-        }
-        __threadfence();
-        __syncthreads();
+    // Add up what the count kernel's workgroups left behind.  Everything that does not depend on anything else is
+    // loaded first, in one go: key range and order flags per workgroup, and (up to kPartialSegs queues) the
+    // workgroups' queue lengths, of which thread (slice, g) holds queue g of the workgroups [slice * len, (slice + 1) * len).
+    __shared__ uint32_t mm[2][16];
+    __shared__ uint32_t seen;
+    __shared__ uint32_t qlen[kPartialSegs];
+    __shared__ unsigned long long cfull_l[kPartialSegs];   // the stage costs at full queue length, when there are few queues
+    constexpr int kHeld = 32;                             // per-workgroup counts a thread keeps in registers
+    const bool few = segs <= kPartialSegs;
+    const int g_mine = tid & (kPartialSegs - 1), slice = tid / kPartialSegs;
+    const int len = (A.stream_blocks + kSlices - 1) / kSlices;
+    const int b0 = slice * len, b1 = b0 + len < A.stream_blocks ? b0 + len : A.stream_blocks;
+    uint32_t held[kHeld];
+    uint32_t a = 0, b = 0, f = 0;
+    for (int i = tid; i < A.stream_blocks; i += 1024) {
+        const uint32_t x = A.part_minmax[2 * i], y = A.part_minmax[2 * i + 1];
+        a = x > a ? x : a;
+        b = y > b ? y : b;
+        f |= A.part_flag[i];
     }
-    if (tid == 0) {
-        const uint32_t umin = ~A.params->inv_min;
-        const uint32_t range = A.n > 0 ? A.params->max_key - umin : 0u;
-        const uint32_t kb = 32u - (range ? (uint32_t)__clz((int)range) : 32u);
-        const uint32_t total = kb + (uint32_t)A.seg_bits;
-        uint32_t passes = (total + kRadixBits - 1) / kRadixBits;
-        A.params->kb = kb;
-        A.params->total_bits = total;
-        A.params->passes = passes < 1 ? 1 : passes;
-        carry = 0;
+    uint32_t sum = 0;
+    if (few) {
+#pragma unroll
+        for (int k = 0; k < kHeld; ++k) held[k] = b0 + k < b1 ? A.part_cnt[(int64_t)(b0 + k) * kPartialSegs + g_mine] : 0u;
+#pragma unroll
+        for (int k = 0; k < kHeld; ++k) sum += held[k];
+        for (int bb = b0 + kHeld; bb < b1; ++bb) sum += A.part_cnt[(int64_t)bb * kPartialSegs + g_mine];
+        slice_tot[slice][g_mine] = sum;
     }
+    if (tid == 0) { seen = 0; carry = 0; }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const uint32_t x = __shfl_xor(a, off), y = __shfl_xor(b, off);
+        a = x > a ? x : a;
+        b = y > b ? y : b;
+        f |= __shfl_xor(f, off);
+    }
+    if (lane == 0) { mm[0][wave] = a; mm[1][wave] = b; }
+    __syncthreads();
+    if (lane == 0 && f) atomicOr(&seen, f);
+    if (few && tid < segs) {
+        uint32_t v = 0;
+        for (int sl = 0; sl < kSlices; ++sl) v += slice_tot[sl][tid];
+        qlen[tid] = v;
+        A.seg_count[tid] = v;
+    }
+    __syncthreads();
     // Requests in deadline order: the queues are a stable split by stage, done by split_kernel; the radix passes, the
     // epilogue and the unpacking then find nothing to do (passes = 0).
-    {
-        __shared__ uint32_t seen;
-        if (tid == 0) seen = 0;
-        __syncthreads();
-        uint32_t f = 0;
-        for (int i = tid; i < A.stream_blocks; i += 1024) f |= A.part_flag[i];
-        if (f) atomicOr(&seen, f);
-        __syncthreads();
-        const bool hbf = P.uniform_mode == PARD_ORDER_HBF;
-        const bool split = A.n > 0 && !A.consistent && segs <= kPartialSegs && !(seen & kSawFall) && !(hbf && (seen & kSawLongTie));
-        if (tid == 0) {
-            A.params->split = split ? 1u : 0u;
-            if (split) A.params->passes = 0;
+    const bool hbf = P.uniform_mode == PARD_ORDER_HBF;
+    const bool split = A.n > 0 && !A.consistent && few && !(seen & kSawFall) && !(hbf && (seen & kSawLongTie));
+    if (tid == 0) {
+        uint32_t inv_min = mm[0][0], max_key = mm[1][0];
+        for (int w = 1; w < 16; ++w) {
+            inv_min = mm[0][w] > inv_min ? mm[0][w] : inv_min;
+            max_key = mm[1][w] > max_key ? mm[1][w] : max_key;
         }
-        if (split) {
-            // a snapshot beyond the promised bound is flagged as the radix passes would flag it (their payload word
-            // holds idx_bits of index); the split itself has no such limit
-            for (int u = tid; u < P.K; u += 1024) {
-                const int64_t size = (int64_t)A.snap_ptr[u + 1] - (int64_t)A.snap_ptr[u];
-                if (A.idx_bits < 32 && size > ((int64_t)1 << A.idx_bits)) atomicOr(A.status_word, kStatusSnapshotTooLarge);
-            }
-            // part_cnt[b][g] becomes the number of requests of queue g in the workgroups before b
-            const int g = tid & (kPartialSegs - 1), slice = tid / kPartialSegs;
-            const int len = (A.stream_blocks + kSlices - 1) / kSlices;
-            const int b0 = slice * len, b1 = b0 + len < A.stream_blocks ? b0 + len : A.stream_blocks;
-            uint32_t run = 0;
-            for (int sl = 0; sl < slice; ++sl) run += slice_tot[sl][g];
-            for (int b = b0; b < b1; b += 8) {
-                uint32_t v[8];
+        const uint32_t umin = ~inv_min;
+        const uint32_t range = A.n > 0 ? max_key - umin : 0u;
+        const uint32_t kb = 32u - (range ? (uint32_t)__clz((int)range) : 32u);
+        const uint32_t total = kb + (uint32_t)A.seg_bits;
+        const uint32_t passes = (total + kRadixBits - 1) / kRadixBits;
+        A.params->inv_min = inv_min;
+        A.params->max_key = max_key;
+        A.params->kb = kb;
+        A.params->total_bits = total;
+        A.params->passes = split ? 0u : (passes < 1 ? 1u : passes);
+        A.params->split = split ? 1u : 0u;
+    }
+    if (split) {
+        // a snapshot beyond the promised bound is flagged as the radix passes would flag it (their payload word
+        // holds idx_bits of index); the split itself has no such limit
+        for (int u = tid; u < P.K; u += 1024) {
+            const int64_t size = (int64_t)A.snap_ptr[u + 1] - (int64_t)A.snap_ptr[u];
+            if (A.idx_bits < 32 && size > ((int64_t)1 << A.idx_bits)) atomicOr(A.status_word, kStatusSnapshotTooLarge);
+        }
+        // part_cnt[b][g] becomes the number of requests of queue g in the workgroups before b
+        uint32_t run = 0;
+        for (int sl = 0; sl < slice; ++sl) run += slice_tot[sl][g_mine];
 #pragma unroll
-                for (int k = 0; k < 8; ++k) v[k] = b + k < b1 ? A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] : 0u;
-#pragma unroll
-                for (int k = 0; k < 8; ++k) {
-                    if (b + k < b1) A.part_cnt[(int64_t)(b + k) * kPartialSegs + g] = run;
-                    run += v[k];
-                }
-            }
+        for (int k = 0; k < kHeld; ++k) {
+            if (b0 + k < b1) A.part_cnt[(int64_t)(b0 + k) * kPartialSegs + g_mine] = run;
+            run += held[k];
+        }
+        for (int bb = b0 + kHeld; bb < b1; ++bb) {
+            const uint32_t v = A.part_cnt[(int64_t)bb * kPartialSegs + g_mine];
+            A.part_cnt[(int64_t)bb * kPartialSegs + g_mine] = run;
+            run += v;
         }
     }
+    __threadfence();
     __syncthreads();
     // queue offsets: exclusive scan of the queue lengths, 1024 at a time
     for (int64_t base = 0; base < segs + 1; base += 1024) {
         const int64_t g = base + tid;
-        const uint32_t v = g < segs ? __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
+        const uint32_t v = g < segs ? (few ? qlen[g] : __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) : 0u;
         uint32_t inc = v;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
@@ -564,8 +555,10 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     // cost of every stage at its full queue length
     for (int64_t g = tid; g < segs; g += 1024) {
         const int64_t rec = P.shared ? g % P.S : g;
-        A.cfull[g] = stage_cost(P.recs[rec], __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
-                                P.lat + rec * PARD_LAT_ENTRIES);
+        const uint64_t full = stage_cost(P.recs[rec], few ? qlen[g] : __hip_atomic_load(&A.seg_count[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                                         P.lat + rec * PARD_LAT_ENTRIES);
+        A.cfull[g] = full;
+        if (few) cfull_l[g] = full;
     }
     // smallest execution latency of every queue: lat[min(B, a + 1)] over all positions a
     // (consistent dropping only)
@@ -600,7 +593,15 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         else { e = (int32_t)b; u = P.entry_dag[e]; }
         const int32_t end = P.entry_end[e];
         unsigned long long sum = 0;
-        for (int32_t t = e + 1; t < end; ++t) sum += A.cfull[(int64_t)u * P.S + P.entry_stage[t]];
+        // the later stages of the path, eight ids in flight (a path is a dependent walk otherwise)
+        for (int32_t t0 = e + 1; t0 < end; t0 += 8) {
+            int32_t later[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) later[k] = t0 + k < end ? P.entry_stage[t0 + k] : -1;
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (later[k] >= 0) sum += few ? cfull_l[(int64_t)u * P.S + later[k]] : A.cfull[(int64_t)u * P.S + later[k]];
+        }
         atomicMax(&A.down[(int64_t)u * P.S + P.entry_stage[e]], sum);
     }
 }
