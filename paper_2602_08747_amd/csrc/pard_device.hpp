@@ -122,6 +122,15 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t v) {
     return v;
 }
 
+// Estimates and decisions are written once and not read again by the call that writes them: streaming stores
+// (they leave the caches early and do not push out what the next kernel reads).
+typedef int pard_v4i __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void stream_store(int4* p, int4 v) {
+    pard_v4i x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<pard_v4i*>(p));
+}
+__device__ __forceinline__ void stream_store(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
+
 // Where a snapshot's staged survivors start inside the snapshot's own stretch of the staging array.  Snapshots
 // of equal size start at equal distances; if every one staged its few survivors at its very start, they would
 // all fall into the same few memory channels (measured: the kernel that moves them ran at an eighth of the

@@ -486,9 +486,9 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
                 drp[c] = (uint8_t)(v >> 31);
             }
             if (whole(base)) {
-                *reinterpret_cast<int4*>(A.est + lo_s + base) = make_int4(est[0], est[1], est[2], est[3]);
-                *reinterpret_cast<uint32_t*>(A.drop + lo_s + base) =
-                    (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
+                stream_store(reinterpret_cast<int4*>(A.est + lo_s + base), make_int4(est[0], est[1], est[2], est[3]));
+                stream_store(reinterpret_cast<uint32_t*>(A.drop + lo_s + base),
+                    (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24));
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c)
@@ -541,9 +541,9 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
                 if (live(base + c) && drp[c]) ord_l[se[g][c] & 0x1FFFu] = (uint16_t)((uint32_t)(base + c) | 0x8000u);
         }
         if (whole(base)) {
-            *reinterpret_cast<int4*>(A.est + lo_s + base) = make_int4(est[0], est[1], est[2], est[3]);
-            *reinterpret_cast<uint32_t*>(A.drop + lo_s + base) =
-                (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
+            stream_store(reinterpret_cast<int4*>(A.est + lo_s + base), make_int4(est[0], est[1], est[2], est[3]));
+            stream_store(reinterpret_cast<uint32_t*>(A.drop + lo_s + base),
+                (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24));
         } else {
 #pragma unroll
             for (int c = 0; c < 4; ++c)

@@ -31,26 +31,16 @@ namespace pard {
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-// The request arrays are read exactly once: streaming loads (they leave the caches early).  The outputs are
-// stored normally, the compaction that follows reads two of them again.
-#define PARD_PS_NT_LOAD 1
-#ifdef PARD_PS_NT_STORE
-__device__ __forceinline__ void out_store(int4* p, int4 v) {
-    v4i x = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(x, reinterpret_cast<v4i*>(p));
-}
-__device__ __forceinline__ void out_store(uint32_t* p, uint32_t v) { __builtin_nontemporal_store(v, p); }
-#else
+// The request arrays are read exactly once, and the estimates and decisions are written once and not looked at
+// again by this call: streaming loads and stores (they leave the caches early).  The queue order is stored
+// normally: the compaction that follows reads it again, slot by slot.  Measured on 4096 snapshots of 8192:
+// streaming stores for estimates and decisions 122.8 -> 117.0 us per call and the compaction 47.7 -> 46.4;
+// for the queue order as well 119.3 and 52.0.
 template <typename V> __device__ __forceinline__ void out_store(V* p, V v) { *p = v; }
-#endif
-#ifdef PARD_PS_NT_LOAD
 __device__ __forceinline__ int4 in_load(const int4* p) {
     const v4i x = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
     return make_int4(x.x, x.y, x.z, x.w);
 }
-#else
-template <typename V> __device__ __forceinline__ V in_load(const V* p) { return *p; }
-#endif
 
 constexpr int kPsStages = kPresortedMaxStages;     // 3-bit count fields of stages 0..5 plus one for slots that are not live
 constexpr uint32_t kDeadStage = 7;
@@ -280,8 +270,8 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
             }
         }
         if (whole(base)) {
-            out_store(reinterpret_cast<int4*>(A.est + lo_s + base), make_int4(est[0], est[1], est[2], est[3]));
-            out_store(reinterpret_cast<uint32_t*>(A.drop + lo_s + base),
+            stream_store(reinterpret_cast<int4*>(A.est + lo_s + base), make_int4(est[0], est[1], est[2], est[3]));
+            stream_store(reinterpret_cast<uint32_t*>(A.drop + lo_s + base),
                       (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24));
         } else {
 #pragma unroll

@@ -1378,7 +1378,8 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                 A.order[(int64_t)q.start + pos] = (int32_t)r;
             }
             if (vec_out && r0 + 3 < A.n) {
-                *reinterpret_cast<int4*>(A.est + r0) = make_int4(est[0], est[1], est[2], est[3]);
+                // (the decisions are stored normally: the streamed compaction gathers them right afterwards)
+                stream_store(reinterpret_cast<int4*>(A.est + r0), make_int4(est[0], est[1], est[2], est[3]));
                 *reinterpret_cast<uint32_t*>(A.drop + r0) =
                     (uint32_t)drp[0] | ((uint32_t)drp[1] << 8) | ((uint32_t)drp[2] << 16) | ((uint32_t)drp[3] << 24);
             } else {
