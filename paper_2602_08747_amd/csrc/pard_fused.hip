@@ -126,8 +126,11 @@ __device__ __forceinline__ void snapshot_body(const FusedArgs& A, SnapshotLds<CA
         if (dead_group(g)) continue;
         const int base = (g * T + tid) * 4;
         if (FULL || (aligned && base < m_s && lo_s + base + 3 < A.n)) {      // neighbours' values may ride along: they are not live
-            const int4 d4 = *reinterpret_cast<const int4*>(A.deadline + lo_s + base);
-            const int4 s4 = *reinterpret_cast<const int4*>(A.stage + lo_s + base);
+            // read once: streaming loads (measured with the request order shuffled: the call 182 -> 178 us, the
+            // compaction behind it 51 -> 47)
+            const pard_v4i d4_ = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(A.deadline + lo_s + base));
+            const pard_v4i s4_ = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(A.stage + lo_s + base));
+            const int4 d4 = make_int4(d4_.x, d4_.y, d4_.z, d4_.w), s4 = make_int4(s4_.x, s4_.y, s4_.z, s4_.w);
             dl[g][0] = d4.x; dl[g][1] = d4.y; dl[g][2] = d4.z; dl[g][3] = d4.w;
             st[g][0] = s4.x; st[g][1] = s4.y; st[g][2] = s4.z; st[g][3] = s4.w;
         } else {

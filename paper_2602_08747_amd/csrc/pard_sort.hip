@@ -683,8 +683,12 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
             key[i] = 0;
             pay[i] = 0;
             if (e < valid) {
-                key[i] = src_key[tile_base + e];
-                if (need_pay) pay[i] = src_pay[tile_base + e];
+                if (need_pay) {                 // the downsweep is the last reader of this buffer: streaming loads
+                    key[i] = __builtin_nontemporal_load(src_key + tile_base + e);
+                    pay[i] = __builtin_nontemporal_load(src_pay + tile_base + e);
+                } else {
+                    key[i] = src_key[tile_base + e];
+                }
             }
         }
     }
@@ -1153,9 +1157,11 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
     for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < groups; g += stride) {
         const int64_t r0 = g * 4;
         if (vec && r0 + 3 < A.n) {
-            const uint4 v = *reinterpret_cast<const uint4*>(packed + r0);
-            *reinterpret_cast<int4*>(A.est + r0) = make_int4((int32_t)(v.x & 0x7FFFFFFFu), (int32_t)(v.y & 0x7FFFFFFFu),
-                                                             (int32_t)(v.z & 0x7FFFFFFFu), (int32_t)(v.w & 0x7FFFFFFFu));
+            // read once, written once: streaming accesses
+            const pard_v4i v_ = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(packed + r0));
+            const uint4 v = make_uint4((uint32_t)v_.x, (uint32_t)v_.y, (uint32_t)v_.z, (uint32_t)v_.w);
+            stream_store(reinterpret_cast<int4*>(A.est + r0), make_int4((int32_t)(v.x & 0x7FFFFFFFu), (int32_t)(v.y & 0x7FFFFFFFu),
+                                                             (int32_t)(v.z & 0x7FFFFFFFu), (int32_t)(v.w & 0x7FFFFFFFu)));
             *reinterpret_cast<uint32_t*>(A.drop + r0) = (v.x >> 31) | ((v.y >> 31) << 8) | ((v.z >> 31) << 16) | ((v.w >> 31) << 24);
         } else {
             for (int64_t r = r0; r < r0 + 4 && r < A.n; ++r) {
