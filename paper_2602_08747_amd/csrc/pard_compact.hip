@@ -655,10 +655,10 @@ __global__ __launch_bounds__(kWave) void move_staged_kernel(CompactArgs A, const
     for (uint32_t i0 = 0; i0 < mine; i0 += 16 * kWave) {
         int32_t v[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = i0 + i * kWave + lane < mine ? src[i0 + i * kWave + lane] : 0;
+        for (int i = 0; i < 16; ++i) v[i] = i0 + i * kWave + lane < mine ? __builtin_nontemporal_load(src + i0 + i * kWave + lane) : 0;
 #pragma unroll
         for (int i = 0; i < 16; ++i)
-            if (i0 + i * kWave + lane < mine) dst[first + i0 + i * kWave + lane] = v[i];
+            if (i0 + i * kWave + lane < mine) __builtin_nontemporal_store(v[i], dst + first + i0 + i * kWave + lane);
     }
     if (lane < A.stages) A.surv_ptr[u * A.stages + lane] = (int32_t)(first + loc);
     if (u + 1 == K && lane == 0) A.surv_ptr[K * A.stages] = (int32_t)(first + mine);
