@@ -78,6 +78,12 @@ __global__ __launch_bounds__(kRxThreads) void window_scan_kernel(WindowArgs A) {
     int64_t t1 = t0 + (kRxChunks + 1) * kWave;            // one chunk of look-ahead
     if (t1 > A.n) t1 = A.n;
     const int g_lo = queue_of_slot(A.seg_ptr, t0, 0, G - 1), g_hi = queue_of_slot(A.seg_ptr, t1 - 1, g_lo, G - 1);
+    // A walk that lies inside one queue has nothing to add once a fitting window before its first slot is known
+    // (workgroups start roughly in the order of the slots, so the earlier part of a queue has usually reported).
+    if (g_lo == g_hi) {
+        const int32_t known = __hip_atomic_load(A.first + g_lo, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((int64_t)known <= t0 - (int64_t)A.seg_ptr[g_lo]) return;
+    }
     int32_t req[kRxChunks + 1], dl[kRxChunks + 1];
 #pragma unroll
     for (int c = 0; c <= kRxChunks; ++c) {
