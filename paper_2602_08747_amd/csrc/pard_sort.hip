@@ -37,6 +37,10 @@ constexpr int kConsTile = 256;                         // queue slots per workgr
 constexpr int kConsRanges = 8192;                      // workgroups of those kernels at most (each owns a range of tiles)
 constexpr int kFusedScanChunks = 64;                   // up to here every chunk scans the chunk totals itself
 
+constexpr int kRetBuckets = 512;                       // ranges of request ids the results are first gathered by, at most
+constexpr int kRetMaxShift = 15;                       // a range holds at most 2^15 request ids: its packed results fit one workgroup's LDS
+constexpr int kRetMinShift = 11;                       // and at least 2^11 (few requests: more, smaller ranges keep the chip busy)
+
 constexpr uint32_t kSegScan = 1u << 31;                // queue flag: consistent positions by prefix minimum (see below)
 
 struct SortParams {                 // lives in device memory, written by the setup kernel
@@ -52,10 +56,10 @@ constexpr int kStreamBlocksMax = 1024;                 // upper bound on the gri
 constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
 
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, keepm, chunk_tot, zero_end, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
+    int64_t params, seg_count, cfull, down, keepm, chunk_tot, ret_cursor, zero_end, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
             min_lat, alive, wkept, tile_tot, range_tot, carry, total;
     int64_t tiles, chunks;
-    int32_t max_passes, idx_bits, seg_bits;
+    int32_t max_passes, idx_bits, seg_bits, ret_shift;
 };
 
 int bits_of(uint64_t x) { int b = 0; while (x) { ++b; x >>= 1; } return b; }
@@ -68,6 +72,8 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.idx_bits = bits_of(span > 0 ? (uint64_t)(span - 1) : 0);
     L.seg_bits = bits_of((uint64_t)(segs - 1));
     L.max_passes = (32 + L.seg_bits + kRadixBits - 1) / kRadixBits;
+    L.ret_shift = bits_of(n > 0 ? (uint64_t)(n - 1) : 0) - 9;       // kRetBuckets ranges of 2^ret_shift request ids cover n
+    if (L.ret_shift < kRetMinShift) L.ret_shift = kRetMinShift;     // (beyond kRetMaxShift the results go back one by one)
     L.tiles = (n + kTile - 1) / kTile;
     L.chunks = (L.tiles + kChunkTiles - 1) / kChunkTiles;
     int64_t off = 0;
@@ -78,6 +84,7 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     const int64_t words = (n + 63) / 64 + 1;                     // 64 queue slots per mask word
     L.keepm = off;      off = align256(off + words * 8);
     L.chunk_tot = off;  off = align256(off + (int64_t)L.max_passes * L.chunks * kRadix * 4);
+    L.ret_cursor = off; off = align256(off + (int64_t)kRetBuckets * 4);
     L.zero_end = off;
     L.tile_hist = off;  off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
     L.part_minmax = off; off = align256(off + (int64_t)kStreamBlocksMax * 8);
@@ -124,6 +131,9 @@ struct SortDev {                    // everything the sort kernels need, by valu
     uint32_t* pay[2];
     int64_t tiles;
     int32_t idx_bits, seg_bits, max_passes;
+    uint32_t* ret_cursor;           // [kRetBuckets] results gathered so far per range of request ids (zeroed with the counters)
+    int32_t ret_shift;              // a range holds 2^ret_shift request ids
+    int32_t finish_in_last_pass;    // the last radix pass forms the results and hands them on by range (epilogue_return_kernel finishes)
     // sequentially consistent dropping
     uint32_t* min_lat;              // [K*S] smallest execution latency a request of the queue can see
     unsigned long long* alive;      // bit j: the request in queue slot j survives at the smallest possible cost
@@ -854,6 +864,110 @@ __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass)
     }
 }
 
+// ---- epilogue: positions -> estimates, drop decisions, queue order ------------------------
+// A request's queue position is its sorted position minus the start of its queue; with it come its own stage's
+// cost, the downstream maximum and the decision.  The results are formed in queue order and belong in request
+// order.  Written straight to their places, 4 bytes at a time and far from one another, every write reaches
+// memory as a partial cache line (shuffled input: 37 bytes written per 4 bytes of payload).  So they go back in
+// two steps.  The last radix pass does not write its keys out: it knows every element's final slot, forms the
+// result there and then, writes the queue order (runs per digit, like the keys it would have written), and hands
+// the pairs (request id, estimate | drop << 31) on gathered by the range of request ids they belong to: staged in
+// LDS a second time and written as one run per range.  The order inside a range does not matter, so a tile
+// reserves its place in every range with one atomic add (every id occurs once: a range holds exactly its share).
+// A second kernel gives every range to one workgroup that puts each packed word at its request's place in LDS
+// and writes the estimates and decisions of the range out in request order.  Up to kRetBuckets ranges of at most
+// 2^kRetMaxShift ids; beyond that (more than 2^24 requests) the last pass writes its keys like any other, and
+// epilogue_kernel scatters est | drop as ONE 4-byte write per request into the key buffer the last pass no
+// longer needs, which unpack_kernel then streams out.
+//
+// With at most kEpiSegs queues everything a request needs about its queue (stage constants, queue start,
+// downstream maximum, snapshot time) sits in LDS.
+constexpr int kEpiSegs = 64;
+constexpr int kEpiThreads = 256;
+
+struct EpiSeg {                     // 80 bytes
+    uint32_t B, W, latB, mode;
+    uint32_t mB, shB, mW, shW;
+    int32_t start, now;
+    uint32_t down_lo, down_hi;
+    int32_t first;                  // first request of the queue's snapshot
+    int32_t len;                    // queue length
+    uint32_t aux;                   // smallest execution latency | kSegScan << 31
+    int32_t rec;                    // the queue's stage record and latency row in the plan
+    uint32_t aW, bW;                // latB = aW * W + bW
+    uint32_t pad[2];
+};
+
+// own-stage cost at queue position pos plus the downstream maximum: stage_cost() with the record
+// held in registers
+__device__ __forceinline__ uint64_t epilogue_estimate(const EpiSeg& q, const int32_t* lat_row, uint32_t pos) {
+    const uint32_t batches = magic_div_dev(pos + q.B - 1u, q.mB, q.shB);
+    const uint64_t p = (uint64_t)batches * q.bW;
+    uint64_t wait = (uint64_t)batches * q.aW;
+    if ((p >> 32) == 0) wait += magic_div_dev((uint32_t)p, q.mW, q.shW);
+    else wait += wide_div(p, q.W);
+    uint32_t ex = q.latB;
+    if (pos + 1u < q.B) ex = (uint32_t)lat_row[pos];             // only the first B-1 requests of a queue
+    uint64_t c = wait + ex;
+    c = c < kCostCap ? c : kCostCap;
+    return c + (((uint64_t)q.down_hi << 32) | q.down_lo);
+}
+
+// the deadline of request r back from its sort key (or from the input when the key is the arrival)
+__device__ __forceinline__ int32_t epilogue_deadline(const SortDev& A, const EpiSeg& q, uint32_t key, uint32_t r, uint32_t umin) {
+    const uint32_t uk = key + umin;
+    const int32_t mode = (int32_t)(q.mode & 0xFF);
+    if (mode == PARD_ORDER_LBF) return (int32_t)(uk ^ 0x80000000u);
+    if (mode == PARD_ORDER_HBF) return (int32_t)(~uk ^ 0x80000000u);
+    return (int64_t)r < A.n ? A.deadline[r] : 0;
+}
+
+__device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
+                                                 uint32_t key, uint32_t r, uint32_t umin) {
+    const uint64_t e64 = epilogue_estimate(q, lat_row, (uint32_t)(j - (int64_t)q.start));
+    int32_t est;
+    uint8_t drp;
+    finish_request(e64, q.now, epilogue_deadline(A, q, key, r, umin), est, drp);
+    return (uint32_t)est | ((uint32_t)drp << 31);
+}
+
+__device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t seg) {
+    const PlanDev& P = A.plan;
+    const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
+    const StageRec sr = P.recs[P.shared ? (int64_t)k : (int64_t)seg];
+    const unsigned long long dn = A.down[seg];
+    EpiSeg q;
+    q.B = (uint32_t)sr.B; q.W = (uint32_t)sr.W; q.latB = (uint32_t)sr.latB; q.mode = (uint32_t)sr.mode;
+    q.mB = sr.mB; q.shB = sr.shB; q.mW = sr.mW; q.shW = sr.shW;
+    q.start = A.seg_ptr[seg]; q.now = A.now[u];
+    q.first = A.snap_ptr[u];
+    q.len = A.seg_ptr[seg + 1] - q.start;
+    q.aux = A.consistent ? A.min_lat[seg] : 0u;
+    q.rec = (int32_t)(P.shared ? k : seg);
+    q.aW = sr.aW; q.bW = sr.bW; q.pad[0] = q.pad[1] = 0;
+    q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
+    return q;
+}
+
+// request id and packed result (estimate | drop << 31) of queue slot j
+__device__ __forceinline__ void epilogue_slot(const SortDev& A, const EpiSeg* tab, bool cached, int64_t j, uint32_t key,
+                                              uint32_t pay, uint32_t umin, uint32_t idx_mask, uint32_t& r, uint32_t& out) {
+    const PlanDev& P = A.plan;
+    const uint32_t local = pay & idx_mask;
+    const uint32_t seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
+    const uint32_t k = seg % (uint32_t)P.S;
+    const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+    if (cached) {
+        const EpiSeg& q = tab[seg];
+        r = (uint32_t)q.first + local;
+        out = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j, key, r, umin);
+    } else {
+        const EpiSeg q = epilogue_segment(A, seg);
+        r = (uint32_t)q.first + local;
+        out = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j, key, r, umin);
+    }
+}
+
 // Downsweep: rank the tile's elements among equal digits, reorder in LDS, write runs out.
 template <bool FIRST>
 __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, int pass) {
@@ -865,9 +979,15 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     __shared__ uint32_t tile_start[kRadix];
     __shared__ uint32_t gbase[kRadix];
     __shared__ uint32_t scan_tmp[kSortWaves];
+    __shared__ EpiSeg tab[kEpiSegs];                 // last pass only
+    __shared__ uint32_t tile_total;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
+    // the last pass forms the results instead of writing its keys out
+    const bool finish = A.finish_in_last_pass && pass == (int)A.params->passes - 1;
+    const bool cached = (int64_t)A.plan.K * A.plan.S <= kEpiSegs;
+    if (finish && cached && tid < A.plan.K * A.plan.S) tab[tid] = epilogue_segment(A, (uint32_t)tid);
     const int rem_bits = (int)A.params->total_bits - kRadixBits * pass;
     const int nbits = rem_bits < kRadixBits ? (rem_bits < 1 ? 1 : rem_bits) : kRadixBits;   // digit bits that can differ
     uint32_t* dst_key = A.key[pass & 1];
@@ -946,91 +1066,105 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         }
     }
     __syncthreads();
+    if (!finish) {
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            const int j = i * kSortThreads + tid;
+            if (j < valid) {
+                const uint32_t k = lds_key[j], p = lds_pay[j];
+                const uint32_t d = digit_of(k, A.idx_bits < 32 ? (p >> A.idx_bits) : 0u, kb, pass);
+                const uint32_t dst = gbase[d] + (uint32_t)j;
+                if ((int64_t)dst < A.n) { dst_key[dst] = k; dst_pay[dst] = p; }
+            }
+        }
+        return;
+    }
+
+    // Last pass: element j of the reordered tile lands in queue slot gbase[digit] + j.
+    uint32_t* first_place = &whist[0][0];            // results of the tile per range, then the range's first place in the tile
+    uint32_t* delta = &whist[0][0] + kRetBuckets;    // the range's reserved place in memory minus its first place in the tile
+    static_assert(2 * kRetBuckets <= kSortWaves * kRadix && kRetBuckets == kSortThreads, "the range counters reuse the digit counters");
+    const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
+    const int shift = A.ret_shift;
+    const int64_t range = (int64_t)1 << shift;
+    uint32_t r[kSortItems], out[kSortItems], rb[kSortItems];    // rb = place among the tile's results of its range | range << 16
+    first_place[tid] = 0;                            // (the digit counters were last read before the barrier above)
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const int j = i * kSortThreads + tid;
+        r[i] = 0xFFFFFFFFu;
+        out[i] = 0;
         if (j < valid) {
             const uint32_t k = lds_key[j], p = lds_pay[j];
             const uint32_t d = digit_of(k, A.idx_bits < 32 ? (p >> A.idx_bits) : 0u, kb, pass);
             const uint32_t dst = gbase[d] + (uint32_t)j;
-            if ((int64_t)dst < A.n) { dst_key[dst] = k; dst_pay[dst] = p; }
+            if ((int64_t)dst < A.n) {
+                epilogue_slot(A, tab, cached, (int64_t)dst, k, p, umin, idx_mask, r[i], out[i]);
+                A.order[dst] = (int32_t)r[i];
+            }
         }
     }
-}
-
-// ---- epilogue: positions -> estimates, drop decisions, queue order ------------------------
-// The estimate (31 bits, never negative) and the drop bit leave as ONE scattered 4-byte write
-// per request into the key buffer the last pass no longer needs; a streaming kernel then
-// unpacks that buffer into est[] and drop[] with coalesced accesses.
-//
-// Persistent workgroups; with at most kEpiSegs queues everything a request needs about its
-// queue (stage constants, queue start, downstream maximum, snapshot time) sits in LDS, so the
-// only global traffic per request is its key and payload in, its order entry and packed result out.
-constexpr int kEpiSegs = 64;
-constexpr int kEpiThreads = 256;
-
-struct EpiSeg {                     // 80 bytes
-    uint32_t B, W, latB, mode;
-    uint32_t mB, shB, mW, shW;
-    int32_t start, now;
-    uint32_t down_lo, down_hi;
-    int32_t first;                  // first request of the queue's snapshot
-    int32_t len;                    // queue length
-    uint32_t aux;                   // smallest execution latency | kSegScan << 31
-    int32_t rec;                    // the queue's stage record and latency row in the plan
-    uint32_t aW, bW;                // latB = aW * W + bW
-    uint32_t pad[2];
-};
-
-// own-stage cost at queue position pos plus the downstream maximum: stage_cost() with the record
-// held in registers
-__device__ __forceinline__ uint64_t epilogue_estimate(const EpiSeg& q, const int32_t* lat_row, uint32_t pos) {
-    const uint32_t batches = magic_div_dev(pos + q.B - 1u, q.mB, q.shB);
-    const uint64_t p = (uint64_t)batches * q.bW;
-    uint64_t wait = (uint64_t)batches * q.aW;
-    if ((p >> 32) == 0) wait += magic_div_dev((uint32_t)p, q.mW, q.shW);
-    else wait += wide_div(p, q.W);
-    uint32_t ex = q.latB;
-    if (pos + 1u < q.B) ex = (uint32_t)lat_row[pos];             // only the first B-1 requests of a queue
-    uint64_t c = wait + ex;
-    c = c < kCostCap ? c : kCostCap;
-    return c + (((uint64_t)q.down_hi << 32) | q.down_lo);
-}
-
-// the deadline of request r back from its sort key (or from the input when the key is the arrival)
-__device__ __forceinline__ int32_t epilogue_deadline(const SortDev& A, const EpiSeg& q, uint32_t key, uint32_t r, uint32_t umin) {
-    const uint32_t uk = key + umin;
-    const int32_t mode = (int32_t)(q.mode & 0xFF);
-    if (mode == PARD_ORDER_LBF) return (int32_t)(uk ^ 0x80000000u);
-    if (mode == PARD_ORDER_HBF) return (int32_t)(~uk ^ 0x80000000u);
-    return (int64_t)r < A.n ? A.deadline[r] : 0;
-}
-
-__device__ __forceinline__ uint32_t epilogue_one(const SortDev& A, const EpiSeg& q, const int32_t* lat_row, int64_t j,
-                                                 uint32_t key, uint32_t r, uint32_t umin) {
-    const uint64_t e64 = epilogue_estimate(q, lat_row, (uint32_t)(j - (int64_t)q.start));
-    int32_t est;
-    uint8_t drp;
-    finish_request(e64, q.now, epilogue_deadline(A, q, key, r, umin), est, drp);
-    return (uint32_t)est | ((uint32_t)drp << 31);
-}
-
-__device__ __forceinline__ EpiSeg epilogue_segment(const SortDev& A, uint32_t seg) {
-    const PlanDev& P = A.plan;
-    const uint32_t u = seg / (uint32_t)P.S, k = seg - u * (uint32_t)P.S;
-    const StageRec sr = P.recs[P.shared ? (int64_t)k : (int64_t)seg];
-    const unsigned long long dn = A.down[seg];
-    EpiSeg q;
-    q.B = (uint32_t)sr.B; q.W = (uint32_t)sr.W; q.latB = (uint32_t)sr.latB; q.mode = (uint32_t)sr.mode;
-    q.mB = sr.mB; q.shB = sr.shB; q.mW = sr.mW; q.shW = sr.shW;
-    q.start = A.seg_ptr[seg]; q.now = A.now[u];
-    q.first = A.snap_ptr[u];
-    q.len = A.seg_ptr[seg + 1] - q.start;
-    q.aux = A.consistent ? A.min_lat[seg] : 0u;
-    q.rec = (int32_t)(P.shared ? k : seg);
-    q.aW = sr.aW; q.bW = sr.bW; q.pad[0] = q.pad[1] = 0;
-    q.down_lo = (uint32_t)dn; q.down_hi = (uint32_t)(dn >> 32);
-    return q;
+    __syncthreads();                                 // the tile's keys are out of LDS, the range counters are zero
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        // a snapshot larger than promised can leave ids beyond the end: they are not returned
+        const bool ok = (int64_t)r[i] < A.n;
+        const uint32_t b = r[i] >> shift;
+        // Input in arrival order puts one range into a whole wave, and 64 lanes adding to one LDS word serialise:
+        // the most common range takes its places with one add.
+        unsigned long long todo = __ballot(ok);
+        uint32_t place = 0;
+        if (todo != 0ull) {
+            const int leader = __ffsll((long long)todo) - 1;
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)b, leader);
+            const unsigned long long same = __ballot(b == b0) & todo;
+            uint32_t old = 0;
+            if (lane == leader) old = atomicAdd(&first_place[b0], (uint32_t)__popcll(same));
+            old = (uint32_t)__builtin_amdgcn_readlane((int)old, leader);
+            if ((same >> lane) & 1ull)
+                place = old + __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+            todo &= ~same;
+        }
+        if ((todo >> lane) & 1ull) place = atomicAdd(&first_place[b], 1u);
+        rb[i] = ok ? (place | (b << 16)) : 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    // one thread per range: the range's first place in the tile, and room for the tile's results in the range
+    {
+        const uint32_t cnt = first_place[tid];
+        const uint32_t start = block_exclusive_scan(cnt, scan_tmp, tid);
+        uint32_t base = 0;
+        if (cnt) base = atomicAdd(&A.ret_cursor[tid], cnt);
+        first_place[tid] = start;
+        delta[tid] = base - start;
+        if (tid == kSortThreads - 1) tile_total = start + cnt;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        if (rb[i] != 0xFFFFFFFFu) {
+            const uint32_t lp = first_place[rb[i] >> 16] + (rb[i] & 0xFFFFu);
+            lds_key[lp] = out[i];
+            lds_pay[lp] = r[i];
+        }
+    }
+    __syncthreads();
+    const uint32_t total = tile_total;
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const uint32_t j = (uint32_t)(i * kSortThreads + tid);
+        if (j < total) {
+            const uint32_t rr = lds_pay[j];
+            const uint32_t b = rr >> shift;
+            const int64_t first = (int64_t)b << shift;
+            const int64_t room = A.n - first < range ? A.n - first : range;
+            const uint32_t at = delta[b] + j;             // place inside the range
+            if ((int64_t)at < room) {
+                dst_pay[first + at] = rr;
+                dst_key[first + at] = lds_key[j];
+            }
+        }
+    }
 }
 
 // Order of the work.  Walking the queue slots front to back writes the packed results of one queue at a
@@ -1168,6 +1302,66 @@ __global__ __launch_bounds__(256) void unpack_kernel(SortDev A) {
                 const uint32_t v = packed[r];
                 A.est[r] = (int32_t)(v & 0x7FFFFFFFu);
                 A.drop[r] = (uint8_t)(v >> 31);
+            }
+        }
+    }
+}
+
+// Second step of the way back to request order: one workgroup per range of request ids.
+template <int SHIFT, int kRetWgThreads>
+__global__ __launch_bounds__(kRetWgThreads) void epilogue_return_kernel(SortDev A) {
+    constexpr int kRetShift = SHIFT, kRetRange = 1 << SHIFT;
+    __shared__ uint32_t by_request[kRetRange];
+    if (A.params->split) return;
+    const int last = ((int)A.params->passes - 1) & 1;            // where the last pass would have written its keys
+    const uint32_t* ret_out = A.key[last];
+    const uint32_t* ret_r = A.pay[last];
+    const int tid = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x << kRetShift;
+    if (first >= A.n) return;
+    const int room = (int)(A.n - first < kRetRange ? A.n - first : kRetRange);
+    int cnt = (int)A.ret_cursor[blockIdx.x];
+    if (cnt > room) cnt = room;
+    constexpr int kAhead = 4;                                   // groups of four per thread in flight
+    for (int i0 = tid * 4; i0 < cnt; i0 += kRetWgThreads * 4 * kAhead) {
+        uint32_t rr[kAhead][4], oo[kAhead][4];
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int i = i0 + a * kRetWgThreads * 4;
+            if (i + 3 < cnt) {
+                const pard_v4i rv = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(ret_r + first + i));
+                const pard_v4i ov = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(ret_out + first + i));
+                rr[a][0] = (uint32_t)rv.x; rr[a][1] = (uint32_t)rv.y; rr[a][2] = (uint32_t)rv.z; rr[a][3] = (uint32_t)rv.w;
+                oo[a][0] = (uint32_t)ov.x; oo[a][1] = (uint32_t)ov.y; oo[a][2] = (uint32_t)ov.z; oo[a][3] = (uint32_t)ov.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    rr[a][c] = i + c < cnt ? ret_r[first + i + c] : 0u;
+                    oo[a][c] = i + c < cnt ? ret_out[first + i + c] : 0u;
+                }
+            }
+        }
+#pragma unroll
+        for (int a = 0; a < kAhead; ++a) {
+            const int i = i0 + a * kRetWgThreads * 4;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (i + c < cnt) by_request[rr[a][c] & (kRetRange - 1)] = oo[a][c];      // the id lies in this range
+        }
+    }
+    __syncthreads();
+    const bool vec = ((reinterpret_cast<uintptr_t>(A.est) & 15) | (reinterpret_cast<uintptr_t>(A.drop) & 3)) == 0;
+    for (int i = tid * 4; i < room; i += kRetWgThreads * 4) {
+        if (vec && i + 3 < room) {
+            const uint4 v = *reinterpret_cast<const uint4*>(&by_request[i]);
+            stream_store(reinterpret_cast<int4*>(A.est + first + i), make_int4((int32_t)(v.x & 0x7FFFFFFFu), (int32_t)(v.y & 0x7FFFFFFFu),
+                                                                                  (int32_t)(v.z & 0x7FFFFFFFu), (int32_t)(v.w & 0x7FFFFFFFu)));
+            *reinterpret_cast<uint32_t*>(A.drop + first + i) = (v.x >> 31) | ((v.y >> 31) << 8) | ((v.z >> 31) << 16) | ((v.w >> 31) << 24);
+        } else {
+            for (int c = 0; c < 4 && i + c < room; ++c) {
+                const uint32_t v = by_request[i + c];
+                A.est[first + i + c] = (int32_t)(v & 0x7FFFFFFFu);
+                A.drop[first + i + c] = (uint8_t)(v >> 31);
             }
         }
     }
@@ -1827,6 +2021,9 @@ SortDev make_dev(const SortArgs& a, const SortLayout& L) {
     D.idx_bits = L.idx_bits;
     D.seg_bits = L.seg_bits;
     D.max_passes = L.max_passes;
+    D.ret_cursor = reinterpret_cast<uint32_t*>(ws + L.ret_cursor);
+    D.ret_shift = L.ret_shift;
+    D.finish_in_last_pass = (!a.consistent && L.ret_shift <= kRetMaxShift) ? 1 : 0;
     return D;
 }
 
@@ -1893,9 +2090,22 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             int64_t eg = (a.n / 4 + kEpiThreads - 1) / kEpiThreads;       // persistent: a few workgroups per compute unit
             if (eg > 8 * (int64_t)a.num_cus) eg = 8 * (int64_t)a.num_cus;
             if (eg < 1) eg = 1;
-            epilogue_kernel<<<(unsigned)eg, kEpiThreads, 0, stream>>>(D);
+            if (!D.finish_in_last_pass) {
+                // more requests than kRetBuckets ranges of the largest size hold: results go back one by one
+                epilogue_kernel<<<(unsigned)eg, kEpiThreads, 0, stream>>>(D);
+                unpack_kernel<<<gb, 256, 0, stream>>>(D);
+            } else {
+                const unsigned ranges = (unsigned)((a.n + ((int64_t)1 << L.ret_shift) - 1) >> L.ret_shift);
+                switch (L.ret_shift) {
+                    case 11: epilogue_return_kernel<11, 256><<<ranges, 256, 0, stream>>>(D); break;
+                    case 12: epilogue_return_kernel<12, 256><<<ranges, 256, 0, stream>>>(D); break;
+                    case 13: epilogue_return_kernel<13, 512><<<ranges, 512, 0, stream>>>(D); break;
+                    case 14: epilogue_return_kernel<14, 1024><<<ranges, 1024, 0, stream>>>(D); break;
+                    default: epilogue_return_kernel<15, 1024><<<ranges, 1024, 0, stream>>>(D); break;
+                }
+            }
         }
-        unpack_kernel<<<gb, 256, 0, stream>>>(D);
+        if (a.consistent) unpack_kernel<<<gb, 256, 0, stream>>>(D);
     }
     return hipGetLastError();
 }
