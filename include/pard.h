@@ -181,7 +181,7 @@ int pard_estimate_drop(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_
  *
  * Snapshots up to PARD_FUSED_SNAPSHOT_CAPACITY need a few bytes of the buffer, so any n is
  * served; larger snapshots need what pard_workspace_bytes reports, and the call returns
- * PARD_E_SCRATCH when that exceeds PARD_STATIC_SCRATCH_BYTES (about 1.7 million requests).
+ * PARD_E_SCRATCH when that exceeds PARD_STATIC_SCRATCH_BYTES (about 1.5 million requests).
  * All calls on one GPU share that GPU's buffer: two such calls that overlap in time on one GPU
  * (different streams) race; calls on one stream are ordered and safe.  The first call on a
  * device looks up the buffer's address (no allocation); make it outside a stream capture.

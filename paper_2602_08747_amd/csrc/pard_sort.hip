@@ -20,6 +20,7 @@
 // carries the request's index inside its snapshot (as many bits as the promised snapshot
 // bound needs) and the segment id above it; the epilogue adds the snapshot's first request.
 #include "pard_device.hpp"
+#include <type_traits>
 
 namespace pard {
 
@@ -28,8 +29,10 @@ namespace {
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
 constexpr int kSortThreads = 512;
-constexpr int kSortItems = 16;
-constexpr int kTile = kSortThreads * kSortItems;       // 8192 elements per tile
+constexpr int kSortItems = 16;                         // elements per thread of a radix pass: a tile holds 8192 elements,
+constexpr int kSmallItems = 4;                         // or 2048 when there are few requests: more, shorter-lived workgroups
+                                                       // (a million shuffled requests: 0.171 -> 0.133 ms per call; 4096 was no better)
+constexpr int64_t kSmallTileMax = (int64_t)1 << 22;    // up to this many requests the small tile is used
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
@@ -59,7 +62,7 @@ struct SortLayout {
     int64_t params, seg_count, cfull, down, keepm, chunk_tot, ret_cursor, zero_end, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
             min_lat, alive, wkept, tile_tot, range_tot, carry, total;
     int64_t tiles, chunks;
-    int32_t max_passes, idx_bits, seg_bits, ret_shift;
+    int32_t max_passes, idx_bits, seg_bits, ret_shift, tile_items;
 };
 
 int bits_of(uint64_t x) { int b = 0; while (x) { ++b; x >>= 1; } return b; }
@@ -74,7 +77,9 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.max_passes = (32 + L.seg_bits + kRadixBits - 1) / kRadixBits;
     L.ret_shift = bits_of(n > 0 ? (uint64_t)(n - 1) : 0) - 9;       // kRetBuckets ranges of 2^ret_shift request ids cover n
     if (L.ret_shift < kRetMinShift) L.ret_shift = kRetMinShift;     // (beyond kRetMaxShift the results go back one by one)
-    L.tiles = (n + kTile - 1) / kTile;
+    L.tile_items = n <= kSmallTileMax ? kSmallItems : kSortItems;
+    const int64_t tile = (int64_t)kSortThreads * L.tile_items;
+    L.tiles = (n + tile - 1) / tile;
     L.chunks = (L.tiles + kChunkTiles - 1) / kChunkTiles;
     int64_t off = 0;
     L.params = off;     off = align256(off + (int64_t)sizeof(SortParams));
@@ -641,9 +646,10 @@ __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* t
 // ---- one radix pass ----------------------------------------------------------------------
 // Element e of a tile: wave w owns 1024 consecutive elements, item i lane l is element
 // w*1024 + i*64 + l.
-template <bool FIRST>
+template <bool FIRST, int ITEMS>
 __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t tile_base, int valid, int wave, int lane,
-                                          uint32_t umin, bool need_pay, uint32_t (&key)[kSortItems], uint32_t (&pay)[kSortItems]) {
+                                          uint32_t umin, bool need_pay, uint32_t (&key)[ITEMS], uint32_t (&pay)[ITEMS]) {
+    constexpr int kSortItems = ITEMS;
     if (FIRST) {
         // every load is issued before the first key is formed (elements past the end re-read the
         // tile's first request and are zeroed afterwards)
@@ -705,8 +711,9 @@ __device__ __forceinline__ void load_tile(const SortDev& A, int pass, int64_t ti
 }
 
 // Upsweep: digit histogram of every tile, and of every chunk of kChunkTiles tiles.
-template <bool FIRST>
+template <bool FIRST, int ITEMS>
 __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int pass) {
+    constexpr int kSortItems = ITEMS, kTile = kSortThreads * ITEMS;
     if (pass >= (int)A.params->passes) return;
     __shared__ uint32_t h[kRadix];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -734,7 +741,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
             pay[4 * g] = pv.x; pay[4 * g + 1] = pv.y; pay[4 * g + 2] = pv.z; pay[4 * g + 3] = pv.w;
         }
     } else {
-        load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
+        load_tile<FIRST, ITEMS>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
     }
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
@@ -969,8 +976,9 @@ __device__ __forceinline__ void epilogue_slot(const SortDev& A, const EpiSeg* ta
 }
 
 // Downsweep: rank the tile's elements among equal digits, reorder in LDS, write runs out.
-template <bool FIRST>
+template <bool FIRST, int ITEMS>
 __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, int pass) {
+    constexpr int kSortItems = ITEMS, kTile = kSortThreads * ITEMS;
     if (pass >= (int)A.params->passes) return;
 
     __shared__ uint32_t lds_key[kTile];
@@ -1005,7 +1013,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     const uint32_t first_slot = tid < kRadix ? A.tile_hist[((int64_t)pass * A.tiles + tile) * kRadix + tid] : 0u;
 
     uint32_t key[kSortItems], pay[kSortItems], rd[kSortItems];   // rd = rank | digit << 16
-    load_tile<FIRST>(A, pass, tile_base, valid, wave, lane, umin, true, key, pay);
+    load_tile<FIRST, ITEMS>(A, pass, tile_base, valid, wave, lane, umin, true, key, pay);
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
@@ -2064,9 +2072,10 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             if (a.plan.uniform_mode == PARD_ORDER_HBF) split_kernel<true><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
             else if (a.plan.uniform_mode == PARD_ORDER_LBF) split_kernel<false><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
         }
-        for (int p = 0; p < L.max_passes; ++p) {
-            if (p == 0) upsweep_kernel<true><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
-            else upsweep_kernel<false><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+        auto radix_pass = [&](auto items_tag, int p) {
+            constexpr int ITEMS = decltype(items_tag)::value;
+            if (p == 0) upsweep_kernel<true, ITEMS><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
+            else upsweep_kernel<false, ITEMS><<<(unsigned)L.tiles, kSortThreads, 0, stream>>>(D, p);
             if (L.chunks > kFusedScanChunks) {
                 digit_scan_kernel<<<1, 1024, 0, stream>>>(D, p);
                 chunk_scan_kernel<true><<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
@@ -2074,8 +2083,12 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
                 chunk_scan_kernel<false><<<(unsigned)L.chunks, kRadix, 0, stream>>>(D, p);
             }
             const unsigned dg = (unsigned)((L.tiles + kDies - 1) / kDies * kDies);
-            if (p == 0) downsweep_kernel<true><<<dg, kSortThreads, 0, stream>>>(D, p);
-            else downsweep_kernel<false><<<dg, kSortThreads, 0, stream>>>(D, p);
+            if (p == 0) downsweep_kernel<true, ITEMS><<<dg, kSortThreads, 0, stream>>>(D, p);
+            else downsweep_kernel<false, ITEMS><<<dg, kSortThreads, 0, stream>>>(D, p);
+        };
+        for (int p = 0; p < L.max_passes; ++p) {
+            if (L.tile_items == kSmallItems) radix_pass(std::integral_constant<int, kSmallItems>{}, p);
+            else radix_pass(std::integral_constant<int, kSortItems>{}, p);
         }
         if (a.consistent) {
             int64_t pg = (a.n + kConsTile - 1) / kConsTile;
