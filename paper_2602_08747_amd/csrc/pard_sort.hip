@@ -728,6 +728,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
     // A histogram does not care which element a lane holds: later passes read four consecutive
     // elements per lane with 16-byte loads (element (i/4)*256 + lane*4 + i%4 of the wave's 1024).
     const bool quads = !FIRST && valid == kTile;
+    bool key_only = false;
     if (quads) {
         const uint32_t* src_key = A.key[(pass + 1) & 1];
         const uint32_t* src_pay = A.pay[(pass + 1) & 1];
@@ -740,12 +741,37 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
             if (need_pay) pv = *reinterpret_cast<const uint4*>(src_pay + at);
             pay[4 * g] = pv.x; pay[4 * g + 1] = pv.y; pay[4 * g + 2] = pv.z; pay[4 * g + 3] = pv.w;
         }
+    } else if (FIRST && !need_pay && A.plan.uniform_mode >= 0) {
+        // One order for every stage and a digit without queue bits: the digit comes from the deadline (or the
+        // arrival) alone, so neither the stage nor the snapshot of a request is looked at (half the bytes).
+        const int32_t mode = A.plan.uniform_mode;
+        const int32_t* src = mode == PARD_ORDER_FCFS ? A.arrival : A.deadline;
+        const bool vec = valid == kTile && (reinterpret_cast<uintptr_t>(src) & 15) == 0;
+#pragma unroll
+        for (int g = 0; g < kSortItems / 4; ++g) {
+            const int e0 = wave * (kWave * kSortItems) + g * (kWave * 4) + lane * 4;
+            int32_t v[4];
+            if (vec) {
+                const int4 q = *reinterpret_cast<const int4*>(src + tile_base + e0);
+                v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) v[c] = e0 + c < valid ? src[tile_base + e0 + c] : 0;
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                key[4 * g + c] = order_key(mode, v[c], v[c]) - umin;
+                pay[4 * g + c] = e0 + c < valid ? 0u : 0xFFFFFFFFu;       // marks the elements past the end
+            }
+        }
+        key_only = true;
     } else {
         load_tile<FIRST, ITEMS>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
     }
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
-        const int e = quads ? 0 : wave * (kWave * kSortItems) + i * kWave + lane;       // a full tile: every element counts
+        int e = quads ? 0 : wave * (kWave * kSortItems) + i * kWave + lane;       // a full tile: every element counts
+        if (key_only) { e = pay[i] ? valid : 0; pay[i] = 0; }
         const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
         // Sorted input puts long runs of one digit into a wave, and 64 lanes adding to one LDS
         // word serialise: the two most common leading digits are counted with a ballot, the
@@ -832,19 +858,27 @@ __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass)
     const int d = threadIdx.x, lane = d & 63, wave = d >> 6;
     const int64_t c = blockIdx.x;
     const uint32_t* tot = A.chunk_tot + (int64_t)pass * A.chunks * kRadix;
+    // the chunk's own tile counts do not depend on the chunk totals: all of these loads are issued before either is used
+    const int64_t t_lo = c * kChunkTiles, t_hi = t_lo + kChunkTiles < A.tiles ? t_lo + kChunkTiles : A.tiles;
+    uint32_t* th = A.tile_hist + (int64_t)pass * A.tiles * kRadix;
+    uint32_t x[kChunkTiles];
+#pragma unroll
+    for (int i = 0; i < kChunkTiles; ++i) x[i] = t_lo + i < t_hi ? th[(t_lo + i) * kRadix + d] : 0u;
     uint32_t run;
     if (SCANNED) {
         run = tot[c * kRadix + d];
     } else {
+        static_assert(kFusedScanChunks == 64, "the chunk totals of a digit are loaded in two halves of 32");
         uint32_t all = 0, before = 0;
-        for (int64_t c0 = 0; c0 < A.chunks; c0 += 16) {
-            uint32_t x[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) x[i] = c0 + i < A.chunks ? tot[(c0 + i) * kRadix + d] : 0u;
+        for (int64_t c0 = 0; c0 < kFusedScanChunks; c0 += 32) {
+            uint32_t y[32];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                all += x[i];
-                if (c0 + i < c) before += x[i];
+            for (int i = 0; i < 32; ++i) y[i] = c0 + i < A.chunks ? tot[(c0 + i) * kRadix + d] : 0u;
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                all += y[i];
+                if (c0 + i < c) before += y[i];
             }
         }
         uint32_t inc = all;
@@ -859,11 +893,6 @@ __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass)
         for (int w = 0; w < wave; ++w) pre += scan_tmp[w];
         run = pre + inc - all + before;
     }
-    const int64_t t_lo = c * kChunkTiles, t_hi = t_lo + kChunkTiles < A.tiles ? t_lo + kChunkTiles : A.tiles;
-    uint32_t* th = A.tile_hist + (int64_t)pass * A.tiles * kRadix;
-    uint32_t x[kChunkTiles];
-#pragma unroll
-    for (int i = 0; i < kChunkTiles; ++i) x[i] = t_lo + i < t_hi ? th[(t_lo + i) * kRadix + d] : 0u;
 #pragma unroll
     for (int i = 0; i < kChunkTiles; ++i) {
         if (t_lo + i < t_hi) th[(t_lo + i) * kRadix + d] = run;
