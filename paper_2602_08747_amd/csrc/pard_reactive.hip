@@ -27,11 +27,17 @@ constexpr int kRxThreads = 256;
 constexpr int kRxChunks = 16;                            // chunks of 64 queue slots a wave walks
 constexpr int32_t kNoWindow = 0x7fffffff;
 
-// The queue that holds slot j: the last g in [lo, hi] with seg_ptr[g] <= j (queues may be empty).
-__device__ __forceinline__ int queue_of_slot(const int32_t* seg_ptr, int64_t j, int lo, int hi) {
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if ((int64_t)seg_ptr[mid] <= j) lo = mid; else hi = mid - 1;
+// The queue that holds slot j: the last g in [lo, hi] with seg_ptr[g] <= j (queues may be empty).  The slot is the
+// same in every lane of a wave and all 64 lanes call this: each round the lanes probe 64 evenly spaced queues at
+// once, so thousands of queues take three dependent loads instead of fifteen.
+__device__ __forceinline__ int queue_of_slot_wave(const int32_t* seg_ptr, int64_t j, int lo, int hi, int lane) {
+    while (hi > lo) {
+        const int step = (hi - lo + kWave - 1) / kWave;
+        const int probe = lo + (lane + 1) * step;
+        const bool le = probe <= hi && (int64_t)seg_ptr[probe] <= j;       // offsets never fall: these lanes are a prefix
+        const int below = __popcll(__ballot(le));
+        lo += below * step;
+        hi = lo + step - 1 < hi ? lo + step - 1 : hi;
     }
     return lo;
 }
@@ -47,6 +53,8 @@ struct WindowArgs {
     const int32_t *deadline, *order, *seg_ptr, *now;
     uint8_t* drop;
     int32_t* first;
+    int32_t mask_cap;                                       // snapshots of at most this many requests get their mask from
+                                                            // window_mask_snapshot_kernel (0: none do)
 };
 
 // What a lane keeps about the queue its slots are in; reloaded only when the queue changes along the walk.
@@ -77,7 +85,7 @@ __global__ __launch_bounds__(kRxThreads) void window_scan_kernel(WindowArgs A) {
     if (t0 >= A.n) return;
     int64_t t1 = t0 + (kRxChunks + 1) * kWave;            // one chunk of look-ahead
     if (t1 > A.n) t1 = A.n;
-    const int g_lo = queue_of_slot(A.seg_ptr, t0, 0, G - 1), g_hi = queue_of_slot(A.seg_ptr, t1 - 1, g_lo, G - 1);
+    const int g_lo = queue_of_slot_wave(A.seg_ptr, t0, 0, G - 1, lane), g_hi = queue_of_slot_wave(A.seg_ptr, t1 - 1, g_lo, G - 1, lane);
     // A walk that lies inside one queue has nothing to add once a fitting window before its first slot is known
     // (workgroups start roughly in the order of the slots, so the earlier part of a queue has usually reported).
     if (g_lo == g_hi) {
@@ -166,15 +174,83 @@ __global__ __launch_bounds__(kWave) void window_tail_kernel(WindowArgs A) {
     if (lane == 0) A.first[g] = first;
 }
 
-// Step 3.  The same walk (a wave takes kRxChunks chunks of 64 slots, request ids loaded up front).
+// Step 3.  The queue slots of a snapshot hold exactly the snapshot's own requests, which are neighbours in the
+// request arrays: a snapshot of at most kMaskCap requests gets one workgroup that collects its decisions in LDS by
+// request and writes them out in request order (one byte per request written straight from the queue slots costs a
+// write request per cache line touched: 126 us for 33.5 million requests against 38 this way).
+constexpr int kMaskCap = 16384;
+constexpr int kMaskThreads = 256;
+__global__ __launch_bounds__(kMaskThreads) void window_mask_snapshot_kernel(WindowArgs A) {
+    __shared__ __align__(16) uint8_t mask[kMaskCap];
+    __shared__ int32_t qstart[PARD_MAX_STAGES + 1];
+    __shared__ int32_t qfirst[PARD_MAX_STAGES];
+    const int S = A.plan.S, u = blockIdx.x, tid = threadIdx.x;
+    const int64_t lo = A.seg_ptr[(int64_t)u * S], hi = A.seg_ptr[(int64_t)(u + 1) * S];
+    const int64_t m = hi - lo;
+    if (lo < 0 || hi > A.n || m <= 0 || m > (int64_t)A.mask_cap) return;          // larger ones: window_mask_kernel
+    if (tid <= S) qstart[tid] = A.seg_ptr[(int64_t)u * S + tid];
+    if (tid < S) qfirst[tid] = A.first[(int64_t)u * S + tid];
+    for (int i = tid * 4; i < (int)m; i += kMaskThreads * 4) *reinterpret_cast<uint32_t*>(&mask[i]) = 0u;
+    __syncthreads();
+    const bool vec = (reinterpret_cast<uintptr_t>(A.order) & 15) == 0 && (lo & 3) == 0;
+    for (int64_t j0 = lo + (int64_t)tid * 4; j0 < hi; j0 += kMaskThreads * 4) {
+        int32_t req[4];
+        if (vec && j0 + 3 < hi) {
+            const int4 v = *reinterpret_cast<const int4*>(A.order + j0);
+            req[0] = v.x; req[1] = v.y; req[2] = v.z; req[3] = v.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) req[c] = j0 + c < hi ? A.order[j0 + c] : -1;
+        }
+        int g = 0, top = S - 1;                              // the queue of slot j0: the last g with qstart[g] <= j0
+        while (g < top) {
+            const int mid = (g + top + 1) >> 1;
+            if ((int64_t)qstart[mid] <= j0) g = mid; else top = mid - 1;
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int64_t j = j0 + c;
+            if (j >= hi) break;
+            while (g < S - 1 && j >= (int64_t)qstart[g + 1]) ++g;
+            const uint8_t d = (int32_t)(j - qstart[g]) < qfirst[g] ? 1 : 0;
+            const int64_t at = (int64_t)req[c] - lo;
+            if (at >= 0 && at < m) mask[at] = d;
+            else if (req[c] >= 0 && (int64_t)req[c] < A.n) A.drop[req[c]] = d;      // not from this snapshot's range
+        }
+    }
+    __syncthreads();
+    uint8_t* out = A.drop + lo;
+    if ((reinterpret_cast<uintptr_t>(out) & 15) == 0) {
+        for (int i = tid * 16; i < (int)m; i += kMaskThreads * 16) {
+            if (i + 15 < (int)m) *reinterpret_cast<uint4*>(out + i) = *reinterpret_cast<const uint4*>(&mask[i]);
+            else for (int c = i; c < (int)m; ++c) out[c] = mask[c];
+        }
+    } else {
+        for (int i = tid; i < (int)m; i += kMaskThreads) out[i] = mask[i];
+    }
+}
+
+// Larger snapshots: the same walk as in step 1 (a wave takes kRxChunks chunks of 64 slots, request ids loaded up
+// front), one byte per slot written at its request's place.
 __global__ __launch_bounds__(kRxThreads) void window_mask_kernel(WindowArgs A) {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int G = A.plan.K * A.plan.S;
+    const int G = A.plan.K * A.plan.S, S = A.plan.S;
     const int64_t t0 = ((int64_t)blockIdx.x * (kRxThreads / kWave) + wave) * (kRxChunks * kWave);
     if (t0 >= A.n) return;
     int64_t t1 = t0 + kRxChunks * kWave;
     if (t1 > A.n) t1 = A.n;
-    const int g_lo = queue_of_slot(A.seg_ptr, t0, 0, G - 1), g_hi = queue_of_slot(A.seg_ptr, t1 - 1, g_lo, G - 1);
+    const int g_lo = queue_of_slot_wave(A.seg_ptr, t0, 0, G - 1, lane), g_hi = queue_of_slot_wave(A.seg_ptr, t1 - 1, g_lo, G - 1, lane);
+    // snapshots the other kernel takes care of; a walk that only meets such snapshots has nothing to do
+    auto taken = [&](int g) {
+        const int u = g / S;
+        const int64_t size = (int64_t)A.seg_ptr[(int64_t)(u + 1) * S] - (int64_t)A.seg_ptr[(int64_t)u * S];
+        return size <= (int64_t)A.mask_cap;
+    };
+    if (A.mask_cap > 0) {
+        bool all_taken = true;
+        for (int u = g_lo / S; u <= g_hi / S; ++u) all_taken = all_taken && taken(u * S);
+        if (all_taken) return;
+    }
     int32_t req[kRxChunks];
 #pragma unroll
     for (int c = 0; c < kRxChunks; ++c) {
@@ -184,12 +260,16 @@ __global__ __launch_bounds__(kRxThreads) void window_mask_kernel(WindowArgs A) {
     // the slots of a lane rise along the walk, so its queue only moves forward (empty queues are stepped over)
     int g = g_lo;
     int32_t start = A.seg_ptr[g_lo], end = A.seg_ptr[g_lo + 1], first = A.first[g_lo];
+    bool skip = A.mask_cap > 0 && taken(g_lo);
 #pragma unroll
     for (int c = 0; c < kRxChunks; ++c) {
         const int64_t j = t0 + (int64_t)c * kWave + lane;
         if (j < t1) {
-            while (g < g_hi && j >= (int64_t)end) { ++g; start = end; end = A.seg_ptr[g + 1]; first = A.first[g]; }
-            A.drop[req[c]] = (int32_t)(j - start) < first ? 1 : 0;
+            while (g < g_hi && j >= (int64_t)end) {
+                ++g; start = end; end = A.seg_ptr[g + 1]; first = A.first[g];
+                if (A.mask_cap > 0 && g % S == 0) skip = taken(g);
+            }
+            if (!skip) A.drop[req[c]] = (int32_t)(j - start) < first ? 1 : 0;
         }
     }
 }
@@ -270,8 +350,11 @@ __global__ __launch_bounds__(kRxThreads) void slo_split_kernel(SplitArgs A) {
 
 hipError_t launch_window_scan(const PlanDev& plan, int64_t n, const int32_t* deadline, const int32_t* order, const int32_t* seg_ptr,
                               const int32_t* now, uint8_t* drop, int32_t* first, hipStream_t stream) {
-    WindowArgs a{plan, n, deadline, order, seg_ptr, now, drop, first};
+    WindowArgs a{plan, n, deadline, order, seg_ptr, now, drop, first, 0};
     const int G = plan.K * plan.S;
+    // snapshots of a few thousand requests on average: one workgroup per snapshot writes its mask (smaller ones
+    // would leave most of a workgroup idle, and the host cannot see the single sizes)
+    if (n / plan.K >= 1024 && n / plan.K <= kMaskCap) a.mask_cap = kMaskCap;
     window_init_kernel<<<(G + 255) / 256, 256, 0, stream>>>(first, G);
     if (n > 0) {
         const int64_t per_block = (int64_t)(kRxThreads / kWave) * kRxChunks * kWave;
@@ -280,6 +363,7 @@ hipError_t launch_window_scan(const PlanDev& plan, int64_t n, const int32_t* dea
     window_tail_kernel<<<(unsigned)G, kWave, 0, stream>>>(a);
     if (n > 0) {
         const int64_t per_block = (int64_t)(kRxThreads / kWave) * kRxChunks * kWave;
+        if (a.mask_cap > 0) window_mask_snapshot_kernel<<<(unsigned)plan.K, kMaskThreads, 0, stream>>>(a);
         window_mask_kernel<<<(unsigned)((n + per_block - 1) / per_block), kRxThreads, 0, stream>>>(a);
     }
     return hipGetLastError();
