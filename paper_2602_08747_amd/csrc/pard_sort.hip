@@ -11,9 +11,11 @@
 //             reads the tile again, ranks it and writes it out.  No workgroup waits for
 //             another one (a decoupled look-back over ~2000 co-resident tiles cost more
 //             than the second read of the keys)
-//   epilogue  queue position = sorted position - queue offset; own-stage cost +
-//             downstream maximum; drop decision; est|drop scattered to request order as one
-//             word, then unpacked by a streaming kernel.
+//   results   queue position = sorted position - queue offset; own-stage cost + downstream maximum; drop
+//             decision.  Formed inside the last pass (which then writes the queue order instead of its keys)
+//             and brought back to request order in two steps: gathered by range of request ids, then one
+//             workgroup per range.  Beyond 2^24 requests: est|drop scattered to request order as one word by
+//             a kernel of its own, then unpacked by a streaming kernel.
 //
 // The sort key is the virtual integer  V = segment << kb | (key - min key)  where kb is
 // the number of bits of the key range; only ceil(bits(V)/8) passes run.  The payload word

@@ -63,6 +63,21 @@ def test_config_shapes(gpu, oracle_mod, cfg, kw, fcfs):
             assert 0 < a < 1, a
 
 
+@pytest.mark.parametrize("order", ["arrival", "plan"])
+def test_mixed_snapshot_sizes(gpu, oracle_mod, order):
+    """Snapshots of a few thousand requests on average, whose drop mask one workgroup each collects in request order,
+    next to ones too large for that (they keep the walk over the queue slots), empty ones, sizes that leave the next
+    snapshot on an odd address, and a single-request one."""
+    sizes = [20000, 3001, 0, 17, 16384, 16385, 1, 8192, 5003, 0, 12289, 4099]
+    base = wl.make_workload(5, n_snapshots=len(sizes), per_snapshot=max(sizes), permute=True,
+                            order_mode=wl.MODE_FCFS if order == "arrival" else None)
+    w = wl.with_snapshot_sizes(base, np.array(sizes))
+    assert 1024 <= w.n // w.K <= 16384
+    w.now[:] = np.maximum(0, w.now.astype(np.int64) - 150_000).astype(np.int32)
+    a, b = run_both(gpu, oracle_mod, w, max_snap=FORCE_SORT)
+    assert 0 < b < 1
+
+
 def test_full_config5_and_4(gpu, oracle_mod):
     for cfg in (5, 4):
         w = wl.make_workload(cfg, order_mode=wl.MODE_FCFS)
