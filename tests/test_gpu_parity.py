@@ -266,6 +266,18 @@ def test_sizes_sort_path(gpu, oracle_mod, n):
     check(gpu, oracle_mod, w, max_snap=FORCE_SORT)
 
 
+@pytest.mark.parametrize("n,what", [((1 << 22) + 12345, "large tiles, a ragged last tile and a ragged last range of request ids"),
+                                    (1 << 22, "the largest request count on small tiles"),
+                                    ((1 << 21) + 2049, "small tiles, ranges of 2^13 ids"),
+                                    ((1 << 20) - 3, "ranges of 2^11 ids, the last one short")])
+def test_sort_path_tile_and_range_steps(gpu, oracle_mod, n, what):
+    """Request counts on either side of the steps the radix passes take (tiles of 2048 or 8192 elements; the way
+    back to request order through ranges of 2^11 to 2^15 request ids), shuffled, with a mixed drop mask."""
+    w = wl.half_survivors(wl.make_workload(4, n_requests=n, permute=True))
+    s, ref = check(gpu, oracle_mod, w, threads=16)
+    assert 0.1 < ref["drop"].mean() < 0.9, what
+
+
 def test_many_queues_sort_path(gpu, oracle_mod):
     """More queues (snapshots x stages) than the large-snapshot path keeps on chip per workgroup."""
     w = wl.random_workload(31, K=12, S=8, n_per_snapshot=700, dag_shared=0)
