@@ -55,6 +55,8 @@ struct SortParams {                 // lives in device memory, written by the se
     uint32_t passes;                // radix passes actually needed
     uint32_t total_bits;            // bits of the virtual sort key
     uint32_t split;                 // the requests come in deadline order: the queues are a stable split by stage (no sort)
+    uint32_t presplit;              // the same under sequentially consistent dropping: the split leaves the sorted keys and
+                                    // payloads where the radix passes would have, and the consistent_* kernels go on from there
 };
 
 constexpr int kStreamBlocksMax = 1024;                 // upper bound on the grid of the streaming kernels
@@ -311,7 +313,7 @@ constexpr uint32_t kSawFall = 1u, kSawLongTie = 2u;
 constexpr int kTieReach = 32;
 constexpr int kCountLds = 16384;
 constexpr int kCountPrivate = kCountLds / kScanThreads;    // up to 16 queues: one counter column per thread
-// MODE: PARD_ORDER_LBF or PARD_ORDER_HBF when every stage orders that way, nothing is dropped consistently and
+// MODE: PARD_ORDER_LBF or PARD_ORDER_HBF when every stage orders that way and
 // there are at most kPartialSegs queues (then the order of the deadlines is watched); -1 otherwise.
 template <int MODE>
 __global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
@@ -508,7 +510,8 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     // Requests in deadline order: the queues are a stable split by stage, done by split_kernel; the radix passes, the
     // epilogue and the unpacking then find nothing to do (passes = 0).
     const bool hbf = P.uniform_mode == PARD_ORDER_HBF;
-    const bool split = A.n > 0 && !A.consistent && few && !(seen & kSawFall) && !(hbf && (seen & kSawLongTie));
+    const bool in_order = A.n > 0 && few && !(seen & kSawFall) && !(hbf && (seen & kSawLongTie));
+    const bool split = in_order && !A.consistent, presplit = in_order && A.consistent;
     if (tid == 0) {
         uint32_t inv_min = mm[0][0], max_key = mm[1][0];
         for (int w = 1; w < 16; ++w) {
@@ -524,10 +527,11 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
         A.params->max_key = max_key;
         A.params->kb = kb;
         A.params->total_bits = total;
-        A.params->passes = split ? 0u : (passes < 1 ? 1u : passes);
+        A.params->passes = (split || presplit) ? 0u : (passes < 1 ? 1u : passes);
         A.params->split = split ? 1u : 0u;
+        A.params->presplit = presplit ? 1u : 0u;
     }
-    if (split) {
+    if (split || presplit) {
         // a snapshot beyond the promised bound is flagged as the radix passes would flag it (their payload word
         // holds idx_bits of index); the split itself has no such limit
         for (int u = tid; u < P.K; u += 1024) {
@@ -1441,9 +1445,11 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
 constexpr uint32_t kFieldBits = 10, kFieldMask = (1u << kFieldBits) - 1u;
 constexpr uint32_t kNoWord = 31;
 
-template <bool HBF>
+// CONS (sequentially consistent dropping): nothing is decided here; the sort key and payload of every request go
+// to its queue slot in the buffers the consistent_* kernels read (those of an odd last pass: no pass has run).
+template <bool HBF, bool CONS>
 __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
-    if (!A.params->split) return;
+    if (!(CONS ? A.params->presplit : A.params->split)) return;
     __shared__ EpiSeg tab[kPartialSegs];
     __shared__ __align__(16) uint32_t halo_key[HBF ? kSplitThreads / kWave : 1][HBF ? kHaloSpan : 4];
     __shared__ __align__(16) uint8_t halo_seg[HBF ? kSplitThreads / kWave : 1][HBF ? kHaloSpan : 16];
@@ -1470,6 +1476,8 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
     const bool vec = arrays_vectorizable(A);
     const bool vec_out = ((reinterpret_cast<uintptr_t>(A.est) & 15) | (reinterpret_cast<uintptr_t>(A.drop) & 3)) == 0;
     const int32_t bound = snapshot_bound(A, lane);
+    const uint32_t umin = ~A.params->inv_min;
+    const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     int64_t first, last;
     wave_range(A.n, blocks, block, wave, first, last);
     __syncthreads();
@@ -1612,10 +1620,19 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                     const uint32_t after = near_after[i] + ((uint32_t)(ties_after >> (8 * i)) & 0xFFu);
                     pos = (uint32_t)q.len - 1u - j[i] - after + before;
                 }
+                if constexpr (CONS) {
+                    const int64_t slot = (int64_t)q.start + pos;
+                    if (slot < A.n) {
+                        A.key[1][slot] = uk - umin;
+                        A.pay[1][slot] = ((uint32_t)(r - (int64_t)q.first) & idx_mask) | (A.idx_bits < 32 ? seg[i] << A.idx_bits : 0u);
+                    }
+                    continue;
+                }
                 const uint64_t e64 = epilogue_estimate(q, P.lat + (int64_t)q.rec * PARD_LAT_ENTRIES, pos);
                 finish_request(e64, q.now, d, est[c], drp[c]);
                 A.order[(int64_t)q.start + pos] = (int32_t)r;
             }
+            if constexpr (CONS) continue;
             if (vec_out && r0 + 3 < A.n) {
                 // (the decisions are stored normally: the streamed compaction gathers them right afterwards)
                 stream_store(reinterpret_cast<int4*>(A.est + r0), make_int4(est[0], est[1], est[2], est[3]));
@@ -2092,16 +2109,19 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     if (sb < 1) sb = 1;
     D.stream_blocks = sb;
     // the split below may finish the call: then the count also watches the order of the deadlines
-    const bool may_split = a.n > 0 && !a.consistent && (int64_t)a.plan.K * a.plan.S <= kPartialSegs;
+    const bool may_split = a.n > 0 && (int64_t)a.plan.K * a.plan.S <= kPartialSegs;
     if (may_split && a.plan.uniform_mode == PARD_ORDER_LBF) count_kernel<PARD_ORDER_LBF><<<sb, kScanThreads, 0, stream>>>(D);
     else if (may_split && a.plan.uniform_mode == PARD_ORDER_HBF) count_kernel<PARD_ORDER_HBF><<<sb, kScanThreads, 0, stream>>>(D);
     else count_kernel<-1><<<sb, kScanThreads, 0, stream>>>(D);
     setup_kernel<<<1, 1024, 0, stream>>>(D);
     if (a.n > 0) {
         // finishes the call when the requests come in deadline order; everything below then finds nothing to do
-        if (!a.consistent && (int64_t)a.plan.K * a.plan.S <= kPartialSegs) {
-            if (a.plan.uniform_mode == PARD_ORDER_HBF) split_kernel<true><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
-            else if (a.plan.uniform_mode == PARD_ORDER_LBF) split_kernel<false><<<sb * kSplitPerCount, kSplitThreads, 0, stream>>>(D);
+        if (may_split) {
+            const unsigned sg = (unsigned)(sb * kSplitPerCount);
+            if (a.plan.uniform_mode == PARD_ORDER_HBF && a.consistent) split_kernel<true, true><<<sg, kSplitThreads, 0, stream>>>(D);
+            else if (a.plan.uniform_mode == PARD_ORDER_HBF) split_kernel<true, false><<<sg, kSplitThreads, 0, stream>>>(D);
+            else if (a.plan.uniform_mode == PARD_ORDER_LBF && a.consistent) split_kernel<false, true><<<sg, kSplitThreads, 0, stream>>>(D);
+            else if (a.plan.uniform_mode == PARD_ORDER_LBF) split_kernel<false, false><<<sg, kSplitThreads, 0, stream>>>(D);
         }
         auto radix_pass = [&](auto items_tag, int p) {
             constexpr int ITEMS = decltype(items_tag)::value;

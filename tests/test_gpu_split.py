@@ -23,12 +23,12 @@ def gpu():
     return binding
 
 
-def check(gpu, oracle_mod, w, max_snap=FORCE_SORT, sub=None, threads=8):
+def check(gpu, oracle_mod, w, max_snap=FORCE_SORT, sub=None, threads=8, consistent=False):
     import torch
-    print(f"case {w.name} n={w.n} K={w.K} S={w.S} max_snap={max_snap}", flush=True)
-    ref = oracle_mod.run(w, threads=threads, sub=sub)
+    print(f"case {w.name} n={w.n} K={w.K} S={w.S} max_snap={max_snap} consistent={consistent}", flush=True)
+    ref = oracle_mod.run(w, threads=threads, sub=sub, consistent=consistent)
     s = gpu.Session(w, max_snapshot_requests=max(max_snap, w.max_snapshot_requests))
-    s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev))
+    s.run(sub=None if sub is None else torch.from_numpy(sub).to(s.dev), consistent=consistent)
     got = s.results()
     for k in KEYS:
         if not np.array_equal(got[k], ref[k]):
@@ -51,6 +51,9 @@ def test_configurations_in_arrival_order(gpu, oracle_mod, cfg, n, mode):
         w.lat_us[:] = np.maximum(1, w.lat_us // 400)
         _, ref = check(gpu, oracle_mod, w)
         assert 0 < ref["drop"].mean() < 1
+        # sequentially consistent dropping on the same queues: the split then only orders them
+        _, cons = check(gpu, oracle_mod, w, consistent=True)
+        assert 0 < cons["drop"].mean() < 1
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -66,6 +69,8 @@ def test_random_plans_in_deadline_order(gpu, oracle_mod, seed):
     check(gpu, oracle_mod, w)
     sub = np.random.default_rng(seed).integers(0, 60_000, size=w.K * w.S).astype(np.int64)
     check(gpu, oracle_mod, w, sub=sub)
+    check(gpu, oracle_mod, w, consistent=True)
+    check(gpu, oracle_mod, w, sub=sub // 8, consistent=True)
 
 
 def test_runs_of_equal_deadlines(gpu, oracle_mod):
@@ -84,6 +89,7 @@ def test_runs_of_equal_deadlines(gpu, oracle_mod):
         w.lat_us[:] = np.maximum(1, w.lat_us // 2000)
         _, ref = check(gpu, oracle_mod, w)
         assert 0 < ref["drop"].mean() < 1
+        check(gpu, oracle_mod, w, consistent=True)
 
 
 def test_one_falling_pair_takes_the_radix_passes(gpu, oracle_mod):
@@ -101,6 +107,7 @@ def test_extremes_in_deadline_order(gpu, oracle_mod):
     w.stage[::11] = -7
     w.stage[5::13] = 1000
     check(gpu, oracle_mod, w)
+    check(gpu, oracle_mod, w, consistent=True)
     w.now[:] = INT32_MAX
     check(gpu, oracle_mod, w)
     w.now[:] = -(2**31)
