@@ -125,9 +125,9 @@ int pard_plan_info(const pard_plan_t* plan, int64_t* total_paths, int32_t* max_p
  * max_requests requests in total and up to max_snapshot_requests in any one snapshot
  * (pass max_requests when unknown).  The workspace must be 256-byte aligned.  Its first
  * 32-bit word accumulates status bits (bit 0: a snapshot was larger than promised and was
- * truncated; bit 1: an internal wait between workgroups timed out and the outputs of that
- * call are invalid); the caller zero-fills the workspace once after allocating it and may
- * copy the word back at any time.
+ * truncated; no other bit is in use: no kernel of this library waits for another workgroup);
+ * the caller zero-fills the workspace once after allocating it and may copy the word back at
+ * any time.
  */
 int pard_workspace_bytes(const pard_plan_t* plan, int64_t max_requests,
                          int64_t max_snapshot_requests, int64_t* bytes);
@@ -206,16 +206,8 @@ int pard_estimate_drop_static(const pard_plan_t* plan, int64_t n, int64_t max_sn
  *                          such a bound can hold (the bound rounded up to 4096 or 8192)
  *                          raises bit 0 of the status word; the outputs are then unspecified
  *                          (never out of bounds)
- *                          Where the queues are compacted as one stream, the kernel's workgroups
- *                          (as many as the device holds at once, counted when the plan was made)
- *                          hand tile offsets to each other and wait for them: such a call must have
- *                          the device's compute units to itself while it runs - no second such call,
- *                          and no other kernel that occupies them, on another stream at the same
- *                          time.  A wait that does not end (the grid was not resident as a whole)
- *                          gives up after a bounded number of polls, every kernel still runs to its
- *                          end, bit 1 of the status word is raised and d_surv_idx / d_surv_ptr of that
- *                          call are invalid (never out of bounds).  The per-snapshot form has no
- *                          such waits.
+ *                          Neither form makes a workgroup wait for another one: like every call
+ *                          here it may share the device with other work on other streams.
  *   d_order, d_seg_ptr     as written by pard_estimate_drop
  *   d_drop                 device uint8[n], request order; zero = keep, anything else = drop
  *   d_surv_idx             device out int32[n] (capacity): d_order with dropped requests

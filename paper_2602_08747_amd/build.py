@@ -11,9 +11,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libpard.so")
-# the same library with the streamed compaction's waits cut to a few polls: for the test of their give-up path
-SPINTEST_LIB_PATH = os.path.join(HERE, "libpard_spintest.so")
-SPINTEST_DEFINE = "-DPARD_COMPACT_SPIN_LIMIT=2u"
 HASH_PATH = os.path.join(HERE, "libpard.srchash")
 SOURCES = ["pard_api.hip", "pard_fused.hip", "pard_presorted.hip", "pard_sort.hip", "pard_compact.hip", "pard_planner.hip", "pard_ranked.hip", "pard_reactive.hip", "pard_wave.hip"]
 HEADERS = ["pard_host.hpp", "pard_device.hpp"]
@@ -93,17 +90,6 @@ def build_library(verbose: bool = False, jobs: int = 8, incremental: bool = Fals
     if res.returncode != 0:
         raise RuntimeError("linking libpard.so failed:\n" + _filtered(res.stdout))
     os.replace(tmp, LIB_PATH)
-    # test build: only the compaction source differs
-    spin_obj = os.path.join(OBJ_DIR, "pard_compact_spintest.o")
-    res = subprocess.run([_hipcc(), *compile_flags(), SPINTEST_DEFINE, "-c", os.path.join(CSRC, "pard_compact.hip"), "-o", spin_obj],
-                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode == 0:
-        objs = [spin_obj if os.path.basename(obj) == "pard_compact.o" else obj for _, obj, _, _ in results]
-        res = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", SPINTEST_LIB_PATH + ".tmp"],
-                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("building the spin-limit test library failed:\n" + _filtered(res.stdout))
-    os.replace(SPINTEST_LIB_PATH + ".tmp", SPINTEST_LIB_PATH)
     with open(HASH_PATH, "w") as f:
         f.write(digest + "\n")
     if verbose and log.strip():

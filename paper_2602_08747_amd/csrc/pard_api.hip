@@ -14,7 +14,6 @@ struct pard_plan {
     uint32_t* drawn = nullptr; // inside blob: scratch of pard_sub_latency, PARD_MAX_WAIT_SAMPLES * S words
     int device = 0;
     int num_cus = 1;
-    int compact_resident = 1;  // co-resident workgroups of the look-back kernels on this device
 };
 
 namespace {
@@ -150,7 +149,6 @@ int pard_plan_create(pard_plan_t** out, const pard_plan_desc_t* desc) {
             p->num_cus = prop.multiProcessorCount;
         else
             (void)hipGetLastError();
-        p->compact_resident = p->num_cus * compact_blocks_per_cu();
     }
     PlanDev& d = p->dev;
     d.K = h.K; d.S = h.S; d.shared = h.shared; d.any_fcfs = h.any_fcfs ? 1 : 0;
@@ -317,7 +315,6 @@ int pard_estimate_drop_compact(const pard_plan_t* plan, int64_t n, int64_t max_s
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
     a.status = static_cast<uint32_t*>(d_workspace);
     a.workspace = region;
-    a.resident_blocks = plan->compact_resident;
     a.kept = reinterpret_cast<const uint32_t*>(region);
     a.loc_ptr = reinterpret_cast<const int32_t*>(stage);
     a.staged = reinterpret_cast<const int32_t*>(stage + align256((int64_t)plan->host.K * plan->host.S * 4));
@@ -484,7 +481,6 @@ int pard_compact(const pard_plan_t* plan, int64_t n, int64_t max_snapshot_reques
     a.surv_idx = d_surv_idx; a.surv_ptr = d_surv_ptr;
     a.status = static_cast<uint32_t*>(d_workspace);
     a.workspace = static_cast<char*>(d_workspace) + kHeaderBytes + marks_bytes(plan);
-    a.resident_blocks = plan->compact_resident;
     hipError_t e = launch_compact(a, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? PARD_OK : PARD_E_HIP;
 }

@@ -4,33 +4,20 @@
 // keep[j] = !drop[order[j]] for every queue slot j; surv_idx is order filtered by keep;
 // surv_ptr[g] = number of kept slots before queue g starts.
 //
-// Two paths.  Snapshots that fit one workgroup are compacted one per workgroup with no
-// dependency between workgroups (second half of this file).  Anything larger is compacted as
-// one stream of tiles:
-//
-// One pass over the data.  A workgroup counts the kept slots of a tile of 4096 queue slots,
-// publishes the count, and receives the number of kept slots in all earlier tiles from a
-// scan service: one wave of a helper workgroup walks the tile counts in order (64 tiles per
-// load, eight loads in flight, running total in a register) and hands each tile its offset
-// as soon as the tiles up to it have published.  A waiting tile polls one word.  (A
-// look-back in which every waiting tile re-reads a window of predecessor words floods the
-// memory fabric with polling traffic when ~1500 tiles are resident.)
-//
-// A workgroup does not wait for the offset of the tile it has just counted: it parks that
-// tile's survivors in LDS, counts its next tile, and only then collects the offset and
-// writes the parked survivors out as one contiguous run.  The scan service therefore has a
-// whole tile's processing time to answer before anybody stalls on it.
-//
-// Tile order: a tile must only wait for tiles that already run.  Workgroups are persistent
-// and claim tiles from one of 16 interleaved pools (pool y owns tiles y, y+16, y+32, ... and
-// hands them out in increasing order through its own counter; a workgroup uses pool
-// blockIdx % 16).  The lowest tile without a published count is then either claimed (its
-// owner publishes it after at most finishing an earlier tile, whose offset is available) or
-// next in line in a pool whose workgroups only hold earlier tiles, so every wait ends as
-// long as the grid fits on the device.  A single ticket counter would give the same order,
-// but atomics on one address cost ~11 ns each here (~95 us for 8192 tiles); 16 counters on
-// separate cache lines run in parallel.  The first workgroup of pool 0 to arrive becomes the
-// helper.
+// Two paths.  Snapshots that fit one workgroup are compacted one per workgroup (second half of this
+// file).  Anything larger is compacted as one stream of tiles of 4096 queue slots in three steps, none of
+// which waits for another workgroup:
+//   count   every tile looks its slots' decisions up and leaves the keep flags by slot (four to a byte) and
+//           its number of kept slots
+//   (scan)  beyond 4096 tiles one workgroup turns the counts into offsets; up to there every workgroup of
+//           the last step adds up the counts before its tile itself
+//   write   every tile reads its keep flags, loads the request ids of the groups of four slots that keep
+//           somebody, and writes its survivors as one contiguous run, together with the offsets of the queues
+//           that start inside it.
+// (An earlier one-pass form, in which persistent workgroups published their counts and a scan wave handed out
+// the offsets, needed every workgroup resident at once to be sure that its bounded waits end; this form costs
+// a second read of the kept slots' ids and nothing else: 16.8 million slots 45 -> 41 us, 8.4 million in
+// snapshots of 64 requests 42 -> 32 us, 33.5 million in snapshots of 1024 88 -> 95 us.)
 #include <type_traits>
 
 #include "pard_device.hpp"
@@ -43,17 +30,6 @@ constexpr int kCThreads = 256;
 constexpr int kCItems = 16;
 constexpr int kCTile = kCThreads * kCItems;            // 4096 queue slots per tile
 constexpr int kCWaves = kCThreads / kWave;
-constexpr uint32_t kFlagReady = 1u << 31;              // word has been published
-constexpr uint32_t kValueMask = (1u << 30) - 1;
-// Polls a waiting workgroup makes before it gives up (status bit 1).  A test build of the library sets it to a
-// handful, so that the give-up path can be exercised from the host with every kernel still running to its end.
-#ifndef PARD_COMPACT_SPIN_LIMIT
-#define PARD_COMPACT_SPIN_LIMIT (1u << 22)
-#endif
-constexpr uint32_t kSpinLimit = PARD_COMPACT_SPIN_LIMIT;
-constexpr int kPools = 16;                             // tile pools (see above)
-constexpr int kLook = 8;                               // groups of 64 tile counts the scan service requests per step
-constexpr int kPoolStride = 64;                        // counters 256 bytes apart
 constexpr int kStageLds = 2 * kCTile + 256;            // bytes of LDS that stage a tile's slice of drop[]
 constexpr int kStageBytes = kStageLds - 32;            // widest request-id range staged in LDS
 constexpr int kStageChunks = (kStageLds / 16 + kCThreads - 1) / kCThreads;   // 16-byte chunks per thread
@@ -65,115 +41,16 @@ struct TileInfo {
     int32_t g0, g1;     // queues g0 <= g < g1 start in this tile (their offsets are its to write)
 };
 
-// Zeroes the counters and tile words and tabulates TileInfo for every tile.
-//
 // Queue g = u * S + s holds requests of snapshot u only, and the requests of snapshot u are
 // the ids [seg_ptr[u*S], seg_ptr[(u+1)*S]) (snapshots are contiguous in the request arrays
 // and their queues contiguous in queue order), so the snapshots a tile overlaps bound its
-// ids.  The bound is only a hint: a slot whose id falls outside it is looked up in global
-// memory instead.
+// ids.  The bound is only a hint: a slot whose id falls outside it is looked up by request id
+// instead.
 //
-// keep_bits (when given): bit r of the array says that request r is kept, 32 requests to a word.  Snapshots too
-// large to stage a tile's slice of drop[] look every slot's decision up by request id; from the byte array that
-// fetches a whole memory sector per byte (16.8 million shuffled ids: 1 GB for 16.8 MB of decisions), while the
-// packed bits of as many requests are 2 MB and stay in the L2.
-__global__ void compact_prepare_kernel(uint32_t* words, int64_t count, const int32_t* seg_ptr, int32_t num_segments,
-                                       int32_t stages, int64_t n, TileInfo* info, int64_t tiles, const uint8_t* drop,
-                                       uint32_t* keep_bits) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t j = i; j < count; j += stride) words[j] = 0;
-    if (keep_bits) {
-        const bool vec = (reinterpret_cast<uintptr_t>(drop) & 15) == 0;
-        const int64_t nwords = (n + 31) / 32;
-        for (int64_t w = i; w < nwords; w += stride) {
-            const int64_t r0 = w * 32;
-            uint32_t bits = 0;
-            if (vec && r0 + 31 < n) {
-                const uint4 a = *reinterpret_cast<const uint4*>(drop + r0), b = *reinterpret_cast<const uint4*>(drop + r0 + 16);
-                const uint32_t v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-                for (int q = 0; q < 8; ++q)
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) bits |= (uint32_t)(((v[q] >> (8 * c)) & 0xFFu) == 0u) << (4 * q + c);
-            } else {
-                for (int c = 0; c < 32; ++c)
-                    if (r0 + c < n && drop[r0 + c] == 0) bits |= 1u << c;
-            }
-            keep_bits[w] = bits;
-        }
-    }
-    for (int64_t t = i; t < tiles; t += stride) {
-        // first queue whose offset is >= the tile's first slot / >= the next tile's first slot
-        const int64_t ta = t * kCTile, tb = ta + kCTile;
-        int32_t la = 0, ha = num_segments + 1, lb = 0, hb = num_segments + 1;
-        while (la < ha || lb < hb) {
-            const int32_t ma = (int32_t)(((int64_t)la + ha) >> 1), mb = (int32_t)(((int64_t)lb + hb) >> 1);
-            const int64_t va = la < ha ? seg_ptr[ma] : 0, vb = lb < hb ? seg_ptr[mb] : 0;
-            if (la < ha) { if (va < ta) la = ma + 1; else ha = ma; }
-            if (lb < hb) { if (vb < tb) lb = mb + 1; else hb = mb; }
-        }
-        TileInfo ti;
-        ti.g0 = la;
-        ti.g1 = t + 1 == tiles ? num_segments + 1 : lb;       // the last tile also takes offsets equal to n
-        // queue holding the first slot, queue holding the last slot, their snapshots
-        int32_t x = (la <= num_segments && (int64_t)seg_ptr[la] == ta) ? la : la - 1;
-        int32_t y = lb - 1;
-        x = x < 0 ? 0 : (x > num_segments - 1 ? num_segments - 1 : x);
-        y = y < 0 ? 0 : (y > num_segments - 1 ? num_segments - 1 : y);
-        const int64_t lo = seg_ptr[(x / stages) * stages], hi = seg_ptr[(y / stages + 1) * stages];
-        const bool ok = lo >= 0 && hi > lo && hi <= n && hi - lo <= kStageBytes;
-        ti.id_lo = ok ? (int32_t)lo : 0;
-        ti.id_span = ok ? (int32_t)(hi - lo) : 0;
-        info[t] = ti;
-    }
-}
-
-// The scan service (one wave).  state[t] = ready | kept slots of tile t, written by the tile;
-// prefix[t] = ready | kept slots of tiles 0..t-1, written here.
-__device__ __forceinline__ void compact_scan_service(const uint32_t* state, uint32_t* prefix, int64_t tiles,
-                                                     int lane, uint32_t* status_word) {
-    int64_t base = 0;
-    uint32_t running = 0, idle = 0;
-    while (base < tiles) {
-        uint32_t v[kLook];
-#pragma unroll
-        for (int c = 0; c < kLook; ++c) {
-            const int64_t t = base + 64 * c + lane;
-            const uint32_t x = __hip_atomic_load(state + (t < tiles ? t : tiles - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            v[c] = t < tiles ? x : kFlagReady;                   // past the end: nothing to add
-        }
-        int processed = 0;
-        bool go = true;
-#pragma unroll
-        for (int c = 0; c < kLook; ++c) {
-            if (!go) continue;
-            const unsigned long long ready = __ballot((v[c] & kFlagReady) != 0);
-            const int nready = ready == ~0ull ? 64 : __ffsll((long long)~ready) - 1;   // leading published tiles
-            const uint32_t val = lane < nready ? (v[c] & kValueMask) : 0u;
-            uint32_t inc = val;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const uint32_t t = __shfl_up(inc, off);
-                if (lane >= off) inc += t;
-            }
-            const int64_t t = base + 64 * c + lane;
-            if (lane < nready && t < tiles)
-                __hip_atomic_store(prefix + t, kFlagReady | ((running + inc - val) & kValueMask), __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            running += __shfl(inc, 63);
-            processed += nready;
-            if (nready < 64) go = false;
-        }
-        base += processed;
-        if (processed == 0) {
-            if (++idle > kSpinLimit) { if (lane == 0) atomicOr(status_word, kStatusLookbackTimeout); return; }
-            __builtin_amdgcn_s_sleep(2);
-        } else {
-            idle = 0;
-        }
-    }
-}
+// Lookups by request id: from the byte array such a lookup fetches a whole memory sector per byte (16.8
+// million shuffled ids: 1 GB for 16.8 MB of decisions), so when the promised snapshot bound is above what a
+// tile can stage, the decisions are first packed into keep bits (bit r of the array: request r is kept; 2 MB
+// for as many requests, which stay in the L2) and the lookups read those.
 
 // 16 queue slots per thread: wave w owns slots [w*1024, (w+1)*1024) of the tile, load k covers
 // 256 of them, 4 consecutive slots per lane.  Slots past the end of the data read as -1.
@@ -197,94 +74,86 @@ __global__ void compact_empty_kernel(int32_t* surv_ptr, int32_t num_segments) {
     for (int g = blockIdx.x * blockDim.x + threadIdx.x; g <= num_segments; g += gridDim.x * blockDim.x) surv_ptr[g] = 0;
 }
 
-struct CompactLds {
-    int32_t surv[kCTile + kWave];       // survivors of the tile counted last, parked until written out; + one dump word per lane
-    uint32_t group[kCTile / 4];         // same tile, per group of 4 slots: kept slots of the tile before it | keep bits << 13
-    __align__(16) uint8_t drop[kStageLds];   // the current tile's slice of drop[]
-    uint32_t wave_tot[kCWaves];
-    uint32_t excl;
-    int64_t tile;
-};
-
-// Writes out the parked tile: survivors as one contiguous run at the tile's global offset, and
-// the offsets of the queues that start inside it.
-__device__ __forceinline__ void write_parked_tile(const CompactArgs& A, CompactLds& L, const uint32_t* tile_prefix,
-                                                  int64_t ptile, uint32_t ptotal, int32_t g0, int32_t g1, int tid,
-                                                  uint32_t* status_word) {
-    const int64_t pbase = ptile * kCTile;
-    const int64_t pleft = A.n - pbase;
-    const int pvalid = (int)(pleft < kCTile ? pleft : kCTile);
-    if (tid == 0) {
-        uint32_t pv, spins = 0;
-        while (!((pv = __hip_atomic_load(&tile_prefix[ptile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) & kFlagReady)) {
-            if (++spins > kSpinLimit) { atomicOr(status_word, kStatusLookbackTimeout); break; }
-            __builtin_amdgcn_s_sleep(2);
-        }
-        L.excl = pv & kValueMask;
+// ---- the stream of tiles: count, (scan), write ------------------------------------------------------------
+// Smallest g in [0, count] with seg_ptr[g] >= x (count when there is none); seg_ptr never falls.  All 64 lanes of a
+// wave call this with the same arguments: every round they probe 64 evenly spaced entries at once.
+__device__ __forceinline__ int first_at_least_wave(const int32_t* seg_ptr, int count, int64_t x, int lane) {
+    int lo = 0, hi = count;                      // entries before lo are below x, entries from hi on are not
+    while (lo < hi) {
+        const int step = (hi - lo + kWave - 1) / kWave;
+        const int probe = lo + (lane + 1) * step - 1;
+        const bool below = probe < hi && (int64_t)seg_ptr[probe] < x;
+        const int cnt = __popcll(__ballot(below));          // these lanes are a prefix
+        const int old = lo;
+        lo = old + cnt * step;
+        const int stop = old + (cnt + 1) * step - 1;        // the first probe that was not below x
+        if (stop < hi) hi = stop;
+        if (lo > hi) lo = hi;
     }
-    __syncthreads();
-    const uint32_t off0 = L.excl;
-    for (uint32_t j = tid; j < ptotal; j += kCThreads) A.surv_idx[off0 + j] = L.surv[j];
-    for (int32_t g = g0 + tid; g < g1; g += kCThreads) {
-        int64_t p = (int64_t)A.seg_ptr[g] - pbase;
-        if (p < 0) p = 0;
-        uint32_t before = ptotal;
-        if (p < pvalid) {
-            const uint32_t v = L.group[p >> 2];
-            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
+    return lo;
+}
+
+// TileInfo of tile t, computed by a wave.
+__device__ __forceinline__ TileInfo tile_info_wave(const int32_t* seg_ptr, int32_t num_segments, int32_t stages, int64_t n,
+                                                   int64_t t, int64_t tiles, int lane) {
+    const int64_t ta = t * kCTile, tb = ta + kCTile;
+    const int la = first_at_least_wave(seg_ptr, num_segments + 1, ta, lane);
+    const int lb = first_at_least_wave(seg_ptr, num_segments + 1, tb, lane);
+    TileInfo ti;
+    ti.g0 = la;
+    ti.g1 = t + 1 == tiles ? num_segments + 1 : lb;           // the last tile also takes offsets equal to n
+    int32_t x = (la <= num_segments && (int64_t)seg_ptr[la] == ta) ? la : la - 1;
+    int32_t y = lb - 1;
+    x = x < 0 ? 0 : (x > num_segments - 1 ? num_segments - 1 : x);
+    y = y < 0 ? 0 : (y > num_segments - 1 ? num_segments - 1 : y);
+    const int64_t lo = seg_ptr[(x / stages) * stages], hi = seg_ptr[(y / stages + 1) * stages];
+    const bool ok = lo >= 0 && hi > lo && hi <= n && hi - lo <= kStageBytes;
+    ti.id_lo = ok ? (int32_t)lo : 0;
+    ti.id_span = ok ? (int32_t)(hi - lo) : 0;
+    return ti;
+}
+
+// Packs the decisions into keep bits.
+__global__ void compact_pack_kernel(const uint8_t* drop, int64_t n, uint32_t* keep_bits) {
+    const bool vec = (reinterpret_cast<uintptr_t>(drop) & 15) == 0;
+    const int64_t nwords = (n + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; w < nwords; w += stride) {
+        const int64_t r0 = w * 32;
+        uint32_t bits = 0;
+        if (vec && r0 + 31 < n) {
+            const uint4 a = *reinterpret_cast<const uint4*>(drop + r0), b = *reinterpret_cast<const uint4*>(drop + r0 + 16);
+            const uint32_t v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) bits |= (uint32_t)(((v[q] >> (8 * c)) & 0xFFu) == 0u) << (4 * q + c);
+        } else {
+            for (int c = 0; c < 32; ++c)
+                if (r0 + c < n && drop[r0 + c] == 0) bits |= 1u << c;
         }
-        A.surv_ptr[g] = (int32_t)(off0 + before);
+        keep_bits[w] = bits;
     }
 }
 
-// tile_state[0..tiles), tile_prefix[0..tiles): see the scan service; pool_ctr[y * kPoolStride]: next tile of
-// pool y; pool_ctr[kPools * kPoolStride]: arrival counter that elects the helper.  All zero at launch.
-//
-// drop[] is indexed by request id.  When the tile's id range is known and narrow (TileInfo),
-// drop[id_lo .. id_lo + id_span) is fetched with coalesced 16-byte loads, at the same time as
-// the tile's slots, and the per-slot lookups become LDS reads; otherwise every slot costs a
-// global byte load.
-//
-// Per tile: count it, publish the count, and only then collect the offset of the tile counted
-// one round earlier and write that one out, so the scan service has had a whole round to
-// answer.
-__global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, uint32_t* tile_state, uint32_t* tile_prefix,
-                                                            uint32_t* pool_ctr, const TileInfo* info, int64_t tiles,
-                                                            int pools, uint32_t* status_word, const uint32_t* keep_bits) {
-    __shared__ CompactLds L;
+// First kernel: the keep flags of every slot of a tile (four to a byte, laid out as the loads of load_tile_ids are)
+// and the tile's number of kept slots.
+__global__ __launch_bounds__(kCThreads) void compact_count_kernel(CompactArgs A, TileInfo* info, uint32_t* tile_count,
+                                                                  uint8_t* slot_keep, const uint32_t* keep_bits, int64_t tiles) {
+    __shared__ __align__(16) uint8_t drop_l[kStageLds];
+    __shared__ uint32_t wave_tot[kCWaves];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int pool = (int)(blockIdx.x % (unsigned)pools);
-    if (pool == 0) {                    // the first workgroup of pool 0 to arrive runs the scan service
-        if (tid == 0) L.excl = atomicAdd(&pool_ctr[kPools * kPoolStride], 1u);
-        __syncthreads();
-        const bool helper = L.excl == 0;
-        __syncthreads();
-        if (helper) {
-            if (wave == 0) compact_scan_service(tile_state, tile_prefix, tiles, lane, status_word);
-            return;
-        }
-    }
-    const bool vec = ((reinterpret_cast<uintptr_t>(A.order) | reinterpret_cast<uintptr_t>(A.surv_idx)) & 15) == 0;
+    const int64_t tile = blockIdx.x;
+    const TileInfo ti = tile_info_wave(A.seg_ptr, A.num_segments, A.stages, A.n, tile, tiles, lane);
+    if (tid == 0) info[tile] = ti;
+    const bool vec = (reinterpret_cast<uintptr_t>(A.order) & 15) == 0;
     const uintptr_t drop_addr = reinterpret_cast<uintptr_t>(A.drop);
     const uintptr_t end_addr = drop_addr + (uintptr_t)A.n;
-
-    if (tid == 0) L.tile = (int64_t)atomicAdd(&pool_ctr[pool * kPoolStride], 1u) * pools + pool;
-    __syncthreads();
-    int64_t tile = L.tile;
-    int64_t prev_tile = -1;             // counted and parked, not yet written out
-    uint32_t prev_total = 0;
-    int32_t prev_g0 = 0, prev_g1 = 0;
-
-    while (tile < tiles) {
-    const int32_t tile_u = __builtin_amdgcn_readfirstlane((int32_t)tile);     // same in every lane: scalar loads below
-    const TileInfo ti = info[tile_u];
-    const int64_t base = (int64_t)tile_u * kCTile;
+    const int64_t base = tile * kCTile;
     const int64_t left = A.n - base;
     const int valid = (int)(left < kCTile ? left : kCTile);
     int32_t ids[4][4];
     load_tile_ids(A, base, valid, vec, wave, lane, ids);
-    uint32_t next_ticket = 0;
-    if (tid == 0) next_ticket = atomicAdd(&pool_ctr[pool * kPoolStride], 1u);
     const bool staged = ti.id_span > 0;
     uint32_t delta = 0;
     if (staged) {
@@ -318,14 +187,12 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
 #pragma unroll
         for (int q = 0; q < kStageChunks; ++q) {
             const uint32_t c = (uint32_t)(q * kCThreads + tid);
-            if (c < chunks) *reinterpret_cast<uint4*>(L.drop + 16u * c) = chunk[q];
+            if (c < chunks) *reinterpret_cast<uint4*>(drop_l + 16u * c) = chunk[q];
         }
     }
     __syncthreads();
-
-    // ---- count this tile ----
     uint32_t keep[4];
-    bool slow = !staged;                // some slot of this thread needs a global lookup
+    bool slow = !staged;                // some slot of this thread needs a lookup by request id
     if (staged) {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -334,7 +201,7 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
             for (int c = 0; c < 4; ++c) {
                 const uint32_t d = (uint32_t)ids[k][c] - (uint32_t)ti.id_lo;
                 const bool in = d < (uint32_t)ti.id_span;
-                const uint32_t byte = L.drop[delta + (in ? d : 0u)];
+                const uint32_t byte = drop_l[delta + (in ? d : 0u)];
                 keep[k] |= (uint32_t)(in && byte == 0) << c;
                 slow |= !in;
             }
@@ -354,9 +221,102 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
             }
         }
     }
-    // Kept slots before each of this lane's four groups inside the wave's 1024 slots: one scan
-    // for all four loads, their counts packed into bytes.  The scan runs over the counts shifted
-    // up by one lane, so every partial sum is an exclusive count (<= 252 fits a byte).
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        slot_keep[tile * (kCTile / 4) + wave * 256 + k * 64 + lane] = (uint8_t)keep[k];
+        cnt += (uint32_t)__popc(keep[k]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) cnt += __shfl_xor(cnt, off);
+    if (lane == 0) wave_tot[wave] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t total = 0;
+        for (int w = 0; w < kCWaves; ++w) total += wave_tot[w];
+        tile_count[tile] = total;
+    }
+}
+
+// Exclusive scan of the tile counts by one workgroup (only for more tiles than a workgroup of the writing kernel
+// adds up by itself).
+__global__ __launch_bounds__(1024) void compact_tile_scan_kernel(const uint32_t* tile_count, int64_t tiles, uint32_t* tile_off) {
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t carry;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) carry = 0;
+    __syncthreads();
+    for (int64_t b = 0; b < tiles; b += 1024 * 8) {
+        uint32_t v[8], sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const int64_t t = b + (int64_t)tid * 8 + i; v[i] = t < tiles ? tile_count[t] : 0u; sum += v[i]; }
+        uint32_t inc = sum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) { const uint32_t x = __shfl_up(inc, off); if (lane >= off) inc += x; }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        uint32_t run = carry + inc - sum;
+        for (int w = 0; w < wave; ++w) run += wave_tot[w];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { const int64_t t = b + (int64_t)tid * 8 + i; if (t < tiles) tile_off[t] = run; run += v[i]; }
+        __syncthreads();
+        if (tid == 1023) carry = run;
+        __syncthreads();
+    }
+}
+
+// Last kernel: a tile's survivors leave as one contiguous run at the number of kept slots in the tiles before it,
+// together with the offsets of the queues that start inside it.  Slots that were dropped are not even loaded.
+constexpr int kSelfSumTiles = kCThreads * 16;          // up to here a workgroup adds up the counts before its tile itself
+__global__ __launch_bounds__(kCThreads) void compact_write_kernel(CompactArgs A, const TileInfo* info, const uint32_t* tile_count,
+                                                                  const uint32_t* tile_off, const uint8_t* slot_keep) {
+    __shared__ int32_t surv[kCTile + kWave];           // + one dump word per lane
+    __shared__ uint32_t group[kCTile / 4];             // per group of 4 slots: kept slots of the tile before it | keep bits << 13
+    __shared__ uint32_t wave_tot[kCWaves];
+    __shared__ uint32_t wave_sum[kCWaves];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t tile = blockIdx.x;
+    const int64_t base = tile * kCTile;
+    const int64_t left = A.n - base;
+    const int valid = (int)(left < kCTile ? left : kCTile);
+    const bool vec = (reinterpret_cast<uintptr_t>(A.order) & 15) == 0;
+    // kept slots in the tiles before this one
+    uint32_t before_me = 0;
+    if (tile_off) {
+        before_me = tile_off[tile];
+    } else {
+        uint32_t part[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { const int64_t t = (int64_t)i * kCThreads + tid; part[i] = t < tile ? tile_count[t] : 0u; }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) before_me += part[i];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) before_me += __shfl_xor(before_me, off);
+        if (lane == 0) wave_sum[wave] = before_me;
+    }
+    uint32_t keep[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) keep[k] = slot_keep[tile * (kCTile / 4) + wave * 256 + k * 64 + lane];
+    // the ids of the groups with a kept slot
+    int32_t ids[4][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int e = wave * 1024 + k * 256 + lane * 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ids[k][c] = -1;
+        if (keep[k]) {
+            if (vec && e + 3 < valid) {
+                const int4 v = *reinterpret_cast<const int4*>(A.order + base + e);
+                ids[k][0] = v.x; ids[k][1] = v.y; ids[k][2] = v.z; ids[k][3] = v.w;
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) ids[k][c] = e + c < valid ? A.order[base + e + c] : -1;
+            }
+        }
+    }
+    // Kept slots before each of this lane's four groups inside the wave's 1024 slots: one scan for all four loads,
+    // their counts packed into bytes.  The scan runs over the counts shifted up by one lane, so every partial sum
+    // is an exclusive count (<= 252 fits a byte).
     const uint32_t cnt = (uint32_t)__popc(keep[0]) | ((uint32_t)__popc(keep[1]) << 8) |
                          ((uint32_t)__popc(keep[2]) << 16) | ((uint32_t)__popc(keep[3]) << 24);
     uint32_t exc = __shfl_up(cnt, 1);
@@ -367,50 +327,50 @@ __global__ __launch_bounds__(kCThreads, 5) void compact_kernel(CompactArgs A, ui
         if (lane >= off) exc += t;
     }
     const uint32_t e63 = (uint32_t)__builtin_amdgcn_readlane((int)exc, 63), c63 = (uint32_t)__builtin_amdgcn_readlane((int)cnt, 63);
-    uint32_t load_tot[4], load_before[4], wave_total = 0;
+    uint32_t load_before[4], wave_total = 0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        load_tot[k] = ((e63 >> (8 * k)) & 0xFFu) + ((c63 >> (8 * k)) & 0xFFu);
         load_before[k] = wave_total;
-        wave_total += load_tot[k];
+        wave_total += ((e63 >> (8 * k)) & 0xFFu) + ((c63 >> (8 * k)) & 0xFFu);
     }
-    if (lane == 0) L.wave_tot[wave] = wave_total;
+    if (lane == 0) wave_tot[wave] = wave_total;
     __syncthreads();
     uint32_t wave_before = 0, total = 0;
 #pragma unroll
     for (int w = 0; w < kCWaves; ++w) {
-        const uint32_t t = L.wave_tot[w];
+        const uint32_t t = wave_tot[w];
         if (w < wave) wave_before += t;
         total += t;
     }
-    if (tid == 0)
-        __hip_atomic_store(&tile_state[tile_u], kFlagReady | total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-
-    // ---- write out the tile counted in the previous round, then park this one ----
-    if (prev_tile >= 0) {
-        write_parked_tile(A, L, tile_prefix, prev_tile, prev_total, prev_g0, prev_g1, tid, status_word);
-        __syncthreads();
+    if (!tile_off) {
+        before_me = 0;
+#pragma unroll
+        for (int w = 0; w < kCWaves; ++w) before_me += wave_sum[w];
     }
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint32_t o = wave_before + load_before[k] + ((exc >> (8 * k)) & 0xFFu);
-        L.group[wave * 256 + k * 64 + lane] = o | (keep[k] << 13);
+        group[wave * 256 + k * 64 + lane] = o | (keep[k] << 13);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const bool kept = (keep[k] >> c) & 1u;
             const uint32_t at = kept ? o + (uint32_t)__popc(keep[k] & ((1u << c) - 1u)) : (uint32_t)(kCTile + lane);
-            L.surv[at] = ids[k][c];
+            surv[at] = ids[k][c];
         }
     }
-    if (tid == 0) L.tile = (int64_t)next_ticket * pools + pool;
     __syncthreads();
-    prev_tile = tile_u;
-    prev_total = total;
-    prev_g0 = ti.g0;
-    prev_g1 = ti.g1;
-    tile = L.tile;
+    for (uint32_t j = tid; j < total; j += kCThreads) A.surv_idx[before_me + j] = surv[j];
+    const TileInfo ti = info[tile];
+    for (int32_t g = ti.g0 + tid; g < ti.g1; g += kCThreads) {
+        int64_t p = (int64_t)A.seg_ptr[g] - base;
+        if (p < 0) p = 0;
+        uint32_t before = total;
+        if (p < valid) {
+            const uint32_t v = group[p >> 2];
+            before = (v & 0x1FFFu) + (uint32_t)__popc((v >> 13) & ((1u << (p & 3)) - 1u));
+        }
+        A.surv_ptr[g] = (int32_t)(before_me + before);
     }
-    if (prev_tile >= 0) write_parked_tile(A, L, tile_prefix, prev_tile, prev_total, prev_g0, prev_g1, tid, status_word);
 }
 
 // =====================================================================================
@@ -699,20 +659,12 @@ bool compact_per_snapshot(int64_t max_snapshot) { return max_snapshot > kLocalMi
 
 int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots) {
     const int64_t tiles = (n + kCTile - 1) / kCTile;
-    const int64_t chain = (int64_t)(kPools + 1) * kPoolStride * 4 + 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255) +
+    const int64_t chain = 2 * (((tiles + 1) * 4 + 255) & ~(int64_t)255) +                // tile counts, tile offsets
                           (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255) +
-                          (((n + 31) / 32 * 4 + 255) & ~(int64_t)255);                   // one keep bit per request
+                          (((n + 31) / 32 * 4 + 255) & ~(int64_t)255) +                  // one keep bit per request
+                          (((tiles * (kCTile / 4)) + 255) & ~(int64_t)255);              // keep flags by queue slot, four to a byte
     const int64_t local = 2 * ((num_snapshots * 4 + 255) & ~(int64_t)255);
     return chain > local ? chain : local;
-}
-
-int compact_blocks_per_cu() {
-    int per_cu = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, compact_kernel, kCThreads, 0) != hipSuccess || per_cu < 1) {
-        (void)hipGetLastError();
-        per_cu = 1;
-    }
-    return per_cu;
 }
 
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
@@ -743,26 +695,25 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
         else run(std::integral_constant<int, 512>{}, std::integral_constant<int, 256>{});
         return hipGetLastError();
     }
-    uint32_t* pool_ctr = static_cast<uint32_t*>(a.workspace);
+    // the stream of tiles: count, (scan), write; no workgroup waits for another
+    uint32_t* tile_count = static_cast<uint32_t*>(a.workspace);
     const int64_t row = ((tiles + 1) * 4 + 255) / 256 * 64;          // words per array, 256-byte multiple
-    uint32_t* tile_state = pool_ctr + (kPools + 1) * kPoolStride;
-    uint32_t* tile_prefix = tile_state + row;
-    TileInfo* info = reinterpret_cast<TileInfo*>(tile_prefix + row);
-    const int64_t words = (int64_t)(kPools + 1) * kPoolStride + 2 * row;
+    uint32_t* tile_off = tile_count + row;
+    TileInfo* info = reinterpret_cast<TileInfo*>(tile_off + row);
+    char* after_info = reinterpret_cast<char*>(info) + (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255);
+    uint32_t* bits = reinterpret_cast<uint32_t*>(after_info);
+    uint8_t* slot_keep = reinterpret_cast<uint8_t*>(after_info + (((a.n + 31) / 32 * 4 + 255) & ~(int64_t)255));
     // snapshots promised larger than a tile can stage: the lookups by request id read packed bits
-    uint32_t* keep_bits = a.max_snapshot > kStageBytes
-                              ? reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(info) + (((tiles + 1) * (int64_t)sizeof(TileInfo) + 255) & ~(int64_t)255))
-                              : nullptr;
-    int64_t work = words > tiles ? words : tiles;
-    if (keep_bits && (a.n + 31) / 32 > work) work = (a.n + 31) / 32;
-    int zb = (int)((work + 255) / 256);
-    if (zb > 1024) zb = 1024;
-    compact_prepare_kernel<<<zb, 256, 0, stream>>>(pool_ctr, words, a.seg_ptr, a.num_segments, a.stages, a.n, info, tiles, a.drop, keep_bits);
-    // persistent: no more workgroups than the device holds at once, one of them the scan service
-    int64_t grid = a.resident_blocks > 2 ? a.resident_blocks : 2;
-    if (grid > tiles + 1) grid = tiles + 1;
-    const int pools = grid - 1 < kPools ? (int)(grid - 1) : kPools;       // pool 0 holds the helper and at least one worker
-    compact_kernel<<<(unsigned)grid, kCThreads, 0, stream>>>(a, tile_state, tile_prefix, pool_ctr, info, tiles, pools, a.status, keep_bits);
+    uint32_t* keep_bits = a.max_snapshot > kStageBytes ? bits : nullptr;
+    if (keep_bits) {
+        int pb = (int)(((a.n + 31) / 32 + 255) / 256);
+        if (pb > 2048) pb = 2048;
+        compact_pack_kernel<<<pb, 256, 0, stream>>>(a.drop, a.n, keep_bits);
+    }
+    compact_count_kernel<<<(unsigned)tiles, kCThreads, 0, stream>>>(a, info, tile_count, slot_keep, keep_bits, tiles);
+    const bool scan = tiles > kSelfSumTiles;
+    if (scan) compact_tile_scan_kernel<<<1, 1024, 0, stream>>>(tile_count, tiles, tile_off);
+    compact_write_kernel<<<(unsigned)tiles, kCThreads, 0, stream>>>(a, info, tile_count, scan ? tile_off : nullptr, slot_keep);
     return hipGetLastError();
 }
 

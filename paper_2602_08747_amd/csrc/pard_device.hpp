@@ -31,8 +31,7 @@ struct PlanDev {
 
 // Status bits a kernel may raise in the workspace's status word.
 enum : uint32_t {
-    kStatusSnapshotTooLarge = 1u,      // a snapshot exceeded the promised bound
-    kStatusLookbackTimeout = 2u        // a decoupled look-back gave up waiting
+    kStatusSnapshotTooLarge = 1u       // a snapshot exceeded the promised bound
 };
 
 __device__ __forceinline__ uint32_t magic_div_dev(uint32_t n, uint32_t m, uint32_t sh) {
@@ -208,7 +207,6 @@ struct CompactArgs {
     int32_t *surv_idx, *surv_ptr;
     uint32_t* status;
     void* workspace;
-    int32_t resident_blocks;           // workgroups of the compaction kernel the device holds at once
     // after an estimate call that counted and staged the survivors along the way (all three null otherwise):
     const uint32_t* kept;              // [K] survivors per snapshot
     const int32_t* staged;             // [n] a snapshot's survivors in queue order, from its first request's place on
@@ -217,7 +215,6 @@ struct CompactArgs {
 // True when pard_compact gives every snapshot to one workgroup for this promised bound (the form the
 // estimate kernels can prepare).
 bool compact_per_snapshot(int64_t max_snapshot);
-int compact_blocks_per_cu();
 int64_t compact_workspace_bytes(int64_t n, int64_t num_snapshots);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
 
