@@ -552,7 +552,7 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
             run += v;
         }
     }
-    __threadfence();
+    __threadfence_block();           // nothing written so far is read by another workgroup of this kernel (there is none)
     __syncthreads();
     // queue offsets: exclusive scan of the queue lengths, 1024 at a time
     for (int64_t base = 0; base < segs + 1; base += 1024) {
