@@ -63,7 +63,7 @@ constexpr int kStreamBlocksMax = 1024;                 // upper bound on the gri
 constexpr int kPartialSegs = 64;                       // up to this many queues: per-workgroup partial counts
 
 struct SortLayout {
-    int64_t params, seg_count, cfull, down, keepm, chunk_tot, ret_cursor, zero_end, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
+    int64_t params, seg_count, cfull, down, keepm, chunk_tot, ret_cursor, zero_end, zero_end_consistent, tile_hist, part_minmax, part_cnt, part_flag, wave_cnt, key[2], pay[2],
             min_lat, alive, wkept, tile_tot, range_tot, carry, total;
     int64_t tiles, chunks;
     int32_t max_passes, idx_bits, seg_bits, ret_shift, tile_items;
@@ -91,10 +91,11 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.cfull = off;      off = align256(off + segs * 8);
     L.down = off;       off = align256(off + segs * 8);
     const int64_t words = (n + 63) / 64 + 1;                     // 64 queue slots per mask word
-    L.keepm = off;      off = align256(off + words * 8);
     L.chunk_tot = off;  off = align256(off + (int64_t)L.max_passes * L.chunks * kRadix * 4);
     L.ret_cursor = off; off = align256(off + (int64_t)kRetBuckets * 4);
-    L.zero_end = off;
+    L.zero_end = off;                                            // zeroed by every call up to here,
+    L.keepm = off;      off = align256(off + words * 8);
+    L.zero_end_consistent = off;                                 // up to here under sequentially consistent dropping
     L.tile_hist = off;  off = align256(off + (int64_t)L.max_passes * L.tiles * kRadix * 4);
     L.part_minmax = off; off = align256(off + (int64_t)kStreamBlocksMax * 8);
     L.part_cnt = off;    off = align256(off + (int64_t)kStreamBlocksMax * kPartialSegs * 4);
@@ -2095,7 +2096,7 @@ bool sort_supported(int32_t K, int32_t S, int64_t n, int64_t max_snapshot) {
 hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
     const SortLayout L = make_layout(a.plan.K, a.plan.S, a.n, a.max_snapshot);
     SortDev D = make_dev(a, L);
-    const int64_t zero16 = L.zero_end / 16;
+    const int64_t zero16 = (a.consistent ? L.zero_end_consistent : L.zero_end) / 16;
     int zb = (int)((zero16 + 255) / 256);
     if (zb > 4096) zb = 4096;
     if (zb < 1) zb = 1;
