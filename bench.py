@@ -34,15 +34,16 @@ def estimate_drop_bytes_per_request(fused: bool, passes: int, fcfs: bool) -> flo
     return float(io + 16 * (passes - 1) + 8)
 
 
-def arrives_in_deadline_order(w, consistent: bool) -> bool:
-    """Whether the large-snapshot path finds the requests in deadline order and finishes with a stable split by stage
-    instead of sorting (the library decides this on the device; this is the same rule on the host, for the label and
-    the byte count of the roofline only): every stage orders by deadline the same way, at most 64 queues, no deadline
-    below its predecessor inside a snapshot, and under high budget first no long run of equal deadlines."""
+def arrives_in_deadline_order(w) -> bool:
+    """Whether the large-snapshot path finds the requests in deadline order and orders the queues with a stable split by
+    stage instead of sorting (the library decides this on the device; this is the same rule on the host, for the label
+    and the byte count of the roofline only): every stage orders by deadline the same way, at most 64 queues, no
+    deadline below its predecessor inside a snapshot, and under high budget first no long run of equal deadlines.
+    Under sequentially consistent dropping the split only orders the queues and the consistent kernels follow."""
     import numpy as np
     from paper_2602_08747_amd import workloads
     n = w.n
-    if consistent or n == 0 or w.K * w.S > 64:
+    if n == 0 or w.K * w.S > 64:
         return False
     modes = np.unique(w.order_mode)
     if len(modes) != 1 or int(modes[0]) == workloads.MODE_FCFS:
@@ -539,7 +540,7 @@ def main():
 
     # roofline of the dominant kernel
     fcfs = bool((w.order_mode == workloads.MODE_FCFS).any())
-    in_order = not fused and not args.ranked and arrives_in_deadline_order(w, args.consistent)
+    in_order = not fused and not args.ranked and arrives_in_deadline_order(w)
     if fused:
         small = s.max_snap <= 128
         kernel = ("wave_snapshot_kernel (the estimate step: one launch)" if small else
@@ -549,7 +550,8 @@ def main():
     else:
         kernel = ("pard_estimate_drop call: count_kernel (which finds the requests in deadline order), setup_kernel, "
                   "split_kernel; the radix launches that follow find nothing to do" if in_order else
-                  "pard_estimate_drop call (count, setup, histogram, radix passes, epilogue)")
+                  "pard_estimate_drop call (count, setup, histograms and radix passes, the last of which forms the results, "
+                  "and their way back to request order)")
         # The denominator for snapshots beyond the chip's LDS is the out-of-core sort model with p passes of 8 bits
         # over the key range, also when the call exploits input that is already in order and moves less: that
         # lowers the bytes moved, not the model (the 17 B/request I/O floor is reported beside it).
