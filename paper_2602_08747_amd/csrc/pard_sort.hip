@@ -998,16 +998,14 @@ __device__ __forceinline__ void epilogue_slot(const SortDev& A, const EpiSeg* ta
     const PlanDev& P = A.plan;
     const uint32_t local = pay & idx_mask;
     const uint32_t seg = A.idx_bits < 32 ? (pay >> A.idx_bits) : 0u;
-    const uint32_t k = seg % (uint32_t)P.S;
-    const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
     if (cached) {
         const EpiSeg& q = tab[seg];
         r = (uint32_t)q.first + local;
-        out = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j, key, r, umin);
+        out = epilogue_one(A, q, P.lat + (int64_t)q.rec * PARD_LAT_ENTRIES, j, key, r, umin);
     } else {
         const EpiSeg q = epilogue_segment(A, seg);
         r = (uint32_t)q.first + local;
-        out = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j, key, r, umin);
+        out = epilogue_one(A, q, P.lat + (int64_t)q.rec * PARD_LAT_ENTRIES, j, key, r, umin);
     }
 }
 
@@ -1256,23 +1254,9 @@ __global__ __launch_bounds__(kEpiThreads) void epilogue_kernel(SortDev A) {
         uint32_t r4[4], out[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const uint32_t local = p4[c] & idx_mask;
-            const uint32_t seg = A.idx_bits < 32 ? (p4[c] >> A.idx_bits) : 0u;
-            const uint32_t k = seg % (uint32_t)P.S;
-            const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
             out[c] = 0;
             r4[c] = 0;
-            if (j0 + c < A.n) {
-                if (cached) {
-                    const EpiSeg& q = tab[seg];
-                    r4[c] = (uint32_t)q.first + local;
-                    out[c] = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
-                } else {
-                    const EpiSeg q = epilogue_segment(A, seg);
-                    r4[c] = (uint32_t)q.first + local;
-                    out[c] = epilogue_one(A, q, P.lat + rec * PARD_LAT_ENTRIES, j0 + c, k4[c], r4[c], umin);
-                }
-            }
+            if (j0 + c < A.n) epilogue_slot(A, tab, cached, j0 + c, k4[c], p4[c], umin, idx_mask, r4[c], out[c]);
         }
         if (vec && j0 + 3 < A.n) {
             *reinterpret_cast<int4*>(A.order + j0) = make_int4((int32_t)r4[0], (int32_t)r4[1], (int32_t)r4[2], (int32_t)r4[3]);
@@ -1765,7 +1749,7 @@ __global__ __launch_bounds__(kConsTile) void consistent_prepare_kernel(SortDev A
             const unsigned long long dn = ((unsigned long long)q.down_hi << 32) | q.down_lo;
             f = j == (int64_t)q.start ? 1u : 0u;
             if (q.aux & kSegScan) {
-                const int64_t rec = P.shared ? (int64_t)(seg % (uint32_t)P.S) : (int64_t)seg;
+                const int64_t rec = q.rec;
                 const uint32_t i = (uint32_t)(j - (int64_t)q.start);
                 const uint32_t c = deadline == kInt32Max ? (uint32_t)q.len
                                    : positions_in_time(q, P.lat + rec * PARD_LAT_ENTRIES, (int64_t)deadline - (int64_t)q.now - (int64_t)dn);
@@ -2013,8 +1997,7 @@ __global__ __launch_bounds__(kConsTile) void consistent_finish_kernel(SortDev A)
         __syncthreads();
         if (ok) {
             const uint32_t local = pay & idx_mask;
-            const uint32_t k = seg % (uint32_t)P.S;
-            const int64_t rec = P.shared ? (int64_t)k : (int64_t)seg;
+            const int64_t rec = q.rec;
             const uint32_t i = (uint32_t)(j - (int64_t)q.start);
             uint32_t pos;
             if (scanned) {
