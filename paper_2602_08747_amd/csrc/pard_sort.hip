@@ -775,6 +775,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
     } else {
         load_tile<FIRST, ITEMS>(A, pass, tile_base, valid, wave, lane, umin, need_pay, key, pay);
     }
+    bool runs = true;                          // this wave still looks for runs of one digit (below)
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         int e = quads ? 0 : wave * (kWave * kSortItems) + i * kWave + lane;       // a full tile: every element counts
@@ -782,16 +783,20 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
         const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
         // Sorted input puts long runs of one digit into a wave, and 64 lanes adding to one LDS
         // word serialise: the two most common leading digits are counted with a ballot, the
-        // remaining lanes add for themselves.
+        // remaining lanes add for themselves.  A wave that finds its digits spread out (the leading
+        // digit shared by fewer than eight lanes) stops looking for runs: there the ballots only cost.
         unsigned long long todo = __ballot(e < valid);
+        if (runs) {
 #pragma unroll
-        for (int round = 0; round < 2; ++round) {
-            if (todo == 0ull) break;
-            const int leader = __ffsll((long long)todo) - 1;
-            const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, leader);
-            const unsigned long long same = __ballot(d == d0) & todo;
-            if (lane == leader) atomicAdd(&h[d0], (uint32_t)__popcll(same));
-            todo &= ~same;
+            for (int round = 0; round < 2; ++round) {
+                if (todo == 0ull) break;
+                const int leader = __ffsll((long long)todo) - 1;
+                const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, leader);
+                const unsigned long long same = __ballot(d == d0) & todo;
+                if (lane == leader) atomicAdd(&h[d0], (uint32_t)__popcll(same));
+                if (round == 0 && __popcll(same) < 8 && __popcll(todo) >= 32) runs = false;
+                todo &= ~same;
+            }
         }
         if ((todo >> lane) & 1ull) atomicAdd(&h[d], 1u);
     }
@@ -1147,6 +1152,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         }
     }
     __syncthreads();                                 // the tile's keys are out of LDS, the range counters are zero
+    bool range_runs = true;
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         // a snapshot larger than promised can leave ids beyond the end: they are not returned
@@ -1156,7 +1162,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         // the most common range takes its places with one add.
         unsigned long long todo = __ballot(ok);
         uint32_t place = 0;
-        if (todo != 0ull) {
+        if (todo != 0ull && range_runs) {
             const int leader = __ffsll((long long)todo) - 1;
             const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)b, leader);
             const unsigned long long same = __ballot(b == b0) & todo;
@@ -1165,6 +1171,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
             old = (uint32_t)__builtin_amdgcn_readlane((int)old, leader);
             if ((same >> lane) & 1ull)
                 place = old + __builtin_amdgcn_mbcnt_hi((uint32_t)(same >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)same, 0u));
+            if (__popcll(same) < 8 && __popcll(todo) >= 32) range_runs = false;      // spread out: stop looking for runs
             todo &= ~same;
         }
         if ((todo >> lane) & 1ull) place = atomicAdd(&first_place[b], 1u);
