@@ -1059,18 +1059,31 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         const int e = wave * (kWave * kSortItems) + i * kWave + lane;
         const bool ok = e < valid;
         const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
-        unsigned long long peers = __ballot(ok);
+        // peers: the lanes that hold the same digit, found bit by bit.  Written on 32-bit halves as
+        // peers & ~(vote ^ all) with all = every bit set when the lane's digit has bit b: one three-input
+        // bit operation per half and bit (the 64-bit select it replaces took nine vector instructions per bit,
+        // and this loop is what the kernel's time goes into).
+        const unsigned long long live = __ballot(ok);
+        uint32_t peers_lo = (uint32_t)live, peers_hi = (uint32_t)(live >> 32);
+        if (nbits == kRadixBits) {                 // (every pass but the last one)
 #pragma unroll
-        for (int b = 0; b < kRadixBits; ++b) {
-            if (b < nbits) {                       // higher bits of this digit are zero for every key
-                const bool bit = (d >> b) & 1u;
-                const unsigned long long vote = __ballot(bit);
-                peers &= bit ? vote : ~vote;
+            for (int b = 0; b < kRadixBits; ++b) {
+                const int32_t all = (int32_t)(d << (31 - b)) >> 31;
+                const unsigned long long vote = __ballot(all < 0);
+                // x & ~(y ^ z): truth table 0x90 of the three-input bit operation
+                peers_lo = __builtin_amdgcn_bitop3_b32(peers_lo, (uint32_t)vote, (uint32_t)all, 0x90);
+                peers_hi = __builtin_amdgcn_bitop3_b32(peers_hi, (uint32_t)(vote >> 32), (uint32_t)all, 0x90);
+            }
+        } else {
+            for (int b = 0; b < nbits; ++b) {      // higher bits of this digit are zero for every key
+                const uint32_t all = 0u - ((d >> b) & 1u);
+                const unsigned long long vote = __ballot(all != 0u);
+                peers_lo &= ~((uint32_t)vote ^ all);
+                peers_hi &= ~((uint32_t)(vote >> 32) ^ all);
             }
         }
-        const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(peers >> 32),
-                                    __builtin_amdgcn_mbcnt_lo((uint32_t)peers, 0u));
-        const uint32_t count = (uint32_t)__popcll(peers);
+        const uint32_t before = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
+        const uint32_t count = (uint32_t)(__popc(peers_lo) + __popc(peers_hi));
         uint32_t prev = 0;
         if (ok) {
             prev = whist[wave][d];
