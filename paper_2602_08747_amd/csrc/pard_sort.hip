@@ -628,9 +628,32 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     }
 }
 
-__device__ __forceinline__ uint32_t digit_of(uint32_t key, uint32_t seg, uint32_t kb, int pass) {
-    const uint64_t v = ((uint64_t)seg << kb) | (uint64_t)key;
-    return (uint32_t)(v >> (kRadixBits * pass)) & (kRadix - 1);
+// Digit `pass` of the virtual key  V = segment << kb | key  (key < 2^kb), without forming V: what the digit takes
+// from the key and from the segment id are two shifts each, fixed for a whole pass.
+struct DigitOf {
+    uint32_t key_shift;             // the key contributes key >> key_shift (nothing when the digit starts at or above bit 32)
+    uint32_t seg_left, seg_right;   // the segment contributes (segment << seg_left) >> seg_right
+    uint32_t idx_bits;              // the segment id sits above this many bits of the payload word
+    bool from_key, from_segment;
+};
+
+__device__ __forceinline__ DigitOf digit_plan(uint32_t kb, int pass, int idx_bits) {
+    DigitOf D;
+    const uint32_t sh = (uint32_t)(kRadixBits * pass);
+    D.from_key = sh < 32u && sh < kb;
+    D.key_shift = sh < 32u ? sh : 31u;
+    D.from_segment = sh + kRadixBits > kb && idx_bits < 32;
+    // a left shift of 8 or more leaves nothing of the segment inside the digit: 31 stands for all of them
+    D.seg_left = kb > sh ? (kb - sh < 31u ? kb - sh : 31u) : 0u;
+    D.seg_right = sh > kb ? (sh - kb < 31u ? sh - kb : 31u) : 0u;
+    D.idx_bits = idx_bits < 32 ? (uint32_t)idx_bits : 31u;
+    return D;
+}
+
+__device__ __forceinline__ uint32_t digit_of(const DigitOf& D, uint32_t key, uint32_t pay) {
+    uint32_t v = D.from_key ? key >> D.key_shift : 0u;
+    if (D.from_segment) v |= ((pay >> D.idx_bits) << D.seg_left) >> D.seg_right;
+    return v & (kRadix - 1);
 }
 
 // exclusive scan of one value per thread over the radix-pass workgroup
@@ -725,6 +748,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
     __shared__ uint32_t h[kRadix];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
+    const DigitOf dig = digit_plan(kb, pass, A.idx_bits);
     const bool need_pay = kRadixBits * (pass + 1) > (int)kb;      // the digit holds segment bits
     if (tid < kRadix) h[tid] = 0;
     __syncthreads();
@@ -780,7 +804,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void upsweep_kernel(SortDev A, int
     for (int i = 0; i < kSortItems; ++i) {
         int e = quads ? 0 : wave * (kWave * kSortItems) + i * kWave + lane;       // a full tile: every element counts
         if (key_only) { e = pay[i] ? valid : 0; pay[i] = 0; }
-        const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
+        const uint32_t d = digit_of(dig, key[i], pay[i]);
         // Sorted input puts long runs of one digit into a wave, and 64 lanes adding to one LDS
         // word serialise: the two most common leading digits are counted with a ballot, the
         // remaining lanes add for themselves.  A wave that finds its digits spread out (the leading
@@ -1031,6 +1055,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t umin = ~A.params->inv_min, kb = A.params->kb;
+    const DigitOf dig = digit_plan(kb, pass, A.idx_bits);
     // the last pass forms the results instead of writing its keys out
     const bool finish = A.finish_in_last_pass && pass == (int)A.params->passes - 1;
     const bool cached = (int64_t)A.plan.K * A.plan.S <= kEpiSegs;
@@ -1058,7 +1083,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     for (int i = 0; i < kSortItems; ++i) {
         const int e = wave * (kWave * kSortItems) + i * kWave + lane;
         const bool ok = e < valid;
-        const uint32_t d = digit_of(key[i], A.idx_bits < 32 ? (pay[i] >> A.idx_bits) : 0u, kb, pass);
+        const uint32_t d = digit_of(dig, key[i], pay[i]);
         // peers: the lanes that hold the same digit, found bit by bit.  Written on 32-bit halves as
         // peers & ~(vote ^ all) with all = every bit set when the lane's digit has bit b: one three-input
         // bit operation per half and bit (the 64-bit select it replaces took nine vector instructions per bit,
@@ -1132,7 +1157,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
             const int j = i * kSortThreads + tid;
             if (j < valid) {
                 const uint32_t k = lds_key[j], p = lds_pay[j];
-                const uint32_t d = digit_of(k, A.idx_bits < 32 ? (p >> A.idx_bits) : 0u, kb, pass);
+                const uint32_t d = digit_of(dig, k, p);
                 const uint32_t dst = gbase[d] + (uint32_t)j;
                 if ((int64_t)dst < A.n) { dst_key[dst] = k; dst_pay[dst] = p; }
             }
@@ -1156,7 +1181,7 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         out[i] = 0;
         if (j < valid) {
             const uint32_t k = lds_key[j], p = lds_pay[j];
-            const uint32_t d = digit_of(k, A.idx_bits < 32 ? (p >> A.idx_bits) : 0u, kb, pass);
+            const uint32_t d = digit_of(dig, k, p);
             const uint32_t dst = gbase[d] + (uint32_t)j;
             if ((int64_t)dst < A.n) {
                 epilogue_slot(A, tab, cached, (int64_t)dst, k, p, umin, idx_mask, r[i], out[i]);
