@@ -31,16 +31,18 @@ namespace {
 constexpr int kRadixBits = 8;
 constexpr int kRadix = 1 << kRadixBits;
 constexpr int kSortThreads = 512;
-constexpr int kSortItems = 16;                         // elements per thread of a radix pass: a tile holds 8192 elements,
+constexpr int kSortItems = 8;                          // elements per thread of a radix pass: a tile holds 4096 elements (three
+                                                       // workgroups per compute unit; with 8192, two fit: first downsweep 91 -> 72 us
+                                                       // on 16.8 million requests, the call 0.574 -> 0.562 ms),
 constexpr int kSmallItems = 4;                         // or 2048 when there are few requests: more, shorter-lived workgroups
-                                                       // (a million shuffled requests: 0.171 -> 0.133 ms per call; 4096 was no better)
+                                                       // (a million shuffled requests: 0.171 -> 0.133 ms per call)
 constexpr int64_t kSmallTileMax = (int64_t)1 << 22;    // up to this many requests the small tile is used
 constexpr int kSortWaves = kSortThreads / kWave;
 constexpr int kDies = 8;                               // accelerator dies (XCDs), each with its own L2
 constexpr int kChunkTiles = 32;                        // tiles per chunk of the two-level scan over tiles
 constexpr int kConsTile = 256;                         // queue slots per workgroup in the consistent-dropping kernels
 constexpr int kConsRanges = 8192;                      // workgroups of those kernels at most (each owns a range of tiles)
-constexpr int kFusedScanChunks = 64;                   // up to here every chunk scans the chunk totals itself
+constexpr int kFusedScanChunks = 128;                  // up to here every chunk scans the chunk totals itself
 
 constexpr int kRetBuckets = 512;                       // ranges of request ids the results are first gathered by, at most
 constexpr int kRetMaxShift = 15;                       // a range holds at most 2^15 request ids: its packed results fit one workgroup's LDS
@@ -904,7 +906,7 @@ __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass)
     if (SCANNED) {
         run = tot[c * kRadix + d];
     } else {
-        static_assert(kFusedScanChunks == 64, "the chunk totals of a digit are loaded in two halves of 32");
+        static_assert(kFusedScanChunks % 32 == 0, "the chunk totals of a digit are loaded in batches of 32");
         uint32_t all = 0, before = 0;
 #pragma unroll
         for (int64_t c0 = 0; c0 < kFusedScanChunks; c0 += 32) {

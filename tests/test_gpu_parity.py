@@ -82,7 +82,7 @@ def test_config4_half_survivors(gpu, oracle_mod, n, permute):
 
 def test_large_path_beyond_64_chunks(gpu, oracle_mod):
     """More than 2^24 requests in one snapshot: the radix passes then scan their chunk totals in a kernel of
-    their own (up to 64 chunks every chunk workgroup scans them itself).  Configuration 4's shape, shuffled,
+    their own (up to 128 chunks every chunk workgroup scans them itself).  Configuration 4's shape, shuffled,
     with latencies scaled so that the drop mask is mixed."""
     w = wl.half_survivors(wl.make_workload(4, n_requests=(1 << 24) + 8193, permute=True))
     s, ref = check(gpu, oracle_mod, w, threads=16)
@@ -271,7 +271,7 @@ def test_sizes_sort_path(gpu, oracle_mod, n):
                                     ((1 << 21) + 2049, "small tiles, ranges of 2^13 ids"),
                                     ((1 << 20) - 3, "ranges of 2^11 ids, the last one short")])
 def test_sort_path_tile_and_range_steps(gpu, oracle_mod, n, what):
-    """Request counts on either side of the steps the radix passes take (tiles of 2048 or 8192 elements; the way
+    """Request counts on either side of the steps the radix passes take (tiles of 2048 or 4096 elements; the way
     back to request order through ranges of 2^11 to 2^15 request ids), shuffled, with a mixed drop mask."""
     w = wl.half_survivors(wl.make_workload(4, n_requests=n, permute=True))
     s, ref = check(gpu, oracle_mod, w, threads=16)
