@@ -1062,8 +1062,6 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     const bool finish = A.finish_in_last_pass && pass == (int)A.params->passes - 1;
     const bool cached = (int64_t)A.plan.K * A.plan.S <= kEpiSegs;
     if (finish && cached && tid < A.plan.K * A.plan.S) tab[tid] = epilogue_segment(A, (uint32_t)tid);
-    const int rem_bits = (int)A.params->total_bits - kRadixBits * pass;
-    const int nbits = rem_bits < kRadixBits ? (rem_bits < 1 ? 1 : rem_bits) : kRadixBits;   // digit bits that can differ
     uint32_t* dst_key = A.key[pass & 1];
     uint32_t* dst_pay = A.pay[pass & 1];
     for (int i = tid; i < kSortWaves * kRadix; i += kSortThreads) (&whist[0][0])[i] = 0;
@@ -1092,22 +1090,14 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         // and this loop is what the kernel's time goes into).
         const unsigned long long live = __ballot(ok);
         uint32_t peers_lo = (uint32_t)live, peers_hi = (uint32_t)(live >> 32);
-        if (nbits == kRadixBits) {                 // (every pass but the last one)
+        // (the bits of the last digit above the key's top bit are zero in every lane: they vote alike and change nothing)
 #pragma unroll
-            for (int b = 0; b < kRadixBits; ++b) {
-                const int32_t all = (int32_t)(d << (31 - b)) >> 31;
-                const unsigned long long vote = __ballot(all < 0);
-                // x & ~(y ^ z): truth table 0x90 of the three-input bit operation
-                peers_lo = __builtin_amdgcn_bitop3_b32(peers_lo, (uint32_t)vote, (uint32_t)all, 0x90);
-                peers_hi = __builtin_amdgcn_bitop3_b32(peers_hi, (uint32_t)(vote >> 32), (uint32_t)all, 0x90);
-            }
-        } else {
-            for (int b = 0; b < nbits; ++b) {      // higher bits of this digit are zero for every key
-                const uint32_t all = 0u - ((d >> b) & 1u);
-                const unsigned long long vote = __ballot(all != 0u);
-                peers_lo &= ~((uint32_t)vote ^ all);
-                peers_hi &= ~((uint32_t)(vote >> 32) ^ all);
-            }
+        for (int b = 0; b < kRadixBits; ++b) {
+            const int32_t all = (int32_t)(d << (31 - b)) >> 31;
+            const unsigned long long vote = __ballot(all < 0);
+            // x & ~(y ^ z): truth table 0x90 of the three-input bit operation
+            peers_lo = __builtin_amdgcn_bitop3_b32(peers_lo, (uint32_t)vote, (uint32_t)all, 0x90);
+            peers_hi = __builtin_amdgcn_bitop3_b32(peers_hi, (uint32_t)(vote >> 32), (uint32_t)all, 0x90);
         }
         const uint32_t before = __builtin_amdgcn_mbcnt_hi(peers_hi, __builtin_amdgcn_mbcnt_lo(peers_lo, 0u));
         const uint32_t count = (uint32_t)(__popc(peers_lo) + __popc(peers_hi));
