@@ -44,6 +44,7 @@ __device__ __forceinline__ int4 in_load(const int4* p) {
 
 constexpr int kPsStages = kPresortedMaxStages;     // 3-bit count fields of stages 0..5 plus one for slots that are not live
 constexpr uint32_t kDeadStage = 7;
+constexpr int kPsEntries = 128;                    // path entries of a DAG kept in LDS (longer lists are read in place)
 
 template <int T>
 struct PresortedLds {
@@ -62,6 +63,7 @@ struct PresortedLds {
     int32_t seg_start[kPsStages + 1];
     uint32_t disorder[T / kWave];                             // per wave: it saw a deadline fall
     uint32_t ktot[SUB];                                       // kept slots per sub-block
+    uint32_t ent[kPsEntries];                                 // the DAG's path entries: stage | (end of the entry's path) << 8
     uint32_t verdict;                                         // 0: in order and finished here, 1: left to the general kernel
 };
 
@@ -112,6 +114,13 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
         }
     }
     for (int i = tid; i < S * PARD_LAT_ENTRIES; i += T) L.lat[i] = (uint32_t)lat_dag[i];
+    // The path entries are walked by one wave while the others wait (step 3): from LDS that walk is a few reads, from
+    // memory a chain of dependent loads, one per stage of a path.  They are fetched here, behind the request loads.
+    const int e_lo = P.dag_entry_ptr[dag], n_entries = P.dag_entry_ptr[dag + 1] - e_lo;
+    const bool entries_cached = n_entries <= kPsEntries;
+    if (entries_cached)
+        for (int e = tid; e < n_entries; e += T)
+            L.ent[e] = (uint32_t)P.entry_stage[e_lo + e] | ((uint32_t)(P.entry_end[e_lo + e] - e_lo) << 8);
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(P.recs + (int64_t)dag * S);
         uint32_t* dst = reinterpret_cast<uint32_t*>(L.recs);
@@ -189,7 +198,7 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
             if (lane == 0) L.seg_start[k] = (int32_t)start;
             if (lane == k && k < S) {
                 const StageRec& r = L.recs[k];
-                L.cfull[k] = stage_cost(r, total, lat_dag + k * PARD_LAT_ENTRIES);
+                L.cfull[k] = stage_cost(r, total, reinterpret_cast<const int32_t*>(L.lat) + k * PARD_LAT_ENTRIES);
                 L.quick[k][0] = (uint32_t)r.B - 1u;
                 L.quick[k][1] = __float_as_uint(r.rcpB);
                 L.quick[k][2] = __float_as_uint(r.rcpW);
@@ -215,9 +224,16 @@ __device__ __forceinline__ void presorted_body(const FusedArgs& A, PresortedLds<
                     const int64_t v = A.sub[(int64_t)u * S + lane];
                     L.down[lane] = v < 0 ? 0ull : ((uint64_t)v < kCostCap ? (unsigned long long)v : (unsigned long long)kCostCap);
                 }
+            } else if (entries_cached) {
+                for (int e = lane; e < n_entries; e += kWave) {
+                    const uint32_t me = L.ent[e];
+                    const int end = (int)(me >> 8);
+                    unsigned long long sum = 0;
+                    for (int t = e + 1; t < end; ++t) sum += L.cfull[L.ent[t] & 0xFFu];
+                    atomicMax(&L.down[me & 0xFFu], sum);
+                }
             } else {
-                const int e_lo = P.dag_entry_ptr[dag], e_hi = P.dag_entry_ptr[dag + 1];
-                for (int e = e_lo + lane; e < e_hi; e += kWave) {
+                for (int e = e_lo + lane; e < e_lo + n_entries; e += kWave) {
                     const int end = P.entry_end[e];
                     unsigned long long sum = 0;
                     for (int t = e + 1; t < end; ++t) sum += L.cfull[P.entry_stage[t]];
