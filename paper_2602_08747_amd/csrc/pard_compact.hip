@@ -480,12 +480,13 @@ __global__ __launch_bounds__(THREADS, 4) void compact_local_kernel(CompactArgs A
     __shared__ LocalLds<THREADS> L;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t u = blockIdx.x;
+    const uint32_t my_kept = kept[u];   // asked for together with the snapshot's bounds: what is loaded below depends on both
     int64_t a, b;
     if (!snapshot_range(A.seg_ptr, u, A.stages, A.n, (int64_t)THREADS * 16, a, b)) return;     // reported by the counting kernel
     const int size = (int)(b - a);
     // a snapshot without survivors (its slice of drop[] has no zero byte) only owes its queue offsets:
     // neither its slots nor its drop bytes are read
-    const int load_size = kept[u] == 0 ? 0 : size;
+    const int load_size = my_kept == 0 ? 0 : size;
 
     // this snapshot's slots: wave w owns [w*1024, (w+1)*1024), load k covers 256 of them, 4 per lane.
     // Slot q of the snapshot is element q + off of that layout, off = a mod 4 when order[] allows 16-byte
