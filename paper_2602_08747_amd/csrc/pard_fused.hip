@@ -649,10 +649,12 @@ __global__ __launch_bounds__(T, 4) void fused_snapshot_kernel(FusedArgs A) {
     constexpr int kCap = CAP;
     __shared__ SnapshotLds<CAP, SCAP> L;
     const int u = blockIdx.x;
-    if (A.todo && A.todo[u] == 0u) return;       // already done by the kernel for snapshots that come in queue order
+    // (the mark and the snapshot's bounds are asked for together: one wait instead of two for a marked snapshot)
+    const uint32_t marked = A.todo ? A.todo[u] : 1u;
+    int64_t lo = A.snap_ptr[u], hi = A.snap_ptr[u + 1];
+    if (marked == 0u) return;                    // already done by the kernel for snapshots that come in queue order
     const int64_t n = A.n;
     // snapshot bounds, made safe whatever snap_ptr holds
-    int64_t lo = A.snap_ptr[u], hi = A.snap_ptr[u + 1];
     if (lo < 0) lo = 0;
     if (lo > n) lo = n;
     if (hi > n) hi = n;
