@@ -70,7 +70,7 @@ constexpr unsigned long long kNoRequest = ~0ull;          // sorts behind every 
 constexpr int kStageShift = 40, kKeyShift = 8;            // word = stage << 40 | key << 8 | local index
 
 // LDS words (4 bytes) a snapshot of up to 64 * R requests and S stages needs.
-__host__ __device__ constexpr int wave_lds_words(int R, int S) { return kWave * R + 17 * S + 2; }
+__host__ __device__ constexpr int wave_lds_words(int R, int S) { return kWave * R + 17 * S + 2 + kWave; }
 
 // Lanes l of slot row r (slots r * 64 + l) with first <= r * 64 + l < end.
 __device__ __forceinline__ unsigned long long row_mask(int r, int first, int end) {
@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
     unsigned long long* down = cfull + S;                                              // [S]
     StageRec* recs = reinterpret_cast<StageRec*>(lds + N + 4 * S);                     // [S]
     int32_t* seg_start = reinterpret_cast<int32_t*>(lds + N + 16 * S);                 // [S + 1]
+    uint32_t* ent = lds + N + 17 * S + 2;                                              // [64] the DAG's path entries (up to 64)
     static_assert(sizeof(StageRec) == 48, "LDS layout");
 
     const int u = blockIdx.x;
@@ -131,6 +132,11 @@ __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
         for (int i = lane; i < S * (int)(sizeof(StageRec) / 4); i += kWave) dst[i] = src[i];
         for (int i = lane; i < S; i += kWave) down[i] = 0;
     }
+    // The path entries (stage | end of the entry's path << 8) are fetched now, behind the request loads: walked in
+    // memory after the sort they are a chain of dependent loads, one per stage of a path.
+    const bool entries_cached = n_entries <= kWave;
+    if (entries_cached && lane < n_entries)
+        ent[lane] = (uint32_t)P.entry_stage[e_lo + lane] | ((uint32_t)(P.entry_end[e_lo + lane] - e_lo) << 8);
     __syncthreads();
     unsigned long long c[R];
 #pragma unroll
@@ -171,6 +177,14 @@ __global__ __launch_bounds__(kWave, 8) void wave_snapshot_kernel(FusedArgs A) {
         for (int i = lane; i < S; i += kWave) {
             const int64_t v = A.sub[(int64_t)u * S + i];
             down[i] = v < 0 ? 0ull : ((uint64_t)v < kCostCap ? (unsigned long long)v : (unsigned long long)kCostCap);
+        }
+    } else if (entries_cached) {
+        if (lane < n_entries) {
+            const uint32_t me = ent[lane];
+            const int end = (int)(me >> 8);
+            unsigned long long sum = 0;
+            for (int t = lane + 1; t < end; ++t) sum += cfull[ent[t] & 0xFFu];
+            atomicMax(&down[me & 0xFFu], sum);
         }
     } else {
         for (int e = e_lo + lane; e < e_lo + n_entries; e += kWave) {
