@@ -693,7 +693,7 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
             compact_local_kernel<THREADS><<<(unsigned)K, THREADS, 0, stream>>>(a, kept, scan ? snap_off : nullptr);
         };
         if (a.max_snapshot <= 4096) run(std::integral_constant<int, 256>{}, std::integral_constant<int, 128>{});
-        else run(std::integral_constant<int, 512>{}, std::integral_constant<int, 256>{});
+        else run(std::integral_constant<int, 512>{}, std::integral_constant<int, 128>{});
         return hipGetLastError();
     }
     // the stream of tiles: count, (scan), write; no workgroup waits for another
