@@ -68,6 +68,29 @@ def test_static_scratch_calls_in_a_row(gpu, oracle_mod):
     _both(gpu, oracle_mod, first, FORCE_SORT)
 
 
+def test_static_scratch_at_its_limit(gpu, oracle_mod):
+    """The largest request count of the large-snapshot path the built-in buffer serves (found by asking: one request
+    more is refused with PARD_E_SCRATCH before anything is launched): the call uses the buffer up to its last tables
+    and gives the oracle's results; a smaller call right after it shares the buffer."""
+    probe = gpu.Session(wl.make_workload(3, n_requests=1000), max_snapshot_requests=FORCE_SORT)
+
+    def fits(n):
+        return gpu.pard_estimate_drop_static(probe.plan, n, FORCE_SORT, probe.arrival, None, probe.stage, probe.snap_ptr,
+                                             probe.now, probe.est, probe.drop, probe.order, probe.seg_ptr, None,
+                                             check=False) != -12
+    lo, hi = 1000, 4_000_000                       # fits(lo), not fits(hi); the null deadline keeps every probe from launching
+    assert fits(lo) and not fits(hi)
+    while hi - lo > 1:
+        mid = (lo + hi) // 2
+        if fits(mid):
+            lo = mid
+        else:
+            hi = mid
+    assert 1_000_000 < lo < 2_000_000, lo
+    _both(gpu, oracle_mod, wl.make_workload(3, n_requests=lo, permute=True), None)      # one snapshot: the promise is its size
+    _both(gpu, oracle_mod, wl.make_workload(4, n_requests=123_457, permute=True), FORCE_SORT)
+
+
 def test_static_scratch_limits_and_status(gpu):
     import torch
     w = wl.make_workload(2, n_requests=1000)
