@@ -350,6 +350,15 @@ __global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
         if constexpr (!watch) load_chunk(A, base, lane, vec, seg, key, ok);
         if constexpr (watch) {
             uint32_t snap[kScanItems];
+            // The deadline just before the chunk (lane 0) and, under high budget first, the ones kTieReach before
+            // the lowest lanes' first requests are asked for here, so that they travel with the chunk's own loads
+            // instead of costing a wait of their own each.
+            int32_t d_before = 0, d_far = 0;
+            const bool has_before = lane == 0 && base > 0 && base < A.n;
+            if (has_before) d_before = A.deadline[base - 1];
+            const int64_t r_far = lane_first(base, lane, 0) - kTieReach;
+            const bool has_far = MODE == PARD_ORDER_HBF && lane < kTieReach / 4 && r_far >= 0 && r_far + kTieReach < A.n;
+            if (has_far) d_far = A.deadline[r_far];
             load_chunk_by_deadline<MODE>(A, base, lane, vec, bound, snap, seg, key, ok);
             // the request before a lane's four: the last of the lane below; lane 0: the last request of the group
             // before, or for the chunk's first group the one in memory
@@ -363,8 +372,8 @@ __global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
                 } else if (lane == 0) {
                     before = key[0];
                     before_snap = snap[0];
-                    if (base > 0 && base < A.n) {
-                        before = order_key(MODE, A.deadline[base - 1], 0);
+                    if (has_before) {
+                        before = order_key(MODE, d_before, 0);
                         before_snap = (uint32_t)snapshot_of(A.snap_ptr, A.plan.K, base - 1);
                     }
                 }
@@ -390,9 +399,8 @@ __global__ __launch_bounds__(kScanThreads, 8) void count_kernel(SortDev A) {
                         const uint32_t wrapped = (uint32_t)__shfl((int)key[g * 4 - 4], lane + kWave - kTieReach / 4);
                         if (lane < kTieReach / 4) far = wrapped;
                     } else if (lane < kTieReach / 4) {
-                        const int64_t r = lane_first(base, lane, g) - kTieReach;
                         far = ~key[g * 4];
-                        if (r >= 0 && r + kTieReach < A.n) far = order_key(MODE, A.deadline[r], 0);
+                        if (has_far) far = order_key(MODE, d_far, 0);
                     }
                     if (ok[g * 4] && key[g * 4] == far) saw |= kSawLongTie;
                 }
@@ -1507,6 +1515,17 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
         const int64_t base = chunk * kWaveChunk;
         uint32_t snap[kScanItems], seg[kScanItems], key[kScanItems], j[kScanItems];
         bool ok[kScanItems];
+        // (the neighbours on either side of the chunk, needed under high budget first, are asked for before the chunk
+        // itself so that all of them travel together: a wait of their own per chunk otherwise)
+        int32_t halo_d[2] = {0, 0}, halo_st[2] = {0, 0};
+        if constexpr (HBF) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int h = lane + t * kWave;
+                const int64_t r = h < kTieSearch ? base - kTieSearch + h : base + kWaveChunk + (h - kTieSearch);
+                if (h < 2 * kTieSearch && r >= 0 && r < A.n) { halo_d[t] = A.deadline[r]; halo_st[t] = A.stage[r]; }
+            }
+        }
         load_chunk_by_deadline<HBF ? PARD_ORDER_HBF : PARD_ORDER_LBF>(A, base, lane, vec, bound, snap, seg, key, ok);
         // same queue, same deadline, to the left / right of a request: among the lane's own four, and beyond them (a byte each)
         uint32_t near_before[kScanItems] = {0, 0, 0, 0, 0, 0, 0, 0}, near_after[kScanItems] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -1524,9 +1543,9 @@ __global__ __launch_bounds__(kSplitThreads) void split_kernel(SortDev A) {
                     const int at = left ? h : kTieSearch + kWaveChunk + (h - kTieSearch);
                     uint32_t k = 0, sg = 0xFFu;
                     if (r >= 0 && r < A.n) {
-                        k = order_key(PARD_ORDER_HBF, A.deadline[r], 0);
+                        k = order_key(PARD_ORDER_HBF, halo_d[t], 0);
                         const uint32_t u = P.K == 1 ? 0u : (uint32_t)snapshot_of(A.snap_ptr, P.K, r);
-                        sg = u * (uint32_t)P.S + (uint32_t)clamp_stage(A.stage[r], P.S);
+                        sg = u * (uint32_t)P.S + (uint32_t)clamp_stage(halo_st[t], P.S);
                     }
                     hk[at] = k;
                     hs[at] = (uint8_t)sg;
