@@ -1393,15 +1393,18 @@ __global__ __launch_bounds__(kRetWgThreads) void epilogue_return_kernel(SortDev 
     const int64_t first = (int64_t)blockIdx.x << kRetShift;
     if (first >= A.n) return;
     const int room = (int)(A.n - first < kRetRange ? A.n - first : kRetRange);
+    // A range holds exactly its share of results unless a snapshot broke its promise, so the loads do not wait for the
+    // count: they cover the range's whole room (all of it inside the buffer), and the count only decides which of the
+    // words loaded are results.
     int cnt = (int)A.ret_cursor[blockIdx.x];
     if (cnt > room) cnt = room;
     constexpr int kAhead = 4;                                   // groups of four per thread in flight
-    for (int i0 = tid * 4; i0 < cnt; i0 += kRetWgThreads * 4 * kAhead) {
+    for (int i0 = tid * 4; i0 < room; i0 += kRetWgThreads * 4 * kAhead) {
         uint32_t rr[kAhead][4], oo[kAhead][4];
 #pragma unroll
         for (int a = 0; a < kAhead; ++a) {
             const int i = i0 + a * kRetWgThreads * 4;
-            if (i + 3 < cnt) {
+            if (i + 3 < room) {
                 const pard_v4i rv = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(ret_r + first + i));
                 const pard_v4i ov = __builtin_nontemporal_load(reinterpret_cast<const pard_v4i*>(ret_out + first + i));
                 rr[a][0] = (uint32_t)rv.x; rr[a][1] = (uint32_t)rv.y; rr[a][2] = (uint32_t)rv.z; rr[a][3] = (uint32_t)rv.w;
@@ -1409,8 +1412,8 @@ __global__ __launch_bounds__(kRetWgThreads) void epilogue_return_kernel(SortDev 
             } else {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
-                    rr[a][c] = i + c < cnt ? ret_r[first + i + c] : 0u;
-                    oo[a][c] = i + c < cnt ? ret_out[first + i + c] : 0u;
+                    rr[a][c] = i + c < room ? ret_r[first + i + c] : 0u;
+                    oo[a][c] = i + c < room ? ret_out[first + i + c] : 0u;
                 }
             }
         }
