@@ -619,22 +619,73 @@ __global__ __launch_bounds__(1024) void setup_kernel(SortDev A) {
     }
     const int64_t per_dag = P.dag_entry_ptr[1];                              // entries of the one shared DAG
     const int64_t items = P.shared ? per_dag * P.K : P.total_entries;        // (snapshot, path entry) pairs
-    for (int64_t b = tid; b < items; b += 1024) {
-        int32_t u, e;
-        if (P.shared) { u = (int32_t)(b / per_dag); e = (int32_t)(b - (int64_t)u * per_dag); }
-        else { e = (int32_t)b; u = P.entry_dag[e]; }
-        const int32_t end = P.entry_end[e];
-        unsigned long long sum = 0;
-        // the later stages of the path, eight ids in flight (a path is a dependent walk otherwise)
-        for (int32_t t0 = e + 1; t0 < end; t0 += 8) {
-            int32_t later[8];
+    // Four pairs per thread at a time, each step of the walk issued for all four before any is used: with thousands of
+    // queues this one workgroup has tens of thousands of pairs to walk, and a pair is a chain of dependent loads
+    // (its snapshot, the end of its path, the stages behind it, their costs).
+    constexpr int kPairs = 4;
+    if (items <= 1024) {                     // a pair per thread at most: the plain walk
+        const int64_t b = tid;
+        if (b < items) {
+            int32_t u, e;
+            if (P.shared) { u = (int32_t)(b / per_dag); e = (int32_t)(b - (int64_t)u * per_dag); }
+            else { e = (int32_t)b; u = P.entry_dag[e]; }
+            const int32_t end = P.entry_end[e];
+            unsigned long long sum = 0;
+            for (int32_t t0 = e + 1; t0 < end; t0 += 8) {
+                int32_t later[8];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) later[k] = t0 + k < end ? P.entry_stage[t0 + k] : -1;
+                for (int k = 0; k < 8; ++k) later[k] = t0 + k < end ? P.entry_stage[t0 + k] : -1;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (later[k] >= 0) sum += few ? cfull_l[(int64_t)u * P.S + later[k]] : A.cfull[(int64_t)u * P.S + later[k]];
+            }
+            atomicMax(&A.down[(int64_t)u * P.S + P.entry_stage[e]], sum);
+        }
+        return;
+    }
+    for (int64_t b0 = tid; b0 < items; b0 += 1024 * kPairs) {
+        int32_t u[kPairs], e[kPairs], end[kPairs], own[kPairs];
+        bool live[kPairs];
+#pragma unroll
+        for (int q = 0; q < kPairs; ++q) {
+            const int64_t b = b0 + (int64_t)q * 1024;
+            live[q] = b < items;
+            u[q] = 0;
+            e[q] = 0;
+            if (live[q]) {
+                if (P.shared) { u[q] = (int32_t)(b / per_dag); e[q] = (int32_t)(b - (int64_t)u[q] * per_dag); }
+                else { e[q] = (int32_t)b; u[q] = P.entry_dag[e[q]]; }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < kPairs; ++q) {
+            end[q] = live[q] ? P.entry_end[e[q]] : e[q] + 1;
+            own[q] = live[q] ? P.entry_stage[e[q]] : 0;
+        }
+        unsigned long long sum[kPairs] = {0, 0, 0, 0};
+        int32_t later[kPairs][8];
+#pragma unroll
+        for (int q = 0; q < kPairs; ++q)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) later[q][k] = e[q] + 1 + k < end[q] ? P.entry_stage[e[q] + 1 + k] : -1;
+#pragma unroll
+        for (int q = 0; q < kPairs; ++q)
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                if (later[k] >= 0) sum += few ? cfull_l[(int64_t)u * P.S + later[k]] : A.cfull[(int64_t)u * P.S + later[k]];
+                if (later[q][k] >= 0) sum[q] += few ? cfull_l[(int64_t)u[q] * P.S + later[q][k]] : A.cfull[(int64_t)u[q] * P.S + later[q][k]];
+#pragma unroll
+        for (int q = 0; q < kPairs; ++q) {
+            // paths with more than eight stages behind the entry: the rest, eight ids in flight
+            for (int32_t t0 = e[q] + 9; t0 < end[q]; t0 += 8) {
+                int32_t more[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) more[k] = t0 + k < end[q] ? P.entry_stage[t0 + k] : -1;
+#pragma unroll
+                for (int k = 0; k < 8; ++k)
+                    if (more[k] >= 0) sum[q] += few ? cfull_l[(int64_t)u[q] * P.S + more[k]] : A.cfull[(int64_t)u[q] * P.S + more[k]];
+            }
+            if (live[q]) atomicMax(&A.down[(int64_t)u[q] * P.S + own[q]], sum[q]);
         }
-        atomicMax(&A.down[(int64_t)u * P.S + P.entry_stage[e]], sum);
     }
 }
 
