@@ -14,7 +14,7 @@
 //   results   queue position = sorted position - queue offset; own-stage cost + downstream maximum; drop
 //             decision.  Formed inside the last pass (which then writes the queue order instead of its keys)
 //             and brought back to request order in two steps: gathered by range of request ids, then one
-//             workgroup per range.  Beyond 2^24 requests: est|drop scattered to request order as one word by
+//             workgroup per range.  Beyond 2^25 requests: est|drop scattered to request order as one word by
 //             a kernel of its own, then unpacked by a streaming kernel.
 //
 // The sort key is the virtual integer  V = segment << kb | (key - min key)  where kb is
@@ -44,7 +44,8 @@ constexpr int kConsTile = 256;                         // queue slots per workgr
 constexpr int kConsRanges = 8192;                      // workgroups of those kernels at most (each owns a range of tiles)
 constexpr int kFusedScanChunks = 128;                  // up to here every chunk scans the chunk totals itself
 
-constexpr int kRetBuckets = 512;                       // ranges of request ids the results are first gathered by, at most
+constexpr int kRetBuckets = 1024;                      // ranges of request ids the results are first gathered by, at most
+                                                       // (up to 512 as long as ranges of 2^15 ids cover the requests)
 constexpr int kRetMaxShift = 15;                       // a range holds at most 2^15 request ids: its packed results fit one workgroup's LDS
 constexpr int kRetMinShift = 11;                       // and at least 2^11 (few requests: more, smaller ranges keep the chip busy)
 
@@ -81,8 +82,10 @@ SortLayout make_layout(int32_t K, int32_t S, int64_t n, int64_t max_snap) {
     L.idx_bits = bits_of(span > 0 ? (uint64_t)(span - 1) : 0);
     L.seg_bits = bits_of((uint64_t)(segs - 1));
     L.max_passes = (32 + L.seg_bits + kRadixBits - 1) / kRadixBits;
-    L.ret_shift = bits_of(n > 0 ? (uint64_t)(n - 1) : 0) - 9;       // kRetBuckets ranges of 2^ret_shift request ids cover n
-    if (L.ret_shift < kRetMinShift) L.ret_shift = kRetMinShift;     // (beyond kRetMaxShift the results go back one by one)
+    L.ret_shift = bits_of(n > 0 ? (uint64_t)(n - 1) : 0) - 9;       // 512 ranges of 2^ret_shift request ids cover n;
+    if (L.ret_shift < kRetMinShift) L.ret_shift = kRetMinShift;
+    if (L.ret_shift == kRetMaxShift + 1) L.ret_shift = kRetMaxShift; // up to 2^25 requests: kRetBuckets ranges of the largest size
+                                                                    // (beyond that the results go back one by one)
     L.tile_items = n <= kSmallTileMax ? kSmallItems : kSortItems;
     const int64_t tile = (int64_t)kSortThreads * L.tile_items;
     L.tiles = (n + tile - 1) / tile;
@@ -1009,7 +1012,7 @@ __global__ __launch_bounds__(kRadix) void chunk_scan_kernel(SortDev A, int pass)
 // reserves its place in every range with one atomic add (every id occurs once: a range holds exactly its share).
 // A second kernel gives every range to one workgroup that puts each packed word at its request's place in LDS
 // and writes the estimates and decisions of the range out in request order.  Up to kRetBuckets ranges of at most
-// 2^kRetMaxShift ids; beyond that (more than 2^24 requests) the last pass writes its keys like any other, and
+// 2^kRetMaxShift ids; beyond that (more than 2^25 requests) the last pass writes its keys like any other, and
 // epilogue_kernel scatters est | drop as ONE 4-byte write per request into the key buffer the last pass no
 // longer needs, which unpack_kernel then streams out.
 //
@@ -1219,12 +1222,13 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
     // Last pass: element j of the reordered tile lands in queue slot gbase[digit] + j.
     uint32_t* first_place = &whist[0][0];            // results of the tile per range, then the range's first place in the tile
     uint32_t* delta = &whist[0][0] + kRetBuckets;    // the range's reserved place in memory minus its first place in the tile
-    static_assert(2 * kRetBuckets <= kSortWaves * kRadix && kRetBuckets == kSortThreads, "the range counters reuse the digit counters");
+    static_assert(2 * kRetBuckets <= kSortWaves * kRadix && kRetBuckets == 2 * kSortThreads, "the range counters reuse the digit counters, two ranges to a thread");
     const uint32_t idx_mask = A.idx_bits >= 32 ? 0xFFFFFFFFu : ((1u << A.idx_bits) - 1u);
     const int shift = A.ret_shift;
     const int64_t range = (int64_t)1 << shift;
     uint32_t r[kSortItems], out[kSortItems], rb[kSortItems];    // rb = place among the tile's results of its range | range << 16
     first_place[tid] = 0;                            // (the digit counters were last read before the barrier above)
+    first_place[tid + kSortThreads] = 0;
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const int j = i * kSortThreads + tid;
@@ -1267,15 +1271,27 @@ __global__ __launch_bounds__(kSortThreads, 4) void downsweep_kernel(SortDev A, i
         rb[i] = ok ? (place | (b << 16)) : 0xFFFFFFFFu;
     }
     __syncthreads();
-    // one thread per range: the range's first place in the tile, and room for the tile's results in the range
+    // Thread t takes ranges t and t + 512 (the second only exists beyond 2^24 requests): a range's first place in the
+    // tile, and room for the tile's results in the range.  Both counts ride one scan, 16 bits each (a tile holds at
+    // most 4096 results); the upper ranges come behind all the lower ones.  A wave's atomic adds cover 64
+    // neighbouring counters, whole cache lines: two half-filled requests per line and tile (neighbouring ranges to a
+    // thread) took the last pass from 146 to 203 us, the adds of all tiles to one line being served one after the other.
     {
-        const uint32_t cnt = first_place[tid];
-        const uint32_t start = block_exclusive_scan(cnt, scan_tmp, tid);
-        uint32_t base = 0;
-        if (cnt) base = atomicAdd(&A.ret_cursor[tid], cnt);
-        first_place[tid] = start;
-        delta[tid] = base - start;
-        if (tid == kSortThreads - 1) tile_total = start + cnt;
+        const uint32_t cnt0 = first_place[tid], cnt1 = first_place[tid + kSortThreads];
+        const uint32_t before = block_exclusive_scan(cnt0 | (cnt1 << 16), scan_tmp, tid);
+        uint32_t base0 = 0, base1 = 0;
+        if (cnt0) base0 = atomicAdd(&A.ret_cursor[tid], cnt0);
+        if (cnt1) base1 = atomicAdd(&A.ret_cursor[tid + kSortThreads], cnt1);
+        uint32_t totals = 0;                         // the scan leaves every wave's total behind: both fields of the whole tile
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) totals += scan_tmp[w];
+        const uint32_t lower_total = totals & 0xFFFFu;
+        if (tid == 0) tile_total = lower_total + (totals >> 16);
+        const uint32_t start0 = before & 0xFFFFu, start1 = lower_total + (before >> 16);
+        first_place[tid] = start0;
+        first_place[tid + kSortThreads] = start1;
+        delta[tid] = base0 - start0;
+        delta[tid + kSortThreads] = base1 - start1;
     }
     __syncthreads();
 #pragma unroll
@@ -2249,7 +2265,7 @@ hipError_t launch_sort_path(const SortArgs& a, hipStream_t stream) {
             if (eg > 8 * (int64_t)a.num_cus) eg = 8 * (int64_t)a.num_cus;
             if (eg < 1) eg = 1;
             if (!D.finish_in_last_pass) {
-                // more requests than kRetBuckets ranges of the largest size hold: results go back one by one
+                // more requests than kRetBuckets ranges of the largest size hold (2^25): results go back one by one
                 epilogue_kernel<<<(unsigned)eg, kEpiThreads, 0, stream>>>(D);
                 unpack_kernel<<<gb, 256, 0, stream>>>(D);
             } else {

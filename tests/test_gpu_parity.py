@@ -80,10 +80,20 @@ def test_config4_half_survivors(gpu, oracle_mod, n, permute):
     assert (ref["est"] < INT32_MAX).mean() > 0.5
 
 
+def test_large_path_beyond_two_to_the_25(gpu, oracle_mod):
+    """More than 2^25 requests in one snapshot: beyond the 1024 ranges of 2^15 request ids through which the results
+    of smaller calls go back to request order, so every result is written at its request's place by a kernel of its
+    own and unpacked by a streaming one.  Configuration 4's shape, shuffled, with a mixed drop mask."""
+    w = wl.half_survivors(wl.make_workload(4, n_requests=(1 << 25) + 4097, permute=True))
+    s, ref = check(gpu, oracle_mod, w, threads=16)
+    assert 0.1 < ref["drop"].mean() < 0.9
+
+
 def test_large_path_beyond_64_chunks(gpu, oracle_mod):
     """More than 2^24 requests in one snapshot: the radix passes then scan their chunk totals in a kernel of
-    their own (up to 128 chunks every chunk workgroup scans them itself).  Configuration 4's shape, shuffled,
-    with latencies scaled so that the drop mask is mixed."""
+    their own (up to 128 chunks every chunk workgroup scans them itself), and the results go back to request order
+    through more than 512 ranges of request ids (two ranges to a thread in the last pass).  Configuration 4's shape,
+    shuffled, with latencies scaled so that the drop mask is mixed."""
     w = wl.half_survivors(wl.make_workload(4, n_requests=(1 << 24) + 8193, permute=True))
     s, ref = check(gpu, oracle_mod, w, threads=16)
     assert 0.1 < ref["drop"].mean() < 0.9
